@@ -1,0 +1,256 @@
+"""CPU oracle for the packed structured contractions -- TEST INFRASTRUCTURE ONLY.
+
+This package wraps ``dastac_oracle.c`` (plain C, double-precision accumulation,
+packed positions obtained by walking the iteration domain with a running
+counter; see the header of that file for the passages of the paper it
+follows).  It shares no code with the GPU library.  Only the tests, the smoke
+check and the benchmark's CPU-baseline leg may import it; the GPU library and
+its Python binding never do.
+
+All arrays are host NumPy arrays.  ``build()`` compiles the C file with gcc.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "dastac_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+DOM_TRIU, DOM_TRIL, DOM_TET, DOM_UHC, DOM_BAND = 0, 1, 2, 3, 4
+
+_i64 = ctypes.c_int64
+_fp = ctypes.POINTER(ctypes.c_float)
+_dp = ctypes.POINTER(ctypes.c_double)
+_ip = ctypes.POINTER(ctypes.c_int64)
+
+
+def build(force: bool = True) -> str:
+    """Compile the oracle with gcc (-O2, no fast-math: the loop order is the definition)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        )
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        build(force=False)
+        L = ctypes.CDLL(_LIB)
+        L.oracle_count_preceding.restype = _i64
+        L.oracle_count_preceding.argtypes = [ctypes.c_int, _ip, _ip]
+        L.oracle_count_domain.restype = _i64
+        L.oracle_count_domain.argtypes = [ctypes.c_int, _ip]
+        L.oracle_point_at.restype = ctypes.c_int
+        L.oracle_point_at.argtypes = [ctypes.c_int, _ip, _i64, _ip]
+        L.oracle_triu_row_starts.restype = None
+        L.oracle_triu_row_starts.argtypes = [_i64, _ip]
+        L.oracle_tet_fibre_starts.restype = _i64
+        L.oracle_tet_fibre_starts.argtypes = [_i64, _ip]
+        L.oracle_triu_position.restype = _i64
+        L.oracle_triu_position.argtypes = [_i64, _i64, _i64]
+        L.oracle_tet_position.restype = _i64
+        L.oracle_tet_position.argtypes = [_i64, _i64, _i64, _i64]
+        L.oracle_triu_point_at.restype = ctypes.c_int
+        L.oracle_triu_point_at.argtypes = [_i64, _i64, _ip, _ip]
+        L.oracle_tet_point_at.restype = ctypes.c_int
+        L.oracle_tet_point_at.argtypes = [_i64, _i64, _ip, _ip, _ip]
+        L.oracle_pack_triu_f32.argtypes = [_i64, _fp, _i64, _fp]
+        L.oracle_unpack_triu_f32.argtypes = [_i64, _fp, _fp, _i64]
+        L.oracle_pack_tet_f32.argtypes = [_i64, _fp, _fp]
+        L.oracle_unpack_tet_f32.argtypes = [_i64, _fp, _fp]
+        L.oracle_pack_band_f32.argtypes = [_i64, _i64, _fp, _i64, _fp]
+        L.oracle_unpack_band_f32.argtypes = [_i64, _i64, _fp, _fp, _i64]
+        L.oracle_trmv_f32.argtypes = [_i64, _fp, _fp, _fp, _dp, _i64, _i64]
+        L.oracle_trmm_f32.argtypes = [_i64, _i64, _fp, _fp, _i64, _fp, _i64, _dp, _i64, _i64]
+        L.oracle_band_spmv_f32.argtypes = [_i64, _i64, _fp, _fp, _fp, _dp, _i64, _i64]
+        L.oracle_tet_ttv_f32.argtypes = [_i64, _fp, _fp, _fp, _dp, _i64, _i64]
+        L.oracle_tet_mttkrp_f32.argtypes = [_i64, _i64, _fp, _fp, _i64, _fp, _i64, _fp, _i64, _dp, _i64, _i64]
+        for name in ("pack_triu", "unpack_triu", "pack_tet", "unpack_tet", "pack_band", "unpack_band",
+                     "trmv", "trmm", "band_spmv", "tet_ttv", "tet_mttkrp"):
+            getattr(L, "oracle_%s_f32" % name).restype = None
+        _lib = L
+    return _lib
+
+
+def _f(a: np.ndarray):
+    assert a.dtype == np.float32 and a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(_fp)
+
+
+def _d(a: np.ndarray):
+    assert a.dtype == np.float64 and a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(_dp)
+
+
+def _i(a: np.ndarray):
+    assert a.dtype == np.int64 and a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(_ip)
+
+
+def _f32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+# ---- counting definition -----------------------------------------------------
+
+def count_preceding(dom: int, params, idx) -> int:
+    p = np.asarray(list(params) + [0, 0, 0], dtype=np.int64)
+    x = np.asarray(list(idx) + [0, 0, 0], dtype=np.int64)
+    return int(lib().oracle_count_preceding(dom, _i(p), _i(x)))
+
+
+def count_domain(dom: int, params) -> int:
+    p = np.asarray(list(params) + [0, 0, 0], dtype=np.int64)
+    return int(lib().oracle_count_domain(dom, _i(p)))
+
+
+def point_at(dom: int, params, p: int):
+    prm = np.asarray(list(params) + [0, 0, 0], dtype=np.int64)
+    out = np.zeros(3, dtype=np.int64)
+    rc = lib().oracle_point_at(dom, _i(prm), int(p), _i(out))
+    if rc != 0:
+        return None
+    rank = 3 if dom in (DOM_TET, DOM_UHC) else 2
+    return tuple(int(t) for t in out[:rank])
+
+
+def triu_row_starts(n: int) -> np.ndarray:
+    s = np.zeros(n + 1, dtype=np.int64)
+    lib().oracle_triu_row_starts(n, _i(s))
+    return s
+
+
+def tet_fibre_starts(n: int):
+    s = np.zeros(n * n, dtype=np.int64) if n > 0 else np.zeros(1, dtype=np.int64)
+    total = int(lib().oracle_tet_fibre_starts(n, _i(s)))
+    return s[: n * n].reshape(n, n), total
+
+
+def triu_position(n, i, j) -> int:
+    return int(lib().oracle_triu_position(n, i, j))
+
+
+def tet_position(n, i, j, k) -> int:
+    return int(lib().oracle_tet_position(n, i, j, k))
+
+
+def triu_point_at(n, p):
+    i, j = _i64(), _i64()
+    rc = lib().oracle_triu_point_at(n, int(p), ctypes.byref(i), ctypes.byref(j))
+    return None if rc else (i.value, j.value)
+
+
+def tet_point_at(n, p):
+    i, j, k = _i64(), _i64(), _i64()
+    rc = lib().oracle_tet_point_at(n, int(p), ctypes.byref(i), ctypes.byref(j), ctypes.byref(k))
+    return None if rc else (i.value, j.value, k.value)
+
+
+# ---- compression / decompression --------------------------------------------
+
+def pack_triu(dense: np.ndarray) -> np.ndarray:
+    dense = _f32(dense)
+    n = dense.shape[0]
+    out = np.empty(int(triu_row_starts(n)[n]), dtype=np.float32)
+    lib().oracle_pack_triu_f32(n, _f(dense), dense.shape[1], _f(out))
+    return out
+
+
+def unpack_triu(n: int, packed: np.ndarray) -> np.ndarray:
+    packed = _f32(packed)
+    out = np.full((n, n), np.nan, dtype=np.float32)
+    lib().oracle_unpack_triu_f32(n, _f(packed), _f(out), n)
+    return out
+
+
+def pack_tet(dense: np.ndarray) -> np.ndarray:
+    dense = _f32(dense)
+    n = dense.shape[0]
+    _, total = tet_fibre_starts(n)
+    out = np.empty(total, dtype=np.float32)
+    lib().oracle_pack_tet_f32(n, _f(dense), _f(out))
+    return out
+
+
+def unpack_tet(n: int, packed: np.ndarray) -> np.ndarray:
+    packed = _f32(packed)
+    out = np.full((n, n, n), np.nan, dtype=np.float32)
+    lib().oracle_unpack_tet_f32(n, _f(packed), _f(out))
+    return out
+
+
+def pack_band(dense: np.ndarray, w: int) -> np.ndarray:
+    dense = _f32(dense)
+    n = dense.shape[0]
+    out = np.empty((2 * w + 1) * n, dtype=np.float32)
+    lib().oracle_pack_band_f32(n, w, _f(dense), dense.shape[1], _f(out))
+    return out
+
+
+def unpack_band(n: int, w: int, diag: np.ndarray) -> np.ndarray:
+    diag = _f32(diag)
+    out = np.full((n, n), np.nan, dtype=np.float32)
+    lib().oracle_unpack_band_f32(n, w, _f(diag), _f(out), n)
+    return out
+
+
+# ---- contractions: return (result fp32, scale fp64); rows outside the window are NaN ----
+
+def _window(n, rows):
+    return (0, n) if rows is None else (int(rows[0]), int(rows[1]))
+
+
+def trmv(n, Up, x, rows=None):
+    Up, x = _f32(Up), _f32(x)
+    lo, hi = _window(n, rows)
+    y = np.full(n, np.nan, dtype=np.float32)
+    sc = np.full(n, np.nan, dtype=np.float64)
+    lib().oracle_trmv_f32(n, _f(Up), _f(x), _f(y), _d(sc), lo, hi)
+    return y, sc
+
+
+def trmm(n, m, Up, B, rows=None):
+    Up, B = _f32(Up), _f32(B)
+    lo, hi = _window(n, rows)
+    C = np.full((n, m), np.nan, dtype=np.float32)
+    sc = np.full((n, m), np.nan, dtype=np.float64)
+    lib().oracle_trmm_f32(n, m, _f(Up), _f(B), B.shape[1] if B.ndim == 2 else m, _f(C), m, _d(sc), lo, hi)
+    return C, sc
+
+
+def band_spmv(n, w, D, x, rows=None):
+    D, x = _f32(D), _f32(x)
+    lo, hi = _window(n, rows)
+    y = np.full(n, np.nan, dtype=np.float32)
+    sc = np.full(n, np.nan, dtype=np.float64)
+    lib().oracle_band_spmv_f32(n, w, _f(D), _f(x), _f(y), _d(sc), lo, hi)
+    return y, sc
+
+
+def tet_ttv(n, Ap, v, rows=None):
+    Ap, v = _f32(Ap), _f32(v)
+    lo, hi = _window(n, rows)
+    cnt = int(triu_row_starts(n)[n])
+    M = np.full(cnt, np.nan, dtype=np.float32)
+    sc = np.full(cnt, np.nan, dtype=np.float64)
+    lib().oracle_tet_ttv_f32(n, _f(Ap), _f(v), _f(M), _d(sc), lo, hi)
+    return M, sc
+
+
+def tet_mttkrp(n, R, Ap, B, C, rows=None):
+    Ap, B, C = _f32(Ap), _f32(B), _f32(C)
+    lo, hi = _window(n, rows)
+    M = np.full((n, R), np.nan, dtype=np.float32)
+    sc = np.full((n, R), np.nan, dtype=np.float64)
+    lib().oracle_tet_mttkrp_f32(n, R, _f(Ap), _f(B), B.shape[1], _f(C), C.shape[1], _f(M), R, _d(sc), lo, hi)
+    return M, sc

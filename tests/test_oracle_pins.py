@@ -1,0 +1,326 @@
+"""Pins for the CPU oracle: every check here compares the oracle with something
+that is NOT the oracle -- values the paper prints, closed forms, NumPy library
+routines on the dense (uncompressed) tensor, or brute force on tiny inputs.
+
+A dense implementation that ignores the structure computes the same result
+(Section 6.1), so the dense NumPy product on the masked tensor is the
+definitional reference for every contraction.
+"""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from paper_2407_13726_amd import inputs
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rows(path):
+    with open(os.path.join(GOLDEN, path)) as f:
+        return [tuple(int(t) for t in ln.split()) for ln in f if ln.strip() and not ln.startswith("#")]
+
+
+# ---------------------------------------------------------------- offsets ----
+
+def test_lower_triangle_matches_paper_fused_polynomial(oracle):
+    """Section 4 worked example: counting preceding points of j<=i gives i/2 + i^2/2 + j."""
+    rows = _rows("lower_triangle_fused_polynomial.txt")
+    assert len(rows) == 21
+    for i, j, p in rows:
+        assert oracle.count_preceding(oracle.DOM_TRIL, [6], [i, j]) == p
+    # and the formula itself, for other orders
+    for n in (1, 2, 7, 11):
+        for i in range(n):
+            for j in range(i + 1):
+                want = Fraction(1, 2) * i + Fraction(1, 2) * i * i + j
+                assert oracle.count_preceding(oracle.DOM_TRIL, [n], [i, j]) == want
+
+
+def test_running_example_buffer_b_matches_paper_polynomial(oracle):
+    """Section 3: P_B(i,j,l) = (((N-1/2) Q i - 1/2 Q i^2) + Q j) + l for the upper half cube."""
+    rows = _rows("running_example_buffer_b_polynomial.txt")
+    assert len(rows) == 3 * 10 + 2 * (5 + 4 + 3)
+    for M, N, Q, i, j, l, p in rows:
+        assert oracle.count_preceding(oracle.DOM_UHC, [M, N, Q], [i, j, l]) == p
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 5, 8, 13])
+def test_upper_triangle_is_running_example_with_q1(oracle, n):
+    """With Q=1, l=0 the printed P_B is the packed upper-triangular offset; the
+    running-counter walk and the literal preceding-count must both equal it."""
+    starts = oracle.triu_row_starts(n)
+    for i in range(n):
+        for j in range(i, n):
+            pb = (n - Fraction(1, 2)) * i - Fraction(1, 2) * i * i + j
+            assert pb.denominator == 1
+            assert oracle.count_preceding(oracle.DOM_TRIU, [n], [i, j]) == pb
+            assert oracle.triu_position(n, i, j) == pb
+            assert starts[i] + (j - i) == pb
+            assert oracle.triu_point_at(n, int(pb)) == (i, j)
+    assert oracle.triu_point_at(n, int(starts[n])) is None
+    assert oracle.triu_point_at(n, -1) is None
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 7, 10])
+def test_upper_triangle_mirror_of_lower(oracle, n):
+    """Reversing both axes maps the upper triangle onto the lower one and reverses the order."""
+    total = n * (n + 1) // 2
+    for i in range(n):
+        for j in range(i, n):
+            up = oracle.count_preceding(oracle.DOM_TRIU, [n], [i, j])
+            lo = oracle.count_preceding(oracle.DOM_TRIL, [n], [n - 1 - i, n - 1 - j])
+            assert up == total - 1 - lo
+
+
+@pytest.mark.parametrize("dom,params,count", [
+    ("TRIU", [9], 45), ("TRIL", [9], 45), ("TET", [7], 84), ("UHC", [3, 5, 2], 24), ("BAND", [6, 2], 30),
+])
+def test_counting_is_a_bijection_onto_prefix(oracle, dom, params, count):
+    """The preceding-count numbers the domain 0..count-1 in strictly increasing lexicographic order."""
+    d = getattr(oracle, "DOM_" + dom)
+    assert oracle.count_domain(d, params) == count
+    seen = []
+    p = 0
+    while True:
+        pt = oracle.point_at(d, params, p)
+        if pt is None:
+            break
+        assert oracle.count_preceding(d, params, list(pt)) == p
+        seen.append(pt)
+        p += 1
+    assert p == count
+    assert seen == sorted(seen) and len(set(seen)) == count
+
+
+def test_closed_form_counts(oracle):
+    """Triangular and tetrahedral numbers, including the benchmark orders."""
+    for n in (0, 1, 2, 5, 16, 33):
+        assert oracle.triu_row_starts(n)[n] == n * (n + 1) // 2
+        assert oracle.tet_fibre_starts(n)[1] == n * (n + 1) * (n + 2) // 6
+    assert oracle.triu_row_starts(512)[512] == 131328
+    assert oracle.triu_row_starts(16384)[16384] == 134225920
+    assert oracle.tet_fibre_starts(512)[1] == 22500864
+    assert oracle.tet_fibre_starts(1024)[1] == 179481600
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 6, 9])
+def test_tet_walk_matches_literal_count_and_slices_are_triangles(oracle, n):
+    """Fibre starts from the walk equal the literal preceding-count, and slice i of the
+    tetrahedron is a packed upper triangle of order n-i (shifted by the slice start)."""
+    starts, total = oracle.tet_fibre_starts(n)
+    for i in range(n):
+        tri = oracle.triu_row_starts(n - i)
+        for j in range(i, n):
+            assert starts[i, j] == oracle.count_preceding(oracle.DOM_TET, [n], [i, j, j])
+            assert starts[i, j] - starts[i, i] == tri[j - i]
+            for k in range(j, n):
+                p = oracle.tet_position(n, i, j, k)
+                assert p == starts[i, j] + (k - j)
+                assert oracle.tet_point_at(n, p) == (i, j, k)
+        for j in range(i):
+            assert starts[i, j] == -1
+    assert oracle.tet_point_at(n, total) is None
+
+
+# ------------------------------------------------- compress / decompress ----
+
+@pytest.mark.parametrize("n", [0, 1, 2, 5, 17, 24])
+def test_pack_triu_against_numpy_indices(oracle, n):
+    D = inputs.uniform(100 + n, n, n)
+    P = oracle.pack_triu(D)
+    iu = np.triu_indices(n)  # row-major enumeration of i<=j
+    assert np.array_equal(P, D[iu])
+    U = oracle.unpack_triu(n, P)
+    assert np.array_equal(U, np.triu(D))
+    assert not np.signbit(U[np.tril_indices(n, -1)]).any()
+    assert np.array_equal(oracle.pack_triu(U), P)
+
+
+@pytest.mark.parametrize("n", [0, 1, 2, 4, 9, 12])
+def test_pack_tet_against_numpy_mask(oracle, n):
+    D = inputs.uniform(200 + n, n, n, n)
+    i, j, k = np.meshgrid(np.arange(n), np.arange(n), np.arange(n), indexing="ij")
+    mask = (i <= j) & (j <= k)
+    P = oracle.pack_tet(D)
+    assert np.array_equal(P, D[mask])  # boolean indexing enumerates in C (lexicographic) order
+    U = oracle.unpack_tet(n, P)
+    assert np.array_equal(U, np.where(mask, D, np.float32(0)))
+    assert np.array_equal(oracle.pack_tet(U), P)
+
+
+@pytest.mark.parametrize("n,w", [(1, 0), (1, 3), (5, 0), (7, 2), (12, 16), (24, 5)])
+def test_pack_band_against_numpy_diagonals(oracle, n, w):
+    D = inputs.uniform(300 + n, n, n)
+    P = oracle.pack_band(D, w).reshape(2 * w + 1, n)
+    for d in range(-w, w + 1):
+        row = np.zeros(n, dtype=np.float32)
+        diag = np.diagonal(D, offset=d)  # entries (i, i+d)
+        if d >= 0:
+            row[: len(diag)] = diag
+        else:
+            row[-d: -d + len(diag)] = diag
+        assert np.array_equal(P[d + w], row)
+    U = oracle.unpack_band(n, w, P.ravel())
+    i, j = np.meshgrid(np.arange(n), np.arange(n), indexing="ij")
+    assert np.array_equal(U, np.where(np.abs(j - i) <= w, D, np.float32(0)))
+
+
+# ------------------------------------------------------------ contractions ----
+
+def _close(got, want, scale, rel=1e-6):
+    return np.all(np.abs(got.astype(np.float64) - want) <= rel * scale + 1e-30)
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 7, 16, 24])
+def test_trmv_against_dense_numpy(oracle, n):
+    D = inputs.uniform(400 + n, n, n)
+    x = inputs.uniform(401 + n, n)
+    Up = D[np.triu_indices(n)]
+    y, sc = oracle.trmv(n, Up, x)
+    T = np.triu(D).astype(np.float64)
+    assert _close(y, T @ x.astype(np.float64), sc)
+    assert np.allclose(sc, np.abs(T) @ np.abs(x.astype(np.float64)), rtol=1e-12)
+    # x = e_c picks column c of U (exactly)
+    for c in range(n):
+        e = np.zeros(n, dtype=np.float32)
+        e[c] = 1.0
+        yc, _ = oracle.trmv(n, Up, e)
+        assert np.array_equal(yc, np.triu(D)[:, c])
+
+
+def test_trmv_all_ones_is_suffix_sum(oracle):
+    n = 19
+    x = inputs.small_int(7, -5, 5, n)
+    y, _ = oracle.trmv(n, np.ones(n * (n + 1) // 2, dtype=np.float32), x)
+    assert np.array_equal(y, np.cumsum(x[::-1])[::-1])
+
+
+@pytest.mark.parametrize("n,m", [(1, 1), (3, 2), (9, 5), (20, 33), (24, 7)])
+def test_trmm_against_dense_numpy(oracle, n, m):
+    D = inputs.uniform(500 + n, n, n)
+    B = inputs.uniform(501 + n, n, m)
+    Up = D[np.triu_indices(n)]
+    C, sc = oracle.trmm(n, m, Up, B)
+    T = np.triu(D).astype(np.float64)
+    assert _close(C, T @ B.astype(np.float64), sc)
+    assert np.allclose(sc, np.abs(T) @ np.abs(B.astype(np.float64)), rtol=1e-12)
+    # identity columns reproduce the unpacked matrix; one column equals TRMV
+    if m <= n:
+        Ci, _ = oracle.trmm(n, m, Up, np.eye(n, m, dtype=np.float32))
+        assert np.array_equal(Ci, np.triu(D)[:, :m])
+    y, _ = oracle.trmv(n, Up, np.ascontiguousarray(B[:, 0]))
+    assert np.array_equal(C[:, 0], y)
+
+
+@pytest.mark.parametrize("n,w", [(1, 0), (1, 2), (6, 0), (9, 2), (24, 16), (40, 16), (12, 30)])
+def test_band_spmv_against_dense_numpy(oracle, n, w):
+    Dm = inputs.band_normal(600 + n, n, w)
+    x = inputs.normal(601 + n, n)
+    A = np.zeros((n, n), dtype=np.float64)
+    for d in range(-w, w + 1):
+        for i in range(n):
+            if 0 <= i + d < n:
+                A[i, i + d] = Dm[d + w, i]
+    # poison the padding: the oracle must skip it by the predicate
+    Dp = Dm.copy()
+    for d in range(-w, w + 1):
+        for i in range(n):
+            if not (0 <= i + d < n):
+                Dp[d + w, i] = np.nan
+    y, sc = oracle.band_spmv(n, w, Dp.ravel(), x)
+    assert _close(y, A @ x.astype(np.float64), sc)
+    assert np.allclose(sc, np.abs(A) @ np.abs(x.astype(np.float64)), rtol=1e-12)
+    if w == 0:  # pure diagonal: elementwise product (Table 2, SpMV_D)
+        assert np.array_equal(y, (Dm[0].astype(np.float64) * x).astype(np.float32))
+
+
+def test_band_all_ones_is_window_sum(oracle):
+    n, w = 23, 4
+    x = inputs.small_int(9, -4, 4, n)
+    y, _ = oracle.band_spmv(n, w, np.ones((2 * w + 1) * n, dtype=np.float32), x)
+    want = [x[max(0, i - w): min(n, i + w + 1)].sum() for i in range(n)]
+    assert np.array_equal(y, np.asarray(want, dtype=np.float32))
+
+
+def _tet_dense(n, seed):
+    D = inputs.uniform(seed, n, n, n)
+    i, j, k = np.meshgrid(np.arange(n), np.arange(n), np.arange(n), indexing="ij")
+    mask = (i <= j) & (j <= k)
+    return np.where(mask, D, np.float32(0)), D[mask]
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 6, 12])
+def test_tet_ttv_against_dense_einsum(oracle, n):
+    T, Ap = _tet_dense(n, 700 + n)
+    v = inputs.uniform(701 + n, n)
+    M, sc = oracle.tet_ttv(n, Ap, v)
+    full = np.einsum("ijk,k->ij", T.astype(np.float64), v.astype(np.float64))
+    assert _close(M, full[np.triu_indices(n)], sc)
+    mag = np.einsum("ijk,k->ij", np.abs(T.astype(np.float64)), np.abs(v.astype(np.float64)))
+    assert np.allclose(sc, mag[np.triu_indices(n)], rtol=1e-12)
+    # slice i is a packed triangle of order n-i: TTV slice == TRMV on v[i:]
+    starts, _ = oracle.tet_fibre_starts(n)
+    tri = oracle.triu_row_starts(n)
+    for i in range(n):
+        cnt = (n - i) * (n - i + 1) // 2
+        y, _ = oracle.trmv(n - i, Ap[starts[i, i]: starts[i, i] + cnt], np.ascontiguousarray(v[i:]))
+        assert np.array_equal(M[tri[i]: tri[i] + (n - i)], y)
+
+
+@pytest.mark.parametrize("n,R", [(1, 1), (2, 3), (5, 4), (9, 32), (12, 7)])
+def test_tet_mttkrp_against_dense_einsum(oracle, n, R):
+    T, Ap = _tet_dense(n, 800 + n)
+    B = inputs.normal(801 + n, n, R)
+    C = inputs.normal(802 + n, n, R)
+    M, sc = oracle.tet_mttkrp(n, R, Ap, B, C)
+    T64, B64, C64 = T.astype(np.float64), B.astype(np.float64), C.astype(np.float64)
+    assert _close(M, np.einsum("ijk,jr,kr->ir", T64, B64, C64), sc, rel=1e-5)
+    assert np.allclose(sc, np.einsum("ijk,jr,kr->ir", np.abs(T64), np.abs(B64), np.abs(C64)), rtol=1e-12)
+    # slice identity: M[i,:] = sum_j B[j,:] * (U_i C[i:,:])[j,:]
+    starts, _ = oracle.tet_fibre_starts(n)
+    for i in range(n):
+        cnt = (n - i) * (n - i + 1) // 2
+        Tm, _ = oracle.trmm(n - i, R, Ap[starts[i, i]: starts[i, i] + cnt], np.ascontiguousarray(C[i:]))
+        want = (B64[i:] * Tm.astype(np.float64)).sum(axis=0)
+        assert np.allclose(M[i], want, rtol=1e-5, atol=1e-5)
+
+
+def test_mttkrp_all_ones_closed_form(oracle):
+    n, R = 8, 3
+    B = inputs.small_int(11, -3, 3, n, R)
+    C = inputs.small_int(12, -3, 3, n, R)
+    M, _ = oracle.tet_mttkrp(n, R, np.ones(n * (n + 1) * (n + 2) // 6, dtype=np.float32), B, C)
+    suffC = np.cumsum(C[::-1], axis=0)[::-1]
+    want = np.cumsum((B * suffC)[::-1], axis=0)[::-1]
+    assert np.array_equal(M, want)
+
+
+def test_row_windows_agree_with_full_run(oracle):
+    """The window arguments only select which rows are computed."""
+    n, m, R, w = 11, 4, 5, 3
+    Up = inputs.uniform(1, n * (n + 1) // 2)
+    x = inputs.uniform(2, n)
+    B = inputs.uniform(3, n, m)
+    y, s = oracle.trmv(n, Up, x)
+    y2, s2 = oracle.trmv(n, Up, x, rows=(3, 6))
+    assert np.array_equal(y[3:6], y2[3:6]) and np.isnan(y2[:3]).all() and np.isnan(y2[6:]).all()
+    assert np.array_equal(s[3:6], s2[3:6])
+    C, _ = oracle.trmm(n, m, Up, B)
+    C2, _ = oracle.trmm(n, m, Up, B, rows=(10, 11))
+    assert np.array_equal(C[10], C2[10]) and np.isnan(C2[:10]).all()
+    Ap = inputs.uniform(4, n * (n + 1) * (n + 2) // 6)
+    M, _ = oracle.tet_ttv(n, Ap, x)
+    M2, _ = oracle.tet_ttv(n, Ap, x, rows=(2, 4))
+    tri = oracle.triu_row_starts(n)
+    assert np.array_equal(M[tri[2]: tri[4]], M2[tri[2]: tri[4]])
+    assert np.isnan(M2[: tri[2]]).all() and np.isnan(M2[tri[4]:]).all()
+    Bf, Cf = inputs.normal(5, n, R), inputs.normal(6, n, R)
+    K, _ = oracle.tet_mttkrp(n, R, Ap, Bf, Cf)
+    K2, _ = oracle.tet_mttkrp(n, R, Ap, Bf, Cf, rows=(0, 1))
+    assert np.array_equal(K[0], K2[0]) and np.isnan(K2[1:]).all()
+    D = inputs.band_normal(7, n, w)
+    b, _ = oracle.band_spmv(n, w, D.ravel(), x)
+    b2, _ = oracle.band_spmv(n, w, D.ravel(), x, rows=(4, 9))
+    assert np.array_equal(b[4:9], b2[4:9]) and np.isnan(b2[:4]).all()
