@@ -1,0 +1,132 @@
+/*
+ * dastac.h -- C ABI of libdastac_hip.so: structure-aware contractions over densely
+ * packed tensors on AMD gfx950 (MI355X), after "Compressing Structured Tensor
+ * Algebra" (DASTAC).
+ *
+ * Only the elements of a tensor's structure domain are stored, back to back in one
+ * buffer, in the iteration order of the rule that reads them (Section 4, "Iteration
+ * space extraction": iterators in order of appearance, the last one contiguous).
+ * The position of an element is the number of domain points that precede it
+ * (Section 4, "Access domain linearization"), which for the three domains served
+ * here is a closed-form polynomial in the indices and the size:
+ *
+ *   upper triangle   0<=i<=j<n      tri(n,i,j)   = i*n - i*(i-1)/2 + (j-i)
+ *                                   (Section 3's printed P_B with Q=1, l=0)
+ *   upper tetrahedron 0<=i<=j<=k<n  tet(n,i,j,k) = [Tet(n)-Tet(n-i)] + [Tri(n-i)-Tri(n-j)] + (k-j)
+ *                                   Tri(m)=m(m+1)/2, Tet(m)=m(m+1)(m+2)/6
+ *   band |j-i|<=w                   band(n,w,d,i) = (d+w)*n + i,  d=j-i
+ *                                   one n-slot buffer per diagonal summand (Section 4,
+ *                                   per-summand buffers), buffers in order d=-w..w;
+ *                                   slot i of diagonal d holds A[i][i+d]; the |d| slots of a
+ *                                   diagonal whose column falls outside the matrix are padding.
+ *
+ * All index arithmetic is exact 64-bit integer arithmetic: the rational coefficients
+ * are evaluated on a doubled (or six-fold) numerator that is always divisible
+ * (Fig. 4 of the paper does the same: doubled terms, one exact unsigned division).
+ *
+ * Conventions
+ *   - Status codes: DASTAC_OK on success, otherwise one of the codes below.  No
+ *     exception or signal crosses this boundary.  dastac_strerror() names a code.
+ *   - n == 0 is a successful no-op for every operation.
+ *   - "DEVICE" pointers are device memory of the current HIP device, owned by the
+ *     caller, at least 4-byte aligned.  The library never allocates, frees or
+ *     retains memory.  "HOST" pointers are ordinary host memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Device
+ *     operations are enqueued on it and return without synchronising.  A launch
+ *     failure is reported as DASTAC_EHIP.
+ *   - Outputs are overwritten, not accumulated into (the paper's statement adds into
+ *     a zero-initialised output, Section 5.2; the result is the same).
+ *   - An output buffer that overlaps an input buffer is rejected with DASTAC_EALIAS.
+ *   - The library keeps no mutable global state and may be called from several
+ *     host threads.
+ */
+#ifndef DASTAC_H
+#define DASTAC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DASTAC_OK 0
+#define DASTAC_EINVAL 1    /* negative size, m/R/w out of range, leading dimension too small, p out of range */
+#define DASTAC_ENULL 2     /* a required pointer is NULL */
+#define DASTAC_EOVERFLOW 3 /* the element count would leave the guarded int64 range */
+#define DASTAC_EALIAS 4    /* an output overlaps an input */
+#define DASTAC_EHIP 5      /* the HIP runtime reported an error at launch */
+
+/* Largest sizes accepted: beyond these a count or an intermediate product could overflow int64. */
+#define DASTAC_TRI_MAX_N 2147483647LL /* 2*Tri(n) < 2^63 */
+#define DASTAC_TET_MAX_N 1048576LL    /* Tri(n)*(n+2) < 2^63 */
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char *dastac_strerror(int status);
+
+/* ---- index polynomials: HOST, pure, need no device ------------------------------
+ * Forward polynomials (Section 4, "Access domain linearization"; the closed forms are
+ * listed at the top of this file).  Return the count / offset, or -1 on invalid
+ * arguments (n<0, n above the guard, index outside the domain, w<0). */
+int64_t dastac_tri_count(int64_t n);
+int64_t dastac_tet_count(int64_t n);
+int64_t dastac_band_count(int64_t n, int64_t w);
+int64_t dastac_tri_offset(int64_t n, int64_t i, int64_t j);
+int64_t dastac_tet_offset(int64_t n, int64_t i, int64_t j, int64_t k);
+int64_t dastac_band_offset(int64_t n, int64_t w, int64_t d, int64_t i);
+
+/* Inverse polynomials: the unique domain point whose offset is p.  The paper only
+ * mentions inverting a quasi-polynomial as costly when done per iteration (Section 7,
+ * "Data layout compression"); here it is evaluated once per wavefront to find the row
+ * or slice where a contiguous share of the packed buffer begins.  Exact for every p in
+ * [0,count): a floating-point root seeds an integer correction.  Return DASTAC_OK, or
+ * DASTAC_EINVAL for p outside [0,count) or an invalid n, DASTAC_ENULL for a NULL output. */
+int dastac_tri_inverse(int64_t n, int64_t p, int64_t *i, int64_t *j);
+int dastac_tet_inverse(int64_t n, int64_t p, int64_t *i, int64_t *j, int64_t *k);
+
+/* ---- compression / decompression: DEVICE (Section 3, "Data layout compression") --
+ * pack copies the domain elements of a dense row-major tensor into the packed buffer;
+ * unpack writes the dense tensor back, with +0.0f at every position outside the domain.
+ * Bit-exact copies.  `ld` is the dense row stride in elements (ld >= n).
+ *   triu : dense n x n (stride ld)      <-> packed[tri_count(n)]
+ *   tet  : dense n x n x n, contiguous  <-> packed[tet_count(n)]
+ *   band : dense n x n (stride ld)      <-> diag_major[(2w+1)*n]; pack writes +0.0f into padding slots,
+ *                                           unpack ignores them. */
+int dastac_pack_triu_f32(int64_t n, const float *dense, int64_t ld, float *packed, void *stream);
+int dastac_unpack_triu_f32(int64_t n, const float *packed, float *dense, int64_t ld, void *stream);
+int dastac_pack_tet_f32(int64_t n, const float *dense, float *packed, void *stream);
+int dastac_unpack_tet_f32(int64_t n, const float *packed, float *dense, void *stream);
+int dastac_pack_band_f32(int64_t n, int64_t w, const float *dense, int64_t ld, float *diag_major, void *stream);
+int dastac_unpack_band_f32(int64_t n, int64_t w, const float *diag_major, float *dense, int64_t ld, void *stream);
+
+/* ---- contractions: DEVICE, fp32 storage and arithmetic ---------------------------
+ * Summation order is unspecified (the paper compiles with fast-math, Section 6.1);
+ * each output element is within 1e-4 * sum|products| of the exactly rounded result.
+ */
+
+/* y(i) := U(i,j) * x(j), i<=j   (Table 1/2, SpMV_UT).  Up[tri_count(n)], x[n], y[n]. */
+int dastac_trmv_f32(int64_t n, const float *Up, const float *x, float *y, void *stream);
+
+/* C(i,c) := U(i,k) * B(k,c), i<=k, 0<=c<m  (the SpMV_UT rule with a matrix right-hand side).
+ * B is n x m row-major with row stride ldb >= m, C is n x m with row stride ldc >= m; m >= 1. */
+int dastac_trmm_f32(int64_t n, int64_t m, const float *Up, const float *B, int64_t ldb, float *C, int64_t ldc,
+                    void *stream);
+
+/* y(i) := sum_{d=-w..w, 0<=i+d<n} D(d,i) * x(i+d)   (Section 6.4 strided-band rule, unit stride,
+ * 2w+1 summands; w=0 is Table 2's SpMV_D).  D[(2w+1)*n] diagonal-major as described above; padding
+ * slots are never used for their value.  0 <= w <= 64. */
+int dastac_band_spmv_f32(int64_t n, int64_t w, const float *D, const float *x, float *y, void *stream);
+
+/* M(i,j) := A(i,j,k) * v(k), i<=j<=k.  Ap[tet_count(n)], v[n]; the output is itself packed:
+ * Mp[tri_count(n)] with M(i,j) at tri(n,i,j). */
+int dastac_tet_ttv_f32(int64_t n, const float *Ap, const float *v, float *Mp, void *stream);
+
+/* M(i,r) := A(i,j,k) * B(j,r) * C(k,r), i<=j<=k, 0<=r<R  (Table 1 MTTKRP rule on the upper tetrahedron).
+ * B, C are n x R row-major with row strides ldb, ldc >= R; M is n x R with row stride ldm >= R.
+ * 1 <= R <= 32. */
+int dastac_tet_mttkrp_f32(int64_t n, int64_t R, const float *Ap, const float *B, int64_t ldb, const float *C,
+                          int64_t ldc, float *M, int64_t ldm, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DASTAC_H */

@@ -1,0 +1,39 @@
+// Shared host-side helpers of the C-ABI entry points: status codes, overlap test,
+// launch-error capture.  Device helpers used by more than one kernel file live here too.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/dastac.h"
+#include "index_poly.h"
+
+namespace dastac {
+
+// True when the byte ranges [a, a+na) and [b, b+nb) intersect.
+inline bool overlaps(const void *a, int64_t na, const void *b, int64_t nb) {
+  if (na <= 0 || nb <= 0) return false;
+  uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+  return a0 < b0 + (uintptr_t)nb && b0 < a0 + (uintptr_t)na;
+}
+
+// Status of the launch that was just issued on this thread.
+inline int launch_status() { return hipGetLastError() == hipSuccess ? DASTAC_OK : DASTAC_EHIP; }
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+#if defined(__HIPCC__)
+// 16-byte vector of floats that only promises 4-byte alignment: packed rows start at arbitrary
+// element offsets, and gfx950 global loads of four dwords need dword alignment only.
+typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
+typedef float f4a __attribute__((ext_vector_type(4)));
+
+// Make a wave-uniform 64-bit value provably scalar for the compiler.
+__device__ inline int64_t uniform64(int64_t v) {
+  uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)(uint64_t)v);
+  uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)v >> 32));
+  return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+__device__ inline int uniform32(int v) { return __builtin_amdgcn_readfirstlane(v); }
+#endif
+
+}  // namespace dastac

@@ -1,0 +1,177 @@
+// Compression / decompression kernels (Section 3, "Data layout compression": iterate over the
+// accessed indices and copy the data in and out of the packed buffer).
+//
+// One workgroup handles one 256-element piece of one dense row, so both sides of the copy are
+// contiguous across the lanes of a wavefront; the packed row start is the index polynomial of the
+// row, computed once per workgroup from wave-uniform values and added to the lane's column.
+#include "common.h"
+
+using namespace dastac;
+
+namespace {
+
+constexpr int kBlock = 256;
+
+// flattened (row, piece) -> row index and first column of the piece; `pieces` per row
+__device__ inline void split(int64_t b, int64_t pieces, int64_t &row, int64_t &col0) {
+  row = b / pieces;
+  col0 = (b - row * pieces) * kBlock;
+}
+
+__global__ __launch_bounds__(kBlock) void pack_triu_kernel(int64_t n, const float *__restrict__ dense, int64_t ld,
+                                                           float *__restrict__ packed, int64_t pieces,
+                                                           int64_t nblocks) {
+  for (int64_t b = blockIdx.x; b < nblocks; b += gridDim.x) {
+    int64_t i, c0;
+    split(b, pieces, i, c0);
+    if (c0 + kBlock <= i) continue;  // piece lies wholly left of the diagonal
+    int64_t j = c0 + threadIdx.x;
+    if (j >= i && j < n) packed[tri_row_start(n, i) + (j - i)] = dense[i * ld + j];
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void unpack_triu_kernel(int64_t n, const float *__restrict__ packed,
+                                                             float *__restrict__ dense, int64_t ld, int64_t pieces,
+                                                             int64_t nblocks) {
+  for (int64_t b = blockIdx.x; b < nblocks; b += gridDim.x) {
+    int64_t i, c0;
+    split(b, pieces, i, c0);
+    int64_t j = c0 + threadIdx.x;
+    if (j < n) dense[i * ld + j] = (j >= i) ? packed[tri_row_start(n, i) + (j - i)] : 0.0f;
+  }
+}
+
+// rows of the cube are (i,j) pairs, flattened as i*n+j
+__global__ __launch_bounds__(kBlock) void pack_tet_kernel(int64_t n, const float *__restrict__ dense,
+                                                          float *__restrict__ packed, int64_t pieces,
+                                                          int64_t nblocks) {
+  for (int64_t b = blockIdx.x; b < nblocks; b += gridDim.x) {
+    int64_t ij, c0;
+    split(b, pieces, ij, c0);
+    int64_t i = ij / n, j = ij - i * n;
+    if (j < i || c0 + kBlock <= j) continue;
+    int64_t k = c0 + threadIdx.x;
+    if (k >= j && k < n) packed[tet_row_start(n, i, j) + (k - j)] = dense[ij * n + k];
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void unpack_tet_kernel(int64_t n, const float *__restrict__ packed,
+                                                            float *__restrict__ dense, int64_t pieces,
+                                                            int64_t nblocks) {
+  for (int64_t b = blockIdx.x; b < nblocks; b += gridDim.x) {
+    int64_t ij, c0;
+    split(b, pieces, ij, c0);
+    int64_t i = ij / n, j = ij - i * n;
+    int64_t k = c0 + threadIdx.x;
+    if (k < n) dense[ij * n + k] = (j >= i && k >= j) ? packed[tet_row_start(n, i, j) + (k - j)] : 0.0f;
+  }
+}
+
+// band: rows of the packed block are the diagonals d=-w..w, slot i holds entry (i, i+d)
+__global__ __launch_bounds__(kBlock) void pack_band_kernel(int64_t n, int64_t w, const float *__restrict__ dense,
+                                                           int64_t ld, float *__restrict__ diag, int64_t pieces,
+                                                           int64_t nblocks) {
+  for (int64_t b = blockIdx.x; b < nblocks; b += gridDim.x) {
+    int64_t dd, c0;
+    split(b, pieces, dd, c0);
+    int64_t d = dd - w, i = c0 + threadIdx.x;
+    if (i < n) {
+      int64_t j = i + d;
+      diag[band_offset(n, w, d, i)] = (j >= 0 && j < n) ? dense[i * ld + j] : 0.0f;
+    }
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void unpack_band_kernel(int64_t n, int64_t w, const float *__restrict__ diag,
+                                                             float *__restrict__ dense, int64_t ld, int64_t pieces,
+                                                             int64_t nblocks) {
+  for (int64_t b = blockIdx.x; b < nblocks; b += gridDim.x) {
+    int64_t i, c0;
+    split(b, pieces, i, c0);
+    int64_t j = c0 + threadIdx.x;
+    if (j < n) {
+      int64_t d = j - i;
+      dense[i * ld + j] = (d >= -w && d <= w) ? diag[band_offset(n, w, d, i)] : 0.0f;
+    }
+  }
+}
+
+inline unsigned grid_for(int64_t nblocks) { return (unsigned)(nblocks < (1 << 22) ? nblocks : (1 << 22)); }
+
+// Largest dense extents accepted: the flattened (row, piece) count must stay far inside int64.
+constexpr int64_t kDenseMaxN = 1 << 20;   // n*n row-major matrix
+constexpr int64_t kCubeMaxN = 1 << 13;    // n*n*n cube
+
+}  // namespace
+
+extern "C" {
+
+int dastac_pack_triu_f32(int64_t n, const float *dense, int64_t ld, float *packed, void *stream) {
+  if (n < 0 || ld < n) return DASTAC_EINVAL;
+  if (n > kDenseMaxN) return DASTAC_EOVERFLOW;
+  if (n == 0) return DASTAC_OK;
+  if (!dense || !packed) return DASTAC_ENULL;
+  if (overlaps(dense, n * ld * 4, packed, tri(n) * 4)) return DASTAC_EALIAS;
+  int64_t pieces = ceil_div(n, kBlock), nblocks = n * pieces;
+  pack_triu_kernel<<<grid_for(nblocks), kBlock, 0, (hipStream_t)stream>>>(n, dense, ld, packed, pieces, nblocks);
+  return launch_status();
+}
+
+int dastac_unpack_triu_f32(int64_t n, const float *packed, float *dense, int64_t ld, void *stream) {
+  if (n < 0 || ld < n) return DASTAC_EINVAL;
+  if (n > kDenseMaxN) return DASTAC_EOVERFLOW;
+  if (n == 0) return DASTAC_OK;
+  if (!dense || !packed) return DASTAC_ENULL;
+  if (overlaps(dense, n * ld * 4, packed, tri(n) * 4)) return DASTAC_EALIAS;
+  int64_t pieces = ceil_div(n, kBlock), nblocks = n * pieces;
+  unpack_triu_kernel<<<grid_for(nblocks), kBlock, 0, (hipStream_t)stream>>>(n, packed, dense, ld, pieces, nblocks);
+  return launch_status();
+}
+
+int dastac_pack_tet_f32(int64_t n, const float *dense, float *packed, void *stream) {
+  if (n < 0) return DASTAC_EINVAL;
+  if (n > kCubeMaxN) return DASTAC_EOVERFLOW;
+  if (n == 0) return DASTAC_OK;
+  if (!dense || !packed) return DASTAC_ENULL;
+  if (overlaps(dense, n * n * n * 4, packed, tet(n) * 4)) return DASTAC_EALIAS;
+  int64_t pieces = ceil_div(n, kBlock), nblocks = n * n * pieces;
+  pack_tet_kernel<<<grid_for(nblocks), kBlock, 0, (hipStream_t)stream>>>(n, dense, packed, pieces, nblocks);
+  return launch_status();
+}
+
+int dastac_unpack_tet_f32(int64_t n, const float *packed, float *dense, void *stream) {
+  if (n < 0) return DASTAC_EINVAL;
+  if (n > kCubeMaxN) return DASTAC_EOVERFLOW;
+  if (n == 0) return DASTAC_OK;
+  if (!dense || !packed) return DASTAC_ENULL;
+  if (overlaps(dense, n * n * n * 4, packed, tet(n) * 4)) return DASTAC_EALIAS;
+  int64_t pieces = ceil_div(n, kBlock), nblocks = n * n * pieces;
+  unpack_tet_kernel<<<grid_for(nblocks), kBlock, 0, (hipStream_t)stream>>>(n, packed, dense, pieces, nblocks);
+  return launch_status();
+}
+
+int dastac_pack_band_f32(int64_t n, int64_t w, const float *dense, int64_t ld, float *diag_major, void *stream) {
+  if (n < 0 || w < 0 || ld < n) return DASTAC_EINVAL;
+  if (n > kDenseMaxN || w > kDenseMaxN) return DASTAC_EOVERFLOW;
+  if (n == 0) return DASTAC_OK;
+  if (!dense || !diag_major) return DASTAC_ENULL;
+  if (overlaps(dense, n * ld * 4, diag_major, (2 * w + 1) * n * 4)) return DASTAC_EALIAS;
+  int64_t pieces = ceil_div(n, kBlock), nblocks = (2 * w + 1) * pieces;
+  pack_band_kernel<<<grid_for(nblocks), kBlock, 0, (hipStream_t)stream>>>(n, w, dense, ld, diag_major, pieces,
+                                                                          nblocks);
+  return launch_status();
+}
+
+int dastac_unpack_band_f32(int64_t n, int64_t w, const float *diag_major, float *dense, int64_t ld, void *stream) {
+  if (n < 0 || w < 0 || ld < n) return DASTAC_EINVAL;
+  if (n > kDenseMaxN || w > kDenseMaxN) return DASTAC_EOVERFLOW;
+  if (n == 0) return DASTAC_OK;
+  if (!dense || !diag_major) return DASTAC_ENULL;
+  if (overlaps(dense, n * ld * 4, diag_major, (2 * w + 1) * n * 4)) return DASTAC_EALIAS;
+  int64_t pieces = ceil_div(n, kBlock), nblocks = n * pieces;
+  unpack_band_kernel<<<grid_for(nblocks), kBlock, 0, (hipStream_t)stream>>>(n, w, diag_major, dense, ld, pieces,
+                                                                            nblocks);
+  return launch_status();
+}
+
+}  // extern "C"

@@ -1,0 +1,169 @@
+"""ctypes binding over libdastac_hip.so -- argument marshalling only.
+
+Every function has the name and argument order of the C entry point in
+``include/dastac.h`` (minus the ``dastac_`` prefix and ``_f32`` suffix kept as
+is).  Device operands are ``torch`` tensors on a HIP device (used for their
+memory and for the current stream, nothing else); outputs are passed in by the
+caller.  A non-zero status raises ``DastacError``.  There is no fallback: if
+the library is not built, importing this module's functions raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdastac_hip.so")
+
+OK, EINVAL, ENULL, EOVERFLOW, EALIAS, EHIP = 0, 1, 2, 3, 4, 5
+
+_i64 = ctypes.c_int64
+_vp = ctypes.c_void_p
+
+# name -> (restype, argtypes); this table is also what the symbol-export test walks.
+SIGNATURES = {
+    "dastac_strerror": (ctypes.c_char_p, [ctypes.c_int]),
+    "dastac_tri_count": (_i64, [_i64]),
+    "dastac_tet_count": (_i64, [_i64]),
+    "dastac_band_count": (_i64, [_i64, _i64]),
+    "dastac_tri_offset": (_i64, [_i64, _i64, _i64]),
+    "dastac_tet_offset": (_i64, [_i64, _i64, _i64, _i64]),
+    "dastac_band_offset": (_i64, [_i64, _i64, _i64, _i64]),
+    "dastac_tri_inverse": (ctypes.c_int, [_i64, _i64, ctypes.POINTER(_i64), ctypes.POINTER(_i64)]),
+    "dastac_tet_inverse": (ctypes.c_int, [_i64, _i64, ctypes.POINTER(_i64), ctypes.POINTER(_i64),
+                                          ctypes.POINTER(_i64)]),
+    "dastac_pack_triu_f32": (ctypes.c_int, [_i64, _vp, _i64, _vp, _vp]),
+    "dastac_unpack_triu_f32": (ctypes.c_int, [_i64, _vp, _vp, _i64, _vp]),
+    "dastac_pack_tet_f32": (ctypes.c_int, [_i64, _vp, _vp, _vp]),
+    "dastac_unpack_tet_f32": (ctypes.c_int, [_i64, _vp, _vp, _vp]),
+    "dastac_pack_band_f32": (ctypes.c_int, [_i64, _i64, _vp, _i64, _vp, _vp]),
+    "dastac_unpack_band_f32": (ctypes.c_int, [_i64, _i64, _vp, _vp, _i64, _vp]),
+    "dastac_trmv_f32": (ctypes.c_int, [_i64, _vp, _vp, _vp, _vp]),
+    "dastac_trmm_f32": (ctypes.c_int, [_i64, _i64, _vp, _vp, _i64, _vp, _i64, _vp]),
+    "dastac_band_spmv_f32": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp, _vp]),
+    "dastac_tet_ttv_f32": (ctypes.c_int, [_i64, _vp, _vp, _vp, _vp]),
+    "dastac_tet_mttkrp_f32": (ctypes.c_int, [_i64, _i64, _vp, _vp, _i64, _vp, _i64, _vp, _i64, _vp]),
+}
+
+
+class DastacError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: status %d (%s)" % (where, status, strerror(status)))
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load the built library; raise if it is missing (no CPU fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                "libdastac_hip.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        L = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(L, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = L
+    return _lib
+
+
+def strerror(status: int) -> str:
+    return lib().dastac_strerror(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != OK:
+        raise DastacError(status, where)
+
+
+def _ptr(t):
+    """Device address of a tensor (None -> NULL)."""
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("device tensor expected")
+    if t.dtype.__str__() != "torch.float32":
+        raise ValueError("float32 tensor expected")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream=None):
+    import torch
+
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+# ---- index polynomials (host) -------------------------------------------------
+
+def tri_count(n): return int(lib().dastac_tri_count(n))
+def tet_count(n): return int(lib().dastac_tet_count(n))
+def band_count(n, w): return int(lib().dastac_band_count(n, w))
+def tri_offset(n, i, j): return int(lib().dastac_tri_offset(n, i, j))
+def tet_offset(n, i, j, k): return int(lib().dastac_tet_offset(n, i, j, k))
+def band_offset(n, w, d, i): return int(lib().dastac_band_offset(n, w, d, i))
+
+
+def tri_inverse(n, p):
+    i, j = _i64(), _i64()
+    _check(lib().dastac_tri_inverse(n, p, ctypes.byref(i), ctypes.byref(j)), "tri_inverse")
+    return i.value, j.value
+
+
+def tet_inverse(n, p):
+    i, j, k = _i64(), _i64(), _i64()
+    _check(lib().dastac_tet_inverse(n, p, ctypes.byref(i), ctypes.byref(j), ctypes.byref(k)), "tet_inverse")
+    return i.value, j.value, k.value
+
+
+# ---- device operations -----------------------------------------------------------
+
+def pack_triu_f32(n, dense, ld, packed, stream=None):
+    _check(lib().dastac_pack_triu_f32(n, _ptr(dense), ld, _ptr(packed), _stream(stream)), "pack_triu_f32")
+
+
+def unpack_triu_f32(n, packed, dense, ld, stream=None):
+    _check(lib().dastac_unpack_triu_f32(n, _ptr(packed), _ptr(dense), ld, _stream(stream)), "unpack_triu_f32")
+
+
+def pack_tet_f32(n, dense, packed, stream=None):
+    _check(lib().dastac_pack_tet_f32(n, _ptr(dense), _ptr(packed), _stream(stream)), "pack_tet_f32")
+
+
+def unpack_tet_f32(n, packed, dense, stream=None):
+    _check(lib().dastac_unpack_tet_f32(n, _ptr(packed), _ptr(dense), _stream(stream)), "unpack_tet_f32")
+
+
+def pack_band_f32(n, w, dense, ld, diag_major, stream=None):
+    _check(lib().dastac_pack_band_f32(n, w, _ptr(dense), ld, _ptr(diag_major), _stream(stream)), "pack_band_f32")
+
+
+def unpack_band_f32(n, w, diag_major, dense, ld, stream=None):
+    _check(lib().dastac_unpack_band_f32(n, w, _ptr(diag_major), _ptr(dense), ld, _stream(stream)),
+           "unpack_band_f32")
+
+
+def trmv_f32(n, Up, x, y, stream=None):
+    _check(lib().dastac_trmv_f32(n, _ptr(Up), _ptr(x), _ptr(y), _stream(stream)), "trmv_f32")
+
+
+def trmm_f32(n, m, Up, B, ldb, C, ldc, stream=None):
+    _check(lib().dastac_trmm_f32(n, m, _ptr(Up), _ptr(B), ldb, _ptr(C), ldc, _stream(stream)), "trmm_f32")
+
+
+def band_spmv_f32(n, w, D, x, y, stream=None):
+    _check(lib().dastac_band_spmv_f32(n, w, _ptr(D), _ptr(x), _ptr(y), _stream(stream)), "band_spmv_f32")
+
+
+def tet_ttv_f32(n, Ap, v, Mp, stream=None):
+    _check(lib().dastac_tet_ttv_f32(n, _ptr(Ap), _ptr(v), _ptr(Mp), _stream(stream)), "tet_ttv_f32")
+
+
+def tet_mttkrp_f32(n, R, Ap, B, ldb, C, ldc, M, ldm, stream=None):
+    _check(lib().dastac_tet_mttkrp_f32(n, R, _ptr(Ap), _ptr(B), ldb, _ptr(C), ldc, _ptr(M), ldm, _stream(stream)),
+           "tet_mttkrp_f32")

@@ -1,0 +1,69 @@
+"""The five benchmark workloads: sizes, seeds, and FLOP / byte accounting.
+
+Inputs only (host NumPy arrays from ``inputs``); nothing here computes a
+contraction or a packed offset.  Config c, tensor t uses stream seed
+``20240713*c + t``.  FLOPs follow the paper's convention (Section 6.2:
+structure-aware iterations times the additions and multiplications per
+iteration); for MTTKRP the factored evaluation the kernel actually performs is
+counted (fewer FLOPs than the three-operand convention) and the paper-convention
+figure is reported beside it.  Bytes are the algorithmic minimum: every operand
+and result moved once.
+"""
+from __future__ import annotations
+
+from . import inputs
+
+
+def _seed(c: int, t: int) -> int:
+    return 20240713 * c + t
+
+
+def _tri(n):
+    return n * (n + 1) // 2
+
+
+def _tet(n):
+    return n * (n + 1) * (n + 2) // 6
+
+
+def trmv_inputs(n: int = 512):
+    return {"n": n, "Up": inputs.uniform(_seed(1, 0), _tri(n)), "x": inputs.uniform(_seed(1, 1), n)}
+
+
+def trmm_inputs(n: int = 16384, m: int = 256):
+    return {"n": n, "m": m, "Up": inputs.uniform(_seed(2, 0), _tri(n)), "B": inputs.uniform(_seed(2, 1), n, m)}
+
+
+def band_inputs(n: int = 4194304, w: int = 16):
+    return {"n": n, "w": w, "D": inputs.band_normal(_seed(3, 0), n, w), "x": inputs.normal(_seed(3, 1), n)}
+
+
+def ttv_inputs(n: int = 512):
+    return {"n": n, "Ap": inputs.uniform(_seed(4, 0), _tet(n)), "v": inputs.uniform(_seed(4, 1), n)}
+
+
+def mttkrp_inputs(n: int = 1024, R: int = 32):
+    return {"n": n, "R": R, "Ap": inputs.uniform(_seed(5, 0), _tet(n)),
+            "B": inputs.normal(_seed(5, 1), n, R), "C": inputs.normal(_seed(5, 2), n, R)}
+
+
+def accounting(name: str, **kw) -> dict:
+    """Useful FLOPs and algorithmic bytes of one launch."""
+    if name == "trmv":
+        n = kw["n"]
+        return {"flops": 2 * _tri(n), "bytes": 4 * (_tri(n) + 2 * n)}
+    if name == "trmm":
+        n, m = kw["n"], kw["m"]
+        return {"flops": 2 * _tri(n) * m, "bytes": 4 * (_tri(n) + 2 * n * m)}
+    if name == "band":
+        n, w = kw["n"], kw["w"]
+        inrange = sum(n - abs(d) for d in range(-w, w + 1) if abs(d) < n)
+        return {"flops": 2 * inrange, "bytes": 4 * ((2 * w + 1) * n + 2 * n)}
+    if name == "ttv":
+        n = kw["n"]
+        return {"flops": 2 * _tet(n), "bytes": 4 * (_tet(n) + n + _tri(n))}
+    if name == "mttkrp":
+        n, R = kw["n"], kw["R"]
+        return {"flops": 2 * R * _tet(n) + 2 * R * _tri(n), "flops_paper_convention": 3 * R * _tet(n),
+                "bytes": 4 * (_tet(n) + 3 * n * R)}
+    raise ValueError(name)

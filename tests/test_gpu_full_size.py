@@ -1,0 +1,99 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+The small problems are compared element by element; for the two large contractions
+the oracle computes a sample of output rows one by one (its row-window argument),
+chosen to hit the first and last rows, tile boundaries and random interior rows.
+Bars as in test_gpu_parity.py: 1e-4 * sum|products| per element.
+"""
+import numpy as np
+import pytest
+
+from paper_2407_13726_amd import inputs
+from paper_2407_13726_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+
+    from paper_2407_13726_amd import dastac
+
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    dastac.lib()
+
+    class G:
+        pass
+
+    g = G()
+    g.torch, g.d, g.dev = torch, dastac, torch.device("cuda:0")
+    g.up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(g.dev)
+    g.empty = lambda *shape: torch.full(shape, float("nan"), dtype=torch.float32, device=g.dev)
+    g.down = lambda t: (torch.cuda.synchronize(), t.cpu().numpy())[1]
+    return g
+
+
+def check(got, want, scale, what):
+    got, want, scale = (np.asarray(a, dtype=np.float64).ravel() for a in (got, want, scale))
+    assert np.isfinite(got).all(), what + ": non-finite output"
+    err = np.abs(got - want)
+    assert (err <= TOL * scale).all(), "%s: worst err/scale %.3g" % (what, (err / np.maximum(scale, 1e-300)).max())
+
+
+def test_c1_trmv_512(gpu, oracle):
+    w = wl.trmv_inputs()
+    want, scale = oracle.trmv(w["n"], w["Up"], w["x"])
+    y = gpu.empty(w["n"])
+    gpu.d.trmv_f32(w["n"], gpu.up(w["Up"]), gpu.up(w["x"]), y)
+    check(gpu.down(y), want, scale, "C1 trmv")
+
+
+def test_c2_trmm_16384_sampled_rows(gpu, oracle):
+    w = wl.trmm_inputs()
+    n, m = w["n"], w["m"]
+    C = gpu.empty(n, m)
+    gpu.d.trmm_f32(n, m, gpu.up(w["Up"]), gpu.up(w["B"]), m, C, m)
+    got = gpu.down(C)
+    assert np.isfinite(got).all()
+    rng = np.random.default_rng(2)
+    rows = sorted({0, 1, 31, 32, 63, 64, 127, 128, 129, 8191, 8192, n - 129, n - 128, n - 65, n - 64, n - 33,
+                   n - 32, n - 2, n - 1} | {int(r) for r in rng.integers(0, n, 12)})
+    for i in rows:
+        want, scale = oracle.trmm(n, m, w["Up"], w["B"], rows=(i, i + 1))
+        check(got[i], want[i], scale[i], "C2 trmm row %d" % i)
+
+
+def test_c3_band_4m(gpu, oracle):
+    w = wl.band_inputs()
+    n, hw = w["n"], w["w"]
+    want, scale = oracle.band_spmv(n, hw, w["D"].ravel(), w["x"])
+    y = gpu.empty(n)
+    gpu.d.band_spmv_f32(n, hw, gpu.up(w["D"].ravel()), gpu.up(w["x"]), y)
+    check(gpu.down(y), want, scale, "C3 band")
+
+
+def test_c4_ttv_512(gpu, oracle):
+    w = wl.ttv_inputs()
+    n = w["n"]
+    want, scale = oracle.tet_ttv(n, w["Ap"], w["v"])
+    M = gpu.empty(n * (n + 1) // 2)
+    gpu.d.tet_ttv_f32(n, gpu.up(w["Ap"]), gpu.up(w["v"]), M)
+    check(gpu.down(M), want, scale, "C4 ttv")
+
+
+def test_c5_mttkrp_1024_sampled_slices(gpu, oracle):
+    w = wl.mttkrp_inputs()
+    n, R = w["n"], w["R"]
+    M = gpu.empty(n, R)
+    gpu.d.tet_mttkrp_f32(n, R, gpu.up(w["Ap"]), gpu.up(w["B"]), R, gpu.up(w["C"]), R, M, R)
+    got = gpu.down(M)
+    assert np.isfinite(got).all()
+    rng = np.random.default_rng(3)
+    rows = sorted({0, 1, 31, 32, 33, 511, 512, n - 65, n - 33, n - 32, n - 2, n - 1} |
+                  {int(r) for r in rng.integers(0, n, 8)})
+    for i in rows:
+        want, scale = oracle.tet_mttkrp(n, R, w["Ap"], w["B"], w["C"], rows=(i, i + 1))
+        check(got[i], want[i], scale[i], "C5 mttkrp slice %d" % i)

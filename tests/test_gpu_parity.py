@@ -1,0 +1,261 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on
+the same seeded inputs.
+
+Bars (stated here, used everywhere below):
+  * packed layouts and every copied value: bit-exact;
+  * floating outputs: |gpu - oracle| <= 1e-4 * sum|products| per element, the scale
+    coming from the oracle; with small-integer inputs every partial sum is exact in
+    fp32, so the GPU must then equal the oracle bit for bit whatever its summation order.
+"""
+import numpy as np
+import pytest
+
+from paper_2407_13726_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+
+    from paper_2407_13726_amd import dastac
+
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    dastac.lib()
+
+    class G:
+        pass
+
+    g = G()
+    g.torch = torch
+    g.d = dastac
+    g.dev = torch.device("cuda:0")
+    g.up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(g.dev)
+    g.empty = lambda *shape: torch.full(shape, float("nan"), dtype=torch.float32, device=g.dev)
+    g.down = lambda t: (torch.cuda.synchronize(), t.cpu().numpy())[1]
+    return g
+
+
+def tri(n):
+    return n * (n + 1) // 2
+
+
+def tet(n):
+    return n * (n + 1) * (n + 2) // 6
+
+
+def assert_within(got, want, scale, what):
+    got = np.asarray(got, dtype=np.float64).ravel()
+    want = np.asarray(want, dtype=np.float64).ravel()
+    scale = np.asarray(scale, dtype=np.float64).ravel()
+    assert np.isfinite(got).all(), what + ": non-finite output"
+    err = np.abs(got - want)
+    bad = err > TOL * scale
+    assert not bad.any(), "%s: %d of %d outside tolerance, worst err/scale %.3g at %d" % (
+        what, bad.sum(), bad.size, (err / np.maximum(scale, 1e-300)).max(), int(np.argmax(err - TOL * scale)))
+
+
+# ------------------------------------------------------------ pack / unpack ----
+
+@pytest.mark.parametrize("n,ld", [(1, 1), (2, 5), (17, 17), (255, 255), (256, 300), (257, 257), (700, 704)])
+def test_pack_unpack_triu_bit_exact(gpu, oracle, n, ld):
+    D = inputs.uniform(10 + n, n, ld)
+    want = oracle.pack_triu(np.ascontiguousarray(D[:, :n]))
+    dD, dP = gpu.up(D), gpu.empty(tri(n))
+    gpu.d.pack_triu_f32(n, dD, ld, dP)
+    got = gpu.down(dP)
+    assert got.tobytes() == want.tobytes()
+    dU = gpu.empty(n, ld)
+    gpu.d.unpack_triu_f32(n, dP, dU, ld)
+    U = gpu.down(dU)
+    assert U[:, :n].tobytes() == oracle.unpack_triu(n, want).tobytes()
+    assert np.isnan(U[:, n:]).all()  # padding columns of the dense buffer are not touched
+
+
+@pytest.mark.parametrize("n", [1, 2, 9, 33, 70])
+def test_pack_unpack_tet_bit_exact(gpu, oracle, n):
+    D = inputs.uniform(20 + n, n, n, n)
+    want = oracle.pack_tet(D)
+    dP = gpu.empty(tet(n))
+    gpu.d.pack_tet_f32(n, gpu.up(D), dP)
+    assert gpu.down(dP).tobytes() == want.tobytes()
+    dU = gpu.empty(n, n, n)
+    gpu.d.unpack_tet_f32(n, dP, dU)
+    assert gpu.down(dU).tobytes() == oracle.unpack_tet(n, want).tobytes()
+
+
+@pytest.mark.parametrize("n,w", [(1, 0), (1, 4), (40, 16), (300, 16), (257, 3), (64, 100)])
+def test_pack_unpack_band_bit_exact(gpu, oracle, n, w):
+    D = inputs.uniform(30 + n, n, n)
+    want = oracle.pack_band(D, w)
+    dP = gpu.empty((2 * w + 1) * n)
+    gpu.d.pack_band_f32(n, w, gpu.up(D), n, dP)
+    assert gpu.down(dP).tobytes() == want.tobytes()
+    dU = gpu.empty(n, n)
+    gpu.d.unpack_band_f32(n, w, dP, dU, n)
+    assert gpu.down(dU).tobytes() == oracle.unpack_band(n, w, want).tobytes()
+
+
+# --------------------------------------------------------------------- TRMV ----
+
+TRMV_SIZES = [1, 2, 3, 4, 5, 63, 64, 65, 129, 257, 512, 1000, 2049, 4100]
+
+
+@pytest.mark.parametrize("n", TRMV_SIZES)
+def test_trmv_parity(gpu, oracle, n):
+    Up, x = inputs.uniform(40 + n, tri(n)), inputs.uniform(41 + n, n)
+    want, scale = oracle.trmv(n, Up, x)
+    y = gpu.empty(n)
+    gpu.d.trmv_f32(n, gpu.up(Up), gpu.up(x), y)
+    assert_within(gpu.down(y), want, scale, "trmv n=%d" % n)
+
+
+@pytest.mark.parametrize("n", [1, 7, 130, 515, 1500])
+def test_trmv_integer_inputs_bit_exact(gpu, oracle, n):
+    Up, x = inputs.small_int(50 + n, -3, 3, tri(n)), inputs.small_int(51 + n, -3, 3, n)
+    want, _ = oracle.trmv(n, Up, x)
+    y = gpu.empty(n)
+    gpu.d.trmv_f32(n, gpu.up(Up), gpu.up(x), y)
+    assert gpu.down(y).tobytes() == want.tobytes()
+
+
+def test_trmv_unaligned_operands(gpu, oracle):
+    """Pointers that are only 4-byte aligned are accepted."""
+    n = 777
+    Up, x = inputs.uniform(60, tri(n)), inputs.uniform(61, n)
+    want, scale = oracle.trmv(n, Up, x)
+    dU, dx, dy = gpu.empty(tri(n) + 3), gpu.empty(n + 3), gpu.empty(n + 3)
+    dU[1:1 + tri(n)] = gpu.up(Up)
+    dx[3:] = gpu.up(x)
+    gpu.d.trmv_f32(n, dU[1:], dx[3:], dy[1:])
+    out = gpu.down(dy)
+    assert_within(out[1:1 + n], want, scale, "trmv unaligned")
+    assert np.isnan(out[0]) and np.isnan(out[1 + n:]).all()
+
+
+# ---------------------------------------------------------------------- TTV ----
+
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 5, 17, 64, 65, 130, 200, 300])
+def test_tet_ttv_parity(gpu, oracle, n):
+    Ap, v = inputs.uniform(70 + n, tet(n)), inputs.uniform(71 + n, n)
+    want, scale = oracle.tet_ttv(n, Ap, v)
+    M = gpu.empty(tri(n))
+    gpu.d.tet_ttv_f32(n, gpu.up(Ap), gpu.up(v), M)
+    assert_within(gpu.down(M), want, scale, "ttv n=%d" % n)
+
+
+@pytest.mark.parametrize("n", [6, 131, 260])
+def test_tet_ttv_integer_inputs_bit_exact(gpu, oracle, n):
+    Ap, v = inputs.small_int(80 + n, -3, 3, tet(n)), inputs.small_int(81 + n, -3, 3, n)
+    want, _ = oracle.tet_ttv(n, Ap, v)
+    M = gpu.empty(tri(n))
+    gpu.d.tet_ttv_f32(n, gpu.up(Ap), gpu.up(v), M)
+    assert gpu.down(M).tobytes() == want.tobytes()
+
+
+# --------------------------------------------------------------------- band ----
+
+@pytest.mark.parametrize("n,w", [(1, 0), (1, 16), (5, 16), (31, 16), (33, 16), (1023, 16), (1024, 16), (1025, 16),
+                                 (5000, 16), (4099, 0), (3000, 2), (3001, 4), (2500, 8), (2000, 1), (1500, 7),
+                                 (900, 64), (10, 40)])
+def test_band_spmv_parity(gpu, oracle, n, w):
+    D, x = inputs.band_normal(90 + n, n, w), inputs.normal(91 + n, n)
+    want, scale = oracle.band_spmv(n, w, D.ravel(), x)
+    y = gpu.empty(n)
+    gpu.d.band_spmv_f32(n, w, gpu.up(D.ravel()), gpu.up(x), y)
+    assert_within(gpu.down(y), want, scale, "band n=%d w=%d" % (n, w))
+
+
+@pytest.mark.parametrize("n,w", [(40, 16), (2100, 16), (300, 5)])
+def test_band_spmv_ignores_padding_and_is_exact_on_integers(gpu, oracle, n, w):
+    D = inputs.band_normal(100 + n, n, w, kind="small_int")
+    x = inputs.small_int(101 + n, -3, 3, n)
+    want, _ = oracle.band_spmv(n, w, D.ravel(), x)
+    for d in range(-w, w + 1):  # poison every padding slot
+        for i in range(n):
+            if not 0 <= i + d < n:
+                D[d + w, i] = np.nan
+    y = gpu.empty(n)
+    gpu.d.band_spmv_f32(n, w, gpu.up(D.ravel()), gpu.up(x), y)
+    assert gpu.down(y).tobytes() == want.tobytes()
+
+
+# --------------------------------------------------------------------- TRMM ----
+
+@pytest.mark.parametrize("n,m", [(1, 1), (2, 3), (31, 7), (64, 64), (65, 33), (127, 128), (130, 129), (200, 256),
+                                 (300, 40), (515, 70)])
+def test_trmm_parity(gpu, oracle, n, m):
+    Up, B = inputs.uniform(110 + n, tri(n)), inputs.uniform(111 + n, n, m)
+    want, scale = oracle.trmm(n, m, Up, B)
+    C = gpu.empty(n, m)
+    gpu.d.trmm_f32(n, m, gpu.up(Up), gpu.up(B), m, C, m)
+    assert_within(gpu.down(C), want, scale, "trmm n=%d m=%d" % (n, m))
+
+
+def test_trmm_leading_dimensions_and_integer_exactness(gpu, oracle):
+    n, m, ldb, ldc = 150, 37, 45, 41
+    Up = inputs.small_int(120, -3, 3, tri(n))
+    B = inputs.small_int(121, -3, 3, n, ldb)
+    want, _ = oracle.trmm(n, m, Up, np.ascontiguousarray(B[:, :m]))
+    C = gpu.empty(n, ldc)
+    gpu.d.trmm_f32(n, m, gpu.up(Up), gpu.up(B), ldb, C, ldc)
+    out = gpu.down(C)
+    assert out[:, :m].tobytes() == want.tobytes()
+    assert np.isnan(out[:, m:]).all()
+
+
+# ------------------------------------------------------------------- MTTKRP ----
+
+@pytest.mark.parametrize("n,R", [(1, 1), (2, 32), (5, 3), (31, 32), (33, 32), (64, 32), (70, 17), (100, 32),
+                                 (130, 8)])
+def test_tet_mttkrp_parity(gpu, oracle, n, R):
+    Ap = inputs.uniform(130 + n, tet(n))
+    B, C = inputs.normal(131 + n, n, R), inputs.normal(132 + n, n, R)
+    want, scale = oracle.tet_mttkrp(n, R, Ap, B, C)
+    M = gpu.empty(n, R)
+    gpu.d.tet_mttkrp_f32(n, R, gpu.up(Ap), gpu.up(B), R, gpu.up(C), R, M, R)
+    assert_within(gpu.down(M), want, scale, "mttkrp n=%d R=%d" % (n, R))
+
+
+def test_tet_mttkrp_leading_dimensions_and_integer_exactness(gpu, oracle):
+    n, R, ldb, ldc, ldm = 75, 20, 24, 32, 21
+    Ap = inputs.small_int(140, -2, 2, tet(n))
+    B, C = inputs.small_int(141, -2, 2, n, ldb), inputs.small_int(142, -2, 2, n, ldc)
+    want, _ = oracle.tet_mttkrp(n, R, Ap, np.ascontiguousarray(B[:, :R]), np.ascontiguousarray(C[:, :R]))
+    M = gpu.empty(n, ldm)
+    gpu.d.tet_mttkrp_f32(n, R, gpu.up(Ap), gpu.up(B), ldb, gpu.up(C), ldc, M, ldm)
+    out = gpu.down(M)
+    assert out[:, :R].tobytes() == want.tobytes()
+    assert np.isnan(out[:, R:]).all()
+
+
+# ------------------------------------------------------------- degenerate ----
+
+def test_zero_size_calls_succeed_on_device(gpu):
+    d, e = gpu.d, gpu.empty(4)
+    d.trmv_f32(0, e, e, e)
+    d.tet_ttv_f32(0, e, e, e)
+    d.band_spmv_f32(0, 16, e, e, e)
+    d.trmm_f32(0, 4, e, e, 4, e, 4)
+    d.tet_mttkrp_f32(0, 4, e, e, 4, e, 4, e, 4)
+    d.pack_triu_f32(0, e, 0, e)
+    gpu.torch.cuda.synchronize()
+    assert np.isnan(gpu.down(e)).all()
+
+
+def test_calls_are_stream_ordered(gpu, oracle):
+    """Work is enqueued on the stream that is passed in."""
+    torch = gpu.torch
+    n = 400
+    Up, x = inputs.uniform(150, tri(n)), inputs.uniform(151, n)
+    want, scale = oracle.trmv(n, Up, x)
+    s = torch.cuda.Stream()
+    dU, dx, y = gpu.up(Up), gpu.up(x), gpu.empty(n)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        gpu.d.trmv_f32(n, dU, dx, y)
+    s.synchronize()
+    assert_within(y.cpu().numpy(), want, scale, "trmv on side stream")

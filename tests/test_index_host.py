@@ -1,0 +1,176 @@
+"""Host-side checks of the C-ABI library that need no GPU: the index-polynomial
+module against the oracle's counting definition, the exported symbols, and the
+argument validation of every device entry point (all of which return before any
+HIP call is made).
+"""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2407_13726_amd import dastac
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "dastac.h")).read()
+    declared = set(re.findall(r"\b(dastac_[a-z0-9_]+)\s*\(", hdr))
+    assert declared == set(dastac.SIGNATURES), declared ^ set(dastac.SIGNATURES)
+    L = dastac.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_strerror_names_every_code():
+    names = {dastac.strerror(c) for c in range(6)}
+    assert len(names) == 6 and "unknown status" not in names
+    assert dastac.strerror(99) == "unknown status"
+
+
+@pytest.mark.parametrize("n", [0, 1, 2, 3, 7, 12, 25])
+def test_tri_forward_and_inverse_match_counting(oracle, n):
+    assert dastac.tri_count(n) == oracle.count_domain(oracle.DOM_TRIU, [n])
+    p = 0
+    for i in range(n):
+        for j in range(i, n):
+            assert dastac.tri_offset(n, i, j) == p == oracle.triu_position(n, i, j)
+            assert dastac.tri_inverse(n, p) == (i, j)
+            p += 1
+    assert dastac.tri_offset(n, 1, 0) == -1 and dastac.tri_offset(n, 0, n) == -1
+    for bad in (-1, p):
+        with pytest.raises(dastac.DastacError) as e:
+            dastac.tri_inverse(n, bad)
+        assert e.value.status == dastac.EINVAL
+
+
+@pytest.mark.parametrize("n", [0, 1, 2, 3, 6, 11])
+def test_tet_forward_and_inverse_match_counting(oracle, n):
+    assert dastac.tet_count(n) == oracle.count_domain(oracle.DOM_TET, [n])
+    p = 0
+    for i in range(n):
+        for j in range(i, n):
+            for k in range(j, n):
+                assert dastac.tet_offset(n, i, j, k) == p
+                assert oracle.count_preceding(oracle.DOM_TET, [n], [i, j, k]) == p
+                assert dastac.tet_inverse(n, p) == (i, j, k)
+                p += 1
+    assert dastac.tet_offset(n, 0, 1, 0) == -1 and dastac.tet_offset(n, 0, 0, n) == -1
+    for bad in (-1, p):
+        with pytest.raises(dastac.DastacError):
+            dastac.tet_inverse(n, bad)
+
+
+@pytest.mark.parametrize("n,w", [(1, 0), (5, 2), (7, 16)])
+def test_band_offsets_match_counting(oracle, n, w):
+    assert dastac.band_count(n, w) == oracle.count_domain(oracle.DOM_BAND, [n, w]) == (2 * w + 1) * n
+    for d in range(-w, w + 1):
+        for i in range(n):
+            assert dastac.band_offset(n, w, d, i) == oracle.count_preceding(oracle.DOM_BAND, [n, w], [d, i])
+    assert dastac.band_offset(n, w, w + 1, 0) == -1 and dastac.band_offset(n, w, 0, n) == -1
+    assert dastac.band_count(-1, 0) == -1 and dastac.band_count(1, -1) == -1
+
+
+def test_benchmark_sizes_row_and_slice_boundaries(oracle):
+    """Forward and inverse at every row start of the large triangle and every fibre start of
+    the large tetrahedron, against the oracle's running-counter walk."""
+    n = 16384
+    starts = oracle.triu_row_starts(n)
+    assert dastac.tri_count(n) == starts[n] == 134225920
+    for i in list(range(0, n, 97)) + [n - 2, n - 1]:
+        assert dastac.tri_offset(n, i, i) == starts[i]
+        assert dastac.tri_inverse(n, int(starts[i])) == (i, i)
+        assert dastac.tri_inverse(n, int(starts[i + 1]) - 1) == (i, n - 1)
+    n = 1024
+    fs, total = oracle.tet_fibre_starts(n)
+    assert dastac.tet_count(n) == total == 179481600
+    rng = np.random.default_rng(5)
+    for i in list(range(0, n, 61)) + [n - 1]:
+        for j in sorted({i, min(i + 1, n - 1), n - 1, int(rng.integers(i, n))}):
+            assert dastac.tet_offset(n, i, j, j) == fs[i, j]
+            assert dastac.tet_inverse(n, int(fs[i, j])) == (i, j, j)
+            assert dastac.tet_inverse(n, int(fs[i, j]) + (n - 1 - j)) == (i, j, n - 1)
+
+
+def test_inverse_round_trip_random_positions():
+    rng = np.random.default_rng(11)
+    for n in (512, 16384, 100003, 2 ** 31 - 1):
+        cnt = dastac.tri_count(n)
+        for p in [0, cnt - 1] + [int(v) for v in rng.integers(0, cnt, 200)]:
+            i, j = dastac.tri_inverse(n, p)
+            assert 0 <= i <= j < n and dastac.tri_offset(n, i, j) == p
+    for n in (512, 1024, 4099, 2 ** 20):
+        cnt = dastac.tet_count(n)
+        for p in [0, cnt - 1] + [int(v) for v in rng.integers(0, cnt, 200)]:
+            i, j, k = dastac.tet_inverse(n, p)
+            assert 0 <= i <= j <= k < n and dastac.tet_offset(n, i, j, k) == p
+
+
+def test_guards():
+    assert dastac.tri_count(-1) == -1 and dastac.tri_count(2 ** 31) == -1
+    assert dastac.tri_count(2 ** 31 - 1) == (2 ** 31 - 1) * 2 ** 30
+    assert dastac.tet_count(-1) == -1 and dastac.tet_count(2 ** 20 + 1) == -1
+    n = 2 ** 20
+    assert dastac.tet_count(n) == n * (n + 1) * (n + 2) // 6
+
+
+# ---- argument validation of the device entry points (no launch happens) --------
+
+def _p(v):
+    return ctypes.c_void_p(v)
+
+
+A, B, C, D = 0x10000, 0x20000000, 0x40000000, 0x60000000  # fake, never dereferenced
+
+
+def test_device_entry_points_reject_bad_arguments():
+    L = dastac.lib()
+    # negative sizes / bad leading dimensions / unsupported m, R, w
+    assert L.dastac_pack_triu_f32(-1, _p(A), 4, _p(B), None) == dastac.EINVAL
+    assert L.dastac_pack_triu_f32(8, _p(A), 7, _p(B), None) == dastac.EINVAL
+    assert L.dastac_unpack_triu_f32(8, _p(A), _p(B), 7, None) == dastac.EINVAL
+    assert L.dastac_pack_tet_f32(-3, _p(A), _p(B), None) == dastac.EINVAL
+    assert L.dastac_pack_band_f32(4, -1, _p(A), 4, _p(B), None) == dastac.EINVAL
+    assert L.dastac_trmv_f32(-1, _p(A), _p(B), _p(C), None) == dastac.EINVAL
+    assert L.dastac_trmm_f32(4, 0, _p(A), _p(B), 4, _p(C), 4, None) == dastac.EINVAL
+    assert L.dastac_trmm_f32(4, 8, _p(A), _p(B), 7, _p(C), 8, None) == dastac.EINVAL
+    assert L.dastac_band_spmv_f32(4, -1, _p(A), _p(B), _p(C), None) == dastac.EINVAL
+    assert L.dastac_band_spmv_f32(4, 65, _p(A), _p(B), _p(C), None) == dastac.EINVAL
+    assert L.dastac_tet_ttv_f32(-1, _p(A), _p(B), _p(C), None) == dastac.EINVAL
+    assert L.dastac_tet_mttkrp_f32(4, 0, _p(A), _p(B), 4, _p(C), 4, _p(D), 4, None) == dastac.EINVAL
+    assert L.dastac_tet_mttkrp_f32(4, 33, _p(A), _p(B), 33, _p(C), 33, _p(D), 33, None) == dastac.EINVAL
+    assert L.dastac_tet_mttkrp_f32(4, 8, _p(A), _p(B), 8, _p(C), 8, _p(D), 7, None) == dastac.EINVAL
+    # overflow guards
+    assert L.dastac_tet_ttv_f32(2 ** 20 + 1, _p(A), _p(B), _p(C), None) == dastac.EOVERFLOW
+    assert L.dastac_trmv_f32(2 ** 31, _p(A), _p(B), _p(C), None) == dastac.EOVERFLOW
+    assert L.dastac_pack_tet_f32(2 ** 14, _p(A), _p(B), None) == dastac.EOVERFLOW
+    # NULL pointers
+    assert L.dastac_trmv_f32(4, None, _p(B), _p(C), None) == dastac.ENULL
+    assert L.dastac_trmv_f32(4, _p(A), None, _p(C), None) == dastac.ENULL
+    assert L.dastac_trmv_f32(4, _p(A), _p(B), None, None) == dastac.ENULL
+    assert L.dastac_trmm_f32(4, 2, _p(A), None, 2, _p(C), 2, None) == dastac.ENULL
+    assert L.dastac_band_spmv_f32(4, 1, None, _p(B), _p(C), None) == dastac.ENULL
+    assert L.dastac_tet_ttv_f32(4, _p(A), _p(B), None, None) == dastac.ENULL
+    assert L.dastac_tet_mttkrp_f32(4, 2, _p(A), _p(B), 2, None, 2, _p(D), 2, None) == dastac.ENULL
+    assert L.dastac_pack_triu_f32(4, None, 4, _p(B), None) == dastac.ENULL
+    assert L.dastac_unpack_tet_f32(4, _p(A), None, None) == dastac.ENULL
+    assert L.dastac_unpack_band_f32(4, 1, None, _p(B), 4, None) == dastac.ENULL
+    # output overlapping an input
+    assert L.dastac_trmv_f32(4, _p(A), _p(B), _p(A + 8), None) == dastac.EALIAS
+    assert L.dastac_trmv_f32(4, _p(A), _p(B), _p(B), None) == dastac.EALIAS
+    assert L.dastac_trmm_f32(4, 2, _p(A), _p(B), 2, _p(B + 4), 2, None) == dastac.EALIAS
+    assert L.dastac_band_spmv_f32(4, 1, _p(A), _p(B), _p(A + 44), None) == dastac.EALIAS
+    assert L.dastac_tet_ttv_f32(4, _p(A), _p(B), _p(A + 76), None) == dastac.EALIAS
+    assert L.dastac_tet_mttkrp_f32(4, 2, _p(A), _p(B), 2, _p(C), 2, _p(C), 2, None) == dastac.EALIAS
+    assert L.dastac_pack_triu_f32(4, _p(A), 4, _p(A + 60), None) == dastac.EALIAS
+    # n == 0 is a successful no-op, pointers not needed
+    assert L.dastac_trmv_f32(0, None, None, None, None) == dastac.OK
+    assert L.dastac_trmm_f32(0, 3, None, None, 3, None, 3, None) == dastac.OK
+    assert L.dastac_band_spmv_f32(0, 16, None, None, None, None) == dastac.OK
+    assert L.dastac_tet_ttv_f32(0, None, None, None, None) == dastac.OK
+    assert L.dastac_tet_mttkrp_f32(0, 4, None, None, 4, None, 4, None, 4, None) == dastac.OK
+    assert L.dastac_pack_triu_f32(0, None, 0, None, None) == dastac.OK
+    assert L.dastac_unpack_tet_f32(0, None, None, None) == dastac.OK
+    assert L.dastac_pack_band_f32(0, 2, None, 0, None, None) == dastac.OK
