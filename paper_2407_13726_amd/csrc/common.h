@@ -19,7 +19,7 @@ inline bool overlaps(const void *a, int64_t na, const void *b, int64_t nb) {
 // Status of the launch that was just issued on this thread.
 inline int launch_status() { return hipGetLastError() == hipSuccess ? DASTAC_OK : DASTAC_EHIP; }
 
-inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+DASTAC_HD int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 #if defined(__HIPCC__)
 // 16-byte vector of floats that only promises 4-byte alignment: packed rows start at arbitrary

@@ -1,33 +1,194 @@
-// TRMM over a packed upper triangle:  C(i,c) := U(i,k) * B(k,c), i<=k.
-// First version: one output element per lane, plain FMA loop (no matrix cores yet).
+// TRMM over a packed upper triangle on the fp32 matrix cores:
+//
+//   C(i,c) := U(i,k) * B(k,c),  i<=k        U packed row-major, B and C dense row-major
+//
+// The rule is Table 1's SpMV_UT with a matrix right-hand side; U keeps the packed layout of
+// Section 4 (row i holds k=i..n-1 contiguously, starting at tri_row_start(n,i)).
+//
+// Tiling.  A workgroup (4 wavefronts) owns a 64-row x 128-column tile of C and sweeps k from the
+// diagonal of its row block to n in steps of 32.  Per step the 64x32 tile of U (each packed row
+// piece is 128 contiguous bytes, at its own 4-byte-aligned offset) and the 32x128 tile of B are
+// staged in LDS, double-buffered against the global loads of the next step.  Each wavefront
+// computes a 32x64 sub-tile with v_mfma_f32_32x32x2_f32: lanes 0-31 feed k, lanes 32-63 feed k+1.
+// Because a sum over k may be taken in any order, lane half h is given the four consecutive k
+// values 8t+4h..8t+4h+3 of every group of eight, so its U operand is one 16-byte LDS read.
+//
+// Only the two k-steps that touch the diagonal (and the ragged last step / last row block) take
+// the masked loader, which writes zeros for k<i; every other tile is loaded without predicates.
+//
+// Load balance without atomics: row block b needs (n - 64 b)/32 k-steps, so a workgroup processes
+// the pair (b, nb-1-b), and every workgroup does the same amount of work.  Workgroups that share
+// a row-block pair (different column blocks) get ids that are equal modulo 8, i.e. land on the
+// same XCD, so the packed U rows they both read are fetched from HBM once and hit in that XCD's L2.
 #include "common.h"
 
 using namespace dastac;
 
 namespace {
+
+constexpr int kBM = 64;    // rows of C per workgroup tile
+constexpr int kBN = 128;   // columns of C per workgroup tile
+constexpr int kKT = 32;    // k-step
+constexpr int kUP = kKT + 4;  // LDS pitch of the U tile (floats): 16-byte reads of 8 lanes cover all banks
 constexpr int kBlock = 256;
 
-__global__ __launch_bounds__(kBlock) void trmm_simple_kernel(int64_t n, int64_t m, const float *__restrict__ U,
-                                                             const float *__restrict__ B, int64_t ldb,
-                                                             float *__restrict__ C, int64_t ldc) {
-  const int64_t i = blockIdx.y;
-  const int64_t c = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (c >= m) return;
-  const float *u = U + tri_row_start(n, i);
-  float acc = 0.0f;
-  for (int64_t k = i; k < n; ++k) acc += u[k - i] * B[k * ldb + c];
-  C[i * ldc + c] = acc;
+typedef float f16v __attribute__((ext_vector_type(16)));
+
+struct Stage {
+  f4a u[2];  // U: rows r and r+32 of the tile, four k values each
+  f4a b[4];  // B: k rows kr, kr+8, kr+16, kr+24, four columns each
+};
+
+__global__ __launch_bounds__(kBlock) void trmm_mfma_kernel(int64_t n, int64_t m, const float *__restrict__ U,
+                                                           const float *__restrict__ B, int64_t ldb,
+                                                           float *__restrict__ C, int64_t ldc, int nb, int npairs,
+                                                           int ncb) {
+  __shared__ __attribute__((aligned(16))) float Us[2][kBM * kUP];
+  __shared__ __attribute__((aligned(16))) float Bs[2][kKT * kBN];
+
+  // workgroup id -> (row-block pair, column block); ids equal mod 8 share an XCD
+  const int L = blockIdx.x;
+  const int xcd = L & 7, slot = L >> 3;
+  const int pair = xcd + 8 * (slot / ncb);
+  const int cb = slot % ncb;
+  if (pair >= npairs) return;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wr = wave >> 1, wc = wave & 1;  // 2x2 wavefronts: 32 rows x 64 columns each
+  const int l32 = lane & 31, h = lane >> 5;
+
+  // staging roles
+  const int ur = tid >> 3, uk = (tid & 7) * 4;     // U: row ur (+32), k offset uk
+  const int bk = tid >> 5, bc = (tid & 31) * 4;    // B: k row bk (+8,16,24), column offset bc
+  const int64_t col0 = (int64_t)cb * kBN;
+  const bool cols_full = col0 + kBN <= m;
+
+  for (int which = 0; which < 2; ++which) {
+    const int blk = which == 0 ? pair : nb - 1 - pair;
+    if (which == 1 && blk == pair) break;  // odd number of row blocks: the middle one is alone
+    const int64_t i0 = (int64_t)blk * kBM;
+    const bool rows_full = i0 + kBM <= n;
+    const int nk = (int)ceil_div(n - i0, kKT);
+
+    // per-thread packed row bases: element (i,k) of U is at ubase[i] + k
+    const float *ub[2];
+    bool urow_ok[2];
+    for (int q = 0; q < 2; ++q) {
+      int64_t i = i0 + ur + 32 * q;
+      urow_ok[q] = i < n;
+      ub[q] = U + (urow_ok[q] ? tri_row_start(n, i) - i : 0);
+    }
+
+    auto load_stage = [&](int kt, Stage &s) {
+      const int64_t k0 = i0 + (int64_t)kt * kKT;
+      const bool k_full = k0 + kKT <= n;
+      if (kt >= 2 && k_full && rows_full) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q) s.u[q] = *reinterpret_cast<const f4u *>(ub[q] + k0 + uk);
+      } else {
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+          const int64_t i = i0 + ur + 32 * q;
+          float v[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int64_t k = k0 + uk + e;
+            v[e] = (urow_ok[q] && k >= i && k < n) ? ub[q][k] : 0.0f;
+          }
+          s.u[q] = f4a{v[0], v[1], v[2], v[3]};
+        }
+      }
+      if (k_full && cols_full) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          s.b[q] = *reinterpret_cast<const f4u *>(B + (k0 + bk + 8 * q) * ldb + col0 + bc);
+      } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int64_t k = k0 + bk + 8 * q;
+          float v[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = (k < n && col0 + bc + e < m) ? B[k * ldb + col0 + bc + e] : 0.0f;
+          s.b[q] = f4a{v[0], v[1], v[2], v[3]};
+        }
+      }
+    };
+    auto store_stage = [&](int buf, const Stage &s) {
+#pragma unroll
+      for (int q = 0; q < 2; ++q) *reinterpret_cast<f4a *>(&Us[buf][(ur + 32 * q) * kUP + uk]) = s.u[q];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) *reinterpret_cast<f4a *>(&Bs[buf][(bk + 8 * q) * kBN + bc]) = s.b[q];
+    };
+
+    f16v acc[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
+
+    Stage st;
+    load_stage(0, st);
+    __syncthreads();  // the previous row block's last reads of buffer 0 are done
+    store_stage(0, st);
+    __syncthreads();
+
+    for (int kt = 0; kt < nk; ++kt) {
+      const int buf = kt & 1;
+      if (kt + 1 < nk) load_stage(kt + 1, st);
+      // rows i0+32.. have nothing at or right of the diagonal in the first k-step
+      if (!(kt == 0 && wr == 1)) {
+        const float *us = &Us[buf][(wr * 32 + l32) * kUP + 4 * h];
+        const float *bs = &Bs[buf][(4 * h) * kBN + wc * 64 + l32];
+#pragma unroll
+        for (int t = 0; t < kKT / 8; ++t) {
+          const f4a a = *reinterpret_cast<const f4a *>(us + 8 * t);
+          float b0[4], b1[4];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            b0[q] = bs[(8 * t + q) * kBN];
+            b1[q] = bs[(8 * t + q) * kBN + 32];
+          }
+          acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b0[0], acc[0], 0, 0, 0);
+          acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b1[0], acc[1], 0, 0, 0);
+          acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b0[1], acc[0], 0, 0, 0);
+          acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b1[1], acc[1], 0, 0, 0);
+          acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b0[2], acc[0], 0, 0, 0);
+          acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b1[2], acc[1], 0, 0, 0);
+          acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b0[3], acc[0], 0, 0, 0);
+          acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b1[3], acc[1], 0, 0, 0);
+        }
+      }
+      if (kt + 1 < nk) store_stage(buf ^ 1, st);
+      __syncthreads();
+    }
+
+    // D layout of the 32x32 tile: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int64_t col = col0 + wc * 64 + t * 32 + l32;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int64_t i = i0 + wr * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+        if (i < n && col < m) C[i * ldc + col] = acc[t][v];
+      }
+    }
+  }
 }
+
 }  // namespace
 
 extern "C" int dastac_trmm_f32(int64_t n, int64_t m, const float *Up, const float *B, int64_t ldb, float *C,
                                int64_t ldc, void *stream) {
   if (n < 0 || m < 1 || ldb < m || ldc < m) return DASTAC_EINVAL;
-  if (n > 65535) return DASTAC_EOVERFLOW;
+  if (n > (1 << 24) || m > (1 << 24)) return DASTAC_EOVERFLOW;
   if (n == 0) return DASTAC_OK;
   if (!Up || !B || !C) return DASTAC_ENULL;
   if (overlaps(C, n * ldc * 4, Up, tri(n) * 4) || overlaps(C, n * ldc * 4, B, n * ldb * 4)) return DASTAC_EALIAS;
-  dim3 grid((unsigned)ceil_div(m, kBlock), (unsigned)n);
-  trmm_simple_kernel<<<grid, kBlock, 0, (hipStream_t)stream>>>(n, m, Up, B, ldb, C, ldc);
+  const int nb = (int)ceil_div(n, kBM);
+  const int npairs = (nb + 1) / 2;
+  const int ncb = (int)ceil_div(m, kBN);
+  const int64_t grid = (int64_t)8 * ceil_div(npairs, 8) * ncb;
+  if (grid > 0x7fffffff) return DASTAC_EOVERFLOW;
+  trmm_mfma_kernel<<<(unsigned)grid, kBlock, 0, (hipStream_t)stream>>>(n, m, Up, B, ldb, C, ldc, nb, npairs, ncb);
   return launch_status();
 }
