@@ -1,37 +1,180 @@
-// MTTKRP over a packed upper tetrahedron:  M(i,r) := A(i,j,k) * B(j,r) * C(k,r), i<=j<=k.
-// First version: one workgroup per slice i, one wavefront per row (i,j), plain FMA (no matrix cores yet).
+// MTTKRP over a packed upper tetrahedron on the fp32 matrix cores:
+//
+//   M(i,r) := A(i,j,k) * B(j,r) * C(k,r),   i<=j<=k, 0<=r<R<=32     (Table 1, MTTKRP rule)
+//
+// Factored evaluation.  Slice i of the packed tetrahedron is a packed upper triangle U_i of order
+// n-i, so   M(i,:) = sum_j B(j,:) .* T_i(j,:)   with   T_i = U_i * C[i:, :]   -- a TRMM whose
+// result is consumed at once and never leaves the registers.  A is read exactly once.
+//
+// One workgroup (8 wavefronts) per slice, heaviest slices first.  The workgroup walks k in panels of
+// 256; the panel's rows of C are staged in LDS (the reused dense operand).  Inside a panel the
+// work items are 32-row blocks of the slice; wavefronts draw them from an LDS counter, full blocks
+// first and the blocks cut by the diagonal (shorter) last, which balances the eight wavefronts.
+//
+// For one block a wavefront streams its 32 packed rows in 32x32 tiles: coalesced 16-byte loads
+// (8 lanes cover 128 contiguous bytes of one row; each row starts at its own element offset, given
+// by the index polynomial tet_row_start), a private LDS tile turns them into the operand layout of
+// v_mfma_f32_32x32x2_f32 (row = lane%32), and 16 matrix instructions accumulate the 32x32 block of
+// T.  As in the TRMM kernel, lane half h takes k values 8t+4h..8t+4h+3 of each group of eight.  Only
+// tiles on the diagonal or at the ragged end of a row use predicated loads (zeros for k<j, k>=n).
+// The block of T is then multiplied elementwise by B's rows and folded into 32 running sums.
 #include "common.h"
 
 using namespace dastac;
 
 namespace {
-constexpr int kBlock = 256;
 
-__global__ __launch_bounds__(kBlock) void mttkrp_simple_kernel(int64_t n, int R, const float *__restrict__ A,
-                                                               const float *__restrict__ B, int64_t ldb,
-                                                               const float *__restrict__ C, int64_t ldc,
-                                                               float *__restrict__ M, int64_t ldm) {
-  __shared__ float part[kBlock / 64][32];
+constexpr int kWaves = 8;
+constexpr int kBlock = kWaves * 64;
+constexpr int kPanel = 256;  // k values per staged panel of C
+constexpr int kTP = 36;      // pitch (floats) of a wavefront's private 32x32 tile
+
+typedef float f16v __attribute__((ext_vector_type(16)));
+
+// Orders LDS traffic between the lanes of ONE wavefront (which executes in lockstep): earlier LDS
+// writes are visible to later reads of any lane, and the compiler may not move LDS accesses across.
+__device__ inline void wave_sync_lds() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__global__ __launch_bounds__(kBlock) void mttkrp_mfma_kernel(int64_t n, int R, const float *__restrict__ A,
+                                                             const float *__restrict__ Bm, int64_t ldb,
+                                                             const float *__restrict__ Cm, int64_t ldc,
+                                                             float *__restrict__ M, int64_t ldm) {
+  __shared__ __attribute__((aligned(16))) float Cs[kPanel * 32];
+  __shared__ __attribute__((aligned(16))) float At[kWaves][32 * kTP];
+  __shared__ float Mred[kWaves][32];
+  __shared__ int next_unit;
+
   const int64_t i = blockIdx.x;
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  const int r = lane & 31, half = lane >> 5;
-  float macc = 0.0f;
-  for (int64_t j = i + wv; j < n; j += kBlock / 64) {
-    const float *a = A + tet_row_start(n, i, j);
-    float t = 0.0f;
-    if (r < R)
-      for (int64_t k = j + half; k < n; k += 2) t += a[k - j] * C[k * ldc + r];
-    t += __shfl_xor(t, 32, 64);
-    if (r < R) macc += t * B[j * ldb + r];
+  const int64_t m = n - i;  // order of this slice
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, h = lane >> 5;
+  const int nblk = (int)ceil_div(m, 32);
+  const int npanels = (int)ceil_div(m, kPanel);
+  const int64_t slice0 = tet_slice_start(n, i);  // packed position of (i,i,i)
+
+  // loader role inside a 32x32 tile: rows lr, lr+8, lr+16, lr+24; four k values from lk
+  const int lr = lane >> 3, lk = (lane & 7) * 4;
+  float *tile = At[wave];
+
+  float macc = 0.0f;  // this lane's share of M(i, l32)
+
+  for (int c = 0; c < npanels; ++c) {
+    const int64_t kp0 = i + (int64_t)c * kPanel;
+    __syncthreads();  // every wavefront is done with the previous panel
+    for (int t = tid; t < kPanel * 8; t += kBlock) {
+      const int row = t >> 3, c4 = (t & 7) * 4;
+      const int64_t k = kp0 + row;
+      f4a v = {0.0f, 0.0f, 0.0f, 0.0f};
+      if (k < n) {
+        if (R == 32) {
+          v = *reinterpret_cast<const f4u *>(Cm + k * ldc + c4);
+        } else {
+          if (c4 + 0 < R) v.x = Cm[k * ldc + c4 + 0];
+          if (c4 + 1 < R) v.y = Cm[k * ldc + c4 + 1];
+          if (c4 + 2 < R) v.z = Cm[k * ldc + c4 + 2];
+          if (c4 + 3 < R) v.w = Cm[k * ldc + c4 + 3];
+        }
+      }
+      *reinterpret_cast<f4a *>(&Cs[row * 32 + c4]) = v;
+    }
+    if (tid == 0) next_unit = 0;
+    __syncthreads();
+
+    const int64_t kp1 = (kp0 + kPanel < n) ? kp0 + kPanel : n;
+    const int nunits = (nblk < 8 * (c + 1)) ? nblk : 8 * (c + 1);  // row blocks that reach this panel
+    for (;;) {
+      int u = 0;
+      if (lane == 0) u = atomicAdd(&next_unit, 1);
+      u = __builtin_amdgcn_readfirstlane(u);
+      if (u >= nunits) break;
+
+      const int64_t j0 = i + 32 * (int64_t)u;          // first row of the block
+      const int64_t ks = (j0 > kp0) ? j0 : kp0;        // first k of this block in this panel
+      const int ntiles = (int)ceil_div(kp1 - ks, 32);
+      const bool rows_full = j0 + 32 <= n;
+      // packed row bases for the rows this lane loads: element (i,j,k) is at rb[q] + k
+      const float *rb[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        int64_t j = j0 + lr + 8 * q;
+        if (j >= n) j = n - 1;  // keep the address inside the buffer; values are masked below
+        const int64_t jj = j - i;  // row inside the slice triangle of order m
+        rb[q] = A + slice0 + tri_row_start(m, jj) - j;
+      }
+
+      auto load_tile = [&](int t, f4a (&v)[4]) {
+        const int64_t k0 = ks + 32 * (int64_t)t;
+        if (rows_full && k0 >= j0 + 32 && k0 + 32 <= n) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) v[q] = *reinterpret_cast<const f4u *>(rb[q] + k0 + lk);
+        } else {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int64_t j = j0 + lr + 8 * q;
+            float e[4];
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+              const int64_t k = k0 + lk + s;
+              e[s] = (j < n && k >= j && k < n) ? rb[q][k] : 0.0f;
+            }
+            v[q] = f4a{e[0], e[1], e[2], e[3]};
+          }
+        }
+      };
+
+      f16v acc;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+
+      f4a cur[4], nxt[4];
+      load_tile(0, cur);
+      for (int t = 0; t < ntiles; ++t) {
+        if (t + 1 < ntiles) load_tile(t + 1, nxt);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) *reinterpret_cast<f4a *>(&tile[(lr + 8 * q) * kTP + lk]) = cur[q];
+        wave_sync_lds();  // the tile is private to this wavefront: no workgroup barrier needed
+        const float *cs = &Cs[(int)(ks - kp0 + 32 * t + 4 * h) * 32 + l32];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const f4a a = *reinterpret_cast<const f4a *>(&tile[l32 * kTP + 8 * g + 4 * h]);
+          const float c0 = cs[(8 * g + 0) * 32], c1 = cs[(8 * g + 1) * 32];
+          const float c2 = cs[(8 * g + 2) * 32], c3 = cs[(8 * g + 3) * 32];
+          acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, c0, acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, c1, acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, c2, acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, c3, acc, 0, 0, 0);
+        }
+        wave_sync_lds();  // all lanes have read the tile before the next one overwrites it
+        if (t + 1 < ntiles) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) cur[q] = nxt[q];
+        }
+      }
+
+      // fold the 32x32 block of T with B: register v of lane l is row 8*(v/4)+4*(l/32)+v%4, column l%32
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int64_t j = j0 + 8 * (v / 4) + 4 * h + (v % 4);
+        if (j < n && l32 < R) macc += acc[v] * Bm[j * ldb + l32];
+      }
+    }
   }
-  if (half == 0) part[wv][r] = macc;
+
+  macc += __shfl_xor(macc, 32, 64);
+  if (h == 0) Mred[wave][l32] = macc;
   __syncthreads();
-  if (threadIdx.x < R) {
+  if (tid < R) {
     float s = 0.0f;
-    for (int q = 0; q < kBlock / 64; ++q) s += part[q][threadIdx.x];
-    M[i * ldm + threadIdx.x] = s;
+#pragma unroll
+    for (int q = 0; q < kWaves; ++q) s += Mred[q][tid];
+    M[i * ldm + tid] = s;
   }
 }
+
 }  // namespace
 
 extern "C" int dastac_tet_mttkrp_f32(int64_t n, int64_t R, const float *Ap, const float *B, int64_t ldb,
@@ -43,6 +186,6 @@ extern "C" int dastac_tet_mttkrp_f32(int64_t n, int64_t R, const float *Ap, cons
   if (overlaps(M, n * ldm * 4, Ap, tet(n) * 4) || overlaps(M, n * ldm * 4, B, n * ldb * 4) ||
       overlaps(M, n * ldm * 4, C, n * ldc * 4))
     return DASTAC_EALIAS;
-  mttkrp_simple_kernel<<<(unsigned)n, kBlock, 0, (hipStream_t)stream>>>(n, (int)R, Ap, B, ldb, C, ldc, M, ldm);
+  mttkrp_mfma_kernel<<<(unsigned)n, kBlock, 0, (hipStream_t)stream>>>(n, (int)R, Ap, B, ldb, C, ldc, M, ldm);
   return launch_status();
 }
