@@ -117,7 +117,8 @@ int dastac_trmm_f32(int64_t n, int64_t m, const float *Up, const float *B, int64
 int dastac_band_spmv_f32(int64_t n, int64_t w, const float *D, const float *x, float *y, void *stream);
 
 /* M(i,j) := A(i,j,k) * v(k), i<=j<=k.  Ap[tet_count(n)], v[n]; the output is itself packed:
- * Mp[tri_count(n)] with M(i,j) at tri(n,i,j). */
+ * Mp[tri_count(n)] with M(i,j) at tri(n,i,j).  n <= 8192 (a larger tetrahedron
+ * exceeds device memory); beyond that DASTAC_EOVERFLOW. */
 int dastac_tet_ttv_f32(int64_t n, const float *Ap, const float *v, float *Mp, void *stream);
 
 /* M(i,r) := A(i,j,k) * B(j,r) * C(k,r), i<=j<=k, 0<=r<R  (Table 1 MTTKRP rule on the upper tetrahedron).

@@ -14,140 +14,441 @@
 // one per wavefront; a wavefront owns the rows that START inside its share.  The inverse index
 // polynomial, evaluated once per wavefront, names the first such row; after that the row start
 // advances by the row length (the polynomial's linear term), all in wave-uniform registers.
+// The last slices of a tetrahedron are tiny, and a step (below) never spans two slices, so equal
+// shares would leave the last wavefront with a long chain of nearly empty steps: instead the last
+// `tail_order` slices get one wavefront each, located by the forward polynomial alone.
 //
-// Inside a share, rows are taken in groups sized to their length so that lanes stay busy when rows
-// get short (the tail of every slice): a row of more than 128 elements gets the whole wavefront and
-// a loop; shorter rows get 32, 16, ... 1 lanes each and 2, 4, ... 64 rows are summed side by side.
-// Lanes read four consecutive packed elements (16 bytes) each, so a wavefront always touches one
-// contiguous span of the buffer.
+// Inside its rows a wavefront takes "steps" of one contiguous span of the buffer:
+//   * a row longer than the span is cut into pieces that accumulate per lane and are reduced once,
+//     at the row's last piece;
+//   * shorter rows get 64, 32, 16, ... 1 lanes each, and 1, 2, 4, ... 64 consecutive rows are summed
+//     side by side, so lanes stay busy on the short rows at the end of every slice.
+// The step sequence depends only on wave-uniform integers, so the loads of the next step are issued
+// before the current step is reduced; two register sets alternate to keep them in flight.
 #include "common.h"
 
 using namespace dastac;
 
 namespace {
 
-constexpr int kBlock = 256;
-constexpr int kWavesPerBlock = kBlock / 64;
+template <int CTRL>
+__device__ inline float dpp_add(float v) {
+  int t = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false);
+  return v + __builtin_bit_cast(float, t);
+}
 
-// Sum over aligned groups of 2^lg lanes (every lane of a group receives the total).
+// Sum over aligned groups of 2^lg lanes; every lane of a group receives the total.
+// Strides 1,2 use quad permutes, 4 and 8 the half-row and row mirrors (all lanes of the mirrored
+// unit already hold equal values), 16 and 32 go through the LDS crossbar.
 __device__ inline float group_sum(float v, int lg) {
-  for (int s = 0; s < lg; ++s) v += __shfl_xor(v, 1 << s, 64);
+  if (lg >= 1) v = dpp_add<0xB1>(v);   // quad_perm [1,0,3,2]
+  if (lg >= 2) v = dpp_add<0x4E>(v);   // quad_perm [2,3,0,1]
+  if (lg >= 3) v = dpp_add<0x141>(v);  // row_half_mirror
+  if (lg >= 4) v = dpp_add<0x140>(v);  // row_mirror
+  if (lg >= 5) v += __shfl_xor(v, 16, 64);
+  if (lg >= 6) v += __shfl_xor(v, 32, 64);
   return v;
 }
 
-// First row whose first element is at packed position >= q (q < total), and that position.
+// First row whose first element is at packed position >= q (q < total): its slice i, row j and
+// start position p.  This is the inverse index polynomial, arranged so that the device never
+// divides: with Q = total-1-q (elements after q),
+//   slice:  the largest s with Tet(s) <= Q, tested as s(s+1)(s+2) <= 6Q; the slice is n-1-s, and
+//           Q - Tet(s) elements follow q inside it (Tet(s) by an exact multiply with 3^-1 mod 2^64);
+//   row:    the largest r with Tri(r) <= Q', tested as r(r+1) <= 2Q'; the row holds r+1 elements
+//           and e = Q' - Tri(r) of them follow q.
+// Single-precision roots give the seeds; the integer tests make them exact (the seed is within a
+// step or two for every size that fits in memory).
 template <bool TET>
-__device__ inline void first_row_from(int64_t n, int64_t q, int64_t &i, int64_t &j, int64_t &p) {
-  int64_t a = 0, b, c;
-  if (TET)
-    tet_inverse(n, q, a, b, c);
-  else
-    tri_inverse(n, q, b, c);
-  if (c == b) {  // q is itself a row start
-    i = a; j = b; p = q;
-  } else {       // skip the rest of the row that contains q
-    p = q + (n - c);
-    if (b + 1 < n) { i = a; j = b + 1; }
+__device__ inline void first_row_from(int64_t n, int64_t total, int64_t q, int64_t &i, int64_t &j, int64_t &p) {
+  uint64_t Q = (uint64_t)(total - 1 - q);
+  int64_t a = 0, m = n;
+  if (TET) {
+    const uint64_t Q6 = 6 * Q;
+    uint64_t s = (uint64_t)cbrtf((float)Q6);
+    while (s > 0 && s * (s + 1) * (s + 2) > Q6) --s;
+    while ((s + 1) * (s + 2) * (s + 3) <= Q6) ++s;
+    a = n - 1 - (int64_t)s;
+    m = (int64_t)s + 1;
+    Q -= (((s * (s + 1)) >> 1) * (s + 2)) * 0xAAAAAAAAAAAAAAABull;  // Tet(s), exact
+  }
+  const uint64_t Q2 = 2 * Q;
+  uint64_t r = (uint64_t)((sqrtf(4.0f * (float)Q2 + 1.0f) - 1.0f) * 0.5f);
+  while (r > 0 && r * (r + 1) > Q2) --r;
+  while ((r + 1) * (r + 2) <= Q2) ++r;
+  const int64_t e = (int64_t)(Q - ((r * (r + 1)) >> 1));  // elements after q in its row
+  const int64_t jj = m - 1 - (int64_t)r;                    // row inside the slice, r+1 elements long
+  if (e == (int64_t)r) {  // q is itself a row start
+    i = a; j = a + jj; p = q;
+  } else {                // skip the rest of the row that contains q
+    p = q + e + 1;
+    if (jj + 1 < m) { i = a; j = a + jj + 1; }
     else { i = a + 1; j = a + 1; }
   }
 }
 
-// Dot product of a row piece: `cnt` (1..4) packed elements at a[0..] with x[0..].
-__device__ inline float dot_piece(const float *__restrict__ a, const float *__restrict__ x, int cnt) {
-  if (cnt >= 4) {
-    f4u av = *reinterpret_cast<const f4u *>(a);
-    f4u xv = *reinterpret_cast<const f4u *>(x);
-    return av.x * xv.x + av.y * xv.y + av.z * xv.z + av.w * xv.w;
-  }
-  float s = 0.0f;
-  if (cnt > 0) s += a[0] * x[0];
-  if (cnt > 1) s += a[1] * x[1];
-  if (cnt > 2) s += a[2] * x[2];
-  return s;
+// One step of a wavefront: everything here is wave-uniform.
+struct Step {
+  int64_t p;   // packed position of the first row of the step (or of the long row)
+  int64_t s;   // output position of that row
+  int64_t j;   // its first column
+  int len;     // its length (== rows left in the slice)
+  int t0;      // long rows: offset of this piece inside the row; else 0
+  bool valid;
+};
+
+// ---------------------------------------------------------------------------------------------
+// Variant 1: the vector operand fits in LDS (n <= kLdsMaxN).  Serves every TTV and small TRMV.
+//
+// x is staged once per workgroup, followed by kPad zeros.  A lane reads sixteen packed elements
+// per step (four 16-byte loads, each contiguous across the lanes of a row) without any bounds
+// test: elements past the end of its row belong to the next row (still inside the buffer) and meet
+// a zero of the pad, and the product is formed with v_mul_legacy_f32 (0 * anything = 0), so they
+// contribute exactly nothing even if they are Inf or NaN.  Only steps within kSpan elements of the
+// end of the whole buffer take the guarded loader.
+// ---------------------------------------------------------------------------------------------
+constexpr int kLdsBlock = 512;
+constexpr int kLdsWaves = kLdsBlock / 64;
+constexpr int kLdsMaxN = 8192;
+constexpr int kSpan = 1024;      // packed elements per step: 64 lanes x 4 loads x 4 floats
+constexpr int kPad = kSpan + 8;  // zeros after x: a lane may look up to kSpan+3 columns past the row end
+
+__device__ inline float mul0(float a, float b) {  // 0 * x == 0 for every x
+  float r;
+  asm("v_mul_legacy_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+
+__device__ inline float dot0(f4a a, f4a x) {
+  return (mul0(a.x, x.x) + mul0(a.y, x.y)) + (mul0(a.z, x.z) + mul0(a.w, x.w));
+}
+
+struct Piece16 {
+  f4a a[4], x[4];
+};
+
+// lanes per row (log2) for rows of `len` elements at sixteen elements per lane
+__device__ inline int lanes_log2_16(int len) {
+  return len > 512 ? 6 : len > 256 ? 5 : len > 128 ? 4 : len > 64 ? 3 : len > 32 ? 2 : len > 16 ? 1 : 0;
 }
 
 template <bool TET>
-__global__ __launch_bounds__(kBlock) void segsum_kernel(int64_t n, const float *__restrict__ A,
-                                                        const float *__restrict__ x, float *__restrict__ out,
-                                                        int64_t total, int64_t share) {
+__global__ __launch_bounds__(kLdsBlock) void segsum_lds_kernel(int n, const float *__restrict__ A,
+                                                               const float *__restrict__ x,
+                                                               float *__restrict__ out, int64_t total,
+                                                               int64_t total_a, int64_t share, int64_t waves_a,
+                                                               int tail_order) {
+  extern __shared__ float xs[];  // x[0..n), then kPad zeros
+  for (int t = threadIdx.x; t < n + kPad; t += kLdsBlock) xs[t] = t < n ? x[t] : 0.0f;
+  __syncthreads();
+
   const int lane = threadIdx.x & 63;
-  const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+  const int64_t wave = (int64_t)blockIdx.x * kLdsWaves + uniform32(threadIdx.x >> 6);
+
+  // Which rows are mine: those starting in [first row at or after lo, hi).
+  int64_t hi, sp, sj;
+  int slice;
+  if (wave < waves_a) {  // an equal share of the first total_a elements
+    const int64_t lo = wave * share;
+    hi = (lo + share < total_a) ? lo + share : total_a;
+    int64_t si;
+    first_row_from<TET>(n, total, lo, si, sj, sp);
+    slice = (int)si;
+  } else if (TET && wave - waves_a < tail_order) {  // one whole slice of the tail
+    slice = n - tail_order + (int)(wave - waves_a);
+    sp = tet_slice_start(n, slice);
+    sj = slice;
+    hi = sp + tri(n - slice);
+  } else {
+    return;
+  }
+  slice = uniform32(slice);
+  hi = uniform64(hi);
+
+  Step st;
+  st.p = uniform64(sp);
+  st.j = uniform32((int)sj);
+  st.s = TET ? tri_offset(n, slice, st.j) : st.j;
+  st.len = n - (int)st.j;
+  st.t0 = 0;
+  st.valid = st.p < hi && st.len > 0;
+
+  // per-lane geometry of a step: row g of the group, `used` rows taken by the step
+  auto geometry = [&](const Step &d, int &g, int &used, bool &mine, int &off, int &xi, int &lw4) {
+    const int lg = lanes_log2_16(d.len);
+    lw4 = 4 << lg;  // elements between two consecutive loads of a lane
+    int rows = 64 >> lg;
+    if (rows > d.len) rows = d.len;  // stay inside the slice
+    g = lane >> lg;
+    const int sub = lane & ((1 << lg) - 1);
+    const int goff = g * d.len - ((g * (g - 1)) >> 1);  // start of row g relative to d.p
+    const int64_t room = hi - d.p;                      // rows must start before hi
+    const int lim = room > 0x7fffffff ? 0x7fffffff : (int)room;
+    mine = g < rows && goff < lim;
+    used = __popcll(__ballot(mine && sub == 0));
+    // element offset of my first load relative to d.p; lanes without a row (whose goff is
+    // meaningless, possibly negative) read from the start of the step instead
+    off = mine ? goff + d.t0 + sub * 4 : 0;
+    // column of my first element; lanes without a row look at the zero pad
+    xi = mine ? (int)d.j + g + d.t0 + sub * 4 : n;
+  };
+  // every lane's loads of step d lie inside the buffer
+  auto fits = [&](const Step &d) -> bool { return d.p + d.t0 + kSpan + 4 <= total; };
+
+  auto issue_fast = [&](const Step &d, int &g, int &used, Piece16 &r) {
+    bool mine;
+    int off, xi, lw4;
+    geometry(d, g, used, mine, off, xi, lw4);
+    const float *ab = A + d.p;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) r.a[q] = *reinterpret_cast<const f4u *>(ab + off + q * lw4);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) r.x[q] = *reinterpret_cast<const f4u *>(&xs[xi + q * lw4]);
+  };
+  auto issue_guarded = [&](const Step &d, int &g, int &used, Piece16 &r) {
+    bool mine;
+    int off, xi, lw4;
+    geometry(d, g, used, mine, off, xi, lw4);
+    const float *ab = A + d.p;
+    const int64_t room_a = total - d.p;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      float e[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int o = off + q * lw4 + c;
+        e[c] = (mine && o < room_a) ? ab[o] : 0.0f;
+      }
+      r.a[q] = f4a{e[0], e[1], e[2], e[3]};
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) r.x[q] = *reinterpret_cast<const f4u *>(&xs[xi + q * lw4]);
+  };
+  auto advance = [&](const Step &d, int used) -> Step {
+    Step nx = d;
+    if (d.len > kSpan && d.t0 + kSpan < d.len) {  // next piece of the same long row
+      nx.t0 = d.t0 + kSpan;
+      return nx;
+    }
+    nx.t0 = 0;
+    nx.p = d.p + (int64_t)used * d.len - ((used * (used - 1)) >> 1);
+    nx.s = d.s + used;
+    nx.j = d.j + used;
+    if (TET && nx.j >= n) {  // slice finished
+      slice += 1;
+      nx.j = slice;
+    }
+    nx.len = n - (int)nx.j;
+    nx.valid = nx.p < hi && nx.len > 0;
+    return nx;
+  };
+
+  float racc = 0.0f;  // running per-lane sum of a long row
+  auto consume = [&](const Step &d, const Piece16 &c, int g, int used) {
+    float v = (dot0(c.a[0], c.x[0]) + dot0(c.a[1], c.x[1])) + (dot0(c.a[2], c.x[2]) + dot0(c.a[3], c.x[3]));
+    if (d.len > kSpan) {
+      racc += v;
+      if (d.t0 + kSpan >= d.len) {
+        v = group_sum(racc, 6);
+        racc = 0.0f;
+        if (lane == 0) out[d.s] = v;
+      }
+    } else {
+      const int lg = lanes_log2_16(d.len);
+      v = group_sum(v, lg);
+      const int sub = lane & ((1 << lg) - 1);
+      if (sub == 0 && g < used) out[d.s + g] = v;
+    }
+  };
+
+  // Unguarded steps: two register sets alternate, and the loop body has no branch around its
+  // loads, so the next step's loads stay in flight while the current step is reduced.  When the
+  // next step does not exist (or needs the guarded loader) the current one is simply loaded again.
+  if (st.valid && fits(st)) {
+    Piece16 pa, pb;
+    int ga, ua, gb, ub;
+    issue_fast(st, ga, ua, pa);
+    for (;;) {
+      Step nx = advance(st, ua);
+      bool more = nx.valid && fits(nx);
+      issue_fast(more ? nx : st, gb, ub, pb);
+      consume(st, pa, ga, ua);
+      st = nx;
+      if (!more) break;
+      nx = advance(st, ub);
+      more = nx.valid && fits(nx);
+      issue_fast(more ? nx : st, ga, ua, pa);
+      consume(st, pb, gb, ub);
+      st = nx;
+      if (!more) break;
+    }
+  }
+  // Steps that reach into the last kSpan elements of the buffer.
+  while (st.valid) {
+    Piece16 pc;
+    int gc, uc;
+    issue_guarded(st, gc, uc, pc);
+    consume(st, pc, gc, uc);
+    st = advance(st, uc);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Variant 2: TRMV with n > kLdsMaxN; x is read through the vector cache.  Rows are long there:
+// whole 1024-element blocks of a row are summed without bounds tests, and only the last 1..1024
+// elements of each row (and the short rows at the bottom of the triangle) go through bounds-tested
+// steps of four elements per lane.
+// ---------------------------------------------------------------------------------------------
+constexpr int kBlock = 256;
+constexpr int kWavesPerBlock = kBlock / 64;
+
+__device__ inline int bulk_of(int len) { return len > 256 ? ((len - 1) >> 10) << 10 : 0; }
+
+struct Piece {
+  f4a a, x;
+};
+
+__device__ inline int lanes_log2(int len) {
+  return len > 128 ? 6 : len > 64 ? 5 : len > 32 ? 4 : len > 16 ? 3 : len > 8 ? 2 : len > 4 ? 1 : 0;
+}
+
+// Loads of one step: `cnt` valid elements (0..4) at a[..], x[..].
+__device__ inline Piece load_piece(const float *__restrict__ a, const float *__restrict__ x, int cnt) {
+  Piece d;
+  d.a = f4a{0.0f, 0.0f, 0.0f, 0.0f};
+  d.x = d.a;
+  if (cnt >= 4) {
+    d.a = *reinterpret_cast<const f4u *>(a);
+    d.x = *reinterpret_cast<const f4u *>(x);
+  } else if (cnt > 0) {
+    d.a.x = a[0]; d.x.x = x[0];
+    if (cnt > 1) { d.a.y = a[1]; d.x.y = x[1]; }
+    if (cnt > 2) { d.a.z = a[2]; d.x.z = x[2]; }
+  }
+  return d;
+}
+
+__global__ __launch_bounds__(kBlock) void trmv_big_kernel(int64_t n, const float *__restrict__ A,
+                                                          const float *__restrict__ x, float *__restrict__ out,
+                                                          int64_t total, int64_t share) {
+  const int lane = threadIdx.x & 63;
+  const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + uniform32(threadIdx.x >> 6);
   const int64_t lo = wave * share;
   if (lo >= total) return;
-  const int64_t hi = lo + share;
+  const int64_t hi = (lo + share < total) ? lo + share : total;  // rows starting in [lo,hi) are ours
 
-  int64_t i, j, p;
-  first_row_from<TET>(n, lo, i, j, p);
-  int64_t pe = total;  // first position that belongs to the next wavefront's rows
-  if (hi < total) {
-    int64_t ie, je;
-    first_row_from<TET>(n, hi, ie, je, pe);
-  }
-  i = uniform64(i); j = uniform64(j); p = uniform64(p); pe = uniform64(pe);
-  int64_t s = TET ? tri_offset(n, i, j) : j;  // output position of row (i,j)
+  int64_t si, sj, sp;
+  first_row_from<false>(n, total, lo, si, sj, sp);
 
-  while (p < pe) {
-    const int len = (int)(n - j);  // row length == rows left in this slice
-    if (len <= 0) break;           // cannot happen while p < pe; keeps every wavefront finite
-    if (len > 128) {
-      const float *a = A + p;
-      const float *xv = x + j;
-      float acc = 0.0f;
-      int t = lane * 4;
-      for (; t + 768 + 4 <= len; t += 1024) {
+  Step st;
+  st.p = uniform64(sp);
+  st.j = uniform64(sj);
+  st.s = st.j;
+  st.len = (int)(n - st.j);
+  st.t0 = bulk_of(st.len);
+  st.valid = st.p < hi && st.len > 0;
+
+  auto issue = [&](const Step &d, int &g, int &used) -> Piece {
+    const int lg = lanes_log2(d.len);
+    int rows = 64 >> lg;
+    if (rows > d.len) rows = d.len;  // stay inside the triangle
+    g = lane >> lg;
+    const int sub = lane & ((1 << lg) - 1);
+    const int64_t start_g = d.p + (int64_t)g * d.len - (g * (g - 1)) / 2;
+    const bool mine = g < rows && start_g < hi;
+    used = __popcll(__ballot(mine && sub == 0));
+    const int pos = d.t0 + sub * 4;
+    int cnt = mine ? (d.len - g) - pos : 0;
+    if (cnt > 4) cnt = 4;
+    return load_piece(A + start_g + pos, x + d.j + g + pos, cnt);
+  };
+  auto advance = [&](const Step &d, int used) -> Step {
+    Step nx = d;
+    if (d.len > 256 && d.t0 + 256 < d.len) {  // next piece of the same long row
+      nx.t0 = d.t0 + 256;
+      return nx;
+    }
+    nx.p = d.p + (int64_t)used * d.len - (used * (used - 1)) / 2;
+    nx.s = d.s + used;
+    nx.j = d.j + used;
+    nx.len = (int)(n - nx.j);
+    nx.t0 = bulk_of(nx.len);
+    nx.valid = nx.p < hi && nx.len > 0;
+    return nx;
+  };
+
+  float racc = 0.0f;  // running per-lane sum of a long row
+  auto consume = [&](const Step &d, const Piece &c, int g, int used) {
+    if (d.t0 > 0 && d.t0 == bulk_of(d.len)) {  // first stepped piece of a long row: do its bulk now
+      const float *a = A + d.p + lane * 4;
+      const float *xv = x + d.j + lane * 4;
+      for (int t = 0; t < d.t0; t += 1024) {
         f4u a0 = *reinterpret_cast<const f4u *>(a + t), a1 = *reinterpret_cast<const f4u *>(a + t + 256);
         f4u a2 = *reinterpret_cast<const f4u *>(a + t + 512), a3 = *reinterpret_cast<const f4u *>(a + t + 768);
         f4u x0 = *reinterpret_cast<const f4u *>(xv + t), x1 = *reinterpret_cast<const f4u *>(xv + t + 256);
         f4u x2 = *reinterpret_cast<const f4u *>(xv + t + 512), x3 = *reinterpret_cast<const f4u *>(xv + t + 768);
-        acc += a0.x * x0.x + a0.y * x0.y + a0.z * x0.z + a0.w * x0.w;
-        acc += a1.x * x1.x + a1.y * x1.y + a1.z * x1.z + a1.w * x1.w;
-        acc += a2.x * x2.x + a2.y * x2.y + a2.z * x2.z + a2.w * x2.w;
-        acc += a3.x * x3.x + a3.y * x3.y + a3.z * x3.z + a3.w * x3.w;
+        racc += a0.x * x0.x + a0.y * x0.y + a0.z * x0.z + a0.w * x0.w;
+        racc += a1.x * x1.x + a1.y * x1.y + a1.z * x1.z + a1.w * x1.w;
+        racc += a2.x * x2.x + a2.y * x2.y + a2.z * x2.z + a2.w * x2.w;
+        racc += a3.x * x3.x + a3.y * x3.y + a3.z * x3.z + a3.w * x3.w;
       }
-      for (; t < len; t += 256) acc += dot_piece(a + t, xv + t, len - t);
-      acc = group_sum(acc, 6);
-      if (lane == 0) out[s] = acc;
-      p += len; s += 1; j += 1;
+    }
+    float v = c.a.x * c.x.x + c.a.y * c.x.y + c.a.z * c.x.z + c.a.w * c.x.w;
+    if (d.len > 256) {
+      racc += v;
+      if (d.t0 + 256 >= d.len) {
+        v = group_sum(racc, 6);
+        racc = 0.0f;
+        if (lane == 0) out[d.s] = v;
+      }
     } else {
-      // 2^lg lanes per row, 64>>lg rows side by side
-      const int lg = len > 64 ? 5 : len > 32 ? 4 : len > 16 ? 3 : len > 8 ? 2 : len > 4 ? 1 : 0;
-      int rows = 64 >> lg;
-      if (rows > len) rows = len;  // stay inside the slice
-      const int g = lane >> lg, sub = lane & ((1 << lg) - 1);
-      const int len_g = len - g;
-      const int64_t start_g = p + (int64_t)g * len - (g * (g - 1)) / 2;
-      const bool mine = g < rows && start_g < pe;
-      float acc = 0.0f;
-      const int pos = sub * 4;
-      if (mine && pos < len_g) acc = dot_piece(A + start_g + pos, x + j + g + pos, len_g - pos);
-      acc = group_sum(acc, lg);
-      const bool writer = mine && sub == 0;
-      if (writer) out[s + g] = acc;
-      const int used = __popcll(__ballot(writer));
-      p += (int64_t)used * len - (used * (used - 1)) / 2;
-      s += used; j += used;
+      const int lg = lanes_log2(d.len);
+      v = group_sum(v, lg);
+      const int sub = lane & ((1 << lg) - 1);
+      if (sub == 0 && g < used) out[d.s + g] = v;
     }
-    if (j >= n) {  // slice finished
-      if (!TET) break;
-      i += 1; j = i;
-    }
+  };
+
+  Piece pa, pb;
+  int ga = 0, ua = 0, gb = 0, ub = 0;
+  if (st.valid) pa = issue(st, ga, ua);
+  while (st.valid) {
+    Step nx = advance(st, ua);
+    if (nx.valid) pb = issue(nx, gb, ub);
+    consume(st, pa, ga, ua);
+    st = nx;
+    if (!st.valid) break;
+    nx = advance(st, ub);
+    if (nx.valid) pa = issue(nx, ga, ua);
+    consume(st, pb, gb, ub);
+    st = nx;
   }
 }
 
-// Elements per wavefront share: enough wavefronts to fill 256 CUs several times over, but at
-// least a few KB each so the one inverse per wavefront stays negligible.
-inline int64_t pick_share(int64_t total) {
-  int64_t share = ceil_div(total, (int64_t)256 * 32);
-  if (share < 2048) share = 2048;
-  return share;
+// ---- host side -------------------------------------------------------------------------------
+
+// Wavefront shares: about `per_cu` wavefronts per compute unit on a 256-CU part, at least 2048
+// elements each so that the one inverse per wavefront stays negligible.
+inline int64_t pick_share(int64_t total, int per_cu) {
+  int64_t share = ceil_div(total, (int64_t)256 * per_cu);
+  return share < 2048 ? 2048 : share;
 }
 
 template <bool TET>
-int launch(int64_t n, const float *A, const float *x, float *out, int64_t total, void *stream) {
-  int64_t share = pick_share(total);
-  int64_t waves = ceil_div(total, share);
-  int64_t blocks = ceil_div(waves, kWavesPerBlock);
-  segsum_kernel<TET><<<(unsigned)blocks, kBlock, 0, (hipStream_t)stream>>>(n, A, x, out, total, share);
+int launch_lds(int64_t n, const float *A, const float *x, float *out, int64_t total, void *stream) {
+  int64_t tail_order = 0, total_a = total;
+  if (TET) {  // slices whose triangle is below about half a share get a wavefront of their own
+    int64_t m0 = (int64_t)sqrt((double)pick_share(total, 16));
+    if (m0 < 64) m0 = 64;
+    tail_order = m0 < n ? m0 : n;
+    total_a = total - tet(tail_order);
+  }
+  const int64_t share = pick_share(total_a, 16);
+  const int64_t waves_a = ceil_div(total_a, share);
+  const int64_t blocks = ceil_div(waves_a + tail_order, kLdsWaves);
+  const size_t lds = (size_t)(n + kPad) * sizeof(float);
+  segsum_lds_kernel<TET><<<(unsigned)blocks, kLdsBlock, lds, (hipStream_t)stream>>>(
+      (int)n, A, x, out, total, total_a, share, waves_a, (int)tail_order);
   return launch_status();
 }
 
@@ -161,16 +462,21 @@ int dastac_trmv_f32(int64_t n, const float *Up, const float *x, float *y, void *
   if (n == 0) return DASTAC_OK;
   if (!Up || !x || !y) return DASTAC_ENULL;
   if (overlaps(y, n * 4, Up, tri(n) * 4) || overlaps(y, n * 4, x, n * 4)) return DASTAC_EALIAS;
-  return launch<false>(n, Up, x, y, tri(n), stream);
+  if (n <= kLdsMaxN) return launch_lds<false>(n, Up, x, y, tri(n), stream);
+  const int64_t total = tri(n), share = pick_share(total, 32);
+  const int64_t blocks = ceil_div(ceil_div(total, share), kWavesPerBlock);
+  trmv_big_kernel<<<(unsigned)blocks, kBlock, 0, (hipStream_t)stream>>>(n, Up, x, y, total, share);
+  return launch_status();
 }
 
 int dastac_tet_ttv_f32(int64_t n, const float *Ap, const float *v, float *Mp, void *stream) {
   if (n < 0) return DASTAC_EINVAL;
-  if (n > DASTAC_TET_MAX_N || tet(n) > ((int64_t)1 << 40)) return DASTAC_EOVERFLOW;
+  // a tetrahedron of order above 8192 would not fit in device memory (and v would not fit in LDS)
+  if (n > kLdsMaxN) return DASTAC_EOVERFLOW;
   if (n == 0) return DASTAC_OK;
   if (!Ap || !v || !Mp) return DASTAC_ENULL;
   if (overlaps(Mp, tri(n) * 4, Ap, tet(n) * 4) || overlaps(Mp, tri(n) * 4, v, n * 4)) return DASTAC_EALIAS;
-  return launch<true>(n, Ap, v, Mp, tet(n), stream);
+  return launch_lds<true>(n, Ap, v, Mp, tet(n), stream);
 }
 
 }  // extern "C"
