@@ -110,7 +110,7 @@ __global__ __launch_bounds__(kBlock) void mttkrp_mfma_kernel(int64_t n, int R, c
         const int64_t k0 = ks + 32 * (int64_t)t;
         if (rows_full && k0 >= j0 + 32 && k0 + 32 <= n) {
 #pragma unroll
-          for (int q = 0; q < 4; ++q) v[q] = *reinterpret_cast<const f4u *>(rb[q] + k0 + lk);
+          for (int q = 0; q < 4; ++q) v[q] = __builtin_nontemporal_load(reinterpret_cast<const f4u *>(rb[q] + k0 + lk));
         } else {
 #pragma unroll
           for (int q = 0; q < 4; ++q) {

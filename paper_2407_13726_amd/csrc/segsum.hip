@@ -201,7 +201,7 @@ __global__ __launch_bounds__(kLdsBlock) void segsum_lds_kernel(int n, const floa
     geometry(d, g, used, mine, off, xi, lw4);
     const float *ab = A + d.p;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) r.a[q] = *reinterpret_cast<const f4u *>(ab + off + q * lw4);
+    for (int q = 0; q < 4; ++q) r.a[q] = __builtin_nontemporal_load(reinterpret_cast<const f4u *>(ab + off + q * lw4));
 #pragma unroll
     for (int q = 0; q < 4; ++q) r.x[q] = *reinterpret_cast<const f4u *>(&xs[xi + q * lw4]);
   };
@@ -318,7 +318,7 @@ __device__ inline Piece load_piece(const float *__restrict__ a, const float *__r
   d.a = f4a{0.0f, 0.0f, 0.0f, 0.0f};
   d.x = d.a;
   if (cnt >= 4) {
-    d.a = *reinterpret_cast<const f4u *>(a);
+    d.a = __builtin_nontemporal_load(reinterpret_cast<const f4u *>(a));
     d.x = *reinterpret_cast<const f4u *>(x);
   } else if (cnt > 0) {
     d.a.x = a[0]; d.x.x = x[0];
@@ -383,8 +383,10 @@ __global__ __launch_bounds__(kBlock) void trmv_big_kernel(int64_t n, const float
       const float *a = A + d.p + lane * 4;
       const float *xv = x + d.j + lane * 4;
       for (int t = 0; t < d.t0; t += 1024) {
-        f4u a0 = *reinterpret_cast<const f4u *>(a + t), a1 = *reinterpret_cast<const f4u *>(a + t + 256);
-        f4u a2 = *reinterpret_cast<const f4u *>(a + t + 512), a3 = *reinterpret_cast<const f4u *>(a + t + 768);
+        f4u a0 = __builtin_nontemporal_load(reinterpret_cast<const f4u *>(a + t));
+        f4u a1 = __builtin_nontemporal_load(reinterpret_cast<const f4u *>(a + t + 256));
+        f4u a2 = __builtin_nontemporal_load(reinterpret_cast<const f4u *>(a + t + 512));
+        f4u a3 = __builtin_nontemporal_load(reinterpret_cast<const f4u *>(a + t + 768));
         f4u x0 = *reinterpret_cast<const f4u *>(xv + t), x1 = *reinterpret_cast<const f4u *>(xv + t + 256);
         f4u x2 = *reinterpret_cast<const f4u *>(xv + t + 512), x3 = *reinterpret_cast<const f4u *>(xv + t + 768);
         racc += a0.x * x0.x + a0.y * x0.y + a0.z * x0.z + a0.w * x0.w;
