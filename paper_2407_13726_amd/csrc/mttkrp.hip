@@ -39,7 +39,7 @@ __device__ inline void wave_sync_lds() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-__global__ __launch_bounds__(kBlock) void mttkrp_mfma_kernel(int64_t n, int R, const float *__restrict__ A,
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4, 4))) void mttkrp_mfma_kernel(int64_t n, int R, const float *__restrict__ A,
                                                              const float *__restrict__ Bm, int64_t ldb,
                                                              const float *__restrict__ Cm, int64_t ldc,
                                                              float *__restrict__ M, int64_t ldm) {
@@ -106,23 +106,33 @@ __global__ __launch_bounds__(kBlock) void mttkrp_mfma_kernel(int64_t n, int R, c
         rb[q] = A + slice0 + tri_row_start(m, jj) - j;
       }
 
-      auto load_tile = [&](int t, f4a (&v)[4]) {
+      // Guarded loader for tiles cut by the diagonal or by the ragged end of the rows.
+      auto load_guarded = [&](int t, f4a (&v)[4]) {
         const int64_t k0 = ks + 32 * (int64_t)t;
-        if (rows_full && k0 >= j0 + 32 && k0 + 32 <= n) {
 #pragma unroll
-          for (int q = 0; q < 4; ++q) v[q] = __builtin_nontemporal_load(reinterpret_cast<const f4u *>(rb[q] + k0 + lk));
-        } else {
+        for (int q = 0; q < 4; ++q) {
+          const int64_t j = j0 + lr + 8 * q;
+          float e[4];
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const int64_t j = j0 + lr + 8 * q;
-            float e[4];
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-              const int64_t k = k0 + lk + s;
-              e[s] = (j < n && k >= j && k < n) ? rb[q][k] : 0.0f;
-            }
-            v[q] = f4a{e[0], e[1], e[2], e[3]};
+          for (int s = 0; s < 4; ++s) {
+            const int64_t k = k0 + lk + s;
+            e[s] = (j < n && k >= j && k < n) ? rb[q][k] : 0.0f;
           }
+          v[q] = f4a{e[0], e[1], e[2], e[3]};
+        }
+      };
+      // Branch-free loader for interior tiles; a tile index at or past `fe` loads a harmless dummy
+      // address instead, so that the loop below has no control flow around its loads and the
+      // compiler can leave them in flight across iterations.  Plain (cached) loads: the 128-byte
+      // row pieces are not aligned to cache lines, and the next piece of the same row, requested
+      // right behind, uses the other half of the shared line.
+      const float *dummy = A + slice0;
+      auto load_fast = [&](int t, int fe, f4a (&v)[4]) {
+        const int64_t k0 = ks + 32 * (int64_t)t;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const float *src = (t < fe) ? rb[q] + k0 + lk : dummy;
+          v[q] = *reinterpret_cast<const f4u *>(src);
         }
       };
 
@@ -130,12 +140,10 @@ __global__ __launch_bounds__(kBlock) void mttkrp_mfma_kernel(int64_t n, int R, c
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 
-      f4a cur[4], nxt[4];
-      load_tile(0, cur);
-      for (int t = 0; t < ntiles; ++t) {
-        if (t + 1 < ntiles) load_tile(t + 1, nxt);
+      // one 32x32 tile: registers -> private LDS tile -> matrix-core operand layout -> 16 MFMAs
+      auto compute = [&](int t, const f4a (&v)[4]) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) *reinterpret_cast<f4a *>(&tile[(lr + 8 * q) * kTP + lk]) = cur[q];
+        for (int q = 0; q < 4; ++q) *reinterpret_cast<f4a *>(&tile[(lr + 8 * q) * kTP + lk]) = v[q];
         wave_sync_lds();  // the tile is private to this wavefront: no workgroup barrier needed
         const float *cs = &Cs[(int)(ks - kp0 + 32 * t + 4 * h) * 32 + l32];
 #pragma unroll
@@ -149,10 +157,40 @@ __global__ __launch_bounds__(kBlock) void mttkrp_mfma_kernel(int64_t n, int R, c
           acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, c3, acc, 0, 0, 0);
         }
         wave_sync_lds();  // all lanes have read the tile before the next one overwrites it
-        if (t + 1 < ntiles) {
-#pragma unroll
-          for (int q = 0; q < 4; ++q) cur[q] = nxt[q];
+      };
+
+      // Tiles [fb, fe) need no predicates: not on the diagonal, all 32 rows exist, all 32 k exist.
+      int fb = 0, fe = ntiles;
+      if (!rows_full) {
+        fe = 0;
+      } else {
+        if (ks < j0 + 32) fb = 1;                      // the first tile straddles the diagonal
+        if (ks + 32 * (int64_t)ntiles > n) fe -= 1;    // the last tile runs past n
+        if (fe < fb) fe = fb;
+      }
+      f4a s0[4], s1[4], s2[4];
+      if (fb < fe) {  // three register sets rotate; two tiles are always in flight
+        load_fast(fb, fe, s0);
+        load_fast(fb + 1, fe, s1);
+        for (int t = fb;; t += 3) {
+          load_fast(t + 2, fe, s2);
+          compute(t, s0);
+          if (t + 1 >= fe) break;
+          load_fast(t + 3, fe, s0);
+          compute(t + 1, s1);
+          if (t + 2 >= fe) break;
+          load_fast(t + 4, fe, s1);
+          compute(t + 2, s2);
+          if (t + 3 >= fe) break;
         }
+      }
+      if (fb == 1) {  // the diagonal tile
+        load_guarded(0, s0);
+        compute(0, s0);
+      }
+      for (int t = (fe > fb ? fe : fb); t < ntiles; ++t) {  // the ragged last tile, or all tiles of a ragged row block
+        load_guarded(t, s0);
+        compute(t, s0);
       }
 
       // fold the 32x32 block of T with B: register v of lane l is row 8*(v/4)+4*(l/32)+v%4, column l%32

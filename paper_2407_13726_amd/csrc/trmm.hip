@@ -132,8 +132,9 @@ __global__ __launch_bounds__(kBlock) void trmm_mfma_kernel(int64_t n, int64_t m,
     store_stage(0, st);
     __syncthreads();
 
-    for (int kt = 0; kt < nk; ++kt) {
-      const int buf = kt & 1;
+    // One k-step on LDS buffer `buf` (a literal at both call sites, so every LDS address below is
+    // a compile-time offset), with the global loads of the next step in flight meanwhile.
+    auto step = [&](int kt, int buf) {
       if (kt + 1 < nk) load_stage(kt + 1, st);
       // rows i0+32.. have nothing at or right of the diagonal in the first k-step
       if (!(kt == 0 && wr == 1)) {
@@ -160,6 +161,10 @@ __global__ __launch_bounds__(kBlock) void trmm_mfma_kernel(int64_t n, int64_t m,
       }
       if (kt + 1 < nk) store_stage(buf ^ 1, st);
       __syncthreads();
+    };
+    for (int kt = 0; kt < nk; kt += 2) {
+      step(kt, 0);
+      if (kt + 1 < nk) step(kt + 1, 1);
     }
 
     // D layout of the 32x32 tile: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32
