@@ -5,11 +5,11 @@
 // The rule is Table 1's SpMV_UT with a matrix right-hand side; U keeps the packed layout of
 // Section 4 (row i holds k=i..n-1 contiguously, starting at tri_row_start(n,i)).
 //
-// Tiling.  A workgroup (4 wavefronts) owns a 64-row x 128-column tile of C and sweeps k from the
+// Tiling.  A workgroup (8 wavefronts) owns a 64-row x 128-column tile of C and sweeps k from the
 // diagonal of its row block to n in steps of 32.  Per step the 64x32 tile of U (each packed row
 // piece is 128 contiguous bytes, at its own 4-byte-aligned offset) and the 32x128 tile of B are
 // staged in LDS, double-buffered against the global loads of the next step.  Each wavefront
-// computes a 32x64 sub-tile with v_mfma_f32_32x32x2_f32: lanes 0-31 feed k, lanes 32-63 feed k+1.
+// computes a 32x32 sub-tile with v_mfma_f32_32x32x2_f32: lanes 0-31 feed k, lanes 32-63 feed k+1.
 // Because a sum over k may be taken in any order, lane half h is given the four consecutive k
 // values 8t+4h..8t+4h+3 of every group of eight, so its U operand is one 16-byte LDS read.
 //
@@ -30,13 +30,13 @@ constexpr int kBM = 64;    // rows of C per workgroup tile
 constexpr int kBN = 128;   // columns of C per workgroup tile
 constexpr int kKT = 32;    // k-step
 constexpr int kUP = kKT + 4;  // LDS pitch of the U tile (floats): 16-byte reads of 8 lanes cover all banks
-constexpr int kBlock = 256;
+constexpr int kBlock = 512;
 
 typedef float f16v __attribute__((ext_vector_type(16)));
 
 struct Stage {
-  f4a u[2];  // U: rows r and r+32 of the tile, four k values each
-  f4a b[4];  // B: k rows kr, kr+8, kr+16, kr+24, four columns each
+  f4a u;     // U: row ur of the tile, four k values
+  f4a b[2];  // B: k rows bk and bk+16, four columns each
 };
 
 __global__ __launch_bounds__(kBlock) void trmm_mfma_kernel(int64_t n, int64_t m, const float *__restrict__ U,
@@ -54,12 +54,12 @@ __global__ __launch_bounds__(kBlock) void trmm_mfma_kernel(int64_t n, int64_t m,
   if (pair >= npairs) return;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wr = wave >> 1, wc = wave & 1;  // 2x2 wavefronts: 32 rows x 64 columns each
+  const int wr = wave >> 2, wc = wave & 3;  // 2x4 wavefronts: 32 rows x 32 columns each
   const int l32 = lane & 31, h = lane >> 5;
 
   // staging roles
-  const int ur = tid >> 3, uk = (tid & 7) * 4;     // U: row ur (+32), k offset uk
-  const int bk = tid >> 5, bc = (tid & 31) * 4;    // B: k row bk (+8,16,24), column offset bc
+  const int ur = tid >> 3, uk = (tid & 7) * 4;     // U: row ur, k offset uk
+  const int bk = tid >> 5, bc = (tid & 31) * 4;    // B: k row bk (+16), column offset bc
   const int64_t col0 = (int64_t)cb * kBN;
   const bool cols_full = col0 + kBN <= m;
 
@@ -71,41 +71,32 @@ __global__ __launch_bounds__(kBlock) void trmm_mfma_kernel(int64_t n, int64_t m,
     const int nk = (int)ceil_div(n - i0, kKT);
 
     // per-thread packed row bases: element (i,k) of U is at ubase[i] + k
-    const float *ub[2];
-    bool urow_ok[2];
-    for (int q = 0; q < 2; ++q) {
-      int64_t i = i0 + ur + 32 * q;
-      urow_ok[q] = i < n;
-      ub[q] = U + (urow_ok[q] ? tri_row_start(n, i) - i : 0);
-    }
+    const int64_t iu = i0 + ur;
+    const bool urow_ok = iu < n;
+    const float *ub = U + (urow_ok ? tri_row_start(n, iu) - iu : 0);
 
     auto load_stage = [&](int kt, Stage &s) {
       const int64_t k0 = i0 + (int64_t)kt * kKT;
       const bool k_full = k0 + kKT <= n;
       if (kt >= 2 && k_full && rows_full) {
-#pragma unroll
-        for (int q = 0; q < 2; ++q) s.u[q] = *reinterpret_cast<const f4u *>(ub[q] + k0 + uk);
+        s.u = *reinterpret_cast<const f4u *>(ub + k0 + uk);
       } else {
+        float v[4];
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
-          const int64_t i = i0 + ur + 32 * q;
-          float v[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int64_t k = k0 + uk + e;
-            v[e] = (urow_ok[q] && k >= i && k < n) ? ub[q][k] : 0.0f;
-          }
-          s.u[q] = f4a{v[0], v[1], v[2], v[3]};
+        for (int e = 0; e < 4; ++e) {
+          const int64_t k = k0 + uk + e;
+          v[e] = (urow_ok && k >= iu && k < n) ? ub[k] : 0.0f;
         }
+        s.u = f4a{v[0], v[1], v[2], v[3]};
       }
       if (k_full && cols_full) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-          s.b[q] = *reinterpret_cast<const f4u *>(B + (k0 + bk + 8 * q) * ldb + col0 + bc);
+        for (int q = 0; q < 2; ++q)
+          s.b[q] = *reinterpret_cast<const f4u *>(B + (k0 + bk + 16 * q) * ldb + col0 + bc);
       } else {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int64_t k = k0 + bk + 8 * q;
+        for (int q = 0; q < 2; ++q) {
+          const int64_t k = k0 + bk + 16 * q;
           float v[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) v[e] = (k < n && col0 + bc + e < m) ? B[k * ldb + col0 + bc + e] : 0.0f;
@@ -114,68 +105,73 @@ __global__ __launch_bounds__(kBlock) void trmm_mfma_kernel(int64_t n, int64_t m,
       }
     };
     auto store_stage = [&](int buf, const Stage &s) {
+      *reinterpret_cast<f4a *>(&Us[buf][ur * kUP + uk]) = s.u;
 #pragma unroll
-      for (int q = 0; q < 2; ++q) *reinterpret_cast<f4a *>(&Us[buf][(ur + 32 * q) * kUP + uk]) = s.u[q];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) *reinterpret_cast<f4a *>(&Bs[buf][(bk + 8 * q) * kBN + bc]) = s.b[q];
+      for (int q = 0; q < 2; ++q) *reinterpret_cast<f4a *>(&Bs[buf][(bk + 16 * q) * kBN + bc]) = s.b[q];
     };
 
-    f16v acc[2];
+    f16v acc;
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+
+    // Operands of one group of eight k values: four MFMA steps on the wavefront's 32x32 sub-tile.
+    struct Ops {
+      f4a a;
+      float b0[4];
+    };
+    auto read_ops = [&](int buf, int t, Ops &o) {
+      const float *us = &Us[buf][(wr * 32 + l32) * kUP + 4 * h];
+      const float *bs = &Bs[buf][(4 * h) * kBN + wc * 32 + l32];
+      o.a = *reinterpret_cast<const f4a *>(us + 8 * t);
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
+      for (int q = 0; q < 4; ++q) o.b0[q] = bs[(8 * t + q) * kBN];
+    };
+    auto mma = [&](const Ops &o) {
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(o.a.x, o.b0[0], acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(o.a.y, o.b0[1], acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(o.a.z, o.b0[2], acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(o.a.w, o.b0[3], acc, 0, 0, 0);
+    };
 
     Stage st;
+    Ops oa, ob;
     load_stage(0, st);
     __syncthreads();  // the previous row block's last reads of buffer 0 are done
     store_stage(0, st);
     __syncthreads();
+    read_ops(0, 0, oa);
 
-    // One k-step on LDS buffer `buf` (a literal at both call sites, so every LDS address below is
-    // a compile-time offset), with the global loads of the next step in flight meanwhile.
+    // One k-step on LDS buffer `buf` (a literal at both call sites, so every LDS address is a
+    // compile-time offset).  The global loads of the next step are in flight throughout; its LDS
+    // stores and the workgroup barrier sit BEFORE the last group's matrix instructions, whose
+    // operands are already in registers, so the matrix pipe has work while the barrier settles and
+    // while the first operands of the next step come back from LDS.
     auto step = [&](int kt, int buf) {
-      if (kt + 1 < nk) load_stage(kt + 1, st);
-      // rows i0+32.. have nothing at or right of the diagonal in the first k-step
-      if (!(kt == 0 && wr == 1)) {
-        const float *us = &Us[buf][(wr * 32 + l32) * kUP + 4 * h];
-        const float *bs = &Bs[buf][(4 * h) * kBN + wc * 64 + l32];
-#pragma unroll
-        for (int t = 0; t < kKT / 8; ++t) {
-          const f4a a = *reinterpret_cast<const f4a *>(us + 8 * t);
-          float b0[4], b1[4];
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            b0[q] = bs[(8 * t + q) * kBN];
-            b1[q] = bs[(8 * t + q) * kBN + 32];
-          }
-          acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b0[0], acc[0], 0, 0, 0);
-          acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b1[0], acc[1], 0, 0, 0);
-          acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b0[1], acc[0], 0, 0, 0);
-          acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b1[1], acc[1], 0, 0, 0);
-          acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b0[2], acc[0], 0, 0, 0);
-          acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b1[2], acc[1], 0, 0, 0);
-          acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b0[3], acc[0], 0, 0, 0);
-          acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b1[3], acc[1], 0, 0, 0);
-        }
-      }
-      if (kt + 1 < nk) store_stage(buf ^ 1, st);
+      const bool more = kt + 1 < nk;
+      if (more) load_stage(kt + 1, st);
+      read_ops(buf, 1, ob);
+      mma(oa);
+      read_ops(buf, 2, oa);
+      mma(ob);
+      read_ops(buf, 3, ob);
+      mma(oa);
+      if (more) store_stage(buf ^ 1, st);
       __syncthreads();
+      if (more) read_ops(buf ^ 1, 0, oa);
+      mma(ob);
     };
     for (int kt = 0; kt < nk; kt += 2) {
       step(kt, 0);
       if (kt + 1 < nk) step(kt + 1, 1);
     }
+    __syncthreads();  // all reads of this row block's buffers are done before the next block's stores
 
     // D layout of the 32x32 tile: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32
+    const int64_t col = col0 + wc * 32 + l32;
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const int64_t col = col0 + wc * 64 + t * 32 + l32;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int64_t i = i0 + wr * 32 + 8 * (v / 4) + 4 * h + (v % 4);
-        if (i < n && col < m) C[i * ldc + col] = acc[t][v];
-      }
+    for (int v = 0; v < 16; ++v) {
+      const int64_t i = i0 + wr * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+      if (i < n && col < m) C[i * ldc + col] = acc[v];
     }
   }
 }
