@@ -132,6 +132,18 @@ __device__ inline int lanes_log2_16(int len) {
   return len > 512 ? 6 : len > 256 ? 5 : len > 128 ? 4 : len > 64 ? 3 : len > 32 ? 2 : len > 16 ? 1 : 0;
 }
 
+// A step of the LDS variant in 32-bit arithmetic: positions are relative to the wavefront's first
+// row (packed position p0, output position s0), which keeps every per-step update to single
+// scalar instructions.
+struct Step32 {
+  int p;    // packed position of the step's first row, minus p0
+  int s;    // output position of that row, minus s0
+  int j;    // its first column
+  int len;  // its length (== rows left in the slice)
+  int t0;   // long rows: offset of this piece inside the row; else 0
+  bool valid;
+};
+
 template <bool TET>
 __global__ __launch_bounds__(kLdsBlock) void segsum_lds_kernel(int n, const float *__restrict__ A,
                                                                const float *__restrict__ x,
@@ -139,18 +151,24 @@ __global__ __launch_bounds__(kLdsBlock) void segsum_lds_kernel(int n, const floa
                                                                int64_t total_a, int64_t share, int64_t waves_a,
                                                                int tail_order) {
   extern __shared__ float xs[];  // x[0..n), then kPad zeros
-  for (int t = threadIdx.x; t < n + kPad; t += kLdsBlock) xs[t] = t < n ? x[t] : 0.0f;
-  __syncthreads();
-
+  // Request this thread's first four values of x right away; they arrive while the wavefront
+  // works out which rows it owns.
+  float xr[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int t = threadIdx.x + q * kLdsBlock;
+    xr[q] = t < n ? x[t] : 0.0f;
+  }
   const int lane = threadIdx.x & 63;
   const int64_t wave = (int64_t)blockIdx.x * kLdsWaves + uniform32(threadIdx.x >> 6);
 
   // Which rows are mine: those starting in [first row at or after lo, hi).
-  int64_t hi, sp, sj;
-  int slice;
+  int64_t hi64 = 0, sp = 0, sj = 0;
+  int slice = 0;
+  bool active = true;
   if (wave < waves_a) {  // an equal share of the first total_a elements
     const int64_t lo = wave * share;
-    hi = (lo + share < total_a) ? lo + share : total_a;
+    hi64 = (lo + share < total_a) ? lo + share : total_a;
     int64_t si;
     first_row_from<TET>(n, total, lo, si, sj, sp);
     slice = (int)si;
@@ -158,126 +176,146 @@ __global__ __launch_bounds__(kLdsBlock) void segsum_lds_kernel(int n, const floa
     slice = n - tail_order + (int)(wave - waves_a);
     sp = tet_slice_start(n, slice);
     sj = slice;
-    hi = sp + tri(n - slice);
+    hi64 = sp + tri(n - slice);
   } else {
-    return;
+    active = false;
   }
   slice = uniform32(slice);
-  hi = uniform64(hi);
+  const int64_t p0 = uniform64(sp);
+  const int64_t s0 = TET ? tri_offset(n, slice, uniform32((int)sj)) : uniform32((int)sj);
+  const float *__restrict__ A0 = A + p0;
+  float *__restrict__ out0 = out + s0;
+  const int64_t room_hi = uniform64(hi64) - p0, room_total = total - p0;
+  const int hi = room_hi > 0x3fffffff ? 0x3fffffff : (int)room_hi;          // rows must start before hi
+  const int end = room_total > 0x3fffffff ? 0x3fffffff : (int)room_total;    // one past the last element
 
-  Step st;
-  st.p = uniform64(sp);
+  Step32 st;
+  st.p = 0;
+  st.s = 0;
   st.j = uniform32((int)sj);
-  st.s = TET ? tri_offset(n, slice, st.j) : st.j;
-  st.len = n - (int)st.j;
+  st.len = n - st.j;
   st.t0 = 0;
-  st.valid = st.p < hi && st.len > 0;
+  st.valid = active && st.p < hi && st.len > 0;
 
   // per-lane geometry of a step: row g of the group, `used` rows taken by the step
-  auto geometry = [&](const Step &d, int &g, int &used, bool &mine, int &off, int &xi, int &lw4) {
-    const int lg = lanes_log2_16(d.len);
+  auto geometry = [&](const Step32 &d, int &g, int &used, bool &mine, int &off, int &xi, int &lw4) {
+    const int v = (d.len + 15) >> 4;                          // lanes a row of this length needs
+    int lg = v <= 1 ? 0 : 32 - __builtin_clz(v - 1);         // ceil(log2(v))
+    if (lg > 6) lg = 6;
     lw4 = 4 << lg;  // elements between two consecutive loads of a lane
     int rows = 64 >> lg;
     if (rows > d.len) rows = d.len;  // stay inside the slice
     g = lane >> lg;
     const int sub = lane & ((1 << lg) - 1);
     const int goff = g * d.len - ((g * (g - 1)) >> 1);  // start of row g relative to d.p
-    const int64_t room = hi - d.p;                      // rows must start before hi
-    const int lim = room > 0x7fffffff ? 0x7fffffff : (int)room;
-    mine = g < rows && goff < lim;
+    mine = g < rows && goff < hi - d.p;
     used = __popcll(__ballot(mine && sub == 0));
-    // element offset of my first load relative to d.p; lanes without a row (whose goff is
+    // element offset of my first load relative to p0; lanes without a row (whose goff is
     // meaningless, possibly negative) read from the start of the step instead
-    off = mine ? goff + d.t0 + sub * 4 : 0;
+    off = d.p + (mine ? goff + d.t0 + sub * 4 : 0);
     // column of my first element; lanes without a row look at the zero pad
-    xi = mine ? (int)d.j + g + d.t0 + sub * 4 : n;
+    xi = mine ? d.j + g + d.t0 + sub * 4 : n;
   };
   // every lane's loads of step d lie inside the buffer
-  auto fits = [&](const Step &d) -> bool { return d.p + d.t0 + kSpan + 4 <= total; };
+  auto fits = [&](const Step32 &d) -> bool { return d.p + d.t0 + kSpan + 4 <= end; };
 
-  auto issue_fast = [&](const Step &d, int &g, int &used, Piece16 &r) {
+  auto issue_a = [&](const Step32 &d, int &g, int &used, int &xi, int &lw4, Piece16 &r) {
     bool mine;
-    int off, xi, lw4;
+    int off;
     geometry(d, g, used, mine, off, xi, lw4);
-    const float *ab = A + d.p;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) r.a[q] = __builtin_nontemporal_load(reinterpret_cast<const f4u *>(ab + off + q * lw4));
+    for (int q = 0; q < 4; ++q)
+      r.a[q] = __builtin_nontemporal_load(reinterpret_cast<const f4u *>(A0 + off + q * lw4));
+  };
+  auto issue_x = [&](int xi, int lw4, Piece16 &r) {
 #pragma unroll
     for (int q = 0; q < 4; ++q) r.x[q] = *reinterpret_cast<const f4u *>(&xs[xi + q * lw4]);
   };
-  auto issue_guarded = [&](const Step &d, int &g, int &used, Piece16 &r) {
+  auto issue_guarded = [&](const Step32 &d, int &g, int &used, Piece16 &r) {
     bool mine;
     int off, xi, lw4;
     geometry(d, g, used, mine, off, xi, lw4);
-    const float *ab = A + d.p;
-    const int64_t room_a = total - d.p;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       float e[4];
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         const int o = off + q * lw4 + c;
-        e[c] = (mine && o < room_a) ? ab[o] : 0.0f;
+        e[c] = (mine && o < end) ? A0[o] : 0.0f;
       }
       r.a[q] = f4a{e[0], e[1], e[2], e[3]};
     }
-#pragma unroll
-    for (int q = 0; q < 4; ++q) r.x[q] = *reinterpret_cast<const f4u *>(&xs[xi + q * lw4]);
+    issue_x(xi, lw4, r);
   };
-  auto advance = [&](const Step &d, int used) -> Step {
-    Step nx = d;
+  auto advance = [&](const Step32 &d, int used) -> Step32 {
+    Step32 nx = d;
     if (d.len > kSpan && d.t0 + kSpan < d.len) {  // next piece of the same long row
       nx.t0 = d.t0 + kSpan;
       return nx;
     }
     nx.t0 = 0;
-    nx.p = d.p + (int64_t)used * d.len - ((used * (used - 1)) >> 1);
+    nx.p = d.p + used * d.len - ((used * (used - 1)) >> 1);
     nx.s = d.s + used;
     nx.j = d.j + used;
     if (TET && nx.j >= n) {  // slice finished
       slice += 1;
       nx.j = slice;
     }
-    nx.len = n - (int)nx.j;
+    nx.len = n - nx.j;
     nx.valid = nx.p < hi && nx.len > 0;
     return nx;
   };
 
   float racc = 0.0f;  // running per-lane sum of a long row
-  auto consume = [&](const Step &d, const Piece16 &c, int g, int used) {
+  auto consume = [&](const Step32 &d, const Piece16 &c, int g, int used) {
     float v = (dot0(c.a[0], c.x[0]) + dot0(c.a[1], c.x[1])) + (dot0(c.a[2], c.x[2]) + dot0(c.a[3], c.x[3]));
     if (d.len > kSpan) {
       racc += v;
       if (d.t0 + kSpan >= d.len) {
         v = group_sum(racc, 6);
         racc = 0.0f;
-        if (lane == 0) out[d.s] = v;
+        if (lane == 0) out0[d.s] = v;
       }
     } else {
-      const int lg = lanes_log2_16(d.len);
+      const int w = (d.len + 15) >> 4;
+      int lg = w <= 1 ? 0 : 32 - __builtin_clz(w - 1);
       v = group_sum(v, lg);
       const int sub = lane & ((1 << lg) - 1);
-      if (sub == 0 && g < used) out[d.s + g] = v;
+      if (sub == 0 && g < used) out0[d.s + g] = v;
     }
   };
+
+  // The packed loads of the first step do not depend on LDS: request them before x is staged.
+  Piece16 pa, pb;
+  int ga = 0, ua = 0, gb = 0, ub = 0, xia = 0, lwa = 4, xib = 0, lwb = 4;
+  const bool fast = st.valid && fits(st);
+  if (fast) issue_a(st, ga, ua, xia, lwa, pa);
+
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int t = threadIdx.x + q * kLdsBlock;
+    if (t < n + kPad) xs[t] = xr[q];
+  }
+  for (int t = threadIdx.x + 4 * kLdsBlock; t < n + kPad; t += kLdsBlock) xs[t] = t < n ? x[t] : 0.0f;
+  __syncthreads();
 
   // Unguarded steps: two register sets alternate, and the loop body has no branch around its
   // loads, so the next step's loads stay in flight while the current step is reduced.  When the
   // next step does not exist (or needs the guarded loader) the current one is simply loaded again.
-  if (st.valid && fits(st)) {
-    Piece16 pa, pb;
-    int ga, ua, gb, ub;
-    issue_fast(st, ga, ua, pa);
+  if (fast) {
+    issue_x(xia, lwa, pa);
     for (;;) {
-      Step nx = advance(st, ua);
+      Step32 nx = advance(st, ua);
       bool more = nx.valid && fits(nx);
-      issue_fast(more ? nx : st, gb, ub, pb);
+      issue_a(more ? nx : st, gb, ub, xib, lwb, pb);
+      issue_x(xib, lwb, pb);
       consume(st, pa, ga, ua);
       st = nx;
       if (!more) break;
       nx = advance(st, ub);
       more = nx.valid && fits(nx);
-      issue_fast(more ? nx : st, ga, ua, pa);
+      issue_a(more ? nx : st, ga, ua, xia, lwa, pa);
+      issue_x(xia, lwa, pa);
       consume(st, pb, gb, ub);
       st = nx;
       if (!more) break;
