@@ -26,7 +26,7 @@ namespace {
 
 constexpr int kWaves = 8;
 constexpr int kBlock = kWaves * 64;
-constexpr int kPanel = 256;  // k values per staged panel of C
+constexpr int kPanel = 512;  // k values per staged panel of C
 constexpr int kTP = 36;      // pitch (floats) of a wavefront's private 32x32 tile
 
 typedef float f16v __attribute__((ext_vector_type(16)));
@@ -39,10 +39,10 @@ __device__ inline void wave_sync_lds() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4, 4))) void mttkrp_mfma_kernel(int64_t n, int R, const float *__restrict__ A,
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) void mttkrp_mfma_kernel(int64_t n, int R, const float *__restrict__ A,
                                                              const float *__restrict__ Bm, int64_t ldb,
                                                              const float *__restrict__ Cm, int64_t ldc,
-                                                             float *__restrict__ M, int64_t ldm) {
+                                                             float *__restrict__ M, int64_t ldm, int64_t total) {
   __shared__ __attribute__((aligned(16))) float Cs[kPanel * 32];
   __shared__ __attribute__((aligned(16))) float At[kWaves][32 * kTP];
   __shared__ float Mred[kWaves][32];
@@ -55,6 +55,12 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4, 4))) 
   const int nblk = (int)ceil_div(m, 32);
   const int npanels = (int)ceil_div(m, kPanel);
   const int64_t slice0 = tet_slice_start(n, i);  // packed position of (i,i,i)
+  // a 16-byte load may start up to 31 elements past the end of its row: safe unless the slice is
+  // one of the last few of the buffer
+  const bool vec_ok = slice0 + tri(m) + 32 <= total;
+  const float *__restrict__ As = A + slice0;  // this slice's packed triangle
+  // rows of B can be fetched as 16-byte pieces at 32-bit offsets
+  const bool b_vec = R == 32 && n * ldb < ((int64_t)1 << 31);
 
   // loader role inside a 32x32 tile: rows lr, lr+8, lr+16, lr+24; four k values from lk
   const int lr = lane >> 3, lk = (lane & 7) * 4;
@@ -79,13 +85,20 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4, 4))) 
           if (c4 + 3 < R) v.w = Cm[k * ldc + c4 + 3];
         }
       }
-      *reinterpret_cast<f4a *>(&Cs[row * 32 + c4]) = v;
+      // Layout [k/4][r][k%4]: the four k values a lane feeds to four consecutive matrix
+      // instructions are then one 16-byte read.
+      float *cd = &Cs[((row >> 2) * 32 + c4) * 4 + (row & 3)];
+      cd[0] = v.x;
+      cd[4] = v.y;
+      cd[8] = v.z;
+      cd[12] = v.w;
     }
     if (tid == 0) next_unit = 0;
     __syncthreads();
 
     const int64_t kp1 = (kp0 + kPanel < n) ? kp0 + kPanel : n;
-    const int nunits = (nblk < 8 * (c + 1)) ? nblk : 8 * (c + 1);  // row blocks that reach this panel
+    const int reach = (kPanel / 32) * (c + 1);
+    const int nunits = nblk < reach ? nblk : reach;  // row blocks that reach this panel
     for (;;) {
       int u = 0;
       if (lane == 0) u = atomicAdd(&next_unit, 1);
@@ -96,17 +109,24 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4, 4))) 
       const int64_t ks = (j0 > kp0) ? j0 : kp0;        // first k of this block in this panel
       const int ntiles = (int)ceil_div(kp1 - ks, 32);
       const bool rows_full = j0 + 32 <= n;
-      // packed row bases for the rows this lane loads: element (i,j,k) is at rb[q] + k
-      const float *rb[4];
+      // packed row bases for the rows this lane loads, as 32-bit element offsets from the slice:
+      // element (i,j,k) is at As[ro[q] + (k - i)]  (a slice of a buffer that fits in memory has
+      // far fewer than 2^30 elements)
+      int ro[4];
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        int64_t j = j0 + lr + 8 * q;
-        if (j >= n) j = n - 1;  // keep the address inside the buffer; values are masked below
-        const int64_t jj = j - i;  // row inside the slice triangle of order m
-        rb[q] = A + slice0 + tri_row_start(m, jj) - j;
+        int64_t jj = j0 - i + lr + 8 * q;  // row inside the slice triangle of order m
+        if (jj >= m) jj = m - 1;           // keep the address inside the buffer; values are masked below
+        ro[q] = (int)(tri_row_start(m, jj) - jj);
       }
+      const int kr0 = (int)(ks - i), jr0 = (int)(j0 - i), mi = (int)m;  // relative to the slice
+      // The block's 32 rows of B ride the same pipeline as one more tile behind the last tile of A
+      // (full row blocks of R = 32 columns only), so the fold below never waits for memory.
+      const bool fold_lds = vec_ok && b_vec && rows_full;
+      const int bo = (int)((j0 + lr) * ldb) + lk;  // this lane's piece of B(j0+lr, :), meaningful if fold_lds
 
-      // Guarded loader for tiles cut by the diagonal or by the ragged end of the rows.
+      // Scalar loader with every element bounds-tested; only for the last few slices, where a
+      // vector load could reach past the end of the packed buffer.
       auto load_guarded = [&](int t, f4a (&v)[4]) {
         const int64_t k0 = ks + 32 * (int64_t)t;
 #pragma unroll
@@ -116,23 +136,43 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4, 4))) 
 #pragma unroll
           for (int s = 0; s < 4; ++s) {
             const int64_t k = k0 + lk + s;
-            e[s] = (j < n && k >= j && k < n) ? rb[q][k] : 0.0f;
+            e[s] = (j < n && k >= j && k < n) ? As[ro[q] + (int)(k - i)] : 0.0f;
           }
           v[q] = f4a{e[0], e[1], e[2], e[3]};
         }
       };
-      // Branch-free loader for interior tiles; a tile index at or past `fe` loads a harmless dummy
-      // address instead, so that the loop below has no control flow around its loads and the
-      // compiler can leave them in flight across iterations.  Plain (cached) loads: the 128-byte
-      // row pieces are not aligned to cache lines, and the next piece of the same row, requested
-      // right behind, uses the other half of the shared line.
-      const float *dummy = A + slice0;
-      auto load_fast = [&](int t, int fe, f4a (&v)[4]) {
-        const int64_t k0 = ks + 32 * (int64_t)t;
+      // Branch-free loader for every other tile, including those cut by the diagonal or by the end
+      // of the rows: there the 16-byte pieces also cover elements of the neighbouring rows (still
+      // inside the buffer), which mask_tile() zeroes afterwards.  A tile index at or past `ntiles`
+      // loads a harmless dummy address, so that the loop below has no control flow around its
+      // loads and the compiler can leave them in flight across iterations.  Plain (cached) loads:
+      // the 128-byte row pieces are not aligned to cache lines, and the next piece of the same
+      // row, requested right behind, uses the other half of the shared line.
+      auto load_vec = [&](int t, f4a (&v)[4]) {
+        const int kt = kr0 + 32 * t + lk;
+        // index ntiles+3 lands in the set that holds B: fetch B again rather than a dummy
+        const bool is_a = t < ntiles, is_b = fold_lds && (t == ntiles || t == ntiles + 3);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          const float *src = (t < fe) ? rb[q] + k0 + lk : dummy;
+          const float *src = is_a ? As + (ro[q] + kt) : is_b ? Bm + (bo + q * 8 * (int)ldb) : As;
           v[q] = *reinterpret_cast<const f4u *>(src);
+        }
+      };
+      // Zero what a vector-loaded tile holds outside the domain j<=k<n (and of rows j>=n).  Interior
+      // tiles, the great majority, skip this on a wave-uniform test.
+      auto mask_tile = [&](int t, f4a (&v)[4]) {
+        const int kt = kr0 + 32 * t;
+        if (rows_full && kt >= jr0 + 31 && kt + 32 <= mi) return;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int jr = jr0 + lr + 8 * q;
+          const int lo = jr - (kt + lk);                      // elements below lo are left of the diagonal
+          const int hi = jr < mi ? mi - (kt + lk) : lo;       // elements from hi on are past the row's end
+          const unsigned span = hi > lo ? (unsigned)(hi - lo) : 0u;
+          v[q].x = ((unsigned)(0 - lo) < span) ? v[q].x : 0.0f;
+          v[q].y = ((unsigned)(1 - lo) < span) ? v[q].y : 0.0f;
+          v[q].z = ((unsigned)(2 - lo) < span) ? v[q].z : 0.0f;
+          v[q].w = ((unsigned)(3 - lo) < span) ? v[q].w : 0.0f;
         }
       };
 
@@ -145,59 +185,68 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4, 4))) 
 #pragma unroll
         for (int q = 0; q < 4; ++q) *reinterpret_cast<f4a *>(&tile[(lr + 8 * q) * kTP + lk]) = v[q];
         wave_sync_lds();  // the tile is private to this wavefront: no workgroup barrier needed
-        const float *cs = &Cs[(int)(ks - kp0 + 32 * t + 4 * h) * 32 + l32];
+        const float *cs = &Cs[((((int)(ks - kp0) + 32 * t) >> 2) + h) * 128 + l32 * 4];
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const f4a a = *reinterpret_cast<const f4a *>(&tile[l32 * kTP + 8 * g + 4 * h]);
-          const float c0 = cs[(8 * g + 0) * 32], c1 = cs[(8 * g + 1) * 32];
-          const float c2 = cs[(8 * g + 2) * 32], c3 = cs[(8 * g + 3) * 32];
-          acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, c0, acc, 0, 0, 0);
-          acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, c1, acc, 0, 0, 0);
-          acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, c2, acc, 0, 0, 0);
-          acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, c3, acc, 0, 0, 0);
+          const f4a cv = *reinterpret_cast<const f4a *>(&cs[g * 256]);
+          acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, cv.x, acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, cv.y, acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, cv.z, acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, cv.w, acc, 0, 0, 0);
         }
         wave_sync_lds();  // all lanes have read the tile before the next one overwrites it
       };
 
-      // Tiles [fb, fe) need no predicates: not on the diagonal, all 32 rows exist, all 32 k exist.
-      int fb = 0, fe = ntiles;
-      if (!rows_full) {
-        fe = 0;
-      } else {
-        if (ks < j0 + 32) fb = 1;                      // the first tile straddles the diagonal
-        if (ks + 32 * (int64_t)ntiles > n) fe -= 1;    // the last tile runs past n
-        if (fe < fb) fe = fb;
-      }
       f4a s0[4], s1[4], s2[4];
-      if (fb < fe) {  // three register sets rotate; two tiles are always in flight
-        load_fast(fb, fe, s0);
-        load_fast(fb + 1, fe, s1);
-        for (int t = fb;; t += 3) {
-          load_fast(t + 2, fe, s2);
+      if (vec_ok) {
+        // Three register sets rotate and two tiles are always in flight.  The loop leaves only at
+        // its bottom and its loads are unconditional (past the last tile they fetch a dummy), so
+        // the compiler keeps exact counts of what is in flight.
+        load_vec(0, s0);
+        load_vec(1, s1);
+        int t = 0;
+        do {
+          load_vec(t + 2, s2);
+          mask_tile(t, s0);
           compute(t, s0);
-          if (t + 1 >= fe) break;
-          load_fast(t + 3, fe, s0);
-          compute(t + 1, s1);
-          if (t + 2 >= fe) break;
-          load_fast(t + 4, fe, s1);
-          compute(t + 2, s2);
-          if (t + 3 >= fe) break;
+          load_vec(t + 3, s0);
+          if (t + 1 < ntiles) {
+            mask_tile(t + 1, s1);
+            compute(t + 1, s1);
+          }
+          load_vec(t + 4, s1);
+          if (t + 2 < ntiles) {
+            mask_tile(t + 2, s2);
+            compute(t + 2, s2);
+          }
+          t += 3;
+        } while (t < ntiles);
+      } else {
+        for (int t = 0; t < ntiles; ++t) {
+          load_guarded(t, s0);
+          compute(t, s0);
         }
-      }
-      if (fb == 1) {  // the diagonal tile
-        load_guarded(0, s0);
-        compute(0, s0);
-      }
-      for (int t = (fe > fb ? fe : fb); t < ntiles; ++t) {  // the ragged last tile, or all tiles of a ragged row block
-        load_guarded(t, s0);
-        compute(t, s0);
       }
 
       // fold the 32x32 block of T with B: register v of lane l is row 8*(v/4)+4*(l/32)+v%4, column l%32
+      if (fold_lds) {
+        const int w3 = ntiles % 3;  // the register set that received B
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int64_t j = j0 + 8 * (v / 4) + 4 * h + (v % 4);
-        if (j < n && l32 < R) macc += acc[v] * Bm[j * ldb + l32];
+        for (int q = 0; q < 4; ++q) {
+          const f4a bq = w3 == 0 ? s0[q] : w3 == 1 ? s1[q] : s2[q];
+          *reinterpret_cast<f4a *>(&tile[(lr + 8 * q) * kTP + lk]) = bq;
+        }
+        wave_sync_lds();
+#pragma unroll
+        for (int v = 0; v < 16; ++v) macc += acc[v] * tile[(8 * (v / 4) + 4 * h + (v % 4)) * kTP + l32];
+        wave_sync_lds();  // the tile is free again for the next block
+      } else {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int64_t j = j0 + 8 * (v / 4) + 4 * h + (v % 4);
+          if (j < n && l32 < R) macc += acc[v] * Bm[j * ldb + l32];
+        }
       }
     }
   }
@@ -224,6 +273,6 @@ extern "C" int dastac_tet_mttkrp_f32(int64_t n, int64_t R, const float *Ap, cons
   if (overlaps(M, n * ldm * 4, Ap, tet(n) * 4) || overlaps(M, n * ldm * 4, B, n * ldb * 4) ||
       overlaps(M, n * ldm * 4, C, n * ldc * 4))
     return DASTAC_EALIAS;
-  mttkrp_mfma_kernel<<<(unsigned)n, kBlock, 0, (hipStream_t)stream>>>(n, (int)R, Ap, B, ldb, C, ldc, M, ldm);
+  mttkrp_mfma_kernel<<<(unsigned)n, kBlock, 0, (hipStream_t)stream>>>(n, (int)R, Ap, B, ldb, C, ldc, M, ldm, tet(n));
   return launch_status();
 }

@@ -100,11 +100,13 @@ struct Step {
 // ---------------------------------------------------------------------------------------------
 // Variant 1: the vector operand fits in LDS (n <= kLdsMaxN).  Serves every TTV and small TRMV.
 //
-// x is staged once per workgroup, followed by kPad zeros.  A lane reads sixteen packed elements
+// x is staged once per workgroup, followed by kPad zeros.  A lane handles sixteen packed elements
 // per step (four 16-byte loads, each contiguous across the lanes of a row) without any bounds
-// test: elements past the end of its row belong to the next row (still inside the buffer) and meet
-// a zero of the pad, and the product is formed with v_mul_legacy_f32 (0 * anything = 0), so they
-// contribute exactly nothing even if they are Inf or NaN.  Only steps within kSpan elements of the
+// test: elements past the end of its row meet a zero of the pad, and the product is formed with
+// v_mul_legacy_f32 (0 * anything = 0), so they contribute exactly nothing even if they are Inf or
+// NaN.  A load that would lie wholly past the row's end is aimed at the row's last piece instead,
+// which is on its way anyway: rows use 3/4 of their lanes' capacity on average, and fetching the
+// unused quarter from memory cost 15 % of the bandwidth.  Only steps within kSpan elements of the
 // end of the whole buffer take the guarded loader.
 // ---------------------------------------------------------------------------------------------
 constexpr int kLdsBlock = 512;
@@ -141,6 +143,7 @@ struct Step32 {
   int j;    // its first column
   int len;  // its length (== rows left in the slice)
   int t0;   // long rows: offset of this piece inside the row; else 0
+  int slice;  // slice of the tetrahedron the row belongs to
   bool valid;
 };
 
@@ -195,10 +198,12 @@ __global__ __launch_bounds__(kLdsBlock) void segsum_lds_kernel(int n, const floa
   st.j = uniform32((int)sj);
   st.len = n - st.j;
   st.t0 = 0;
+  st.slice = slice;
   st.valid = active && st.p < hi && st.len > 0;
 
   // per-lane geometry of a step: row g of the group, `used` rows taken by the step
-  auto geometry = [&](const Step32 &d, int &g, int &used, bool &mine, int &off, int &xi, int &lw4) {
+  auto geometry = [&](const Step32 &d, int &g, int &used, bool &mine, int &off, int &sub4, int &lim, int &xi,
+                      int &lw4) {
     const int v = (d.len + 15) >> 4;                          // lanes a row of this length needs
     int lg = v <= 1 ? 0 : 32 - __builtin_clz(v - 1);         // ceil(log2(v))
     if (lg > 6) lg = 6;
@@ -206,26 +211,35 @@ __global__ __launch_bounds__(kLdsBlock) void segsum_lds_kernel(int n, const floa
     int rows = 64 >> lg;
     if (rows > d.len) rows = d.len;  // stay inside the slice
     g = lane >> lg;
-    const int sub = lane & ((1 << lg) - 1);
+    sub4 = (lane & ((1 << lg) - 1)) * 4;
     const int goff = g * d.len - ((g * (g - 1)) >> 1);  // start of row g relative to d.p
     mine = g < rows && goff < hi - d.p;
-    used = __popcll(__ballot(mine && sub == 0));
-    // element offset of my first load relative to p0; lanes without a row (whose goff is
-    // meaningless, possibly negative) read from the start of the step instead
-    off = d.p + (mine ? goff + d.t0 + sub * 4 : 0);
+    used = __popcll(__ballot(mine && sub4 == 0));
+    // element offset (relative to p0) of the first element this lane may use; lanes without a row
+    // (whose goff is meaningless, possibly negative) point at the start of the step instead
+    off = d.p + (mine ? goff + d.t0 : 0);
+    // last 4-element piece that still holds an element of my row (my row has len - g elements, of
+    // which t0 are behind this step)
+    lim = mine ? (d.len - g - d.t0 - 1) & ~3 : 0;
     // column of my first element; lanes without a row look at the zero pad
-    xi = mine ? d.j + g + d.t0 + sub * 4 : n;
+    xi = mine ? d.j + g + d.t0 + sub4 : n;
   };
   // every lane's loads of step d lie inside the buffer
   auto fits = [&](const Step32 &d) -> bool { return d.p + d.t0 + kSpan + 4 <= end; };
 
+  // Loads that would start past the end of the lane's row are pointed at the row's last piece
+  // instead: the line is being fetched anyway, so they cost no memory traffic, and whatever they
+  // return meets a zero of the pad.
   auto issue_a = [&](const Step32 &d, int &g, int &used, int &xi, int &lw4, Piece16 &r) {
     bool mine;
-    int off;
-    geometry(d, g, used, mine, off, xi, lw4);
+    int off, sub4, lim;
+    geometry(d, g, used, mine, off, sub4, lim, xi, lw4);
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
-      r.a[q] = __builtin_nontemporal_load(reinterpret_cast<const f4u *>(A0 + off + q * lw4));
+    for (int q = 0; q < 4; ++q) {
+      int e = sub4 + q * lw4;
+      e = e < lim ? e : lim;
+      r.a[q] = __builtin_nontemporal_load(reinterpret_cast<const f4u *>(A0 + off + e));
+    }
   };
   auto issue_x = [&](int xi, int lw4, Piece16 &r) {
 #pragma unroll
@@ -233,14 +247,14 @@ __global__ __launch_bounds__(kLdsBlock) void segsum_lds_kernel(int n, const floa
   };
   auto issue_guarded = [&](const Step32 &d, int &g, int &used, Piece16 &r) {
     bool mine;
-    int off, xi, lw4;
-    geometry(d, g, used, mine, off, xi, lw4);
+    int off, sub4, lim, xi, lw4;
+    geometry(d, g, used, mine, off, sub4, lim, xi, lw4);
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       float e[4];
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        const int o = off + q * lw4 + c;
+        const int o = off + sub4 + q * lw4 + c;
         e[c] = (mine && o < end) ? A0[o] : 0.0f;
       }
       r.a[q] = f4a{e[0], e[1], e[2], e[3]};
@@ -258,8 +272,8 @@ __global__ __launch_bounds__(kLdsBlock) void segsum_lds_kernel(int n, const floa
     nx.s = d.s + used;
     nx.j = d.j + used;
     if (TET && nx.j >= n) {  // slice finished
-      slice += 1;
-      nx.j = slice;
+      nx.slice = d.slice + 1;
+      nx.j = nx.slice;
     }
     nx.len = n - nx.j;
     nx.valid = nx.p < hi && nx.len > 0;
@@ -299,27 +313,27 @@ __global__ __launch_bounds__(kLdsBlock) void segsum_lds_kernel(int n, const floa
   for (int t = threadIdx.x + 4 * kLdsBlock; t < n + kPad; t += kLdsBlock) xs[t] = t < n ? x[t] : 0.0f;
   __syncthreads();
 
-  // Unguarded steps: two register sets alternate, and the loop body has no branch around its
-  // loads, so the next step's loads stay in flight while the current step is reduced.  When the
-  // next step does not exist (or needs the guarded loader) the current one is simply loaded again.
+  // Unguarded steps: two register sets alternate, and nothing but the reductions is branched
+  // around, so the next step's loads stay in flight while the current step is reduced.  When the
+  // next step does not exist (or needs the guarded loader) the last good one is loaded again and
+  // ignored.  The loop leaves only at its bottom: an exit between the two halves would make the
+  // compiler drain every load at the top of the loop.
   if (fast) {
     issue_x(xia, lwa, pa);
-    for (;;) {
-      Step32 nx = advance(st, ua);
-      bool more = nx.valid && fits(nx);
-      issue_a(more ? nx : st, gb, ub, xib, lwb, pb);
+    bool more2;
+    do {
+      const Step32 n1 = advance(st, ua);
+      const bool more1 = n1.valid && fits(n1);
+      issue_a(more1 ? n1 : st, gb, ub, xib, lwb, pb);
       issue_x(xib, lwb, pb);
       consume(st, pa, ga, ua);
-      st = nx;
-      if (!more) break;
-      nx = advance(st, ub);
-      more = nx.valid && fits(nx);
-      issue_a(more ? nx : st, ga, ua, xia, lwa, pa);
+      const Step32 n2 = advance(n1, ub);  // meaningful only if more1
+      more2 = more1 && n2.valid && fits(n2);
+      issue_a(more2 ? n2 : more1 ? n1 : st, ga, ua, xia, lwa, pa);
       issue_x(xia, lwa, pa);
-      consume(st, pb, gb, ub);
-      st = nx;
-      if (!more) break;
-    }
+      if (more1) consume(n1, pb, gb, ub);
+      st = more1 ? n2 : n1;
+    } while (more2);
   }
   // Steps that reach into the last kSpan elements of the buffer.
   while (st.valid) {
@@ -478,12 +492,12 @@ template <bool TET>
 int launch_lds(int64_t n, const float *A, const float *x, float *out, int64_t total, void *stream) {
   int64_t tail_order = 0, total_a = total;
   if (TET) {  // slices whose triangle is below about half a share get a wavefront of their own
-    int64_t m0 = (int64_t)sqrt((double)pick_share(total, 16));
+    int64_t m0 = (int64_t)sqrt((double)pick_share(total, 24));
     if (m0 < 64) m0 = 64;
     tail_order = m0 < n ? m0 : n;
     total_a = total - tet(tail_order);
   }
-  const int64_t share = pick_share(total_a, 16);
+  const int64_t share = pick_share(total_a, 24);
   const int64_t waves_a = ceil_div(total_a, share);
   const int64_t blocks = ceil_div(waves_a + tail_order, kLdsWaves);
   const size_t lds = (size_t)(n + kPad) * sizeof(float);
