@@ -120,10 +120,21 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
         ro[q] = (int)(tri_row_start(m, jj) - jj);
       }
       const int kr0 = (int)(ks - i), jr0 = (int)(j0 - i), mi = (int)m;  // relative to the slice
-      // The block's 32 rows of B ride the same pipeline as one more tile behind the last tile of A
-      // (full row blocks of R = 32 columns only), so the fold below never waits for memory.
+      // Byte offsets from the slice of this lane's piece of the block's first tile, row by row: a tile
+      // further on is 128 bytes further on, which keeps the per-tile address arithmetic to one add
+      // per load (every VALU instruction here is time taken from the matrix pipe of the same SIMD).
+      unsigned vo[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) vo[q] = (unsigned)(ro[q] + kr0 + lk) * 4u;
+      // The block's 32 rows of B are requested now and used after the last tile (full row blocks
+      // of R = 32 columns only), so the fold below never waits for memory.
       const bool fold_lds = vec_ok && b_vec && rows_full;
-      const int bo = (int)((j0 + lr) * ldb) + lk;  // this lane's piece of B(j0+lr, :), meaningful if fold_lds
+      f4a bv[4];
+      if (fold_lds) {
+        const int bo = (int)((j0 + lr) * ldb) + lk;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) bv[q] = *reinterpret_cast<const f4u *>(Bm + (bo + q * 8 * (int)ldb));
+      }
 
       // Scalar loader with every element bounds-tested; only for the last few slices, where a
       // vector load could reach past the end of the packed buffer.
@@ -144,19 +155,15 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
       // Branch-free loader for every other tile, including those cut by the diagonal or by the end
       // of the rows: there the 16-byte pieces also cover elements of the neighbouring rows (still
       // inside the buffer), which mask_tile() zeroes afterwards.  A tile index at or past `ntiles`
-      // loads a harmless dummy address, so that the loop below has no control flow around its
-      // loads and the compiler can leave them in flight across iterations.  Plain (cached) loads:
+      // loads the last tile again, so that the loop below has no control flow around its loads
+      // and the compiler can leave them in flight across iterations.  Plain (cached) loads:
       // the 128-byte row pieces are not aligned to cache lines, and the next piece of the same
       // row, requested right behind, uses the other half of the shared line.
       auto load_vec = [&](int t, f4a (&v)[4]) {
-        const int kt = kr0 + 32 * t + lk;
-        // index ntiles+3 lands in the set that holds B: fetch B again rather than a dummy
-        const bool is_a = t < ntiles, is_b = fold_lds && (t == ntiles || t == ntiles + 3);
+        const unsigned toff = 128u * (unsigned)(t < ntiles ? t : ntiles - 1);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const float *src = is_a ? As + (ro[q] + kt) : is_b ? Bm + (bo + q * 8 * (int)ldb) : As;
-          v[q] = *reinterpret_cast<const f4u *>(src);
-        }
+        for (int q = 0; q < 4; ++q)
+          v[q] = *reinterpret_cast<const f4u *>(reinterpret_cast<const char *>(As) + (vo[q] + toff));
       };
       // Zero what a vector-loaded tile holds outside the domain j<=k<n (and of rows j>=n).  Interior
       // tiles, the great majority, skip this on a wave-uniform test.
@@ -231,12 +238,8 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
 
       // fold the 32x32 block of T with B: register v of lane l is row 8*(v/4)+4*(l/32)+v%4, column l%32
       if (fold_lds) {
-        const int w3 = ntiles % 3;  // the register set that received B
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const f4a bq = w3 == 0 ? s0[q] : w3 == 1 ? s1[q] : s2[q];
-          *reinterpret_cast<f4a *>(&tile[(lr + 8 * q) * kTP + lk]) = bq;
-        }
+        for (int q = 0; q < 4; ++q) *reinterpret_cast<f4a *>(&tile[(lr + 8 * q) * kTP + lk]) = bv[q];
         wave_sync_lds();
 #pragma unroll
         for (int v = 0; v < 16; ++v) macc += acc[v] * tile[(8 * (v / 4) + 4 * h + (v % 4)) * kTP + l32];
