@@ -147,7 +147,10 @@ struct Step32 {
   bool valid;
 };
 
-template <bool TET>
+// STREAM: the packed buffer is larger than the memory-side cache, so its loads are non-temporal
+// (measured 10 % faster there); a smaller buffer is read through the caches, where the lines
+// shared by two neighbouring rows are fetched once (measured 9 % faster at 90 MB).
+template <bool TET, bool STREAM>
 __global__ __launch_bounds__(kLdsBlock) void segsum_lds_kernel(int n, const float *__restrict__ A,
                                                                const float *__restrict__ x,
                                                                float *__restrict__ out, int64_t total,
@@ -238,7 +241,8 @@ __global__ __launch_bounds__(kLdsBlock) void segsum_lds_kernel(int n, const floa
     for (int q = 0; q < 4; ++q) {
       int e = sub4 + q * lw4;
       e = e < lim ? e : lim;
-      r.a[q] = __builtin_nontemporal_load(reinterpret_cast<const f4u *>(A0 + off + e));
+      const f4u *src = reinterpret_cast<const f4u *>(A0 + off + e);
+      r.a[q] = STREAM ? __builtin_nontemporal_load(src) : *src;
     }
   };
   auto issue_x = [&](int xi, int lw4, Piece16 &r) {
@@ -488,6 +492,8 @@ inline int64_t pick_share(int64_t total, int per_cu) {
   return share < 2048 ? 2048 : share;
 }
 
+constexpr int64_t kStreamBytes = (int64_t)192 << 20;  // above this a buffer does not stay in the 256 MB memory-side cache
+
 template <bool TET>
 int launch_lds(int64_t n, const float *A, const float *x, float *out, int64_t total, void *stream) {
   int64_t tail_order = 0, total_a = total;
@@ -501,8 +507,12 @@ int launch_lds(int64_t n, const float *A, const float *x, float *out, int64_t to
   const int64_t waves_a = ceil_div(total_a, share);
   const int64_t blocks = ceil_div(waves_a + tail_order, kLdsWaves);
   const size_t lds = (size_t)(n + kPad) * sizeof(float);
-  segsum_lds_kernel<TET><<<(unsigned)blocks, kLdsBlock, lds, (hipStream_t)stream>>>(
-      (int)n, A, x, out, total, total_a, share, waves_a, (int)tail_order);
+  if (total * 4 > kStreamBytes)
+    segsum_lds_kernel<TET, true><<<(unsigned)blocks, kLdsBlock, lds, (hipStream_t)stream>>>(
+        (int)n, A, x, out, total, total_a, share, waves_a, (int)tail_order);
+  else
+    segsum_lds_kernel<TET, false><<<(unsigned)blocks, kLdsBlock, lds, (hipStream_t)stream>>>(
+        (int)n, A, x, out, total, total_a, share, waves_a, (int)tail_order);
   return launch_status();
 }
 
