@@ -75,6 +75,9 @@ def lib() -> ctypes.CDLL:
         L.oracle_band_spmv_f32.argtypes = [_i64, _i64, _fp, _fp, _fp, _dp, _i64, _i64]
         L.oracle_tet_ttv_f32.argtypes = [_i64, _fp, _fp, _fp, _dp, _i64, _i64]
         L.oracle_tet_mttkrp_f32.argtypes = [_i64, _i64, _fp, _fp, _i64, _fp, _i64, _fp, _i64, _dp, _i64, _i64]
+        L.oracle_pack_uhc_f32.argtypes = [_i64, _i64, _i64, _fp, _fp]
+        L.oracle_unpack_uhc_f32.argtypes = [_i64, _i64, _i64, _fp, _fp]
+        L.oracle_ttm_ut_f32.argtypes = [_i64, _i64, _i64, _fp, _fp, _i64, _fp, _dp, _i64, _i64]
         for name in ("pack_triu", "unpack_triu", "pack_tet", "unpack_tet", "pack_band", "unpack_band",
                      "trmv", "trmm", "band_spmv", "tet_ttv", "tet_mttkrp"):
             getattr(L, "oracle_%s_f32" % name).restype = None
@@ -254,3 +257,32 @@ def tet_mttkrp(n, R, Ap, B, C, rows=None):
     sc = np.full((n, R), np.nan, dtype=np.float64)
     lib().oracle_tet_mttkrp_f32(n, R, _f(Ap), _f(B), B.shape[1], _f(C), C.shape[1], _f(M), R, _d(sc), lo, hi)
     return M, sc
+
+
+def pack_uhc(dense: np.ndarray) -> np.ndarray:
+    """dense is M x N x Q; returns the points with i<=j in iteration order (i,j,l)."""
+    dense = _f32(dense)
+    M, N, Q = dense.shape
+    cnt = sum(N - i for i in range(min(M, N))) * Q
+    packed = np.empty(cnt, dtype=np.float32)
+    lib().oracle_pack_uhc_f32(M, N, Q, _f(dense), _f(packed))
+    return packed
+
+
+def unpack_uhc(M: int, N: int, Q: int, packed: np.ndarray) -> np.ndarray:
+    packed = _f32(packed)
+    dense = np.empty((M, N, Q), dtype=np.float32)
+    lib().oracle_unpack_uhc_f32(M, N, Q, _f(packed), _f(dense))
+    return dense
+
+
+def ttm_ut(n, Q, K, Bp, C, rows=None):
+    """A(i,j,k) := B(i,j,l)*C(k,l), i<=j; packed in, packed out.  `rows` windows the (i,j) pairs."""
+    Bp, C = _f32(Bp), _f32(C)
+    pairs = int(triu_row_starts(n)[n])
+    lo, hi = (0, pairs) if rows is None else (int(rows[0]), int(rows[1]))
+    A = np.full(pairs * K, np.nan, dtype=np.float32)
+    sc = np.full(pairs * K, np.nan, dtype=np.float64)
+    lib().oracle_ttm_ut_f32(n, Q, K, _f(Bp), _f(C), C.shape[1] if C.ndim == 2 else Q, _f(A), _d(sc), lo, hi)
+    return A, sc
+

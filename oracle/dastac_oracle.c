@@ -257,6 +257,24 @@ void oracle_unpack_tet_f32(int64_t n, const float *packed, float *dense) {
       for (int64_t k = j; k < n; ++k) dense[(i * n + j) * n + k] = packed[p++];
 }
 
+/* Upper half cube (running example, Fig. 3): (i,j,l) with i<=j, all three extents given; the dense
+ * tensor is M x N x Q row-major.  The same walk packs the rule's output A(i,j,k), whose last
+ * extent is the number of rows of C. */
+void oracle_pack_uhc_f32(int64_t M, int64_t N, int64_t Q, const float *dense, float *packed) {
+  int64_t p = 0;
+  for (int64_t i = 0; i < M; ++i)
+    for (int64_t j = i; j < N; ++j)
+      for (int64_t l = 0; l < Q; ++l) packed[p++] = dense[(i * N + j) * Q + l];
+}
+
+void oracle_unpack_uhc_f32(int64_t M, int64_t N, int64_t Q, const float *packed, float *dense) {
+  for (int64_t t = 0; t < M * N * Q; ++t) dense[t] = 0.0f;
+  int64_t p = 0;
+  for (int64_t i = 0; i < M; ++i)
+    for (int64_t j = i; j < N; ++j)
+      for (int64_t l = 0; l < Q; ++l) dense[(i * N + j) * Q + l] = packed[p++];
+}
+
 /* Band: diagonal d is its own summand with its own n-slot buffer, buffers laid
  * out in summand order d=-w..w; slot i of diagonal d holds A[i][i+d]; padding
  * slots (column outside the matrix) are written as +0. */
@@ -421,3 +439,32 @@ void oracle_tet_mttkrp_f32(int64_t n, int64_t R, const float *Ap, const float *B
   free(acc);
   free(mag);
 }
+
+/* A(i,j,k) := B(i,j,l) * C(k,l),  i<=j   (the running example, Fig. 3; Table 1 TTM with the
+ * upper-half-cube structure).  B is packed in iteration order (i,j,l) and the output A, which
+ * inherits the structure, in iteration order (i,j,k): both positions come from running counters
+ * over the same walk.  C is dense, K x Q row-major with leading dimension ldc.  The window
+ * [r_lo, r_hi) selects (i,j) pairs by their number in iteration order. */
+void oracle_ttm_ut_f32(int64_t n, int64_t Q, int64_t K, const float *Bp, const float *C, int64_t ldc,
+                       float *Ap, double *scale, int64_t r_lo, int64_t r_hi) {
+  int64_t pb = 0, pa = 0, pair = 0;
+  for (int64_t i = 0; i < n; ++i)
+    for (int64_t j = i; j < n; ++j) {
+      if (pair >= r_lo && pair < r_hi) {
+        for (int64_t k = 0; k < K; ++k) {
+          double acc = 0.0, mag = 0.0;
+          for (int64_t l = 0; l < Q; ++l) {
+            double t = (double)Bp[pb + l] * (double)C[k * ldc + l];
+            acc += t;
+            mag += fabs(t);
+          }
+          Ap[pa + k] = (float)acc;
+          if (scale) scale[pa + k] = mag;
+        }
+      }
+      pb += Q;
+      pa += K;
+      ++pair;
+    }
+}
+

@@ -324,3 +324,54 @@ def test_row_windows_agree_with_full_run(oracle):
     b, _ = oracle.band_spmv(n, w, D.ravel(), x)
     b2, _ = oracle.band_spmv(n, w, D.ravel(), x, rows=(4, 9))
     assert np.array_equal(b[4:9], b2[4:9]) and np.isnan(b2[:4]).all()
+
+
+# ------------------------------------------------ running example (TTM_UT) ----
+
+@pytest.mark.parametrize("M,N,Q", [(1, 1, 1), (3, 3, 2), (4, 6, 3), (5, 5, 1), (6, 4, 2)])
+def test_pack_uhc_against_numpy_mask_and_paper_polynomial(oracle, M, N, Q):
+    """Packing the upper half cube keeps exactly the points i<=j, in the order the printed
+    polynomial P_B numbers them (Section 3)."""
+    dense = inputs.uniform(900 + M * 17 + N, M, N, Q)
+    packed = oracle.pack_uhc(dense)
+    i, j, l = np.meshgrid(np.arange(M), np.arange(N), np.arange(Q), indexing="ij")
+    keep = i <= j
+    assert np.array_equal(packed, dense[keep])  # boolean indexing walks (i,j,l) lexicographically
+    for (a, b, c), v in zip(zip(i[keep], j[keep], l[keep]), packed):
+        pb = (N - Fraction(1, 2)) * Q * int(a) - Fraction(1, 2) * Q * int(a) ** 2 + Q * int(b) + int(c)
+        assert pb.denominator == 1 and packed[int(pb)] == v
+    back = oracle.unpack_uhc(M, N, Q, packed)
+    assert np.array_equal(back, np.where(keep, dense, np.float32(0)))
+
+
+@pytest.mark.parametrize("n,Q,K", [(1, 1, 1), (2, 3, 2), (5, 4, 7), (7, 8, 3), (9, 5, 5)])
+def test_ttm_ut_against_dense_einsum_and_packed_gemm(oracle, n, Q, K):
+    """A(i,j,k) := B(i,j,l)*C(k,l), i<=j (Fig. 3): equal to the dense einsum on the masked tensor, and --
+    because B and A are packed with the same (i,j) numbering -- to one dense matrix product over the
+    packed rows."""
+    dense = inputs.uniform(910 + n, n, n, Q)
+    i, j = np.meshgrid(np.arange(n), np.arange(n), indexing="ij")
+    dense[i > j] = 0
+    Bp = oracle.pack_uhc(dense)
+    C = inputs.normal(911 + n, K, Q)
+    A, sc = oracle.ttm_ut(n, Q, K, Bp, C)
+    full = np.einsum("ijl,kl->ijk", dense.astype(np.float64), C.astype(np.float64))
+    assert _close(A, full[i <= j].ravel(), sc)
+    mag = np.einsum("ijl,kl->ijk", np.abs(dense.astype(np.float64)), np.abs(C.astype(np.float64)))
+    assert np.allclose(sc, mag[i <= j].ravel(), rtol=1e-12)
+    gemm = Bp.reshape(-1, Q).astype(np.float64) @ C.astype(np.float64).T
+    assert _close(A, gemm.ravel(), sc)
+    # the output is the upper half cube of extent K, packed by the same rule
+    assert np.array_equal(oracle.unpack_uhc(n, n, K, A)[i <= j].ravel(), A)
+
+
+def test_ttm_ut_identity_and_window(oracle):
+    n, Q = 6, 4
+    Bp = inputs.small_int(920, -4, 4, n * (n + 1) // 2 * Q)
+    A, _ = oracle.ttm_ut(n, Q, Q, Bp, np.eye(Q, dtype=np.float32))
+    assert np.array_equal(A, Bp)  # C = I copies B
+    C = inputs.small_int(921, -3, 3, 5, Q)
+    full, s = oracle.ttm_ut(n, Q, 5, Bp, C)
+    part, s2 = oracle.ttm_ut(n, Q, 5, Bp, C, rows=(4, 9))
+    assert np.array_equal(full[4 * 5: 9 * 5], part[4 * 5: 9 * 5]) and np.isnan(part[: 4 * 5]).all()
+    assert np.isnan(part[9 * 5:]).all() and np.array_equal(s[4 * 5: 9 * 5], s2[4 * 5: 9 * 5])
