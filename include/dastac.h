@@ -7,13 +7,15 @@
  * buffer, in the iteration order of the rule that reads them (Section 4, "Iteration
  * space extraction": iterators in order of appearance, the last one contiguous).
  * The position of an element is the number of domain points that precede it
- * (Section 4, "Access domain linearization"), which for the three domains served
+ * (Section 4, "Access domain linearization"), which for the domains served
  * here is a closed-form polynomial in the indices and the size:
  *
  *   upper triangle   0<=i<=j<n      tri(n,i,j)   = i*n - i*(i-1)/2 + (j-i)
  *                                   (Section 3's printed P_B with Q=1, l=0)
  *   upper tetrahedron 0<=i<=j<=k<n  tet(n,i,j,k) = [Tet(n)-Tet(n-i)] + [Tri(n-i)-Tri(n-j)] + (k-j)
  *                                   Tri(m)=m(m+1)/2, Tet(m)=m(m+1)(m+2)/6
+ *   upper half cube 0<=i<=j<n,      uhc(n,Q,i,j,l) = tri(n,i,j)*Q + l
+ *                   0<=l<Q          (Section 3's printed P_B, the running example's buffer B)
  *   band |j-i|<=w                   band(n,w,d,i) = (d+w)*n + i,  d=j-i
  *                                   one n-slot buffer per diagonal summand (Section 4,
  *                                   per-summand buffers), buffers in order d=-w..w;
@@ -73,6 +75,9 @@ int64_t dastac_band_count(int64_t n, int64_t w);
 int64_t dastac_tri_offset(int64_t n, int64_t i, int64_t j);
 int64_t dastac_tet_offset(int64_t n, int64_t i, int64_t j, int64_t k);
 int64_t dastac_band_offset(int64_t n, int64_t w, int64_t d, int64_t i);
+/* Upper half cube of the running example (i<=j<n, 0<=l<Q; Q >= 1): Tri(n)*Q elements. */
+int64_t dastac_uhc_count(int64_t n, int64_t Q);
+int64_t dastac_uhc_offset(int64_t n, int64_t Q, int64_t i, int64_t j, int64_t l);
 
 /* Inverse polynomials: the unique domain point whose offset is p.  The paper only
  * mentions inverting a quasi-polynomial as costly when done per iteration (Section 7,
@@ -90,13 +95,16 @@ int dastac_tet_inverse(int64_t n, int64_t p, int64_t *i, int64_t *j, int64_t *k)
  *   triu : dense n x n (stride ld)      <-> packed[tri_count(n)]
  *   tet  : dense n x n x n, contiguous  <-> packed[tet_count(n)]
  *   band : dense n x n (stride ld)      <-> diag_major[(2w+1)*n]; pack writes +0.0f into padding slots,
- *                                           unpack ignores them. */
+ *                                           unpack ignores them.
+ *   uhc  : dense n x n x Q, contiguous  <-> packed[uhc_count(n,Q)] */
 int dastac_pack_triu_f32(int64_t n, const float *dense, int64_t ld, float *packed, void *stream);
 int dastac_unpack_triu_f32(int64_t n, const float *packed, float *dense, int64_t ld, void *stream);
 int dastac_pack_tet_f32(int64_t n, const float *dense, float *packed, void *stream);
 int dastac_unpack_tet_f32(int64_t n, const float *packed, float *dense, void *stream);
 int dastac_pack_band_f32(int64_t n, int64_t w, const float *dense, int64_t ld, float *diag_major, void *stream);
 int dastac_unpack_band_f32(int64_t n, int64_t w, const float *diag_major, float *dense, int64_t ld, void *stream);
+int dastac_pack_uhc_f32(int64_t n, int64_t Q, const float *dense, float *packed, void *stream);
+int dastac_unpack_uhc_f32(int64_t n, int64_t Q, const float *packed, float *dense, void *stream);
 
 /* ---- contractions: DEVICE, fp32 storage and arithmetic ---------------------------
  * Summation order is unspecified (the paper compiles with fast-math, Section 6.1);
@@ -126,6 +134,13 @@ int dastac_tet_ttv_f32(int64_t n, const float *Ap, const float *v, float *Mp, vo
  * 1 <= R <= 32. */
 int dastac_tet_mttkrp_f32(int64_t n, int64_t R, const float *Ap, const float *B, int64_t ldb, const float *C,
                           int64_t ldc, float *M, int64_t ldm, void *stream);
+
+/* A(i,j,k) := B(i,j,l) * C(k,l), i<=j, 0<=l<Q, 0<=k<K   (the running example, Fig. 3; Table 1 TTM with
+ * the upper-half-cube structure, TTM_UT).  Bp[uhc_count(n,Q)] is packed; C is K x Q row-major with row
+ * stride ldc >= Q; the output inherits the structure and is packed by the same rule:
+ * Ap[uhc_count(n,K)] with A(i,j,k) at uhc(n,K,i,j,k).  Q, K >= 1. */
+int dastac_ttm_ut_f32(int64_t n, int64_t Q, int64_t K, const float *Bp, const float *C, int64_t ldc, float *Ap,
+                      void *stream);
 
 #ifdef __cplusplus
 }

@@ -43,6 +43,11 @@ SIGNATURES = {
     "dastac_band_spmv_f32": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp, _vp]),
     "dastac_tet_ttv_f32": (ctypes.c_int, [_i64, _vp, _vp, _vp, _vp]),
     "dastac_tet_mttkrp_f32": (ctypes.c_int, [_i64, _i64, _vp, _vp, _i64, _vp, _i64, _vp, _i64, _vp]),
+    "dastac_uhc_count": (_i64, [_i64, _i64]),
+    "dastac_uhc_offset": (_i64, [_i64, _i64, _i64, _i64, _i64]),
+    "dastac_pack_uhc_f32": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp]),
+    "dastac_unpack_uhc_f32": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp]),
+    "dastac_ttm_ut_f32": (ctypes.c_int, [_i64, _i64, _i64, _vp, _vp, _i64, _vp, _vp]),
 }
 
 
@@ -167,3 +172,19 @@ def tet_ttv_f32(n, Ap, v, Mp, stream=None):
 def tet_mttkrp_f32(n, R, Ap, B, ldb, C, ldc, M, ldm, stream=None):
     _check(lib().dastac_tet_mttkrp_f32(n, R, _ptr(Ap), _ptr(B), ldb, _ptr(C), ldc, _ptr(M), ldm, _stream(stream)),
            "tet_mttkrp_f32")
+
+
+def uhc_count(n, Q): return int(lib().dastac_uhc_count(n, Q))
+def uhc_offset(n, Q, i, j, l): return int(lib().dastac_uhc_offset(n, Q, i, j, l))
+
+
+def pack_uhc_f32(n, Q, dense, packed, stream=None):
+    _check(lib().dastac_pack_uhc_f32(n, Q, _ptr(dense), _ptr(packed), _stream(stream)), "pack_uhc_f32")
+
+
+def unpack_uhc_f32(n, Q, packed, dense, stream=None):
+    _check(lib().dastac_unpack_uhc_f32(n, Q, _ptr(packed), _ptr(dense), _stream(stream)), "unpack_uhc_f32")
+
+
+def ttm_ut_f32(n, Q, K, Bp, C, ldc, Ap, stream=None):
+    _check(lib().dastac_ttm_ut_f32(n, Q, K, _ptr(Bp), _ptr(C), ldc, _ptr(Ap), _stream(stream)), "ttm_ut_f32")

@@ -1,4 +1,5 @@
-"""The five benchmark workloads: sizes, seeds, and FLOP / byte accounting.
+"""The five benchmark workloads (and the running example measured beside them): sizes, seeds, and
+FLOP / byte accounting.
 
 Inputs only (host NumPy arrays from ``inputs``); nothing here computes a
 contraction or a packed offset.  Config c, tensor t uses stream seed
@@ -47,6 +48,12 @@ def mttkrp_inputs(n: int = 1024, R: int = 32):
             "B": inputs.normal(_seed(5, 1), n, R), "C": inputs.normal(_seed(5, 2), n, R)}
 
 
+def ttm_ut_inputs(n: int = 512, Q: int = 256, K: int = 256):
+    """The paper's running example (Fig. 3) at a size whose packed operand (134 MB) and packed result
+    (134 MB) leave the caches; stream seeds of "config 6"."""
+    return {"n": n, "Q": Q, "K": K, "Bp": inputs.uniform(_seed(6, 0), _tri(n) * Q), "C": inputs.normal(_seed(6, 1), K, Q)}
+
+
 def accounting(name: str, **kw) -> dict:
     """Useful FLOPs and algorithmic bytes of one launch."""
     if name == "trmv":
@@ -66,4 +73,7 @@ def accounting(name: str, **kw) -> dict:
         n, R = kw["n"], kw["R"]
         return {"flops": 2 * R * _tet(n) + 2 * R * _tri(n), "flops_paper_convention": 3 * R * _tet(n),
                 "bytes": 4 * (_tet(n) + 3 * n * R)}
+    if name == "ttm_ut":
+        n, Q, K = kw["n"], kw["Q"], kw["K"]
+        return {"flops": 2 * _tri(n) * Q * K, "bytes": 4 * (_tri(n) * (Q + K) + K * Q)}
     raise ValueError(name)

@@ -97,3 +97,20 @@ def test_c5_mttkrp_1024_sampled_slices(gpu, oracle):
     for i in rows:
         want, scale = oracle.tet_mttkrp(n, R, w["Ap"], w["B"], w["C"], rows=(i, i + 1))
         check(got[i], want[i], scale[i], "C5 mttkrp slice %d" % i)
+
+
+def test_running_example_ttm_ut_512_sampled_pairs(gpu, oracle):
+    """The paper's running example at the size bench.py reports beside the five configurations."""
+    w = wl.ttm_ut_inputs()
+    n, Q, K = w["n"], w["Q"], w["K"]
+    pairs = n * (n + 1) // 2
+    A = gpu.empty(pairs * K)
+    gpu.d.ttm_ut_f32(n, Q, K, gpu.up(w["Bp"]), gpu.up(w["C"]), Q, A)
+    got = gpu.down(A)
+    assert np.isfinite(got).all()
+    rng = np.random.default_rng(6)
+    for p in sorted({0, 1, 63, 64, 65, 511, 512, pairs - 65, pairs - 64, pairs - 2, pairs - 1}
+                    | {int(r) for r in rng.integers(0, pairs, 20)}):
+        want, scale = oracle.ttm_ut(n, Q, K, w["Bp"], w["C"], rows=(p, p + 1))
+        check(got[p * K: (p + 1) * K], want[p * K: (p + 1) * K], scale[p * K: (p + 1) * K], "ttm_ut pair %d" % p)
+

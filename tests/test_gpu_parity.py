@@ -207,6 +207,47 @@ def test_trmm_leading_dimensions_and_integer_exactness(gpu, oracle):
     assert np.isnan(out[:, m:]).all()
 
 
+# ------------------------------------------------- running example (TTM_UT) ----
+
+@pytest.mark.parametrize("n,Q", [(1, 1), (3, 2), (9, 5), (17, 256), (24, 300), (40, 64)])
+def test_pack_unpack_uhc_bit_exact(gpu, oracle, n, Q):
+    D = inputs.uniform(140 + n, n, n, Q)
+    want = oracle.pack_uhc(D)
+    dP = gpu.empty(tri(n) * Q)
+    gpu.d.pack_uhc_f32(n, Q, gpu.up(D), dP)
+    assert gpu.down(dP).tobytes() == want.tobytes()
+    dD = gpu.empty(n, n, Q)
+    gpu.d.unpack_uhc_f32(n, Q, dP, dD)
+    assert gpu.down(dD).tobytes() == oracle.unpack_uhc(n, n, Q, want).tobytes()
+
+
+@pytest.mark.parametrize("n,Q,K", [(1, 1, 1), (2, 3, 5), (5, 32, 128), (11, 33, 129), (12, 31, 127), (16, 64, 64),
+                                   (23, 100, 40), (30, 7, 300), (40, 260, 130), (64, 96, 256)])
+def test_ttm_ut_parity(gpu, oracle, n, Q, K):
+    Bp, C = inputs.uniform(150 + n, tri(n) * Q), inputs.normal(151 + n, K, Q)
+    want, scale = oracle.ttm_ut(n, Q, K, Bp, C)
+    A = gpu.empty(tri(n) * K)
+    gpu.d.ttm_ut_f32(n, Q, K, gpu.up(Bp), gpu.up(C), Q, A)
+    assert_within(gpu.down(A), want, scale, "ttm_ut n=%d Q=%d K=%d" % (n, Q, K))
+
+
+def test_ttm_ut_leading_dimension_integer_exactness_and_identity(gpu, oracle):
+    n, Q, K, ldc = 21, 45, 70, 52
+    Bp = inputs.small_int(160, -3, 3, tri(n) * Q)
+    C = inputs.small_int(161, -3, 3, K, ldc)
+    want, _ = oracle.ttm_ut(n, Q, K, Bp, np.ascontiguousarray(C[:, :Q]))
+    A = gpu.empty(tri(n) * K + 8)
+    gpu.d.ttm_ut_f32(n, Q, K, gpu.up(Bp), gpu.up(C), ldc, A)
+    out = gpu.down(A)
+    assert out[: tri(n) * K].tobytes() == want.tobytes()
+    assert np.isnan(out[tri(n) * K:]).all()  # nothing past the packed result is written
+    # C = identity copies the packed operand into the packed result
+    Bq = inputs.uniform(162, tri(n) * Q)
+    A2 = gpu.empty(tri(n) * Q)
+    gpu.d.ttm_ut_f32(n, Q, Q, gpu.up(Bq), gpu.up(np.eye(Q, dtype=np.float32)), Q, A2)
+    assert gpu.down(A2).tobytes() == Bq.tobytes()
+
+
 # ------------------------------------------------------------------- MTTKRP ----
 
 @pytest.mark.parametrize("n,R", [(1, 1), (2, 32), (5, 3), (31, 32), (33, 32), (64, 32), (70, 17), (100, 32),

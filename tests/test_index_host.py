@@ -73,6 +73,22 @@ def test_band_offsets_match_counting(oracle, n, w):
     assert dastac.band_count(-1, 0) == -1 and dastac.band_count(1, -1) == -1
 
 
+@pytest.mark.parametrize("n,Q", [(1, 1), (4, 3), (6, 2), (5, 7)])
+def test_uhc_offsets_match_counting_and_paper_polynomial(oracle, n, Q):
+    """uhc(n,Q,i,j,l) is the number of preceding points of the running example's buffer B, i.e. the
+    printed P_B(i,j,l) = (((N-1/2) Q i - 1/2 Q i^2) + Q j) + l."""
+    from fractions import Fraction
+    assert dastac.uhc_count(n, Q) == oracle.count_domain(oracle.DOM_UHC, [n, n, Q]) == n * (n + 1) // 2 * Q
+    for i in range(n):
+        for j in range(i, n):
+            for l in range(Q):
+                got = dastac.uhc_offset(n, Q, i, j, l)
+                assert got == oracle.count_preceding(oracle.DOM_UHC, [n, n, Q], [i, j, l])
+                assert got == (n - Fraction(1, 2)) * Q * i - Fraction(1, 2) * Q * i * i + Q * j + l
+    assert dastac.uhc_offset(n, Q, 0, 0, Q) == -1 and dastac.uhc_offset(n, Q, n - 1, n, 0) == -1
+    assert dastac.uhc_count(-1, 1) == -1 and dastac.uhc_count(4, 0) == -1 and dastac.uhc_count(2 ** 20, 2 ** 24) == -1
+
+
 def test_benchmark_sizes_row_and_slice_boundaries(oracle):
     """Forward and inverse at every row start of the large triangle and every fibre start of
     the large tetrahedron, against the oracle's running-counter walk."""
@@ -142,6 +158,17 @@ def test_device_entry_points_reject_bad_arguments():
     assert L.dastac_tet_mttkrp_f32(4, 0, _p(A), _p(B), 4, _p(C), 4, _p(D), 4, None) == dastac.EINVAL
     assert L.dastac_tet_mttkrp_f32(4, 33, _p(A), _p(B), 33, _p(C), 33, _p(D), 33, None) == dastac.EINVAL
     assert L.dastac_tet_mttkrp_f32(4, 8, _p(A), _p(B), 8, _p(C), 8, _p(D), 7, None) == dastac.EINVAL
+    assert L.dastac_ttm_ut_f32(-1, 4, 4, _p(A), _p(B), 4, _p(C), None) == dastac.EINVAL
+    assert L.dastac_ttm_ut_f32(4, 0, 4, _p(A), _p(B), 4, _p(C), None) == dastac.EINVAL
+    assert L.dastac_ttm_ut_f32(4, 4, 0, _p(A), _p(B), 4, _p(C), None) == dastac.EINVAL
+    assert L.dastac_ttm_ut_f32(4, 8, 4, _p(A), _p(B), 7, _p(C), None) == dastac.EINVAL
+    assert L.dastac_pack_uhc_f32(4, 0, _p(A), _p(B), None) == dastac.EINVAL
+    assert L.dastac_ttm_ut_f32(2 ** 20, 2 ** 24, 4, _p(A), _p(B), 2 ** 24, _p(C), None) == dastac.EOVERFLOW
+    assert L.dastac_ttm_ut_f32(4, 4, 4, None, _p(B), 4, _p(C), None) == dastac.ENULL
+    assert L.dastac_ttm_ut_f32(4, 4, 4, _p(A), _p(B), 4, None, None) == dastac.ENULL
+    assert L.dastac_unpack_uhc_f32(4, 2, _p(A), None, None) == dastac.ENULL
+    assert L.dastac_ttm_ut_f32(4, 4, 4, _p(A), _p(B), 4, _p(A + 16), None) == dastac.EALIAS
+    assert L.dastac_ttm_ut_f32(0, 4, 4, None, None, 4, None, None) == dastac.OK
     # overflow guards
     assert L.dastac_tet_ttv_f32(2 ** 20 + 1, _p(A), _p(B), _p(C), None) == dastac.EOVERFLOW
     assert L.dastac_trmv_f32(2 ** 31, _p(A), _p(B), _p(C), None) == dastac.EOVERFLOW
