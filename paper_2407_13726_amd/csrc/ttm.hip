@@ -19,7 +19,9 @@
 // taking the four consecutive l values 8t+4h..8t+4h+3 of every group of eight, as in the TRMM
 // kernel -- both operands of v_mfma_f32_32x32x2_f32 are single 16-byte LDS reads.  Workgroups
 // that share a row block (different blocks of k) get ids that are equal modulo 8, i.e. the same
-// XCD, so the rows of Bp they both read come from HBM once.
+// XCD, so the rows of Bp they both read come from HBM once.  About two workgroups per compute unit
+// are launched; each walks a strided set of row blocks with one uninterrupted pipeline, so the
+// first loads of a row block are in flight while the previous block's last step is multiplied.
 #include "common.h"
 
 using namespace dastac;
@@ -42,16 +44,16 @@ struct Stage {
 __global__ __launch_bounds__(kBlock) void ttm_mfma_kernel(int64_t rows, int64_t Q, int64_t K,
                                                           const float *__restrict__ Bp,
                                                           const float *__restrict__ C, int64_t ldc,
-                                                          float *__restrict__ Ap, int nrb, int ncb) {
+                                                          float *__restrict__ Ap, int lanes, int ncb) {
   __shared__ __attribute__((aligned(16))) float As[2][kBM * kP];
   __shared__ __attribute__((aligned(16))) float Cs[2][kBN * kP];
 
-  // workgroup id -> (row block, block of k); ids equal mod 8 share an XCD
+  // workgroup id -> (first row block, block of k); ids equal mod 8 share an XCD.  A workgroup
+  // then walks every (8*lanes)-th row block, keeping its pipeline full across blocks.
   const int L = blockIdx.x;
   const int xcd = L & 7, slot = L >> 3;
-  const int rb = xcd + 8 * (slot / ncb);
   const int cb = slot % ncb;
-  if (rb >= nrb) return;
+  const int64_t rstride = (int64_t)kBM * 8 * lanes;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave >> 2, wc = wave & 3;  // 2x4 wavefronts: 32 rows x 32 values of k each
@@ -59,17 +61,34 @@ __global__ __launch_bounds__(kBlock) void ttm_mfma_kernel(int64_t rows, int64_t 
 
   // staging role: tile row tid/8 (and +64 for C), l offset 4*(tid%8)
   const int sr = tid >> 3, sl = (tid & 7) * 4;
-  const int64_t r0 = (int64_t)rb * kBM, c0 = (int64_t)cb * kBN;
-  const bool full_rc = r0 + kBM <= rows && c0 + kBN <= K;
+  const int64_t c0 = (int64_t)cb * kBN;
+  const bool full_c = c0 + kBN <= K;
   const int nk = (int)ceil_div(Q, kKT);
 
-  const float *ap = Bp + (r0 + sr < rows ? r0 + sr : rows - 1) * Q;
   const float *cp0 = C + (c0 + sr < K ? c0 + sr : K - 1) * ldc;
   const float *cp1 = C + (c0 + sr + 64 < K ? c0 + sr + 64 : K - 1) * ldc;
 
-  auto load_stage = [&](int kt, Stage &s) {
-    const int64_t l0 = (int64_t)kt * kKT + sl;
-    if (full_rc && (int64_t)kt * kKT + kKT <= Q) {
+  struct Cur {  // wave-uniform cursor over the steps of this workgroup: row block, step along l
+    int64_t r0;
+    int kt;
+    bool valid;
+  };
+  auto next = [&](Cur c) -> Cur {
+    if (!c.valid) return c;
+    if (c.kt + 1 < nk) {
+      c.kt += 1;
+    } else {
+      c.kt = 0;
+      c.r0 += rstride;
+      c.valid = c.r0 < rows;
+    }
+    return c;
+  };
+
+  auto load_stage = [&](const Cur &cu, Stage &s) {
+    const int64_t l0 = (int64_t)cu.kt * kKT + sl;
+    const float *ap = Bp + (cu.r0 + sr < rows ? cu.r0 + sr : rows - 1) * Q;
+    if (full_c && cu.r0 + kBM <= rows && (int64_t)cu.kt * kKT + kKT <= Q) {
       s.a = *reinterpret_cast<const f4u *>(ap + l0);
       s.c[0] = *reinterpret_cast<const f4u *>(cp0 + l0);
       s.c[1] = *reinterpret_cast<const f4u *>(cp1 + l0);
@@ -78,7 +97,7 @@ __global__ __launch_bounds__(kBlock) void ttm_mfma_kernel(int64_t rows, int64_t 
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const bool lok = l0 + e < Q;
-        a[e] = (lok && r0 + sr < rows) ? ap[l0 + e] : 0.0f;
+        a[e] = (lok && cu.r0 + sr < rows) ? ap[l0 + e] : 0.0f;
         u[e] = (lok && c0 + sr < K) ? cp0[l0 + e] : 0.0f;
         v[e] = (lok && c0 + sr + 64 < K) ? cp1[l0 + e] : 0.0f;
       }
@@ -112,19 +131,25 @@ __global__ __launch_bounds__(kBlock) void ttm_mfma_kernel(int64_t rows, int64_t 
     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(o.a.w, o.c.w, acc, 0, 0, 0);
   };
 
+  Cur cc{(int64_t)kBM * (xcd + 8 * (slot / ncb)), 0, true};  // the step being multiplied
+  cc.valid = cc.r0 < rows;
+  if (!cc.valid) return;
+  Cur cl = cc;  // the step being loaded: one ahead
   Stage st;
   Ops oa, ob;
-  load_stage(0, st);
+  load_stage(cl, st);
   store_stage(0, st);
   __syncthreads();
   read_ops(0, 0, oa);
 
   // One step on LDS buffer `buf` (a literal at both call sites).  The global loads of the next
-  // step are in flight throughout; its LDS stores and the workgroup barrier sit before the last
-  // group's matrix instructions, whose operands are already in registers.
-  auto step = [&](int kt, int buf) {
-    const bool more = kt + 1 < nk;
-    if (more) load_stage(kt + 1, st);
+  // step -- of the next row block, at a block's last step -- are in flight throughout; its LDS
+  // stores and the workgroup barrier sit before the last group's matrix instructions, whose
+  // operands are already in registers.
+  auto step = [&](int buf) {
+    cl = next(cl);
+    const bool more = cl.valid;
+    if (more) load_stage(cl, st);
     read_ops(buf, 1, ob);
     mma(oa);
     read_ops(buf, 2, oa);
@@ -135,18 +160,23 @@ __global__ __launch_bounds__(kBlock) void ttm_mfma_kernel(int64_t rows, int64_t 
     __syncthreads();
     if (more) read_ops(buf ^ 1, 0, oa);
     mma(ob);
-  };
-  for (int kt = 0; kt < nk; kt += 2) {
-    step(kt, 0);
-    if (kt + 1 < nk) step(kt + 1, 1);
-  }
-
-  // D layout of the 32x32 tile: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32
-  const int64_t col = c0 + wc * 32 + l32;
+    if (cc.kt == nk - 1) {
+      // D layout of the 32x32 tile: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32
+      const int64_t col = c0 + wc * 32 + l32;
 #pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    const int64_t r = r0 + wr * 32 + 8 * (v / 4) + 4 * h + (v % 4);
-    if (r < rows && col < K) Ap[r * K + col] = acc[v];
+      for (int v = 0; v < 16; ++v) {
+        const int64_t r = cc.r0 + wr * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+        if (r < rows && col < K) Ap[r * K + col] = acc[v];
+        acc[v] = 0.0f;
+      }
+    }
+    cc = next(cc);
+  };
+  for (;;) {
+    step(0);
+    if (!cc.valid) break;
+    step(1);
+    if (!cc.valid) break;
   }
 }
 
@@ -221,9 +251,12 @@ int dastac_ttm_ut_f32(int64_t n, int64_t Q, int64_t K, const float *Bp, const fl
   const int64_t rows = tri(n);
   if (overlaps(Ap, rows * K * 4, Bp, rows * Q * 4) || overlaps(Ap, rows * K * 4, C, K * ldc * 4)) return DASTAC_EALIAS;
   const int64_t nrb = ceil_div(rows, kBM), ncb = ceil_div(K, kBN);
-  const int64_t grid = 8 * ceil_div(nrb, 8) * ncb;
-  if (grid > 0x7fffffff || nrb > 0x7fffffff) return DASTAC_EOVERFLOW;
-  ttm_mfma_kernel<<<(unsigned)grid, kBlock, 0, (hipStream_t)stream>>>(rows, Q, K, Bp, C, ldc, Ap, (int)nrb, (int)ncb);
+  if (ncb > (1 << 20)) return DASTAC_EOVERFLOW;
+  // about two workgroups per compute unit (256 of them), each walking a strided set of row blocks
+  int64_t lanes = ceil_div(512, 8 * ncb);
+  if (lanes > ceil_div(nrb, 8)) lanes = ceil_div(nrb, 8);
+  const int64_t grid = 8 * lanes * ncb;
+  ttm_mfma_kernel<<<(unsigned)grid, kBlock, 0, (hipStream_t)stream>>>(rows, Q, K, Bp, C, ldc, Ap, (int)lanes, (int)ncb);
   return launch_status();
 }
 
