@@ -175,8 +175,8 @@ def main() -> int:
         "kernels": kernels,
     }
 
-    # Measured beside the step, never part of `value`: the paper's running example (TTM_UT), which is
-    # not one of the five benchmark configurations.
+    # Measured beside the step, never part of `value`: the paper's running example (TTM_UT) and the
+    # symmetric product on a packed triangle, which are not among the five benchmark configurations.
     tw = wl.ttm_ut_inputs()
     nt, Qt, Kt = tw["n"], tw["Q"], tw["K"]
     gB, gC, gA = up(tw["Bp"]), up(tw["C"]), out(nt * (nt + 1) // 2 * Kt)
@@ -194,6 +194,23 @@ def main() -> int:
                                    "gflops": ta["flops"] / tms / 1e6, "gbps": ta["bytes"] / tms / 1e6, "bound": "mfma",
                                    "frac": ta["flops"] / tms / 1e9 / MFMA_F32_PEAK_TFLOPS}}
     del gB, gA
+    sw = wl.symv_inputs()
+    ns = sw["n"]
+    gU, gx, gy = up(sw["Up"]), up(sw["x"]), out(ns)
+    for _ in range(args.warmup):
+        d.symv_f32(ns, gU, gx, gy)
+    sev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    sev[0].record()
+    for s in range(args.steps):
+        d.symv_f32(ns, gU, gx, gy)
+        sev[s + 1].record()
+    torch.cuda.synchronize()
+    sms = float(np.mean([sev[s].elapsed_time(sev[s + 1]) for s in range(args.steps)]))
+    sa = wl.accounting("symv", n=ns)
+    result["beside"]["symv"] = {"workload": "SYMV n=%d on the packed upper triangle" % ns, "ms": sms,
+                                "gflops": sa["flops"] / sms / 1e6, "gbps": sa["bytes"] / sms / 1e6, "bound": "hbm",
+                                "frac": sa["bytes"] / sms / 1e6 / HBM_PEAK_GBPS}
+    del gU
 
     if not args.no_cpu_baseline:
         import oracle

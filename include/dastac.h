@@ -114,6 +114,12 @@ int dastac_unpack_uhc_f32(int64_t n, int64_t Q, const float *packed, float *dens
 /* y(i) := U(i,j) * x(j), i<=j   (Table 1/2, SpMV_UT).  Up[tri_count(n)], x[n], y[n]. */
 int dastac_trmv_f32(int64_t n, const float *Up, const float *x, float *y, void *stream);
 
+/* y(i) := S(i,j) * x(j), S symmetric with its unique elements S(i,j), i<=j, packed as an upper triangle
+ * (Section 3, "Redundancy map": the other half is reached by swapping the two indices).  Every packed
+ * element is read once and used twice.  Up[tri_count(n)], x[n], y[n]; n <= 65536 (beyond: DASTAC_EOVERFLOW).
+ * The output is accumulated with floating-point atomics, so its last bits may differ between calls. */
+int dastac_symv_f32(int64_t n, const float *Up, const float *x, float *y, void *stream);
+
 /* C(i,c) := U(i,k) * B(k,c), i<=k, 0<=c<m  (the SpMV_UT rule with a matrix right-hand side).
  * B is n x m row-major with row stride ldb >= m, C is n x m with row stride ldc >= m; m >= 1. */
 int dastac_trmm_f32(int64_t n, int64_t m, const float *Up, const float *B, int64_t ldb, float *C, int64_t ldc,

@@ -77,6 +77,7 @@ def lib() -> ctypes.CDLL:
         L.oracle_tet_mttkrp_f32.argtypes = [_i64, _i64, _fp, _fp, _i64, _fp, _i64, _fp, _i64, _dp, _i64, _i64]
         L.oracle_pack_uhc_f32.argtypes = [_i64, _i64, _i64, _fp, _fp]
         L.oracle_unpack_uhc_f32.argtypes = [_i64, _i64, _i64, _fp, _fp]
+        L.oracle_symv_f32.argtypes = [_i64, _fp, _fp, _fp, _dp, _i64, _i64]
         L.oracle_ttm_ut_f32.argtypes = [_i64, _i64, _i64, _fp, _fp, _i64, _fp, _dp, _i64, _i64]
         for name in ("pack_triu", "unpack_triu", "pack_tet", "unpack_tet", "pack_band", "unpack_band",
                      "trmv", "trmm", "band_spmv", "tet_ttv", "tet_mttkrp"):
@@ -285,4 +286,14 @@ def ttm_ut(n, Q, K, Bp, C, rows=None):
     sc = np.full(pairs * K, np.nan, dtype=np.float64)
     lib().oracle_ttm_ut_f32(n, Q, K, _f(Bp), _f(C), C.shape[1] if C.ndim == 2 else Q, _f(A), _d(sc), lo, hi)
     return A, sc
+
+
+def symv(n, Up, x, rows=None):
+    """y = S x, S symmetric with its upper triangle packed in Up."""
+    Up, x = _f32(Up), _f32(x)
+    lo, hi = _window(n, rows)
+    y = np.full(n, np.nan, dtype=np.float32)
+    sc = np.full(n, np.nan, dtype=np.float64)
+    lib().oracle_symv_f32(n, _f(Up), _f(x), _f(y), _d(sc), lo, hi)
+    return y, sc
 

@@ -468,3 +468,25 @@ void oracle_ttm_ut_f32(int64_t n, int64_t Q, int64_t K, const float *Bp, const f
     }
 }
 
+/* y(i) := S(i,j) * x(j) for the symmetric matrix whose unique elements are the packed upper
+ * triangle (Section 3, "Redundancy map": an index pair outside the unique set is swapped to reach
+ * its unique element).  Positions of the unique elements come from the running-counter row starts. */
+void oracle_symv_f32(int64_t n, const float *Up, const float *x, float *y, double *scale,
+                     int64_t r_lo, int64_t r_hi) {
+  int64_t *start = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n + 1));
+  oracle_triu_row_starts(n, start);
+  for (int64_t i = 0; i < n; ++i) {
+    if (i < r_lo || i >= r_hi) continue;
+    double acc = 0.0, mag = 0.0;
+    for (int64_t j = 0; j < n; ++j) {
+      int64_t a = i <= j ? i : j, b = i <= j ? j : i; /* the unique representative (a,b), a<=b */
+      double t = (double)Up[start[a] + (b - a)] * (double)x[j];
+      acc += t;
+      mag += fabs(t);
+    }
+    y[i] = (float)acc;
+    if (scale) scale[i] = mag;
+  }
+  free(start);
+}
+

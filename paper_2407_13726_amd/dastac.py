@@ -43,6 +43,7 @@ SIGNATURES = {
     "dastac_band_spmv_f32": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp, _vp]),
     "dastac_tet_ttv_f32": (ctypes.c_int, [_i64, _vp, _vp, _vp, _vp]),
     "dastac_tet_mttkrp_f32": (ctypes.c_int, [_i64, _i64, _vp, _vp, _i64, _vp, _i64, _vp, _i64, _vp]),
+    "dastac_symv_f32": (ctypes.c_int, [_i64, _vp, _vp, _vp, _vp]),
     "dastac_uhc_count": (_i64, [_i64, _i64]),
     "dastac_uhc_offset": (_i64, [_i64, _i64, _i64, _i64, _i64]),
     "dastac_pack_uhc_f32": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp]),
@@ -188,3 +189,8 @@ def unpack_uhc_f32(n, Q, packed, dense, stream=None):
 
 def ttm_ut_f32(n, Q, K, Bp, C, ldc, Ap, stream=None):
     _check(lib().dastac_ttm_ut_f32(n, Q, K, _ptr(Bp), _ptr(C), ldc, _ptr(Ap), _stream(stream)), "ttm_ut_f32")
+
+
+def symv_f32(n, Up, x, y, stream=None):
+    _check(lib().dastac_symv_f32(n, _ptr(Up), _ptr(x), _ptr(y), _stream(stream)), "symv_f32")
+

@@ -54,6 +54,11 @@ def ttm_ut_inputs(n: int = 512, Q: int = 256, K: int = 256):
     return {"n": n, "Q": Q, "K": K, "Bp": inputs.uniform(_seed(6, 0), _tri(n) * Q), "C": inputs.normal(_seed(6, 1), K, Q)}
 
 
+def symv_inputs(n: int = 8192):
+    """A symmetric matrix as its packed upper triangle (134 MB), stream seeds of "config 7"."""
+    return {"n": n, "Up": inputs.uniform(_seed(7, 0), _tri(n)), "x": inputs.uniform(_seed(7, 1), n)}
+
+
 def accounting(name: str, **kw) -> dict:
     """Useful FLOPs and algorithmic bytes of one launch."""
     if name == "trmv":
@@ -73,6 +78,9 @@ def accounting(name: str, **kw) -> dict:
         n, R = kw["n"], kw["R"]
         return {"flops": 2 * R * _tet(n) + 2 * R * _tri(n), "flops_paper_convention": 3 * R * _tet(n),
                 "bytes": 4 * (_tet(n) + 3 * n * R)}
+    if name == "symv":  # every unique element is used twice, the diagonal once
+        n = kw["n"]
+        return {"flops": 2 * n * n, "bytes": 4 * (_tri(n) + 2 * n)}
     if name == "ttm_ut":
         n, Q, K = kw["n"], kw["Q"], kw["K"]
         return {"flops": 2 * _tri(n) * Q * K, "bytes": 4 * (_tri(n) * (Q + K) + K * Q)}

@@ -114,3 +114,12 @@ def test_running_example_ttm_ut_512_sampled_pairs(gpu, oracle):
         want, scale = oracle.ttm_ut(n, Q, K, w["Bp"], w["C"], rows=(p, p + 1))
         check(got[p * K: (p + 1) * K], want[p * K: (p + 1) * K], scale[p * K: (p + 1) * K], "ttm_ut pair %d" % p)
 
+
+def test_symv_8192(gpu, oracle):
+    """The symmetric product at the size bench.py reports beside the five configurations."""
+    w = wl.symv_inputs()
+    want, scale = oracle.symv(w["n"], w["Up"], w["x"])
+    y = gpu.empty(w["n"])
+    gpu.d.symv_f32(w["n"], gpu.up(w["Up"]), gpu.up(w["x"]), y)
+    check(gpu.down(y), want, scale, "symv 8192")
+

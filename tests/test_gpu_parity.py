@@ -207,6 +207,28 @@ def test_trmm_leading_dimensions_and_integer_exactness(gpu, oracle):
     assert np.isnan(out[:, m:]).all()
 
 
+# ------------------------------------------------------ symmetric (SYMV) ----
+
+@pytest.mark.parametrize("n", [1, 2, 3, 5, 16, 17, 63, 64, 65, 130, 257, 512, 1000, 1025, 2050, 4100, 8192])
+def test_symv_parity(gpu, oracle, n):
+    Up, x = inputs.uniform(170 + n, tri(n)), inputs.uniform(171 + n, n)
+    want, scale = oracle.symv(n, Up, x)
+    y = gpu.empty(n)
+    gpu.d.symv_f32(n, gpu.up(Up), gpu.up(x), y)
+    assert_within(gpu.down(y), want, scale, "symv n=%d" % n)
+
+
+@pytest.mark.parametrize("n", [1, 7, 130, 515, 1500])
+def test_symv_integer_inputs_bit_exact_and_repeatable(gpu, oracle, n):
+    Up, x = inputs.small_int(180 + n, -3, 3, tri(n)), inputs.small_int(181 + n, -3, 3, n)
+    want, _ = oracle.symv(n, Up, x)
+    y = gpu.empty(n)
+    dU, dx = gpu.up(Up), gpu.up(x)
+    for _ in range(2):  # the output is overwritten, not accumulated into, on every call
+        gpu.d.symv_f32(n, dU, dx, y)
+        assert gpu.down(y).tobytes() == want.tobytes()
+
+
 # ------------------------------------------------- running example (TTM_UT) ----
 
 @pytest.mark.parametrize("n,Q", [(1, 1), (3, 2), (9, 5), (17, 256), (24, 300), (40, 64)])

@@ -158,6 +158,11 @@ def test_device_entry_points_reject_bad_arguments():
     assert L.dastac_tet_mttkrp_f32(4, 0, _p(A), _p(B), 4, _p(C), 4, _p(D), 4, None) == dastac.EINVAL
     assert L.dastac_tet_mttkrp_f32(4, 33, _p(A), _p(B), 33, _p(C), 33, _p(D), 33, None) == dastac.EINVAL
     assert L.dastac_tet_mttkrp_f32(4, 8, _p(A), _p(B), 8, _p(C), 8, _p(D), 7, None) == dastac.EINVAL
+    assert L.dastac_symv_f32(-1, _p(A), _p(B), _p(C), None) == dastac.EINVAL
+    assert L.dastac_symv_f32(65537, _p(A), _p(B), _p(C), None) == dastac.EOVERFLOW
+    assert L.dastac_symv_f32(4, _p(A), None, _p(C), None) == dastac.ENULL
+    assert L.dastac_symv_f32(4, _p(A), _p(B), _p(A + 8), None) == dastac.EALIAS
+    assert L.dastac_symv_f32(0, None, None, None, None) == dastac.OK
     assert L.dastac_ttm_ut_f32(-1, 4, 4, _p(A), _p(B), 4, _p(C), None) == dastac.EINVAL
     assert L.dastac_ttm_ut_f32(4, 0, 4, _p(A), _p(B), 4, _p(C), None) == dastac.EINVAL
     assert L.dastac_ttm_ut_f32(4, 4, 0, _p(A), _p(B), 4, _p(C), None) == dastac.EINVAL

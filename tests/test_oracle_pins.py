@@ -375,3 +375,36 @@ def test_ttm_ut_identity_and_window(oracle):
     part, s2 = oracle.ttm_ut(n, Q, 5, Bp, C, rows=(4, 9))
     assert np.array_equal(full[4 * 5: 9 * 5], part[4 * 5: 9 * 5]) and np.isnan(part[: 4 * 5]).all()
     assert np.isnan(part[9 * 5:]).all() and np.array_equal(s[4 * 5: 9 * 5], s2[4 * 5: 9 * 5])
+
+
+# ------------------------------------------------------ symmetric (redundancy map) ----
+
+@pytest.mark.parametrize("n", [1, 2, 3, 8, 17, 24])
+def test_symv_against_dense_numpy_and_trmv_identity(oracle, n):
+    """Section 3, redundancy map of a symmetric matrix: the packed triangle stands for U + U^T - diag(U)."""
+    Up = inputs.uniform(930 + n, n * (n + 1) // 2)
+    x = inputs.uniform(931 + n, n)
+    U = oracle.unpack_triu(n, Up).astype(np.float64)
+    S = U + U.T - np.diag(np.diag(U))
+    y, sc = oracle.symv(n, Up, x)
+    assert _close(y, S @ x.astype(np.float64), sc)
+    assert np.allclose(sc, np.abs(S) @ np.abs(x.astype(np.float64)), rtol=1e-12)
+    # S x = U x + U^T x - diag(U) x, the first term being the triangular product
+    t, _ = oracle.trmv(n, Up, x)
+    assert np.allclose(y, t.astype(np.float64) + U.T @ x - np.diag(U) * x, rtol=1e-5, atol=1e-5)
+
+
+def test_symv_unit_vectors_read_rows_and_columns(oracle):
+    n = 9
+    Up = inputs.small_int(940, -5, 5, n * (n + 1) // 2)
+    U = oracle.unpack_triu(n, Up)
+    for j in range(n):
+        e = np.zeros(n, dtype=np.float32)
+        e[j] = 1
+        y, _ = oracle.symv(n, Up, e)
+        want = np.concatenate([U[:j, j], U[j, j:]])  # column j above the diagonal, then row j
+        assert np.array_equal(y, want)
+    full, s = oracle.symv(n, Up, np.ones(n, dtype=np.float32))
+    part, s2 = oracle.symv(n, Up, np.ones(n, dtype=np.float32), rows=(2, 5))
+    assert np.array_equal(full[2:5], part[2:5]) and np.isnan(part[:2]).all() and np.isnan(part[5:]).all()
+
