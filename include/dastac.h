@@ -14,6 +14,8 @@
  *                                   (Section 3's printed P_B with Q=1, l=0)
  *   upper tetrahedron 0<=i<=j<=k<n  tet(n,i,j,k) = [Tet(n)-Tet(n-i)] + [Tri(n-i)-Tri(n-j)] + (k-j)
  *                                   Tri(m)=m(m+1)/2, Tet(m)=m(m+1)(m+2)/6
+ *   lower triangle   0<=j<=i<n      tril(n,i,j)  = i*(i+1)/2 + j
+ *                                   (Section 4's worked example, Eq. 2)
  *   upper half cube 0<=i<=j<n,      uhc(n,Q,i,j,l) = tri(n,i,j)*Q + l
  *                   0<=l<Q          (Section 3's printed P_B, the running example's buffer B)
  *   band |j-i|<=w                   band(n,w,d,i) = (d+w)*n + i,  d=j-i
@@ -75,6 +77,8 @@ int64_t dastac_band_count(int64_t n, int64_t w);
 int64_t dastac_tri_offset(int64_t n, int64_t i, int64_t j);
 int64_t dastac_tet_offset(int64_t n, int64_t i, int64_t j, int64_t k);
 int64_t dastac_band_offset(int64_t n, int64_t w, int64_t d, int64_t i);
+/* Lower triangle 0<=j<=i<n (Section 4, worked example): i(i+1)/2 + j; the count is tri_count(n). */
+int64_t dastac_tril_offset(int64_t n, int64_t i, int64_t j);
 /* Upper half cube of the running example (i<=j<n, 0<=l<Q; Q >= 1): Tri(n)*Q elements. */
 int64_t dastac_uhc_count(int64_t n, int64_t Q);
 int64_t dastac_uhc_offset(int64_t n, int64_t Q, int64_t i, int64_t j, int64_t l);
@@ -96,13 +100,16 @@ int dastac_tet_inverse(int64_t n, int64_t p, int64_t *i, int64_t *j, int64_t *k)
  *   tet  : dense n x n x n, contiguous  <-> packed[tet_count(n)]
  *   band : dense n x n (stride ld)      <-> diag_major[(2w+1)*n]; pack writes +0.0f into padding slots,
  *                                           unpack ignores them.
- *   uhc  : dense n x n x Q, contiguous  <-> packed[uhc_count(n,Q)] */
+ *   uhc  : dense n x n x Q, contiguous  <-> packed[uhc_count(n,Q)]
+ *   tril : dense n x n (stride ld)      <-> packed[tri_count(n)], row i holding columns 0..i */
 int dastac_pack_triu_f32(int64_t n, const float *dense, int64_t ld, float *packed, void *stream);
 int dastac_unpack_triu_f32(int64_t n, const float *packed, float *dense, int64_t ld, void *stream);
 int dastac_pack_tet_f32(int64_t n, const float *dense, float *packed, void *stream);
 int dastac_unpack_tet_f32(int64_t n, const float *packed, float *dense, void *stream);
 int dastac_pack_band_f32(int64_t n, int64_t w, const float *dense, int64_t ld, float *diag_major, void *stream);
 int dastac_unpack_band_f32(int64_t n, int64_t w, const float *diag_major, float *dense, int64_t ld, void *stream);
+int dastac_pack_tril_f32(int64_t n, const float *dense, int64_t ld, float *packed, void *stream);
+int dastac_unpack_tril_f32(int64_t n, const float *packed, float *dense, int64_t ld, void *stream);
 int dastac_pack_uhc_f32(int64_t n, int64_t Q, const float *dense, float *packed, void *stream);
 int dastac_unpack_uhc_f32(int64_t n, int64_t Q, const float *packed, float *dense, void *stream);
 
@@ -119,6 +126,18 @@ int dastac_trmv_f32(int64_t n, const float *Up, const float *x, float *y, void *
  * element is read once and used twice.  Up[tri_count(n)], x[n], y[n]; n <= 65536 (beyond: DASTAC_EOVERFLOW).
  * The output is accumulated with floating-point atomics, so its last bits may differ between calls. */
 int dastac_symv_f32(int64_t n, const float *Up, const float *x, float *y, void *stream);
+
+/* The other products one packed triangle admits, same limits and same atomic accumulation as symv:
+ *   trmv_t        y(j) := U(i,j) * x(i), i<=j     the transposed product of the packed upper triangle
+ *   trmv_lower    y(i) := L(i,j) * x(j), j<=i     L packed as a LOWER triangle: row i holds columns 0..i, at
+ *                                                 tril(n,i,j) = i(i+1)/2 + j (Section 4, worked example, Eq. 2)
+ *   trmv_lower_t  y(j) := L(i,j) * x(i), j<=i
+ *   symv_lower    y := S x, S symmetric with its unique elements S(i,j), j<=i, packed as a lower triangle
+ *                 (the arrangement of Section 3's redundancy-map example). */
+int dastac_trmv_t_f32(int64_t n, const float *Up, const float *x, float *y, void *stream);
+int dastac_trmv_lower_f32(int64_t n, const float *Lp, const float *x, float *y, void *stream);
+int dastac_trmv_lower_t_f32(int64_t n, const float *Lp, const float *x, float *y, void *stream);
+int dastac_symv_lower_f32(int64_t n, const float *Lp, const float *x, float *y, void *stream);
 
 /* C(i,c) := U(i,k) * B(k,c), i<=k, 0<=c<m  (the SpMV_UT rule with a matrix right-hand side).
  * B is n x m row-major with row stride ldb >= m, C is n x m with row stride ldc >= m; m >= 1. */

@@ -77,7 +77,9 @@ def lib() -> ctypes.CDLL:
         L.oracle_tet_mttkrp_f32.argtypes = [_i64, _i64, _fp, _fp, _i64, _fp, _i64, _fp, _i64, _dp, _i64, _i64]
         L.oracle_pack_uhc_f32.argtypes = [_i64, _i64, _i64, _fp, _fp]
         L.oracle_unpack_uhc_f32.argtypes = [_i64, _i64, _i64, _fp, _fp]
-        L.oracle_symv_f32.argtypes = [_i64, _fp, _fp, _fp, _dp, _i64, _i64]
+        L.oracle_trimv_f32.argtypes = [_i64, ctypes.c_int, ctypes.c_int, _fp, _fp, _fp, _dp, _i64, _i64]
+        L.oracle_pack_tril_f32.argtypes = [_i64, _fp, _i64, _fp]
+        L.oracle_unpack_tril_f32.argtypes = [_i64, _fp, _fp, _i64]
         L.oracle_ttm_ut_f32.argtypes = [_i64, _i64, _i64, _fp, _fp, _i64, _fp, _dp, _i64, _i64]
         for name in ("pack_triu", "unpack_triu", "pack_tet", "unpack_tet", "pack_band", "unpack_band",
                      "trmv", "trmm", "band_spmv", "tet_ttv", "tet_mttkrp"):
@@ -288,12 +290,31 @@ def ttm_ut(n, Q, K, Bp, C, rows=None):
     return A, sc
 
 
-def symv(n, Up, x, rows=None):
-    """y = S x, S symmetric with its upper triangle packed in Up."""
-    Up, x = _f32(Up), _f32(x)
+def trimv(n, Tp, x, lower=False, mode=0, rows=None):
+    """mode 0: T x; 1: T^T x; 2: S x with S symmetric and T its unique triangle (upper, or lower)."""
+    Tp, x = _f32(Tp), _f32(x)
     lo, hi = _window(n, rows)
     y = np.full(n, np.nan, dtype=np.float32)
     sc = np.full(n, np.nan, dtype=np.float64)
-    lib().oracle_symv_f32(n, _f(Up), _f(x), _f(y), _d(sc), lo, hi)
+    lib().oracle_trimv_f32(n, int(bool(lower)), int(mode), _f(Tp), _f(x), _f(y), _d(sc), lo, hi)
     return y, sc
 
+
+def symv(n, Up, x, rows=None):
+    """y = S x, S symmetric with its upper triangle packed in Up."""
+    return trimv(n, Up, x, lower=False, mode=2, rows=rows)
+
+
+def pack_tril(dense: np.ndarray) -> np.ndarray:
+    dense = _f32(dense)
+    n = dense.shape[0]
+    packed = np.empty(n * (n + 1) // 2, dtype=np.float32)
+    lib().oracle_pack_tril_f32(n, _f(dense), dense.shape[1], _f(packed))
+    return packed
+
+
+def unpack_tril(n: int, packed: np.ndarray) -> np.ndarray:
+    packed = _f32(packed)
+    dense = np.empty((n, n), dtype=np.float32)
+    lib().oracle_unpack_tril_f32(n, _f(packed), _f(dense), n)
+    return dense

@@ -468,19 +468,45 @@ void oracle_ttm_ut_f32(int64_t n, int64_t Q, int64_t K, const float *Bp, const f
     }
 }
 
-/* y(i) := S(i,j) * x(j) for the symmetric matrix whose unique elements are the packed upper
- * triangle (Section 3, "Redundancy map": an index pair outside the unique set is swapped to reach
- * its unique element).  Positions of the unique elements come from the running-counter row starts. */
-void oracle_symv_f32(int64_t n, const float *Up, const float *x, float *y, double *scale,
-                     int64_t r_lo, int64_t r_hi) {
+/* Lower triangle (Section 4 worked example, Eq. 2): row i holds columns 0..i. */
+void oracle_pack_tril_f32(int64_t n, const float *dense, int64_t ld, float *packed) {
+  int64_t p = 0;
+  for (int64_t i = 0; i < n; ++i)
+    for (int64_t j = 0; j <= i; ++j) packed[p++] = dense[i * ld + j];
+}
+
+void oracle_unpack_tril_f32(int64_t n, const float *packed, float *dense, int64_t ld) {
+  for (int64_t i = 0; i < n; ++i)
+    for (int64_t j = 0; j < n; ++j) dense[i * ld + j] = 0.0f;
+  int64_t p = 0;
+  for (int64_t i = 0; i < n; ++i)
+    for (int64_t j = 0; j <= i; ++j) dense[i * ld + j] = packed[p++];
+}
+
+/* Products of one packed triangle T (upper: row i holds columns i..n-1; lower: columns 0..i) with a
+ * vector:  mode 0  y(i) := T(i,j) x(j);  mode 1  y(j) := T(i,j) x(i)  (the transposed product);
+ * mode 2  y(i) := S(i,j) x(j) for the symmetric matrix whose unique elements are T (Section 3,
+ * "Redundancy map": an index pair outside the unique set is swapped to reach its unique element).
+ * Positions come from running-counter row starts. */
+void oracle_trimv_f32(int64_t n, int lower, int mode, const float *Tp, const float *x, float *y,
+                      double *scale, int64_t r_lo, int64_t r_hi) {
   int64_t *start = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n + 1));
-  oracle_triu_row_starts(n, start);
+  int64_t p = 0;
+  for (int64_t i = 0; i < n; ++i) { /* walk the rows in iteration order */
+    start[i] = p;
+    p += lower ? i + 1 : n - i;
+  }
   for (int64_t i = 0; i < n; ++i) {
     if (i < r_lo || i >= r_hi) continue;
     double acc = 0.0, mag = 0.0;
     for (int64_t j = 0; j < n; ++j) {
-      int64_t a = i <= j ? i : j, b = i <= j ? j : i; /* the unique representative (a,b), a<=b */
-      double t = (double)Up[start[a] + (b - a)] * (double)x[j];
+      /* which stored element, if any, is factor (i,j) of output i */
+      int64_t a = i, b = j; /* mode 0: T(i,j) */
+      if (mode == 1) { a = j; b = i; } /* T^T(i,j) = T(j,i) */
+      int inside = lower ? (b <= a) : (a <= b);
+      if (mode == 2 && !inside) { int64_t t = a; a = b; b = t; inside = 1; } /* swap to the unique element */
+      if (!inside) continue;
+      double t = (double)Tp[start[a] + (lower ? b : b - a)] * (double)x[j];
       acc += t;
       mag += fabs(t);
     }
@@ -489,4 +515,3 @@ void oracle_symv_f32(int64_t n, const float *Up, const float *x, float *y, doubl
   }
   free(start);
 }
-

@@ -40,6 +40,11 @@ int64_t dastac_tri_offset(int64_t n, int64_t i, int64_t j) {
   return tri_offset(n, i, j);
 }
 
+int64_t dastac_tril_offset(int64_t n, int64_t i, int64_t j) {
+  if (n < 0 || n > DASTAC_TRI_MAX_N || j < 0 || i < j || i >= n) return -1;
+  return (i * (i + 1)) / 2 + j;
+}
+
 int64_t dastac_tet_offset(int64_t n, int64_t i, int64_t j, int64_t k) {
   if (n < 0 || n > DASTAC_TET_MAX_N || i < 0 || j < i || k < j || k >= n) return -1;
   return tet_offset(n, i, j, k);

@@ -41,6 +41,25 @@ __global__ __launch_bounds__(kBlock) void unpack_triu_kernel(int64_t n, const fl
   }
 }
 
+// lower triangle: row i holds columns 0..i, starting at i(i+1)/2 (Section 4, worked example)
+template <bool PACK>
+__global__ __launch_bounds__(kBlock) void tril_copy_kernel(int64_t n, const float *__restrict__ src,
+                                                           float *__restrict__ dst, int64_t ld, int64_t pieces,
+                                                           int64_t nblocks) {
+  for (int64_t b = blockIdx.x; b < nblocks; b += gridDim.x) {
+    int64_t i, c0;
+    split(b, pieces, i, c0);
+    const int64_t j = c0 + threadIdx.x;
+    if (j >= n) continue;
+    const int64_t at = (i * (i + 1)) / 2 + j;
+    if (PACK) {
+      if (j <= i) dst[at] = src[i * ld + j];
+    } else {
+      dst[i * ld + j] = (j <= i) ? src[at] : 0.0f;
+    }
+  }
+}
+
 // rows of the cube are (i,j) pairs, flattened as i*n+j
 __global__ __launch_bounds__(kBlock) void pack_tet_kernel(int64_t n, const float *__restrict__ dense,
                                                           float *__restrict__ packed, int64_t pieces,
@@ -125,6 +144,28 @@ int dastac_unpack_triu_f32(int64_t n, const float *packed, float *dense, int64_t
   if (overlaps(dense, n * ld * 4, packed, tri(n) * 4)) return DASTAC_EALIAS;
   int64_t pieces = ceil_div(n, kBlock), nblocks = n * pieces;
   unpack_triu_kernel<<<grid_for(nblocks), kBlock, 0, (hipStream_t)stream>>>(n, packed, dense, ld, pieces, nblocks);
+  return launch_status();
+}
+
+int dastac_pack_tril_f32(int64_t n, const float *dense, int64_t ld, float *packed, void *stream) {
+  if (n < 0 || ld < n) return DASTAC_EINVAL;
+  if (n > kDenseMaxN) return DASTAC_EOVERFLOW;
+  if (n == 0) return DASTAC_OK;
+  if (!dense || !packed) return DASTAC_ENULL;
+  if (overlaps(packed, tri(n) * 4, dense, n * ld * 4)) return DASTAC_EALIAS;
+  int64_t pieces = ceil_div(n, kBlock), nblocks = n * pieces;
+  tril_copy_kernel<true><<<grid_for(nblocks), kBlock, 0, (hipStream_t)stream>>>(n, dense, packed, ld, pieces, nblocks);
+  return launch_status();
+}
+
+int dastac_unpack_tril_f32(int64_t n, const float *packed, float *dense, int64_t ld, void *stream) {
+  if (n < 0 || ld < n) return DASTAC_EINVAL;
+  if (n > kDenseMaxN) return DASTAC_EOVERFLOW;
+  if (n == 0) return DASTAC_OK;
+  if (!dense || !packed) return DASTAC_ENULL;
+  if (overlaps(dense, n * ld * 4, packed, tri(n) * 4)) return DASTAC_EALIAS;
+  int64_t pieces = ceil_div(n, kBlock), nblocks = n * pieces;
+  tril_copy_kernel<false><<<grid_for(nblocks), kBlock, 0, (hipStream_t)stream>>>(n, packed, dense, ld, pieces, nblocks);
   return launch_status();
 }
 

@@ -44,6 +44,13 @@ SIGNATURES = {
     "dastac_tet_ttv_f32": (ctypes.c_int, [_i64, _vp, _vp, _vp, _vp]),
     "dastac_tet_mttkrp_f32": (ctypes.c_int, [_i64, _i64, _vp, _vp, _i64, _vp, _i64, _vp, _i64, _vp]),
     "dastac_symv_f32": (ctypes.c_int, [_i64, _vp, _vp, _vp, _vp]),
+    "dastac_trmv_t_f32": (ctypes.c_int, [_i64, _vp, _vp, _vp, _vp]),
+    "dastac_trmv_lower_f32": (ctypes.c_int, [_i64, _vp, _vp, _vp, _vp]),
+    "dastac_trmv_lower_t_f32": (ctypes.c_int, [_i64, _vp, _vp, _vp, _vp]),
+    "dastac_symv_lower_f32": (ctypes.c_int, [_i64, _vp, _vp, _vp, _vp]),
+    "dastac_tril_offset": (_i64, [_i64, _i64, _i64]),
+    "dastac_pack_tril_f32": (ctypes.c_int, [_i64, _vp, _i64, _vp, _vp]),
+    "dastac_unpack_tril_f32": (ctypes.c_int, [_i64, _vp, _vp, _i64, _vp]),
     "dastac_uhc_count": (_i64, [_i64, _i64]),
     "dastac_uhc_offset": (_i64, [_i64, _i64, _i64, _i64, _i64]),
     "dastac_pack_uhc_f32": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp]),
@@ -193,4 +200,31 @@ def ttm_ut_f32(n, Q, K, Bp, C, ldc, Ap, stream=None):
 
 def symv_f32(n, Up, x, y, stream=None):
     _check(lib().dastac_symv_f32(n, _ptr(Up), _ptr(x), _ptr(y), _stream(stream)), "symv_f32")
+
+
+def trmv_t_f32(n, Up, x, y, stream=None):
+    _check(lib().dastac_trmv_t_f32(n, _ptr(Up), _ptr(x), _ptr(y), _stream(stream)), "trmv_t_f32")
+
+
+def trmv_lower_f32(n, Lp, x, y, stream=None):
+    _check(lib().dastac_trmv_lower_f32(n, _ptr(Lp), _ptr(x), _ptr(y), _stream(stream)), "trmv_lower_f32")
+
+
+def trmv_lower_t_f32(n, Lp, x, y, stream=None):
+    _check(lib().dastac_trmv_lower_t_f32(n, _ptr(Lp), _ptr(x), _ptr(y), _stream(stream)), "trmv_lower_t_f32")
+
+
+def symv_lower_f32(n, Lp, x, y, stream=None):
+    _check(lib().dastac_symv_lower_f32(n, _ptr(Lp), _ptr(x), _ptr(y), _stream(stream)), "symv_lower_f32")
+
+
+def tril_offset(n, i, j): return int(lib().dastac_tril_offset(n, i, j))
+
+
+def pack_tril_f32(n, dense, ld, packed, stream=None):
+    _check(lib().dastac_pack_tril_f32(n, _ptr(dense), ld, _ptr(packed), _stream(stream)), "pack_tril_f32")
+
+
+def unpack_tril_f32(n, packed, dense, ld, stream=None):
+    _check(lib().dastac_unpack_tril_f32(n, _ptr(packed), _ptr(dense), ld, _stream(stream)), "unpack_tril_f32")
 

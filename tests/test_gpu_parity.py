@@ -229,6 +229,46 @@ def test_symv_integer_inputs_bit_exact_and_repeatable(gpu, oracle, n):
         assert gpu.down(y).tobytes() == want.tobytes()
 
 
+# -------------------------------- every product of one packed triangle with a vector ----
+
+@pytest.mark.parametrize("n,ld", [(1, 1), (2, 5), (17, 17), (255, 255), (256, 300), (257, 257), (700, 704)])
+def test_pack_unpack_tril_bit_exact(gpu, oracle, n, ld):
+    D = inputs.uniform(190 + n, n, ld)
+    want = oracle.pack_tril(np.ascontiguousarray(D[:, :n]))
+    dP = gpu.empty(tri(n))
+    gpu.d.pack_tril_f32(n, gpu.up(D), ld, dP)
+    assert gpu.down(dP).tobytes() == want.tobytes()
+    dL = gpu.empty(n, ld)
+    gpu.d.unpack_tril_f32(n, dP, dL, ld)
+    Lo = gpu.down(dL)
+    assert Lo[:, :n].tobytes() == oracle.unpack_tril(n, want).tobytes()
+    assert np.isnan(Lo[:, n:]).all()
+
+
+TRIMV = [("trmv_t_f32", False, 1), ("trmv_lower_f32", True, 0), ("trmv_lower_t_f32", True, 1),
+         ("symv_lower_f32", True, 2)]
+
+
+@pytest.mark.parametrize("fn,lower,mode", TRIMV)
+@pytest.mark.parametrize("n", [1, 2, 3, 5, 64, 65, 257, 1000, 1025, 2049, 4100])
+def test_triangle_vector_products_parity(gpu, oracle, fn, lower, mode, n):
+    Tp, x = inputs.uniform(200 + n + mode, tri(n)), inputs.uniform(201 + n, n)
+    want, scale = oracle.trimv(n, Tp, x, lower=lower, mode=mode)
+    y = gpu.empty(n)
+    getattr(gpu.d, fn)(n, gpu.up(Tp), gpu.up(x), y)
+    assert_within(gpu.down(y), want, scale, "%s n=%d" % (fn, n))
+
+
+@pytest.mark.parametrize("fn,lower,mode", TRIMV)
+@pytest.mark.parametrize("n", [7, 515, 2300])
+def test_triangle_vector_products_integer_inputs_bit_exact(gpu, oracle, fn, lower, mode, n):
+    Tp, x = inputs.small_int(210 + n, -3, 3, tri(n)), inputs.small_int(211 + n, -3, 3, n)
+    want, _ = oracle.trimv(n, Tp, x, lower=lower, mode=mode)
+    y = gpu.empty(n)
+    getattr(gpu.d, fn)(n, gpu.up(Tp), gpu.up(x), y)
+    assert gpu.down(y).tobytes() == want.tobytes()
+
+
 # ------------------------------------------------- running example (TTM_UT) ----
 
 @pytest.mark.parametrize("n,Q", [(1, 1), (3, 2), (9, 5), (17, 256), (24, 300), (40, 64)])

@@ -73,6 +73,22 @@ def test_band_offsets_match_counting(oracle, n, w):
     assert dastac.band_count(-1, 0) == -1 and dastac.band_count(1, -1) == -1
 
 
+@pytest.mark.parametrize("n", [1, 2, 6, 11])
+def test_tril_offsets_match_counting_and_paper_polynomial(oracle, n):
+    """tril(n,i,j) = i/2 + i^2/2 + j (Section 4, Eq. 2 after the fusion of its two pieces)."""
+    rows = {(i, j): p for i, j, p in
+            (tuple(int(t) for t in ln.split()) for ln in open(os.path.join(
+                os.path.dirname(__file__), "golden", "lower_triangle_fused_polynomial.txt"))
+             if ln.strip() and not ln.startswith("#"))}
+    for i in range(n):
+        for j in range(i + 1):
+            got = dastac.tril_offset(n, i, j)
+            assert got == oracle.count_preceding(oracle.DOM_TRIL, [n], [i, j])
+            if n == 6:
+                assert got == rows[(i, j)]  # the values printed from the paper's polynomial
+    assert dastac.tril_offset(n, 0, 1) == -1 and dastac.tril_offset(n, n, 0) == -1 and dastac.tril_offset(-1, 0, 0) == -1
+
+
 @pytest.mark.parametrize("n,Q", [(1, 1), (4, 3), (6, 2), (5, 7)])
 def test_uhc_offsets_match_counting_and_paper_polynomial(oracle, n, Q):
     """uhc(n,Q,i,j,l) is the number of preceding points of the running example's buffer B, i.e. the
@@ -158,6 +174,14 @@ def test_device_entry_points_reject_bad_arguments():
     assert L.dastac_tet_mttkrp_f32(4, 0, _p(A), _p(B), 4, _p(C), 4, _p(D), 4, None) == dastac.EINVAL
     assert L.dastac_tet_mttkrp_f32(4, 33, _p(A), _p(B), 33, _p(C), 33, _p(D), 33, None) == dastac.EINVAL
     assert L.dastac_tet_mttkrp_f32(4, 8, _p(A), _p(B), 8, _p(C), 8, _p(D), 7, None) == dastac.EINVAL
+    for fn in (L.dastac_trmv_t_f32, L.dastac_trmv_lower_f32, L.dastac_trmv_lower_t_f32, L.dastac_symv_lower_f32):
+        assert fn(-1, _p(A), _p(B), _p(C), None) == dastac.EINVAL
+        assert fn(65537, _p(A), _p(B), _p(C), None) == dastac.EOVERFLOW
+        assert fn(4, None, _p(B), _p(C), None) == dastac.ENULL
+        assert fn(4, _p(A), _p(B), _p(B), None) == dastac.EALIAS
+        assert fn(0, None, None, None, None) == dastac.OK
+    assert L.dastac_pack_tril_f32(8, _p(A), 7, _p(B), None) == dastac.EINVAL
+    assert L.dastac_unpack_tril_f32(4, None, _p(B), 4, None) == dastac.ENULL
     assert L.dastac_symv_f32(-1, _p(A), _p(B), _p(C), None) == dastac.EINVAL
     assert L.dastac_symv_f32(65537, _p(A), _p(B), _p(C), None) == dastac.EOVERFLOW
     assert L.dastac_symv_f32(4, _p(A), None, _p(C), None) == dastac.ENULL

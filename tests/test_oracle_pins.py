@@ -408,3 +408,38 @@ def test_symv_unit_vectors_read_rows_and_columns(oracle):
     part, s2 = oracle.symv(n, Up, np.ones(n, dtype=np.float32), rows=(2, 5))
     assert np.array_equal(full[2:5], part[2:5]) and np.isnan(part[:2]).all() and np.isnan(part[5:]).all()
 
+
+@pytest.mark.parametrize("n", [1, 2, 5, 12, 23])
+def test_pack_tril_against_numpy_and_paper_polynomial(oracle, n):
+    """Section 4's worked example: the lower triangle is numbered by i/2 + i^2/2 + j."""
+    D = inputs.uniform(950 + n, n, n)
+    packed = oracle.pack_tril(D)
+    assert np.array_equal(packed, D[np.tril_indices(n)])  # tril_indices walks rows, then columns
+    for i in range(n):
+        for j in range(i + 1):
+            pos = Fraction(1, 2) * i + Fraction(1, 2) * i * i + j
+            assert pos.denominator == 1 and packed[int(pos)] == D[i, j]
+            assert oracle.count_preceding(oracle.DOM_TRIL, [n], [i, j]) == pos
+    assert np.array_equal(oracle.unpack_tril(n, packed), np.tril(D))
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 9, 20])
+@pytest.mark.parametrize("lower", [False, True])
+def test_triangle_vector_products_against_dense_numpy(oracle, n, lower):
+    """T x, T^T x and the symmetric product, upper and lower, against NumPy on the unpacked matrix."""
+    Tp = inputs.uniform(960 + n, n * (n + 1) // 2)
+    x = inputs.uniform(961 + n, n)
+    T = (oracle.unpack_tril(n, Tp) if lower else oracle.unpack_triu(n, Tp)).astype(np.float64)
+    S = T + T.T - np.diag(np.diag(T))
+    x64 = x.astype(np.float64)
+    for mode, M in ((0, T), (1, T.T), (2, S)):
+        y, sc = oracle.trimv(n, Tp, x, lower=lower, mode=mode)
+        assert _close(y, M @ x64, sc), (mode, lower)
+        assert np.allclose(sc, np.abs(M) @ np.abs(x64), rtol=1e-12)
+    if not lower:  # mode 0 on the upper triangle is the TRMV routine
+        assert np.array_equal(oracle.trimv(n, Tp, x, mode=0)[0], oracle.trmv(n, Tp, x)[0])
+    # a lower triangle and the upper triangle of its transpose are the same symmetric matrix
+    if lower:
+        Up = oracle.pack_triu(np.ascontiguousarray(T.T.astype(np.float32)))
+        assert np.array_equal(oracle.trimv(n, Tp, x, lower=True, mode=2)[0], oracle.symv(n, Up, x)[0])
+
