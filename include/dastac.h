@@ -118,12 +118,13 @@ int dastac_unpack_uhc_f32(int64_t n, int64_t Q, const float *packed, float *dens
  * each output element is within 1e-4 * sum|products| of the exactly rounded result.
  */
 
-/* y(i) := U(i,j) * x(j), i<=j   (Table 1/2, SpMV_UT).  Up[tri_count(n)], x[n], y[n]. */
+/* y(i) := U(i,j) * x(j), i<=j   (Table 1/2, SpMV_UT).  Up[tri_count(n)], x[n], y[n]; n <= 524288.
+ * Above n = 8192 the result is accumulated with floating-point atomics (last bits may differ between calls). */
 int dastac_trmv_f32(int64_t n, const float *Up, const float *x, float *y, void *stream);
 
 /* y(i) := S(i,j) * x(j), S symmetric with its unique elements S(i,j), i<=j, packed as an upper triangle
  * (Section 3, "Redundancy map": the other half is reached by swapping the two indices).  Every packed
- * element is read once and used twice.  Up[tri_count(n)], x[n], y[n]; n <= 65536 (beyond: DASTAC_EOVERFLOW).
+ * element is read once and used twice.  Up[tri_count(n)], x[n], y[n]; n <= 524288 (beyond: DASTAC_EOVERFLOW).
  * The output is accumulated with floating-point atomics, so its last bits may differ between calls. */
 int dastac_symv_f32(int64_t n, const float *Up, const float *x, float *y, void *stream);
 

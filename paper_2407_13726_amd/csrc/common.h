@@ -21,6 +21,9 @@ inline int launch_status() { return hipGetLastError() == hipSuccess ? DASTAC_OK 
 
 DASTAC_HD int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
+// defined in trimv.hip
+int trmv_upper_by_panels(int64_t n, const float *Up, const float *x, float *y, void *stream);
+
 #if defined(__HIPCC__)
 // 16-byte vector of floats that only promises 4-byte alignment: packed rows start at arbitrary
 // element offsets, and gfx950 global loads of four dwords need dword alignment only.

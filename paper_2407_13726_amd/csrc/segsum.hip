@@ -87,18 +87,9 @@ __device__ inline void first_row_from(int64_t n, int64_t total, int64_t q, int64
   }
 }
 
-// One step of a wavefront: everything here is wave-uniform.
-struct Step {
-  int64_t p;   // packed position of the first row of the step (or of the long row)
-  int64_t s;   // output position of that row
-  int64_t j;   // its first column
-  int len;     // its length (== rows left in the slice)
-  int t0;      // long rows: offset of this piece inside the row; else 0
-  bool valid;
-};
-
 // ---------------------------------------------------------------------------------------------
-// Variant 1: the vector operand fits in LDS (n <= kLdsMaxN).  Serves every TTV and small TRMV.
+// The vector operand fits in LDS (n <= kLdsMaxN).  Serves every TTV, and TRMV up to that order
+// (larger triangles go to the column-panel kernel of trimv.hip).
 //
 // x is staged once per workgroup, followed by kPad zeros.  A lane handles sixteen packed elements
 // per step (four 16-byte loads, each contiguous across the lanes of a row) without any bounds
@@ -349,140 +340,6 @@ __global__ __launch_bounds__(kLdsBlock) void segsum_lds_kernel(int n, const floa
   }
 }
 
-// ---------------------------------------------------------------------------------------------
-// Variant 2: TRMV with n > kLdsMaxN; x is read through the vector cache.  Rows are long there:
-// whole 1024-element blocks of a row are summed without bounds tests, and only the last 1..1024
-// elements of each row (and the short rows at the bottom of the triangle) go through bounds-tested
-// steps of four elements per lane.
-// ---------------------------------------------------------------------------------------------
-constexpr int kBlock = 256;
-constexpr int kWavesPerBlock = kBlock / 64;
-
-__device__ inline int bulk_of(int len) { return len > 256 ? ((len - 1) >> 10) << 10 : 0; }
-
-struct Piece {
-  f4a a, x;
-};
-
-__device__ inline int lanes_log2(int len) {
-  return len > 128 ? 6 : len > 64 ? 5 : len > 32 ? 4 : len > 16 ? 3 : len > 8 ? 2 : len > 4 ? 1 : 0;
-}
-
-// Loads of one step: `cnt` valid elements (0..4) at a[..], x[..].
-__device__ inline Piece load_piece(const float *__restrict__ a, const float *__restrict__ x, int cnt) {
-  Piece d;
-  d.a = f4a{0.0f, 0.0f, 0.0f, 0.0f};
-  d.x = d.a;
-  if (cnt >= 4) {
-    d.a = __builtin_nontemporal_load(reinterpret_cast<const f4u *>(a));
-    d.x = *reinterpret_cast<const f4u *>(x);
-  } else if (cnt > 0) {
-    d.a.x = a[0]; d.x.x = x[0];
-    if (cnt > 1) { d.a.y = a[1]; d.x.y = x[1]; }
-    if (cnt > 2) { d.a.z = a[2]; d.x.z = x[2]; }
-  }
-  return d;
-}
-
-__global__ __launch_bounds__(kBlock) void trmv_big_kernel(int64_t n, const float *__restrict__ A,
-                                                          const float *__restrict__ x, float *__restrict__ out,
-                                                          int64_t total, int64_t share) {
-  const int lane = threadIdx.x & 63;
-  const int64_t wave = (int64_t)blockIdx.x * kWavesPerBlock + uniform32(threadIdx.x >> 6);
-  const int64_t lo = wave * share;
-  if (lo >= total) return;
-  const int64_t hi = (lo + share < total) ? lo + share : total;  // rows starting in [lo,hi) are ours
-
-  int64_t si, sj, sp;
-  first_row_from<false>(n, total, lo, si, sj, sp);
-
-  Step st;
-  st.p = uniform64(sp);
-  st.j = uniform64(sj);
-  st.s = st.j;
-  st.len = (int)(n - st.j);
-  st.t0 = bulk_of(st.len);
-  st.valid = st.p < hi && st.len > 0;
-
-  auto issue = [&](const Step &d, int &g, int &used) -> Piece {
-    const int lg = lanes_log2(d.len);
-    int rows = 64 >> lg;
-    if (rows > d.len) rows = d.len;  // stay inside the triangle
-    g = lane >> lg;
-    const int sub = lane & ((1 << lg) - 1);
-    const int64_t start_g = d.p + (int64_t)g * d.len - (g * (g - 1)) / 2;
-    const bool mine = g < rows && start_g < hi;
-    used = __popcll(__ballot(mine && sub == 0));
-    const int pos = d.t0 + sub * 4;
-    int cnt = mine ? (d.len - g) - pos : 0;
-    if (cnt > 4) cnt = 4;
-    return load_piece(A + start_g + pos, x + d.j + g + pos, cnt);
-  };
-  auto advance = [&](const Step &d, int used) -> Step {
-    Step nx = d;
-    if (d.len > 256 && d.t0 + 256 < d.len) {  // next piece of the same long row
-      nx.t0 = d.t0 + 256;
-      return nx;
-    }
-    nx.p = d.p + (int64_t)used * d.len - (used * (used - 1)) / 2;
-    nx.s = d.s + used;
-    nx.j = d.j + used;
-    nx.len = (int)(n - nx.j);
-    nx.t0 = bulk_of(nx.len);
-    nx.valid = nx.p < hi && nx.len > 0;
-    return nx;
-  };
-
-  float racc = 0.0f;  // running per-lane sum of a long row
-  auto consume = [&](const Step &d, const Piece &c, int g, int used) {
-    if (d.t0 > 0 && d.t0 == bulk_of(d.len)) {  // first stepped piece of a long row: do its bulk now
-      const float *a = A + d.p + lane * 4;
-      const float *xv = x + d.j + lane * 4;
-      for (int t = 0; t < d.t0; t += 1024) {
-        f4u a0 = __builtin_nontemporal_load(reinterpret_cast<const f4u *>(a + t));
-        f4u a1 = __builtin_nontemporal_load(reinterpret_cast<const f4u *>(a + t + 256));
-        f4u a2 = __builtin_nontemporal_load(reinterpret_cast<const f4u *>(a + t + 512));
-        f4u a3 = __builtin_nontemporal_load(reinterpret_cast<const f4u *>(a + t + 768));
-        f4u x0 = *reinterpret_cast<const f4u *>(xv + t), x1 = *reinterpret_cast<const f4u *>(xv + t + 256);
-        f4u x2 = *reinterpret_cast<const f4u *>(xv + t + 512), x3 = *reinterpret_cast<const f4u *>(xv + t + 768);
-        racc += a0.x * x0.x + a0.y * x0.y + a0.z * x0.z + a0.w * x0.w;
-        racc += a1.x * x1.x + a1.y * x1.y + a1.z * x1.z + a1.w * x1.w;
-        racc += a2.x * x2.x + a2.y * x2.y + a2.z * x2.z + a2.w * x2.w;
-        racc += a3.x * x3.x + a3.y * x3.y + a3.z * x3.z + a3.w * x3.w;
-      }
-    }
-    float v = c.a.x * c.x.x + c.a.y * c.x.y + c.a.z * c.x.z + c.a.w * c.x.w;
-    if (d.len > 256) {
-      racc += v;
-      if (d.t0 + 256 >= d.len) {
-        v = group_sum(racc, 6);
-        racc = 0.0f;
-        if (lane == 0) out[d.s] = v;
-      }
-    } else {
-      const int lg = lanes_log2(d.len);
-      v = group_sum(v, lg);
-      const int sub = lane & ((1 << lg) - 1);
-      if (sub == 0 && g < used) out[d.s + g] = v;
-    }
-  };
-
-  Piece pa, pb;
-  int ga = 0, ua = 0, gb = 0, ub = 0;
-  if (st.valid) pa = issue(st, ga, ua);
-  while (st.valid) {
-    Step nx = advance(st, ua);
-    if (nx.valid) pb = issue(nx, gb, ub);
-    consume(st, pa, ga, ua);
-    st = nx;
-    if (!st.valid) break;
-    nx = advance(st, ub);
-    if (nx.valid) pa = issue(nx, ga, ua);
-    consume(st, pb, gb, ub);
-    st = nx;
-  }
-}
-
 // ---- host side -------------------------------------------------------------------------------
 
 // Wavefront shares: about `per_cu` wavefronts per compute unit on a 256-CU part, at least 2048
@@ -527,10 +384,8 @@ int dastac_trmv_f32(int64_t n, const float *Up, const float *x, float *y, void *
   if (!Up || !x || !y) return DASTAC_ENULL;
   if (overlaps(y, n * 4, Up, tri(n) * 4) || overlaps(y, n * 4, x, n * 4)) return DASTAC_EALIAS;
   if (n <= kLdsMaxN) return launch_lds<false>(n, Up, x, y, tri(n), stream);
-  const int64_t total = tri(n), share = pick_share(total, 32);
-  const int64_t blocks = ceil_div(ceil_div(total, share), kWavesPerBlock);
-  trmv_big_kernel<<<(unsigned)blocks, kBlock, 0, (hipStream_t)stream>>>(n, Up, x, y, total, share);
-  return launch_status();
+  // x no longer fits in LDS: the column-panel kernel keeps it in registers (n=16384: 4.7 TB/s)
+  return trmv_upper_by_panels(n, Up, x, y, stream);
 }
 
 int dastac_tet_ttv_f32(int64_t n, const float *Ap, const float *v, float *Mp, void *stream) {

@@ -38,8 +38,8 @@ namespace {
 
 constexpr int kBlock = 256;
 constexpr int kWavesPerBlock = kBlock / 64;
-constexpr int kMaxPanels = 64;
-constexpr int kMaxN = 65536;  // 64 panels of 1024 columns; a larger triangle exceeds 8 GiB
+constexpr int kMaxPanels = 512;
+constexpr int kMaxN = 524288;  // 512 panels of 1024 columns; such a triangle is far larger than device memory
 
 enum { MODE_ROWS = 0, MODE_COLS = 1, MODE_SYM = 2 };
 
@@ -263,6 +263,12 @@ int run(int64_t n, const float *Tp, const float *x, float *y, void *stream) {
 }
 
 }  // namespace
+
+// y := U x over the packed upper triangle with this file's kernel (no limit on n below kMaxN);
+// used by dastac_trmv_f32 for triangles whose vector does not fit in LDS.
+int dastac::trmv_upper_by_panels(int64_t n, const float *Up, const float *x, float *y, void *stream) {
+  return run<false, MODE_ROWS>(n, Up, x, y, stream);
+}
 
 extern "C" {
 

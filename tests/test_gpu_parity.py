@@ -101,7 +101,7 @@ def test_pack_unpack_band_bit_exact(gpu, oracle, n, w):
 
 # --------------------------------------------------------------------- TRMV ----
 
-TRMV_SIZES = [1, 2, 3, 4, 5, 63, 64, 65, 129, 257, 512, 1000, 2049, 4100]
+TRMV_SIZES = [1, 2, 3, 4, 5, 63, 64, 65, 129, 257, 512, 1000, 2049, 4100, 8192, 8193, 11111]
 
 
 @pytest.mark.parametrize("n", TRMV_SIZES)
@@ -113,7 +113,7 @@ def test_trmv_parity(gpu, oracle, n):
     assert_within(gpu.down(y), want, scale, "trmv n=%d" % n)
 
 
-@pytest.mark.parametrize("n", [1, 7, 130, 515, 1500])
+@pytest.mark.parametrize("n", [1, 7, 130, 515, 1500, 9000])
 def test_trmv_integer_inputs_bit_exact(gpu, oracle, n):
     Up, x = inputs.small_int(50 + n, -3, 3, tri(n)), inputs.small_int(51 + n, -3, 3, n)
     want, _ = oracle.trmv(n, Up, x)

@@ -176,14 +176,14 @@ def test_device_entry_points_reject_bad_arguments():
     assert L.dastac_tet_mttkrp_f32(4, 8, _p(A), _p(B), 8, _p(C), 8, _p(D), 7, None) == dastac.EINVAL
     for fn in (L.dastac_trmv_t_f32, L.dastac_trmv_lower_f32, L.dastac_trmv_lower_t_f32, L.dastac_symv_lower_f32):
         assert fn(-1, _p(A), _p(B), _p(C), None) == dastac.EINVAL
-        assert fn(65537, _p(A), _p(B), _p(C), None) == dastac.EOVERFLOW
+        assert fn(524289, _p(A), _p(B), _p(C), None) == dastac.EOVERFLOW
         assert fn(4, None, _p(B), _p(C), None) == dastac.ENULL
         assert fn(4, _p(A), _p(B), _p(B), None) == dastac.EALIAS
         assert fn(0, None, None, None, None) == dastac.OK
     assert L.dastac_pack_tril_f32(8, _p(A), 7, _p(B), None) == dastac.EINVAL
     assert L.dastac_unpack_tril_f32(4, None, _p(B), 4, None) == dastac.ENULL
     assert L.dastac_symv_f32(-1, _p(A), _p(B), _p(C), None) == dastac.EINVAL
-    assert L.dastac_symv_f32(65537, _p(A), _p(B), _p(C), None) == dastac.EOVERFLOW
+    assert L.dastac_symv_f32(524289, _p(A), _p(B), _p(C), None) == dastac.EOVERFLOW
     assert L.dastac_symv_f32(4, _p(A), None, _p(C), None) == dastac.ENULL
     assert L.dastac_symv_f32(4, _p(A), _p(B), _p(A + 8), None) == dastac.EALIAS
     assert L.dastac_symv_f32(0, None, None, None, None) == dastac.OK
