@@ -81,6 +81,15 @@ def lib() -> ctypes.CDLL:
         L.oracle_pack_tril_f32.argtypes = [_i64, _fp, _i64, _fp]
         L.oracle_unpack_tril_f32.argtypes = [_i64, _fp, _fp, _i64]
         L.oracle_ttm_ut_f32.argtypes = [_i64, _i64, _i64, _fp, _fp, _i64, _fp, _dp, _i64, _i64]
+        L.oracle_pack_sband_f32.argtypes = [_i64, _i64, _i64, _fp, _i64, _fp]
+        L.oracle_unpack_sband_f32.argtypes = [_i64, _i64, _i64, _fp, _fp, _i64]
+        L.oracle_sband_spmv_f32.argtypes = [_i64, _i64, _i64, _fp, _fp, _fp, _dp, _i64, _i64]
+        L.oracle_pack_subtri_f32.argtypes = [_i64, _i64, _fp, _i64, _fp]
+        L.oracle_unpack_subtri_f32.argtypes = [_i64, _i64, _fp, _fp, _i64]
+        L.oracle_subtri_spmv_f32.argtypes = [_i64, _i64, _fp, _fp, _fp, _dp, _i64, _i64]
+        L.oracle_pack_leslie_f32.argtypes = [_i64, _fp, _i64, _fp, _fp]
+        L.oracle_unpack_leslie_f32.argtypes = [_i64, _fp, _fp, _fp, _i64]
+        L.oracle_leslie_spmv_f32.argtypes = [_i64, _fp, _fp, _fp, _fp, _dp]
         for name in ("pack_triu", "unpack_triu", "pack_tet", "unpack_tet", "pack_band", "unpack_band",
                      "trmv", "trmm", "band_spmv", "tet_ttv", "tet_mttkrp"):
             getattr(L, "oracle_%s_f32" % name).restype = None
@@ -318,3 +327,77 @@ def unpack_tril(n: int, packed: np.ndarray) -> np.ndarray:
     dense = np.empty((n, n), dtype=np.float32)
     lib().oracle_unpack_tril_f32(n, _f(packed), _f(dense), n)
     return dense
+
+
+# ---- further domains (Section 6.4, Table 2 SpMV_L) ---------------------------
+
+def pack_sband(dense: np.ndarray, w: int, s: int) -> np.ndarray:
+    dense = _f32(dense)
+    n = dense.shape[0]
+    out = np.empty((2 * w + 1) * n, dtype=np.float32)
+    lib().oracle_pack_sband_f32(n, w, s, _f(dense), dense.shape[1], _f(out))
+    return out
+
+
+def unpack_sband(n: int, w: int, s: int, diag: np.ndarray) -> np.ndarray:
+    diag = _f32(diag)
+    out = np.empty((n, n), dtype=np.float32)
+    lib().oracle_unpack_sband_f32(n, w, s, _f(diag), _f(out), n)
+    return out
+
+
+def sband_spmv(n, w, s, D, x, rows=None):
+    D, x = _f32(D), _f32(x)
+    lo, hi = _window(n, rows)
+    y = np.full(n, np.nan, dtype=np.float32)
+    sc = np.full(n, np.nan, dtype=np.float64)
+    lib().oracle_sband_spmv_f32(n, w, s, _f(D), _f(x), _f(y), _d(sc), lo, hi)
+    return y, sc
+
+
+def pack_subtri(dense: np.ndarray, k: int) -> np.ndarray:
+    dense = _f32(dense)
+    N = dense.shape[0]
+    out = np.empty(k * (k + 1) // 2, dtype=np.float32)
+    lib().oracle_pack_subtri_f32(N, k, _f(dense), dense.shape[1], _f(out))
+    return out
+
+
+def unpack_subtri(N: int, k: int, packed: np.ndarray) -> np.ndarray:
+    packed = _f32(packed)
+    out = np.empty((N, N), dtype=np.float32)
+    lib().oracle_unpack_subtri_f32(N, k, _f(packed), _f(out), N)
+    return out
+
+
+def subtri_spmv(N, k, Ap, x, rows=None):
+    Ap, x = _f32(Ap), _f32(x)
+    lo, hi = _window(N, rows)
+    y = np.full(N, np.nan, dtype=np.float32)
+    sc = np.full(N, np.nan, dtype=np.float64)
+    lib().oracle_subtri_spmv_f32(N, k, _f(Ap), _f(x), _f(y), _d(sc), lo, hi)
+    return y, sc
+
+
+def pack_leslie(dense: np.ndarray):
+    dense = _f32(dense)
+    n = dense.shape[0]
+    R = np.empty(n, dtype=np.float32)
+    S = np.empty(max(n - 1, 0), dtype=np.float32)
+    lib().oracle_pack_leslie_f32(n, _f(dense), dense.shape[1], _f(R), _f(S))
+    return R, S
+
+
+def unpack_leslie(n: int, R: np.ndarray, S: np.ndarray) -> np.ndarray:
+    R, S = _f32(R), _f32(S)
+    out = np.empty((n, n), dtype=np.float32)
+    lib().oracle_unpack_leslie_f32(n, _f(R), _f(S), _f(out), n)
+    return out
+
+
+def leslie_spmv(n, R, S, x):
+    R, S, x = _f32(R), _f32(S), _f32(x)
+    y = np.full(n, np.nan, dtype=np.float32)
+    sc = np.full(n, np.nan, dtype=np.float64)
+    lib().oracle_leslie_spmv_f32(n, _f(R), _f(S), _f(x), _f(y), _d(sc))
+    return y, sc

@@ -36,6 +36,9 @@
  *                                            strided-band structure with unit stride);
  *                                            slot (d,i) holds A[i][i+d], and slots whose
  *                                            column i+d falls outside [0,n) are padding.
+ *   SBAND (d,i)    as BAND with slot (d,i) holding A[i][i+d*s]   Section 6.4, strided band, stride s
+ *   SUBTRI (i,j)   0<=i<N, 0<=j<N, j-i>=N-k  Section 6.4, sub-triangular structure
+ *   LESLIE         (i=0)(0<=j<n) + (1<=i<n)(j=i-1)   Table 2, SpMV_L: two summands, two buffers
  */
 #include <math.h>
 #include <stdint.h>
@@ -514,4 +517,116 @@ void oracle_trimv_f32(int64_t n, int lower, int mode, const float *Tp, const flo
     if (scale) scale[i] = mag;
   }
   free(start);
+}
+
+/* ---- further domains of Section 6.4 and Table 2 ------------------------------------------- */
+
+/* Strided band (Section 6.4, "Distance of Elements and Compression"): summands j-i = d*s for
+ * d=-w..w (the paper's experiment is w=1: j=i, j-i=s, i-j=s).  Each summand has its own n-slot
+ * buffer, buffers in summand order; slot i of summand d holds A[i][i+d*s]; slots whose column
+ * falls outside the matrix are padding (+0 on pack, never used). */
+void oracle_pack_sband_f32(int64_t n, int64_t w, int64_t s, const float *dense, int64_t ld, float *diag) {
+  int64_t p = 0;
+  for (int64_t d = -w; d <= w; ++d)
+    for (int64_t i = 0; i < n; ++i) {
+      int64_t j = i + d * s;
+      diag[p++] = (j >= 0 && j < n) ? dense[i * ld + j] : 0.0f;
+    }
+}
+
+void oracle_unpack_sband_f32(int64_t n, int64_t w, int64_t s, const float *diag, float *dense, int64_t ld) {
+  for (int64_t i = 0; i < n; ++i)
+    for (int64_t j = 0; j < n; ++j) dense[i * ld + j] = 0.0f;
+  int64_t p = 0;
+  for (int64_t d = -w; d <= w; ++d)
+    for (int64_t i = 0; i < n; ++i) {
+      int64_t j = i + d * s;
+      if (j >= 0 && j < n) dense[i * ld + j] = diag[p];
+      ++p;
+    }
+}
+
+void oracle_sband_spmv_f32(int64_t n, int64_t w, int64_t s, const float *D, const float *x, float *y,
+                           double *scale, int64_t r_lo, int64_t r_hi) {
+  for (int64_t i = 0; i < n; ++i) {
+    if (i < r_lo || i >= r_hi) continue;
+    double acc = 0.0, mag = 0.0;
+    for (int64_t d = -w; d <= w; ++d) {
+      int64_t j = i + d * s;
+      if (j < 0 || j >= n) continue;
+      double t = (double)D[(d + w) * n + i] * (double)x[j];
+      acc += t;
+      mag += fabs(t);
+    }
+    y[i] = (float)acc;
+    if (scale) scale[i] = mag;
+  }
+}
+
+/* Sub-triangular structure (Section 6.4, "Density and Compression"): the unique set is
+ * 0<=i<N, 0<=j<N, j-i >= N-k.  Packed in iteration order (i,j) by a running counter. */
+void oracle_pack_subtri_f32(int64_t N, int64_t k, const float *dense, int64_t ld, float *packed) {
+  int64_t p = 0;
+  for (int64_t i = 0; i < N; ++i)
+    for (int64_t j = 0; j < N; ++j)
+      if (j - i >= N - k) packed[p++] = dense[i * ld + j];
+}
+
+void oracle_unpack_subtri_f32(int64_t N, int64_t k, const float *packed, float *dense, int64_t ld) {
+  int64_t p = 0;
+  for (int64_t i = 0; i < N; ++i)
+    for (int64_t j = 0; j < N; ++j) dense[i * ld + j] = (j - i >= N - k) ? packed[p++] : 0.0f;
+}
+
+/* y(i) := A(i,j) x(j) over the sub-triangular structure; every one of the N outputs is written
+ * (rows without a stored element give 0). */
+void oracle_subtri_spmv_f32(int64_t N, int64_t k, const float *Ap, const float *x, float *y, double *scale,
+                            int64_t r_lo, int64_t r_hi) {
+  int64_t p = 0;
+  for (int64_t i = 0; i < N; ++i) {
+    double acc = 0.0, mag = 0.0;
+    for (int64_t j = 0; j < N; ++j) {
+      if (j - i < N - k) continue;
+      double t = (double)Ap[p++] * (double)x[j];
+      acc += t;
+      mag += fabs(t);
+    }
+    if (i >= r_lo && i < r_hi) {
+      y[i] = (float)acc;
+      if (scale) scale[i] = mag;
+    }
+  }
+}
+
+/* Leslie structure (Table 2, SpMV_L): (i=0)(0<=j<n) + (1<=i<n)(j=i-1).  Two summands, two
+ * buffers: R[n] is the first row in order of j, S[n-1] the sub-diagonal in order of i. */
+void oracle_pack_leslie_f32(int64_t n, const float *dense, int64_t ld, float *R, float *S) {
+  int64_t p = 0;
+  for (int64_t j = 0; j < n; ++j) R[p++] = dense[j];
+  p = 0;
+  for (int64_t i = 1; i < n; ++i) S[p++] = dense[i * ld + (i - 1)];
+}
+
+void oracle_unpack_leslie_f32(int64_t n, const float *R, const float *S, float *dense, int64_t ld) {
+  for (int64_t i = 0; i < n; ++i)
+    for (int64_t j = 0; j < n; ++j) dense[i * ld + j] = 0.0f;
+  for (int64_t j = 0; j < n; ++j) dense[j] = R[j];
+  for (int64_t i = 1; i < n; ++i) dense[i * ld + (i - 1)] = S[i - 1];
+}
+
+void oracle_leslie_spmv_f32(int64_t n, const float *R, const float *S, const float *x, float *y, double *scale) {
+  if (n <= 0) return;
+  double acc = 0.0, mag = 0.0;
+  for (int64_t j = 0; j < n; ++j) {
+    double t = (double)R[j] * (double)x[j];
+    acc += t;
+    mag += fabs(t);
+  }
+  y[0] = (float)acc;
+  if (scale) scale[0] = mag;
+  for (int64_t i = 1; i < n; ++i) {
+    double t = (double)S[i - 1] * (double)x[i - 1];
+    y[i] = (float)t;
+    if (scale) scale[i] = fabs(t);
+  }
 }

@@ -443,3 +443,98 @@ def test_triangle_vector_products_against_dense_numpy(oracle, n, lower):
         Up = oracle.pack_triu(np.ascontiguousarray(T.T.astype(np.float32)))
         assert np.array_equal(oracle.trimv(n, Tp, x, lower=True, mode=2)[0], oracle.symv(n, Up, x)[0])
 
+
+
+# ------------------------------------- further domains (Section 6.4, SpMV_L) ----
+
+@pytest.mark.parametrize("n,w,s", [(1, 1, 1), (9, 1, 1), (9, 1, 3), (16, 1, 16), (16, 1, 40), (20, 2, 4), (13, 0, 5)])
+def test_strided_band_against_numpy_diagonals(oracle, n, w, s):
+    """Section 6.4 strided band: summand d is the diagonal at offset d*s; s=1 is the unit band,
+    s>=n leaves the main diagonal only."""
+    Dn = inputs.uniform(900 + n + s, n, n)
+    P = oracle.pack_sband(Dn, w, s).reshape(2 * w + 1, n)
+    A = np.zeros((n, n), dtype=np.float32)
+    for d in range(-w, w + 1):
+        row = np.zeros(n, dtype=np.float32)
+        diag = np.diagonal(Dn, offset=d * s)
+        if len(diag):
+            if d >= 0:
+                row[: len(diag)] = diag
+            else:
+                row[-d * s: -d * s + len(diag)] = diag
+            A += np.diag(diag, k=d * s)
+        assert np.array_equal(P[d + w], row)
+    assert np.array_equal(oracle.unpack_sband(n, w, s, P.ravel()), A)
+    if s == 1:
+        assert np.array_equal(P.ravel(), oracle.pack_band(Dn, w))
+    # the product, with poisoned padding
+    x = inputs.normal(901 + n, n)
+    Pp = P.copy()
+    for d in range(-w, w + 1):
+        for i in range(n):
+            if not (0 <= i + d * s < n):
+                Pp[d + w, i] = np.nan
+    y, sc = oracle.sband_spmv(n, w, s, Pp.ravel(), x)
+    assert _close(y, A.astype(np.float64) @ x.astype(np.float64), sc)
+    assert np.allclose(sc, np.abs(A.astype(np.float64)) @ np.abs(x.astype(np.float64)), rtol=1e-12)
+    if s >= n:  # diagonal matrix: elementwise product
+        assert np.array_equal(y, (np.diagonal(Dn).astype(np.float64) * x).astype(np.float32))
+
+
+def test_strided_band_matches_scipy_diags(oracle):
+    import scipy.sparse as sp
+    n, s = 64, 7
+    D = inputs.normal(77, 3, n)
+    x = inputs.normal(78, n)
+    # scipy's diags takes each diagonal as its in-matrix elements, in order of the row index
+    diags = [D[0, s:].astype(np.float64), D[1].astype(np.float64), D[2, : n - s].astype(np.float64)]
+    A = sp.diags(diags, offsets=[-s, 0, s], shape=(n, n), format="csr")
+    y, sc = oracle.sband_spmv(n, 1, s, D.ravel(), x)
+    assert _close(y, A @ x.astype(np.float64), sc)
+
+
+@pytest.mark.parametrize("N,k", [(1, 0), (1, 1), (8, 0), (8, 3), (8, 8), (21, 13), (33, 32)])
+def test_subtriangular_against_numpy_triu(oracle, N, k):
+    """Section 6.4 sub-triangular structure: j-i >= N-k is NumPy's triu with offset N-k, its packed
+    form is the packed upper triangle of the k x k block in the top right corner, and the product
+    is the TRMV of that block on the last k entries of x."""
+    Dn = inputs.uniform(950 + N + k, N, N)
+    A = np.triu(Dn, k=N - k)
+    P = oracle.pack_subtri(Dn, k)
+    assert P.size == k * (k + 1) // 2 == np.count_nonzero(np.triu(np.ones((N, N)), k=N - k))
+    assert np.array_equal(P, Dn[np.triu(np.ones((N, N), dtype=bool), k=N - k)])
+    assert np.array_equal(P, oracle.pack_triu(np.ascontiguousarray(Dn[:k, N - k:])))
+    assert np.array_equal(oracle.unpack_subtri(N, k, P), A)
+    x = inputs.normal(951 + N, N)
+    y, sc = oracle.subtri_spmv(N, k, P, x)
+    assert _close(y, A.astype(np.float64) @ x.astype(np.float64), sc)
+    assert np.all(y[k:] == 0)
+    if k:
+        yt, _ = oracle.trmv(k, P, np.ascontiguousarray(x[N - k:]))
+        assert np.array_equal(y[:k], yt)
+
+
+@pytest.mark.parametrize("n", [1, 2, 5, 32, 77])
+def test_leslie_against_dense_numpy(oracle, n):
+    """Table 2 SpMV_L: first row plus sub-diagonal."""
+    Dn = inputs.uniform(980 + n, n, n)
+    i, j = np.meshgrid(np.arange(n), np.arange(n), indexing="ij")
+    A = np.where((i == 0) | (j == i - 1), Dn, np.float32(0))
+    R, S = oracle.pack_leslie(Dn)
+    assert np.array_equal(R, Dn[0])
+    assert np.array_equal(S, np.diagonal(Dn, offset=-1))
+    assert np.array_equal(oracle.unpack_leslie(n, R, S), A)
+    x = inputs.normal(981 + n, n)
+    y, sc = oracle.leslie_spmv(n, R, S, x)
+    assert _close(y, A.astype(np.float64) @ x.astype(np.float64), sc)
+    assert np.allclose(sc, np.abs(A.astype(np.float64)) @ np.abs(x.astype(np.float64)), rtol=1e-12)
+
+
+def test_leslie_population_step(oracle):
+    """A Leslie matrix advances an age-structured population: newborns are the fertility-weighted
+    sum, every other class is the survivors of the class before it."""
+    f = np.array([0, 1, 2, 1], dtype=np.float32)
+    surv = np.array([0.5, 0.5, 0.25], dtype=np.float32)
+    pop = np.array([8, 4, 4, 8], dtype=np.float32)
+    y, _ = oracle.leslie_spmv(4, f, surv, pop)
+    assert np.array_equal(y, np.array([20, 4, 2, 1], dtype=np.float32))
