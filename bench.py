@@ -241,42 +241,58 @@ def main() -> int:
             del A3
         result["sweep"] = sweep
 
-    # Measured beside the step, never part of `value`: the paper's running example (TTM_UT) and the
-    # symmetric product on a packed triangle, which are not among the five benchmark configurations.
+    # Measured beside the step, never part of `value`: the paper's running example (TTM_UT), the
+    # symmetric product on a packed triangle, and the strided-band, sub-triangular and Leslie SpMVs,
+    # which are not among the five benchmark configurations.
+    def beside(fn):
+        for _ in range(args.warmup):
+            fn()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+        ev[0].record()
+        for s in range(args.steps):
+            fn()
+            ev[s + 1].record()
+        torch.cuda.synchronize()
+        return float(np.mean([ev[s].elapsed_time(ev[s + 1]) for s in range(args.steps)]))
+
+    def entry(workload, ms, a, bound):
+        frac = a["flops"] / ms / 1e9 / MFMA_F32_PEAK_TFLOPS if bound == "mfma" else a["bytes"] / ms / 1e6 / HBM_PEAK_GBPS
+        return {"workload": workload, "ms": ms, "gflops": a["flops"] / ms / 1e6, "gbps": a["bytes"] / ms / 1e6,
+                "bound": bound, "frac": frac}
+
     tw = wl.ttm_ut_inputs()
     nt, Qt, Kt = tw["n"], tw["Q"], tw["K"]
     gB, gC, gA = up(tw["Bp"]), up(tw["C"]), out(nt * (nt + 1) // 2 * Kt)
-    for _ in range(args.warmup):
-        d.ttm_ut_f32(nt, Qt, Kt, gB, gC, Qt, gA)
-    tev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
-    tev[0].record()
-    for s in range(args.steps):
-        d.ttm_ut_f32(nt, Qt, Kt, gB, gC, Qt, gA)
-        tev[s + 1].record()
-    torch.cuda.synchronize()
-    tms = float(np.mean([tev[s].elapsed_time(tev[s + 1]) for s in range(args.steps)]))
-    ta = wl.accounting("ttm_ut", n=nt, Q=Qt, K=Kt)
-    result["beside"] = {"ttm_ut": {"workload": "TTM_UT n=%d Q=%d K=%d, packed in and out" % (nt, Qt, Kt), "ms": tms,
-                                   "gflops": ta["flops"] / tms / 1e6, "gbps": ta["bytes"] / tms / 1e6, "bound": "mfma",
-                                   "frac": ta["flops"] / tms / 1e9 / MFMA_F32_PEAK_TFLOPS}}
-    del gB, gA
+    tms = beside(lambda: d.ttm_ut_f32(nt, Qt, Kt, gB, gC, Qt, gA))
+    result["beside"] = {"ttm_ut": entry("TTM_UT n=%d Q=%d K=%d, packed in and out" % (nt, Qt, Kt), tms,
+                                        wl.accounting("ttm_ut", n=nt, Q=Qt, K=Kt), "mfma")}
+    del gB, gA, tw
     sw = wl.symv_inputs()
     ns = sw["n"]
     gU, gx, gy = up(sw["Up"]), up(sw["x"]), out(ns)
-    for _ in range(args.warmup):
-        d.symv_f32(ns, gU, gx, gy)
-    sev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
-    sev[0].record()
-    for s in range(args.steps):
-        d.symv_f32(ns, gU, gx, gy)
-        sev[s + 1].record()
-    torch.cuda.synchronize()
-    sms = float(np.mean([sev[s].elapsed_time(sev[s + 1]) for s in range(args.steps)]))
-    sa = wl.accounting("symv", n=ns)
-    result["beside"]["symv"] = {"workload": "SYMV n=%d on the packed upper triangle" % ns, "ms": sms,
-                                "gflops": sa["flops"] / sms / 1e6, "gbps": sa["bytes"] / sms / 1e6, "bound": "hbm",
-                                "frac": sa["bytes"] / sms / 1e6 / HBM_PEAK_GBPS}
-    del gU
+    sms = beside(lambda: d.symv_f32(ns, gU, gx, gy))
+    result["beside"]["symv"] = entry("SYMV n=%d on the packed upper triangle" % ns, sms, wl.accounting("symv", n=ns), "hbm")
+    del gU, sw
+    bw = wl.sband_inputs()
+    nb, wb, sb = bw["n"], bw["w"], bw["s"]
+    gD, gx, gy = up(bw["D"]), up(bw["x"]), out(nb)
+    bms = beside(lambda: d.sband_spmv_f32(nb, wb, sb, gD, gx, gy))
+    result["beside"]["sband"] = entry("strided-band SpMV n=%d w=%d s=%d" % (nb, wb, sb), bms,
+                                      wl.accounting("sband", n=nb, w=wb, s=sb), "hbm")
+    del gD, bw
+    uw = wl.subtri_inputs()
+    Nu, ku = uw["N"], uw["k"]
+    gP, gx, gy = up(uw["Ap"]), up(uw["x"]), out(Nu)
+    ums = beside(lambda: d.subtri_spmv_f32(Nu, ku, gP, gx, gy))
+    result["beside"]["subtri"] = entry("sub-triangular SpMV N=%d k=%d" % (Nu, ku), ums,
+                                       wl.accounting("subtri", N=Nu, k=ku), "hbm")
+    del gP, uw
+    lw = wl.leslie_inputs()
+    nl = lw["n"]
+    gR, gS, gx, gy = up(lw["R"]), up(lw["S"]), up(lw["x"]), out(nl)
+    lms = beside(lambda: d.leslie_spmv_f32(nl, gR, gS, gx, gy))
+    result["beside"]["leslie"] = entry("Leslie SpMV n=%d" % nl, lms, wl.accounting("leslie", n=nl), "hbm")
+    del gR, gS, lw
 
     if not args.no_cpu_baseline:
         import oracle

@@ -23,6 +23,12 @@
  *                                   per-summand buffers), buffers in order d=-w..w;
  *                                   slot i of diagonal d holds A[i][i+d]; the |d| slots of a
  *                                   diagonal whose column falls outside the matrix are padding.
+ *   strided band j-i = d*s, |d|<=w  sband(n,w,d,i) = (d+w)*n + i: the same buffers, slot i of summand d
+ *                                   holding A[i][i+d*s] (Section 6.4, strided-band structure)
+ *   sub-triangle j-i >= N-k         subtri(N,k,i,j) = tri(k, i, j-(N-k)): the upper triangle of the
+ *                                   k x k block in the top right corner (Section 6.4, sub-triangular structure)
+ *   Leslie (i=0) + (j=i-1)          two summands, two buffers: R[n] with A[0][j] at j, S[n-1] with
+ *                                   A[i][i-1] at i-1 (Table 2, SpMV_L)
  *
  * All index arithmetic is exact 64-bit integer arithmetic: the rational coefficients
  * are evaluated on a doubled (or six-fold) numerator that is always divisible
@@ -82,6 +88,8 @@ int64_t dastac_tril_offset(int64_t n, int64_t i, int64_t j);
 /* Upper half cube of the running example (i<=j<n, 0<=l<Q; Q >= 1): Tri(n)*Q elements. */
 int64_t dastac_uhc_count(int64_t n, int64_t Q);
 int64_t dastac_uhc_offset(int64_t n, int64_t Q, int64_t i, int64_t j, int64_t l);
+/* Sub-triangular structure j-i >= N-k, 0<=k<=N (Section 6.4): tri_count(k) elements. */
+int64_t dastac_subtri_offset(int64_t N, int64_t k, int64_t i, int64_t j);
 
 /* Inverse polynomials: the unique domain point whose offset is p.  The paper only
  * mentions inverting a quasi-polynomial as costly when done per iteration (Section 7,
@@ -101,7 +109,10 @@ int dastac_tet_inverse(int64_t n, int64_t p, int64_t *i, int64_t *j, int64_t *k)
  *   band : dense n x n (stride ld)      <-> diag_major[(2w+1)*n]; pack writes +0.0f into padding slots,
  *                                           unpack ignores them.
  *   uhc  : dense n x n x Q, contiguous  <-> packed[uhc_count(n,Q)]
- *   tril : dense n x n (stride ld)      <-> packed[tri_count(n)], row i holding columns 0..i */
+ *   tril : dense n x n (stride ld)      <-> packed[tri_count(n)], row i holding columns 0..i
+ *   sband: dense n x n (stride ld)      <-> diag_major[(2w+1)*n], stride s >= 1; padding as for band
+ *   subtri: dense N x N (stride ld)     <-> packed[tri_count(k)], 0 <= k <= N
+ *   leslie: dense n x n (stride ld)     <-> R[n] and S[n-1] (S may be NULL when n == 1) */
 int dastac_pack_triu_f32(int64_t n, const float *dense, int64_t ld, float *packed, void *stream);
 int dastac_unpack_triu_f32(int64_t n, const float *packed, float *dense, int64_t ld, void *stream);
 int dastac_pack_tet_f32(int64_t n, const float *dense, float *packed, void *stream);
@@ -112,6 +123,14 @@ int dastac_pack_tril_f32(int64_t n, const float *dense, int64_t ld, float *packe
 int dastac_unpack_tril_f32(int64_t n, const float *packed, float *dense, int64_t ld, void *stream);
 int dastac_pack_uhc_f32(int64_t n, int64_t Q, const float *dense, float *packed, void *stream);
 int dastac_unpack_uhc_f32(int64_t n, int64_t Q, const float *packed, float *dense, void *stream);
+int dastac_pack_sband_f32(int64_t n, int64_t w, int64_t s, const float *dense, int64_t ld, float *diag_major,
+                          void *stream);
+int dastac_unpack_sband_f32(int64_t n, int64_t w, int64_t s, const float *diag_major, float *dense, int64_t ld,
+                            void *stream);
+int dastac_pack_subtri_f32(int64_t N, int64_t k, const float *dense, int64_t ld, float *packed, void *stream);
+int dastac_unpack_subtri_f32(int64_t N, int64_t k, const float *packed, float *dense, int64_t ld, void *stream);
+int dastac_pack_leslie_f32(int64_t n, const float *dense, int64_t ld, float *R, float *S, void *stream);
+int dastac_unpack_leslie_f32(int64_t n, const float *R, const float *S, float *dense, int64_t ld, void *stream);
 
 /* ---- contractions: DEVICE, fp32 storage and arithmetic ---------------------------
  * Summation order is unspecified (the paper compiles with fast-math, Section 6.1);
@@ -149,6 +168,21 @@ int dastac_trmm_f32(int64_t n, int64_t m, const float *Up, const float *B, int64
  * 2w+1 summands; w=0 is Table 2's SpMV_D).  D[(2w+1)*n] diagonal-major as described above; padding
  * slots are never used for their value.  0 <= w <= 64. */
 int dastac_band_spmv_f32(int64_t n, int64_t w, const float *D, const float *x, float *y, void *stream);
+
+/* y(i) := sum_{d=-w..w, 0<=i+d*s<n} D(d,i) * x(i+d*s)   (Section 6.4, strided band; the paper's experiment
+ * is w=1 with s from 1, tridiagonal, to n, diagonal).  D[(2w+1)*n] as for band_spmv with slot (d,i)
+ * holding A[i][i+d*s]; 0 <= w <= 64, 1 <= s <= 2^40 (s >= n leaves the main diagonal). */
+int dastac_sband_spmv_f32(int64_t n, int64_t w, int64_t s, const float *D, const float *x, float *y, void *stream);
+
+/* y(i) := A(i,j) * x(j), j-i >= N-k   (Section 6.4, sub-triangular structure; k = N is SpMV_UT).
+ * Ap[tri_count(k)], x[N], y[N]; all N outputs are written, rows k..N-1 with +0.  0 <= k <= N,
+ * k <= 524288; above k = 8192 accumulated with atomics like trmv. */
+int dastac_subtri_spmv_f32(int64_t N, int64_t k, const float *Ap, const float *x, float *y, void *stream);
+
+/* y(0) := R(j) * x(j);  y(i) := S(i-1) * x(i-1), 1<=i<n   (Table 2, SpMV_L: first row plus sub-diagonal).
+ * R[n], S[n-1] (may be NULL when n == 1), x[n], y[n].  y(0) is accumulated with one floating-point
+ * atomic per workgroup (last bits may differ between calls); every other output is one exact product. */
+int dastac_leslie_spmv_f32(int64_t n, const float *R, const float *S, const float *x, float *y, void *stream);
 
 /* M(i,j) := A(i,j,k) * v(k), i<=j<=k.  Ap[tet_count(n)], v[n]; the output is itself packed:
  * Mp[tri_count(n)] with M(i,j) at tri(n,i,j).  n <= 8192 (a larger tetrahedron

@@ -1,0 +1,303 @@
+// Three more structures, each a single-piece index polynomial over the same streaming pattern:
+//
+//   strided band   (Section 6.4, "Distance of Elements and Compression"): summands j-i = d*s,
+//                  d=-w..w; the paper's experiment is w=1.  Same diagonal-major buffers as the
+//                  unit-stride band, slot (d,i) holds A[i][i+d*s]; only the column a slot
+//                  multiplies with changes, so the packed streams stay perfectly contiguous
+//                  whatever the stride.
+//   sub-triangular (Section 6.4, "Density and Compression"): j-i >= N-k.  Its unique set is the
+//                  upper triangle of the k x k block in the top right corner, so
+//                  subtri(N,k,i,j) = tri(k,i,j-(N-k)) and the product is the packed TRMV of order
+//                  k on the last k entries of x; rows k..N-1 hold no element and give 0.
+//   Leslie         (Table 2, SpMV_L): (i=0)(0<=j<n) + (1<=i<n)(j=i-1); two summands, two buffers:
+//                  R[n], the first row in order of j, and S[n-1], the sub-diagonal in order of i.
+//                  Output 0 is a dot product over the whole first row, every other output is one
+//                  product; both read x(j) once.
+#include "common.h"
+
+using namespace dastac;
+
+namespace {
+
+constexpr int kBlock = 256;
+constexpr int64_t kDenseMaxN = 1 << 20;
+constexpr int kLeslieMaxBlocks = 1024;  // one atomic per workgroup lands on y(0)
+
+inline unsigned grid_for(int64_t nblocks) { return (unsigned)(nblocks < (1 << 22) ? nblocks : (1 << 22)); }
+
+// ---- strided band ---------------------------------------------------------------------------
+
+// W >= 0: half-width known at compile time; W < 0: run-time half-width `w`.  One row per lane.
+template <int W>
+__global__ __launch_bounds__(kBlock) void sband_kernel(int64_t n, int w, int64_t s, const float *__restrict__ D,
+                                                       const float *__restrict__ x, float *__restrict__ y) {
+  const int hw = W >= 0 ? W : w;
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= n) return;
+  const float *d = D + i;
+  const int64_t reach = (int64_t)hw * s;
+  float acc = 0.0f;
+  if (i >= reach && i + reach < n) {  // interior row: every column exists
+    const float *xw = x + (i - reach);
+    if (W >= 0) {
+#pragma unroll
+      for (int dd = 0; dd <= 2 * (W >= 0 ? W : 0); ++dd)
+        acc += __builtin_nontemporal_load(d + (int64_t)dd * n) * xw[(int64_t)dd * s];
+    } else {
+      for (int dd = 0; dd <= 2 * hw; ++dd)
+        acc += __builtin_nontemporal_load(d + (int64_t)dd * n) * xw[(int64_t)dd * s];
+    }
+  } else {  // a row whose window leaves the matrix: skip the padding slots
+    for (int dd = 0; dd <= 2 * hw; ++dd) {
+      const int64_t c = i + (int64_t)(dd - hw) * s;
+      if (c >= 0 && c < n) acc += d[(int64_t)dd * n] * x[c];
+    }
+  }
+  __builtin_nontemporal_store(acc, y + i);
+}
+
+__global__ __launch_bounds__(kBlock) void pack_sband_kernel(int64_t n, int64_t w, int64_t s,
+                                                            const float *__restrict__ dense, int64_t ld,
+                                                            float *__restrict__ diag, int64_t pieces,
+                                                            int64_t nblocks) {
+  for (int64_t b = blockIdx.x; b < nblocks; b += gridDim.x) {
+    const int64_t dw = b / pieces;  // d + w
+    const int64_t i = (b - dw * pieces) * kBlock + threadIdx.x;
+    if (i >= n) continue;
+    const int64_t j = i + (dw - w) * s;
+    diag[dw * n + i] = (j >= 0 && j < n) ? dense[i * ld + j] : 0.0f;
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void unpack_sband_kernel(int64_t n, int64_t w, int64_t s,
+                                                              const float *__restrict__ diag,
+                                                              float *__restrict__ dense, int64_t ld,
+                                                              int64_t pieces, int64_t nblocks) {
+  for (int64_t b = blockIdx.x; b < nblocks; b += gridDim.x) {
+    const int64_t i = b / pieces;
+    const int64_t j = (b - i * pieces) * kBlock + threadIdx.x;
+    if (j >= n) continue;
+    const int64_t dj = j - i, d = dj / s;  // exact only on a stored diagonal
+    const bool stored = d * s == dj && d >= -w && d <= w;
+    dense[i * ld + j] = stored ? diag[(d + w) * n + i] : 0.0f;
+  }
+}
+
+// ---- sub-triangular -------------------------------------------------------------------------
+
+__global__ __launch_bounds__(kBlock) void unpack_subtri_kernel(int64_t N, int64_t k, const float *__restrict__ packed,
+                                                               float *__restrict__ dense, int64_t ld,
+                                                               int64_t pieces, int64_t nblocks) {
+  for (int64_t b = blockIdx.x; b < nblocks; b += gridDim.x) {
+    const int64_t i = b / pieces;
+    const int64_t j = (b - i * pieces) * kBlock + threadIdx.x;
+    if (j >= N) continue;
+    const int64_t c = j - (N - k);  // column inside the k x k corner block
+    dense[i * ld + j] = (i < k && c >= i) ? packed[tri_offset(k, i, c)] : 0.0f;
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void zero_tail_kernel(float *__restrict__ y, int64_t count) {
+  const int64_t t = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (t < count) y[t] = 0.0f;
+}
+
+// ---- Leslie ---------------------------------------------------------------------------------
+
+__global__ __launch_bounds__(kBlock) void leslie_kernel(int64_t n, const float *__restrict__ R,
+                                                        const float *__restrict__ S, const float *__restrict__ x,
+                                                        float *__restrict__ y) {
+  __shared__ float part[kBlock / 64];
+  const int64_t stride = (int64_t)gridDim.x * kBlock;
+  float acc = 0.0f;
+  int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  for (; j + 3 * stride < n; j += 4 * stride) {  // four independent rows in flight per lane
+    float xv[4], rv[4], sv[4];
+    const bool last = j + 3 * stride + 1 < n;  // only the fourth can be the row without a successor
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      xv[q] = x[j + q * stride];
+      rv[q] = __builtin_nontemporal_load(R + j + q * stride);
+    }
+#pragma unroll
+    for (int q = 0; q < 3; ++q) sv[q] = __builtin_nontemporal_load(S + j + q * stride);
+    sv[3] = last ? __builtin_nontemporal_load(S + j + 3 * stride) : 0.0f;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc += rv[q] * xv[q];
+#pragma unroll
+    for (int q = 0; q < 3; ++q) __builtin_nontemporal_store(sv[q] * xv[q], y + j + q * stride + 1);
+    if (last) __builtin_nontemporal_store(sv[3] * xv[3], y + j + 3 * stride + 1);
+  }
+  for (; j < n; j += stride) {
+    const float xj = x[j];
+    acc += __builtin_nontemporal_load(R + j) * xj;
+    if (j + 1 < n) __builtin_nontemporal_store(__builtin_nontemporal_load(S + j) * xj, y + j + 1);
+  }
+  for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float t = 0.0f;
+    for (int v = 0; v < kBlock / 64; ++v) t += part[v];
+    atomicAdd(y, t);  // y(0) was cleared by the launch before this one
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void pack_leslie_kernel(int64_t n, const float *__restrict__ dense, int64_t ld,
+                                                             float *__restrict__ R, float *__restrict__ S) {
+  const int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (j >= n) return;
+  R[j] = dense[j];
+  if (j + 1 < n) S[j] = dense[(j + 1) * ld + j];
+}
+
+__global__ __launch_bounds__(kBlock) void unpack_leslie_kernel(int64_t n, const float *__restrict__ R,
+                                                               const float *__restrict__ S,
+                                                               float *__restrict__ dense, int64_t ld, int64_t pieces,
+                                                               int64_t nblocks) {
+  for (int64_t b = blockIdx.x; b < nblocks; b += gridDim.x) {
+    const int64_t i = b / pieces;
+    const int64_t j = (b - i * pieces) * kBlock + threadIdx.x;
+    if (j >= n) continue;
+    dense[i * ld + j] = i == 0 ? R[j] : (j == i - 1 ? S[j] : 0.0f);
+  }
+}
+
+int check_sband(int64_t n, int64_t w, int64_t s) {
+  if (n < 0 || w < 0 || s < 1) return DASTAC_EINVAL;
+  if (s > ((int64_t)1 << 40)) return DASTAC_EOVERFLOW;
+  return DASTAC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t dastac_subtri_offset(int64_t N, int64_t k, int64_t i, int64_t j) {
+  if (N < 0 || N > DASTAC_TRI_MAX_N || k < 0 || k > N || i < 0 || j >= N || j - i < N - k) return -1;
+  return tri_offset(k, i, j - (N - k));
+}
+
+int dastac_pack_sband_f32(int64_t n, int64_t w, int64_t s, const float *dense, int64_t ld, float *diag_major,
+                          void *stream) {
+  if (int rc = check_sband(n, w, s)) return rc;
+  if (ld < n) return DASTAC_EINVAL;
+  if (n > kDenseMaxN || w > kDenseMaxN) return DASTAC_EOVERFLOW;
+  if (n == 0) return DASTAC_OK;
+  if (!dense || !diag_major) return DASTAC_ENULL;
+  if (overlaps(dense, n * ld * 4, diag_major, (2 * w + 1) * n * 4)) return DASTAC_EALIAS;
+  const int64_t pieces = ceil_div(n, kBlock), nblocks = (2 * w + 1) * pieces;
+  pack_sband_kernel<<<grid_for(nblocks), kBlock, 0, (hipStream_t)stream>>>(n, w, s, dense, ld, diag_major, pieces,
+                                                                           nblocks);
+  return launch_status();
+}
+
+int dastac_unpack_sband_f32(int64_t n, int64_t w, int64_t s, const float *diag_major, float *dense, int64_t ld,
+                            void *stream) {
+  if (int rc = check_sband(n, w, s)) return rc;
+  if (ld < n) return DASTAC_EINVAL;
+  if (n > kDenseMaxN || w > kDenseMaxN) return DASTAC_EOVERFLOW;
+  if (n == 0) return DASTAC_OK;
+  if (!dense || !diag_major) return DASTAC_ENULL;
+  if (overlaps(dense, n * ld * 4, diag_major, (2 * w + 1) * n * 4)) return DASTAC_EALIAS;
+  const int64_t pieces = ceil_div(n, kBlock), nblocks = n * pieces;
+  unpack_sband_kernel<<<grid_for(nblocks), kBlock, 0, (hipStream_t)stream>>>(n, w, s, diag_major, dense, ld, pieces,
+                                                                             nblocks);
+  return launch_status();
+}
+
+int dastac_sband_spmv_f32(int64_t n, int64_t w, int64_t s, const float *D, const float *x, float *y, void *stream) {
+  if (int rc = check_sband(n, w, s)) return rc;
+  if (w > 64) return DASTAC_EINVAL;
+  if (n > ((int64_t)1 << 40) / (2 * w + 1)) return DASTAC_EOVERFLOW;
+  if (n == 0) return DASTAC_OK;
+  if (!D || !x || !y) return DASTAC_ENULL;
+  if (overlaps(y, n * 4, D, (2 * w + 1) * n * 4) || overlaps(y, n * 4, x, n * 4)) return DASTAC_EALIAS;
+  hipStream_t st = (hipStream_t)stream;
+  const unsigned blocks = (unsigned)ceil_div(n, kBlock);
+  if (w == 1)
+    sband_kernel<1><<<blocks, kBlock, 0, st>>>(n, 1, s, D, x, y);
+  else
+    sband_kernel<-1><<<blocks, kBlock, 0, st>>>(n, (int)w, s, D, x, y);
+  return launch_status();
+}
+
+int dastac_pack_subtri_f32(int64_t N, int64_t k, const float *dense, int64_t ld, float *packed, void *stream) {
+  if (N < 0 || k < 0 || k > N || ld < N) return DASTAC_EINVAL;
+  if (N > kDenseMaxN) return DASTAC_EOVERFLOW;
+  if (k == 0) return DASTAC_OK;
+  if (!dense || !packed) return DASTAC_ENULL;
+  if (overlaps(dense, N * ld * 4, packed, tri(k) * 4)) return DASTAC_EALIAS;
+  // the unique set is the upper triangle of the k x k block whose first column is N-k
+  return dastac_pack_triu_f32(k, dense + (N - k), ld, packed, stream);
+}
+
+int dastac_unpack_subtri_f32(int64_t N, int64_t k, const float *packed, float *dense, int64_t ld, void *stream) {
+  if (N < 0 || k < 0 || k > N || ld < N) return DASTAC_EINVAL;
+  if (N > kDenseMaxN) return DASTAC_EOVERFLOW;
+  if (N == 0) return DASTAC_OK;
+  if (!dense || (k > 0 && !packed)) return DASTAC_ENULL;
+  if (overlaps(dense, N * ld * 4, packed, tri(k) * 4)) return DASTAC_EALIAS;
+  const int64_t pieces = ceil_div(N, kBlock), nblocks = N * pieces;
+  unpack_subtri_kernel<<<grid_for(nblocks), kBlock, 0, (hipStream_t)stream>>>(N, k, packed, dense, ld, pieces,
+                                                                              nblocks);
+  return launch_status();
+}
+
+int dastac_subtri_spmv_f32(int64_t N, int64_t k, const float *Ap, const float *x, float *y, void *stream) {
+  if (N < 0 || k < 0 || k > N) return DASTAC_EINVAL;
+  if (N > ((int64_t)1 << 40)) return DASTAC_EOVERFLOW;
+  if (N == 0) return DASTAC_OK;
+  if (!x || !y || (k > 0 && !Ap)) return DASTAC_ENULL;
+  if (overlaps(y, N * 4, x, N * 4) || overlaps(y, N * 4, Ap, tri(k) * 4)) return DASTAC_EALIAS;
+  if (k > 0) {
+    const int rc = dastac_trmv_f32(k, Ap, x + (N - k), y, stream);  // also bounds k
+    if (rc != DASTAC_OK) return rc;
+  }
+  if (k < N) {
+    zero_tail_kernel<<<(unsigned)ceil_div(N - k, kBlock), kBlock, 0, (hipStream_t)stream>>>(y + k, N - k);
+    return launch_status();
+  }
+  return DASTAC_OK;
+}
+
+int dastac_pack_leslie_f32(int64_t n, const float *dense, int64_t ld, float *R, float *S, void *stream) {
+  if (n < 0 || ld < n) return DASTAC_EINVAL;
+  if (n > kDenseMaxN) return DASTAC_EOVERFLOW;
+  if (n == 0) return DASTAC_OK;
+  if (!dense || !R || (n > 1 && !S)) return DASTAC_ENULL;
+  if (overlaps(dense, n * ld * 4, R, n * 4) || overlaps(dense, n * ld * 4, S, (n - 1) * 4) ||
+      overlaps(R, n * 4, S, (n - 1) * 4))
+    return DASTAC_EALIAS;
+  pack_leslie_kernel<<<(unsigned)ceil_div(n, kBlock), kBlock, 0, (hipStream_t)stream>>>(n, dense, ld, R, S);
+  return launch_status();
+}
+
+int dastac_unpack_leslie_f32(int64_t n, const float *R, const float *S, float *dense, int64_t ld, void *stream) {
+  if (n < 0 || ld < n) return DASTAC_EINVAL;
+  if (n > kDenseMaxN) return DASTAC_EOVERFLOW;
+  if (n == 0) return DASTAC_OK;
+  if (!dense || !R || (n > 1 && !S)) return DASTAC_ENULL;
+  if (overlaps(dense, n * ld * 4, R, n * 4) || overlaps(dense, n * ld * 4, S, (n - 1) * 4)) return DASTAC_EALIAS;
+  const int64_t pieces = ceil_div(n, kBlock), nblocks = n * pieces;
+  unpack_leslie_kernel<<<grid_for(nblocks), kBlock, 0, (hipStream_t)stream>>>(n, R, S, dense, ld, pieces, nblocks);
+  return launch_status();
+}
+
+int dastac_leslie_spmv_f32(int64_t n, const float *R, const float *S, const float *x, float *y, void *stream) {
+  if (n < 0) return DASTAC_EINVAL;
+  if (n > ((int64_t)1 << 40)) return DASTAC_EOVERFLOW;
+  if (n == 0) return DASTAC_OK;
+  if (!R || !x || !y || (n > 1 && !S)) return DASTAC_ENULL;
+  if (overlaps(y, n * 4, x, n * 4) || overlaps(y, n * 4, R, n * 4) || overlaps(y, n * 4, S, (n - 1) * 4))
+    return DASTAC_EALIAS;
+  hipStream_t st = (hipStream_t)stream;
+  zero_tail_kernel<<<1, kBlock, 0, st>>>(y, 1);
+  if (hipGetLastError() != hipSuccess) return DASTAC_EHIP;
+  const int64_t want = ceil_div(n, 4 * kBlock);  // about four rows per lane before the cap
+  const unsigned blocks = (unsigned)(want < 1 ? 1 : want > kLeslieMaxBlocks ? kLeslieMaxBlocks : want);
+  leslie_kernel<<<blocks, kBlock, 0, st>>>(n, R, S, x, y);
+  return launch_status();
+}
+
+}  // extern "C"

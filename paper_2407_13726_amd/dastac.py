@@ -56,6 +56,16 @@ SIGNATURES = {
     "dastac_pack_uhc_f32": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp]),
     "dastac_unpack_uhc_f32": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp]),
     "dastac_ttm_ut_f32": (ctypes.c_int, [_i64, _i64, _i64, _vp, _vp, _i64, _vp, _vp]),
+    "dastac_subtri_offset": (_i64, [_i64, _i64, _i64, _i64]),
+    "dastac_pack_sband_f32": (ctypes.c_int, [_i64, _i64, _i64, _vp, _i64, _vp, _vp]),
+    "dastac_unpack_sband_f32": (ctypes.c_int, [_i64, _i64, _i64, _vp, _vp, _i64, _vp]),
+    "dastac_pack_subtri_f32": (ctypes.c_int, [_i64, _i64, _vp, _i64, _vp, _vp]),
+    "dastac_unpack_subtri_f32": (ctypes.c_int, [_i64, _i64, _vp, _vp, _i64, _vp]),
+    "dastac_pack_leslie_f32": (ctypes.c_int, [_i64, _vp, _i64, _vp, _vp, _vp]),
+    "dastac_unpack_leslie_f32": (ctypes.c_int, [_i64, _vp, _vp, _vp, _i64, _vp]),
+    "dastac_sband_spmv_f32": (ctypes.c_int, [_i64, _i64, _i64, _vp, _vp, _vp, _vp]),
+    "dastac_subtri_spmv_f32": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp, _vp]),
+    "dastac_leslie_spmv_f32": (ctypes.c_int, [_i64, _vp, _vp, _vp, _vp, _vp]),
 }
 
 
@@ -228,3 +238,46 @@ def pack_tril_f32(n, dense, ld, packed, stream=None):
 def unpack_tril_f32(n, packed, dense, ld, stream=None):
     _check(lib().dastac_unpack_tril_f32(n, _ptr(packed), _ptr(dense), ld, _stream(stream)), "unpack_tril_f32")
 
+
+
+def subtri_offset(N, k, i, j): return int(lib().dastac_subtri_offset(N, k, i, j))
+
+
+def pack_sband_f32(n, w, s, dense, ld, diag_major, stream=None):
+    _check(lib().dastac_pack_sband_f32(n, w, s, _ptr(dense), ld, _ptr(diag_major), _stream(stream)),
+           "pack_sband_f32")
+
+
+def unpack_sband_f32(n, w, s, diag_major, dense, ld, stream=None):
+    _check(lib().dastac_unpack_sband_f32(n, w, s, _ptr(diag_major), _ptr(dense), ld, _stream(stream)),
+           "unpack_sband_f32")
+
+
+def pack_subtri_f32(N, k, dense, ld, packed, stream=None):
+    _check(lib().dastac_pack_subtri_f32(N, k, _ptr(dense), ld, _ptr(packed), _stream(stream)), "pack_subtri_f32")
+
+
+def unpack_subtri_f32(N, k, packed, dense, ld, stream=None):
+    _check(lib().dastac_unpack_subtri_f32(N, k, _ptr(packed), _ptr(dense), ld, _stream(stream)),
+           "unpack_subtri_f32")
+
+
+def pack_leslie_f32(n, dense, ld, R, S, stream=None):
+    _check(lib().dastac_pack_leslie_f32(n, _ptr(dense), ld, _ptr(R), _ptr(S), _stream(stream)), "pack_leslie_f32")
+
+
+def unpack_leslie_f32(n, R, S, dense, ld, stream=None):
+    _check(lib().dastac_unpack_leslie_f32(n, _ptr(R), _ptr(S), _ptr(dense), ld, _stream(stream)),
+           "unpack_leslie_f32")
+
+
+def sband_spmv_f32(n, w, s, D, x, y, stream=None):
+    _check(lib().dastac_sband_spmv_f32(n, w, s, _ptr(D), _ptr(x), _ptr(y), _stream(stream)), "sband_spmv_f32")
+
+
+def subtri_spmv_f32(N, k, Ap, x, y, stream=None):
+    _check(lib().dastac_subtri_spmv_f32(N, k, _ptr(Ap), _ptr(x), _ptr(y), _stream(stream)), "subtri_spmv_f32")
+
+
+def leslie_spmv_f32(n, R, S, x, y, stream=None):
+    _check(lib().dastac_leslie_spmv_f32(n, _ptr(R), _ptr(S), _ptr(x), _ptr(y), _stream(stream)), "leslie_spmv_f32")

@@ -59,6 +59,25 @@ def symv_inputs(n: int = 8192):
     return {"n": n, "Up": inputs.uniform(_seed(7, 0), _tri(n)), "x": inputs.uniform(_seed(7, 1), n)}
 
 
+def sband_inputs(n: int = 1 << 24, w: int = 1, s: int = 4096):
+    """Section 6.4's strided band (main diagonal and the two diagonals at distance s) at a size that
+    leaves the caches (the paper's n = 2^16 is 1 MB and stays in L2); stream seeds of "config 8"."""
+    return {"n": n, "w": w, "s": s, "D": inputs.uniform(_seed(8, 0), (2 * w + 1) * n), "x": inputs.uniform(_seed(8, 1), n)}
+
+
+def subtri_inputs(N: int = 1 << 14, k: int = 1 << 13):
+    """Section 6.4's sub-triangular structure at the paper's N = 2^14, triangle size k in the middle
+    of the range it sweeps; stream seeds of "config 9"."""
+    return {"N": N, "k": k, "Ap": inputs.uniform(_seed(9, 0), _tri(k)), "x": inputs.uniform(_seed(9, 1), N)}
+
+
+def leslie_inputs(n: int = 1 << 24):
+    """Table 2's SpMV_L: first row and sub-diagonal, at a size that leaves the caches (the paper
+    notes this kernel does not fit its cache either); stream seeds of "config 10"."""
+    return {"n": n, "R": inputs.uniform(_seed(10, 0), n), "S": inputs.uniform(_seed(10, 1), n - 1),
+            "x": inputs.uniform(_seed(10, 2), n)}
+
+
 def accounting(name: str, **kw) -> dict:
     """Useful FLOPs and algorithmic bytes of one launch."""
     if name == "trmv":
@@ -84,4 +103,14 @@ def accounting(name: str, **kw) -> dict:
     if name == "ttm_ut":
         n, Q, K = kw["n"], kw["Q"], kw["K"]
         return {"flops": 2 * _tri(n) * Q * K, "bytes": 4 * (_tri(n) * (Q + K) + K * Q)}
+    if name == "sband":  # in-range products only; every slot of every diagonal buffer is streamed
+        n, w, st = kw["n"], kw["w"], kw["s"]
+        inrange = sum(max(n - abs(d) * st, 0) for d in range(-w, w + 1))
+        return {"flops": 2 * inrange, "bytes": 4 * ((2 * w + 1) * n + 2 * n)}
+    if name == "subtri":
+        N, k = kw["N"], kw["k"]
+        return {"flops": 2 * _tri(k), "bytes": 4 * (_tri(k) + k + N)}
+    if name == "leslie":
+        n = kw["n"]
+        return {"flops": 2 * n + (n - 1), "bytes": 4 * (n + (n - 1) + 2 * n)}
     raise ValueError(name)

@@ -153,6 +153,51 @@ def test_guards():
 def _p(v):
     return ctypes.c_void_p(v)
 
+@pytest.mark.parametrize("N,k", [(1, 1), (5, 0), (6, 4), (9, 9), (12, 5)])
+def test_subtri_offsets_match_a_walk_of_the_domain(N, k):
+    """subtri(N,k,i,j) is the number of points with j-i >= N-k that precede (i,j) in iteration
+    order (Section 6.4, sub-triangular structure), counted here by a plain walk."""
+    p = 0
+    for i in range(N):
+        for j in range(N):
+            if j - i >= N - k:
+                assert dastac.subtri_offset(N, k, i, j) == p
+                p += 1
+            else:
+                assert dastac.subtri_offset(N, k, i, j) == -1
+    assert p == dastac.tri_count(k)
+    assert dastac.subtri_offset(N, N + 1, 0, 0) == -1 and dastac.subtri_offset(N, k, 0, N) == -1
+
+
+def test_new_domain_entry_points_reject_bad_arguments():
+    L = dastac.lib()
+    assert L.dastac_sband_spmv_f32(-1, 1, 1, _p(A), _p(B), _p(C), None) == dastac.EINVAL
+    assert L.dastac_sband_spmv_f32(4, 1, 0, _p(A), _p(B), _p(C), None) == dastac.EINVAL
+    assert L.dastac_sband_spmv_f32(4, 65, 1, _p(A), _p(B), _p(C), None) == dastac.EINVAL
+    assert L.dastac_sband_spmv_f32(4, 1, 2 ** 41, _p(A), _p(B), _p(C), None) == dastac.EOVERFLOW
+    assert L.dastac_sband_spmv_f32(4, 1, 2, None, _p(B), _p(C), None) == dastac.ENULL
+    assert L.dastac_sband_spmv_f32(4, 1, 2, _p(A), _p(B), _p(B + 4), None) == dastac.EALIAS
+    assert L.dastac_sband_spmv_f32(0, 1, 2, None, None, None, None) == dastac.OK
+    assert L.dastac_pack_sband_f32(8, 1, 0, _p(A), 8, _p(B), None) == dastac.EINVAL
+    assert L.dastac_pack_sband_f32(8, 1, 2, _p(A), 7, _p(B), None) == dastac.EINVAL
+    assert L.dastac_unpack_sband_f32(8, 1, 2, None, _p(B), 8, None) == dastac.ENULL
+    assert L.dastac_subtri_spmv_f32(4, 5, _p(A), _p(B), _p(C), None) == dastac.EINVAL
+    assert L.dastac_subtri_spmv_f32(4, -1, _p(A), _p(B), _p(C), None) == dastac.EINVAL
+    assert L.dastac_subtri_spmv_f32(2 ** 20, 524289, _p(D), _p(A), _p(B), None) == dastac.EOVERFLOW
+    assert L.dastac_subtri_spmv_f32(4, 2, None, _p(B), _p(C), None) == dastac.ENULL
+    assert L.dastac_subtri_spmv_f32(4, 2, _p(A), _p(B), _p(B + 8), None) == dastac.EALIAS
+    assert L.dastac_subtri_spmv_f32(0, 0, None, None, None, None) == dastac.OK
+    assert L.dastac_pack_subtri_f32(8, 9, _p(A), 8, _p(B), None) == dastac.EINVAL
+    assert L.dastac_pack_subtri_f32(8, 4, _p(A), 7, _p(B), None) == dastac.EINVAL
+    assert L.dastac_unpack_subtri_f32(8, 4, _p(A), None, 8, None) == dastac.ENULL
+    assert L.dastac_leslie_spmv_f32(-1, _p(A), _p(B), _p(C), _p(D), None) == dastac.EINVAL
+    assert L.dastac_leslie_spmv_f32(4, _p(A), None, _p(C), _p(D), None) == dastac.ENULL
+    assert L.dastac_leslie_spmv_f32(4, _p(A), _p(B), _p(C), _p(A + 4), None) == dastac.EALIAS
+    assert L.dastac_leslie_spmv_f32(0, None, None, None, None, None) == dastac.OK
+    assert L.dastac_pack_leslie_f32(4, _p(A), 3, _p(B), _p(C), None) == dastac.EINVAL
+    assert L.dastac_pack_leslie_f32(4, _p(A), 4, _p(B), _p(B + 8), None) == dastac.EALIAS
+    assert L.dastac_unpack_leslie_f32(4, None, _p(B), _p(C), 4, None) == dastac.ENULL
+
 
 A, B, C, D = 0x10000, 0x20000000, 0x40000000, 0x60000000  # fake, never dereferenced
 
