@@ -81,6 +81,7 @@ def lib() -> ctypes.CDLL:
         L.oracle_pack_tril_f32.argtypes = [_i64, _fp, _i64, _fp]
         L.oracle_unpack_tril_f32.argtypes = [_i64, _fp, _fp, _i64]
         L.oracle_ttm_ut_f32.argtypes = [_i64, _i64, _i64, _fp, _fp, _i64, _fp, _dp, _i64, _i64]
+        L.oracle_symm_f32.argtypes = [_i64, _i64, _fp, _fp, _i64, _fp, _i64, _dp, _i64, _i64]
         L.oracle_pack_sband_f32.argtypes = [_i64, _i64, _i64, _fp, _i64, _fp]
         L.oracle_unpack_sband_f32.argtypes = [_i64, _i64, _i64, _fp, _fp, _i64]
         L.oracle_sband_spmv_f32.argtypes = [_i64, _i64, _i64, _fp, _fp, _fp, _dp, _i64, _i64]
@@ -401,3 +402,13 @@ def leslie_spmv(n, R, S, x):
     sc = np.full(n, np.nan, dtype=np.float64)
     lib().oracle_leslie_spmv_f32(n, _f(R), _f(S), _f(x), _f(y), _d(sc))
     return y, sc
+
+
+def symm(n, m, Up, B, rows=None):
+    """C = S B, S symmetric with its upper triangle packed in Up; B is n x m."""
+    Up, B = _f32(Up), _f32(B)
+    lo, hi = _window(n, rows)
+    C = np.full((n, m), np.nan, dtype=np.float32)
+    sc = np.full((n, m), np.nan, dtype=np.float64)
+    lib().oracle_symm_f32(n, m, _f(Up), _f(B), B.shape[1] if B.ndim == 2 else m, _f(C), m, _d(sc), lo, hi)
+    return C, sc

@@ -630,3 +630,32 @@ void oracle_leslie_spmv_f32(int64_t n, const float *R, const float *S, const flo
     if (scale) scale[i] = fabs(t);
   }
 }
+
+/* C(i,c) := S(i,j) * B(j,c), S symmetric with its unique elements S(i,j), i<=j, packed as an upper
+ * triangle (Section 3, "Redundancy map": a pair with i>j is swapped to reach its unique element).
+ * Row starts of the packed triangle come from a running counter. */
+void oracle_symm_f32(int64_t n, int64_t m, const float *Up, const float *B, int64_t ldb, float *C,
+                     int64_t ldc, double *scale, int64_t r_lo, int64_t r_hi) {
+  int64_t *start = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n + 1));
+  int64_t p = 0;
+  for (int64_t i = 0; i < n; ++i) {
+    start[i] = p;
+    p += n - i;
+  }
+  for (int64_t i = 0; i < n; ++i) {
+    if (i < r_lo || i >= r_hi) continue;
+    for (int64_t c = 0; c < m; ++c) {
+      double acc = 0.0, mag = 0.0;
+      for (int64_t j = 0; j < n; ++j) {
+        int64_t a = i, b = j;
+        if (a > b) { int64_t t = a; a = b; b = t; } /* the redundancy map */
+        double t = (double)Up[start[a] + (b - a)] * (double)B[j * ldb + c];
+        acc += t;
+        mag += fabs(t);
+      }
+      C[i * ldc + c] = (float)acc;
+      if (scale) scale[i * m + c] = mag;
+    }
+  }
+  free(start);
+}

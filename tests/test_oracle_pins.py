@@ -538,3 +538,31 @@ def test_leslie_population_step(oracle):
     pop = np.array([8, 4, 4, 8], dtype=np.float32)
     y, _ = oracle.leslie_spmv(4, f, surv, pop)
     assert np.array_equal(y, np.array([20, 4, 2, 1], dtype=np.float32))
+
+
+# --------------------------------------------------------------------- SYMM ----
+
+@pytest.mark.parametrize("n,m", [(1, 1), (2, 3), (9, 4), (33, 17), (70, 40)])
+def test_symm_against_dense_numpy_blas_and_symv(oracle, n, m):
+    """Section 3, redundancy map, with a matrix right-hand side: the dense product with
+    U + U^T - diag(U), BLAS's own symmetric product on the same upper triangle, and column by
+    column the symmetric matrix-vector product."""
+    from scipy.linalg.blas import dsymm
+    Up = inputs.uniform(1500 + n, n * (n + 1) // 2)
+    B = inputs.normal(1501 + n, n, m)
+    iu = np.triu_indices(n)
+    U = np.zeros((n, n))
+    U[iu] = Up  # row-major upper triangle, filled by NumPy's own index order
+    S = U + U.T - np.diag(np.diag(U))
+    C, sc = oracle.symm(n, m, Up, B)
+    assert _close(C, S @ B.astype(np.float64), sc)
+    assert np.allclose(sc, np.abs(S) @ np.abs(B.astype(np.float64)), rtol=1e-12)
+    # dsymm reads only the upper triangle of its argument (lower=0): hand it U with garbage below
+    G = U + np.tril(np.full((n, n), 777.0), k=-1)
+    assert _close(C, dsymm(1.0, G, B.astype(np.float64), side=0, lower=0), sc)
+    y, _ = oracle.symv(n, Up, np.ascontiguousarray(B[:, 0]))
+    assert np.array_equal(C[:, 0], y)
+    # rows window
+    if n > 4:
+        Cw, _ = oracle.symm(n, m, Up, B, rows=(2, 4))
+        assert np.array_equal(Cw[2:4], C[2:4]) and np.isnan(Cw[:2]).all() and np.isnan(Cw[4:]).all()
