@@ -273,6 +273,10 @@ def main() -> int:
     sms = beside(lambda: d.symv_f32(ns, gU, gx, gy))
     result["beside"]["symv"] = entry("SYMV n=%d on the packed upper triangle" % ns, sms, wl.accounting("symv", n=ns), "hbm")
     del gU, sw
+    # SYMM on the TRMM configuration's operands (still resident)
+    mms = beside(lambda: d.symm_f32(n2, m2, g["trmm"][0], g["trmm"][1], m2, g["trmm"][2], m2))
+    result["beside"]["symm"] = entry("SYMM n=%d m=%d on the packed upper triangle" % (n2, m2), mms,
+                                     wl.accounting("symm", n=n2, m=m2), "mfma")
     bw = wl.sband_inputs()
     nb, wb, sb = bw["n"], bw["w"], bw["s"]
     gD, gx, gy = up(bw["D"]), up(bw["x"]), out(nb)

@@ -164,6 +164,12 @@ int dastac_symv_lower_f32(int64_t n, const float *Lp, const float *x, float *y, 
 int dastac_trmm_f32(int64_t n, int64_t m, const float *Up, const float *B, int64_t ldb, float *C, int64_t ldc,
                     void *stream);
 
+/* C(i,c) := S(i,k) * B(k,c), S symmetric with its unique elements S(i,k), i<=k, packed as an upper triangle
+ * (Section 3, "Redundancy map", with a matrix right-hand side).  Shapes, strides and limits as trmm; no
+ * atomics (every tile of C has one owner), each packed element is read twice. */
+int dastac_symm_f32(int64_t n, int64_t m, const float *Up, const float *B, int64_t ldb, float *C, int64_t ldc,
+                    void *stream);
+
 /* y(i) := sum_{d=-w..w, 0<=i+d<n} D(d,i) * x(i+d)   (Section 6.4 strided-band rule, unit stride,
  * 2w+1 summands; w=0 is Table 2's SpMV_D).  D[(2w+1)*n] diagonal-major as described above; padding
  * slots are never used for their value.  0 <= w <= 64. */

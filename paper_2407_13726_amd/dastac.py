@@ -56,6 +56,7 @@ SIGNATURES = {
     "dastac_pack_uhc_f32": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp]),
     "dastac_unpack_uhc_f32": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp]),
     "dastac_ttm_ut_f32": (ctypes.c_int, [_i64, _i64, _i64, _vp, _vp, _i64, _vp, _vp]),
+    "dastac_symm_f32": (ctypes.c_int, [_i64, _i64, _vp, _vp, _i64, _vp, _i64, _vp]),
     "dastac_subtri_offset": (_i64, [_i64, _i64, _i64, _i64]),
     "dastac_pack_sband_f32": (ctypes.c_int, [_i64, _i64, _i64, _vp, _i64, _vp, _vp]),
     "dastac_unpack_sband_f32": (ctypes.c_int, [_i64, _i64, _i64, _vp, _vp, _i64, _vp]),
@@ -281,3 +282,7 @@ def subtri_spmv_f32(N, k, Ap, x, y, stream=None):
 
 def leslie_spmv_f32(n, R, S, x, y, stream=None):
     _check(lib().dastac_leslie_spmv_f32(n, _ptr(R), _ptr(S), _ptr(x), _ptr(y), _stream(stream)), "leslie_spmv_f32")
+
+
+def symm_f32(n, m, Up, B, ldb, C, ldc, stream=None):
+    _check(lib().dastac_symm_f32(n, m, _ptr(Up), _ptr(B), ldb, _ptr(C), ldc, _stream(stream)), "symm_f32")

@@ -100,6 +100,9 @@ def accounting(name: str, **kw) -> dict:
     if name == "symv":  # every unique element is used twice, the diagonal once
         n = kw["n"]
         return {"flops": 2 * n * n, "bytes": 4 * (_tri(n) + 2 * n)}
+    if name == "symm":  # every unique element is used twice per column of B, the diagonal once
+        n, m = kw["n"], kw["m"]
+        return {"flops": 2 * n * n * m, "bytes": 4 * (_tri(n) + 2 * n * m)}
     if name == "ttm_ut":
         n, Q, K = kw["n"], kw["Q"], kw["K"]
         return {"flops": 2 * _tri(n) * Q * K, "bytes": 4 * (_tri(n) * (Q + K) + K * Q)}

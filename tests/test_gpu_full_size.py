@@ -123,3 +123,20 @@ def test_symv_8192(gpu, oracle):
     gpu.d.symv_f32(w["n"], gpu.up(w["Up"]), gpu.up(w["x"]), y)
     check(gpu.down(y), want, scale, "symv 8192")
 
+
+
+def test_symm_16384_sampled_rows(gpu, oracle):
+    """The symmetric product with a matrix right-hand side on the TRMM configuration's operands, at
+    the size bench.py reports beside the five configurations."""
+    w = wl.trmm_inputs()
+    n, m = w["n"], w["m"]
+    C = gpu.empty(n, m)
+    gpu.d.symm_f32(n, m, gpu.up(w["Up"]), gpu.up(w["B"]), m, C, m)
+    got = gpu.down(C)
+    assert np.isfinite(got).all()
+    rng = np.random.default_rng(8)
+    rows = sorted({0, 1, 31, 32, 63, 64, 65, 8191, 8192, n - 65, n - 64, n - 33, n - 32, n - 2, n - 1}
+                  | {int(r) for r in rng.integers(0, n, 8)})
+    for i in rows:
+        want, scale = oracle.symm(n, m, w["Up"], w["B"], rows=(i, i + 1))
+        check(got[i], want[i], scale[i], "symm row %d" % i)

@@ -362,3 +362,36 @@ def test_calls_are_stream_ordered(gpu, oracle):
         gpu.d.trmv_f32(n, dU, dx, y)
     s.synchronize()
     assert_within(y.cpu().numpy(), want, scale, "trmv on side stream")
+
+
+# --------------------------------------------------------------------- SYMM ----
+
+@pytest.mark.parametrize("n,m", [(1, 1), (2, 3), (31, 7), (64, 64), (65, 33), (127, 128), (130, 129), (200, 256),
+                                 (300, 40), (515, 70), (1024, 128)])
+def test_symm_parity(gpu, oracle, n, m):
+    Up, B = inputs.uniform(1600 + n, tri(n)), inputs.uniform(1601 + n, n, m)
+    want, scale = oracle.symm(n, m, Up, B)
+    C = gpu.empty(n, m)
+    gpu.d.symm_f32(n, m, gpu.up(Up), gpu.up(B), m, C, m)
+    assert_within(gpu.down(C), want, scale, "symm n=%d m=%d" % (n, m))
+
+
+def test_symm_leading_dimensions_and_integer_exactness(gpu, oracle):
+    n, m, ldb, ldc = 330, 37, 45, 41
+    Up = inputs.small_int(1610, -3, 3, tri(n))
+    B = inputs.small_int(1611, -3, 3, n, ldb)
+    want, _ = oracle.symm(n, m, Up, np.ascontiguousarray(B[:, :m]))
+    C = gpu.empty(n, ldc)
+    gpu.d.symm_f32(n, m, gpu.up(Up), gpu.up(B), ldb, C, ldc)
+    got = gpu.down(C)
+    assert got[:, :m].tobytes() == want.tobytes()
+    assert np.isnan(got[:, m:]).all()
+
+
+def test_symm_one_column_equals_symv(gpu, oracle):
+    n = 700
+    Up, x = inputs.small_int(1620, -3, 3, tri(n)), inputs.small_int(1621, -3, 3, n)
+    dU, dx, C, y = gpu.up(Up), gpu.up(x), gpu.empty(n, 1), gpu.empty(n)
+    gpu.d.symm_f32(n, 1, dU, dx, 1, C, 1)
+    gpu.d.symv_f32(n, dU, dx, y)
+    assert gpu.down(C).ravel().tobytes() == gpu.down(y).tobytes()

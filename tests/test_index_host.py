@@ -171,6 +171,12 @@ def test_subtri_offsets_match_a_walk_of_the_domain(N, k):
 
 def test_new_domain_entry_points_reject_bad_arguments():
     L = dastac.lib()
+    assert L.dastac_symm_f32(4, 0, _p(A), _p(B), 4, _p(C), 4, None) == dastac.EINVAL
+    assert L.dastac_symm_f32(4, 8, _p(A), _p(B), 7, _p(C), 8, None) == dastac.EINVAL
+    assert L.dastac_symm_f32(2 ** 24 + 1, 8, _p(A), _p(B), 8, _p(C), 8, None) == dastac.EOVERFLOW
+    assert L.dastac_symm_f32(4, 2, _p(A), None, 2, _p(C), 2, None) == dastac.ENULL
+    assert L.dastac_symm_f32(4, 2, _p(A), _p(B), 2, _p(B + 8), 2, None) == dastac.EALIAS
+    assert L.dastac_symm_f32(0, 2, None, None, 2, None, 2, None) == dastac.OK
     assert L.dastac_sband_spmv_f32(-1, 1, 1, _p(A), _p(B), _p(C), None) == dastac.EINVAL
     assert L.dastac_sband_spmv_f32(4, 1, 0, _p(A), _p(B), _p(C), None) == dastac.EINVAL
     assert L.dastac_sband_spmv_f32(4, 65, 1, _p(A), _p(B), _p(C), None) == dastac.EINVAL
