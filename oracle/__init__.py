@@ -81,6 +81,8 @@ def lib() -> ctypes.CDLL:
         L.oracle_pack_tril_f32.argtypes = [_i64, _fp, _i64, _fp]
         L.oracle_unpack_tril_f32.argtypes = [_i64, _fp, _fp, _i64]
         L.oracle_ttm_ut_f32.argtypes = [_i64, _i64, _i64, _fp, _fp, _i64, _fp, _dp, _i64, _i64]
+        L.oracle_pr_a2_f32.argtypes = [_i64, _i64, _fp, _i64, _fp, _dp, _i64, _i64]
+        L.oracle_pr_a3_f32.argtypes = [_i64, _i64, _fp, _i64, _fp, _dp, _i64, _i64]
         L.oracle_symm_f32.argtypes = [_i64, _i64, _fp, _fp, _i64, _fp, _i64, _dp, _i64, _i64]
         L.oracle_pack_sband_f32.argtypes = [_i64, _i64, _i64, _fp, _i64, _fp]
         L.oracle_unpack_sband_f32.argtypes = [_i64, _i64, _i64, _fp, _fp, _i64]
@@ -412,3 +414,25 @@ def symm(n, m, Up, B, rows=None):
     sc = np.full((n, m), np.nan, dtype=np.float64)
     lib().oracle_symm_f32(n, m, _f(Up), _f(B), B.shape[1] if B.ndim == 2 else m, _f(C), m, _d(sc), lo, hi)
     return C, sc
+
+
+def _pr(fn, count, B, window):
+    B = _f32(B)
+    N, d = B.shape
+    lo, hi = (0, count) if window is None else (int(window[0]), int(window[1]))
+    out = np.full(count, np.nan, dtype=np.float32)
+    sc = np.full(count, np.nan, dtype=np.float64)
+    fn(N, d, _f(B), d, _f(out), _d(sc), lo, hi)
+    return out, sc
+
+
+def pr_a2(B, window=None):
+    """A2(i,j) = sum_x B(x,i) B(x,j), i<=j, packed; `window` selects packed positions [lo, hi)."""
+    d = B.shape[1]
+    return _pr(lib().oracle_pr_a2_f32, d * (d + 1) // 2, B, window)
+
+
+def pr_a3(B, window=None):
+    """A3(i,j,k) = sum_x B(x,i) B(x,j) B(x,k), i<=j<=k, packed."""
+    d = B.shape[1]
+    return _pr(lib().oracle_pr_a3_f32, d * (d + 1) * (d + 2) // 6, B, window)

@@ -659,3 +659,44 @@ void oracle_symm_f32(int64_t n, int64_t m, const float *Up, const float *B, int6
   }
   free(start);
 }
+
+/* Polynomial-regression tensors (Table 1, "Polynomial Regression Degree-D"):
+ *   A2(i1,i2)    := B(x,i1) * B(x,i2)            summed over x
+ *   A3(i1,i2,i3) := B(x,i1) * B(x,i2) * B(x,i3)  summed over x
+ * B is N x d row-major (leading dimension ldb).  Both tensors are symmetric under any permutation
+ * of their indices; the unique set is the hyper-triangle i1<=i2(<=i3), stored in iteration order
+ * by a running counter.  The window [p_lo, p_hi) selects outputs by packed position. */
+void oracle_pr_a2_f32(int64_t N, int64_t d, const float *B, int64_t ldb, float *A2p, double *scale,
+                      int64_t p_lo, int64_t p_hi) {
+  int64_t p = 0;
+  for (int64_t i = 0; i < d; ++i)
+    for (int64_t j = i; j < d; ++j, ++p) {
+      if (p < p_lo || p >= p_hi) continue;
+      double acc = 0.0, mag = 0.0;
+      for (int64_t x = 0; x < N; ++x) {
+        double t = (double)B[x * ldb + i] * (double)B[x * ldb + j];
+        acc += t;
+        mag += fabs(t);
+      }
+      A2p[p] = (float)acc;
+      if (scale) scale[p] = mag;
+    }
+}
+
+void oracle_pr_a3_f32(int64_t N, int64_t d, const float *B, int64_t ldb, float *A3p, double *scale,
+                      int64_t p_lo, int64_t p_hi) {
+  int64_t p = 0;
+  for (int64_t i = 0; i < d; ++i)
+    for (int64_t j = i; j < d; ++j)
+      for (int64_t k = j; k < d; ++k, ++p) {
+        if (p < p_lo || p >= p_hi) continue;
+        double acc = 0.0, mag = 0.0;
+        for (int64_t x = 0; x < N; ++x) {
+          double t = (double)B[x * ldb + i] * (double)B[x * ldb + j] * (double)B[x * ldb + k];
+          acc += t;
+          mag += fabs(t);
+        }
+        A3p[p] = (float)acc;
+        if (scale) scale[p] = mag;
+      }
+}

@@ -566,3 +566,48 @@ def test_symm_against_dense_numpy_blas_and_symv(oracle, n, m):
     if n > 4:
         Cw, _ = oracle.symm(n, m, Up, B, rows=(2, 4))
         assert np.array_equal(Cw[2:4], C[2:4]) and np.isnan(Cw[:2]).all() and np.isnan(Cw[4:]).all()
+
+
+# ------------------------------------- polynomial-regression tensors (Table 1) ----
+
+@pytest.mark.parametrize("N,d", [(1, 1), (5, 3), (40, 7), (300, 12)])
+def test_pr_tensors_against_einsum_on_the_hyper_triangle(oracle, N, d):
+    """A^k(i1..ik) := B(x,i1)...B(x,ik): NumPy's einsum gives the full symmetric tensor; the packed
+    result is its hyper-triangle in NumPy's own (row-major) order of the boolean mask."""
+    B = inputs.normal(1700 + N + d, N, d)
+    Bd = B.astype(np.float64)
+    F2 = np.einsum("xi,xj->ij", Bd, Bd)
+    F3 = np.einsum("xi,xj,xk->ijk", Bd, Bd, Bd)
+    i, j = np.meshgrid(np.arange(d), np.arange(d), indexing="ij")
+    A2, s2 = oracle.pr_a2(B)
+    assert A2.size == d * (d + 1) // 2
+    assert _close(A2, F2[i <= j], s2)
+    assert np.allclose(s2, np.einsum("xi,xj->ij", np.abs(Bd), np.abs(Bd))[i <= j], rtol=1e-12)
+    i, j, k = np.meshgrid(np.arange(d), np.arange(d), np.arange(d), indexing="ij")
+    A3, s3 = oracle.pr_a3(B)
+    assert A3.size == d * (d + 1) * (d + 2) // 6
+    assert _close(A3, F3[(i <= j) & (j <= k)], s3)
+    # the covariance-style identity: A2 is B^T B
+    assert _close(A2, (Bd.T @ Bd)[np.triu_indices(d)], s2)
+    # a window computes the same values and touches nothing else
+    if A3.size > 6:
+        W, _ = oracle.pr_a3(B, window=(2, 5))
+        assert np.array_equal(W[2:5], A3[2:5]) and np.isnan(W[:2]).all() and np.isnan(W[5:]).all()
+
+
+def test_pr_tensors_closed_forms(oracle):
+    """Rows that do not depend on x: A2 = N c_i c_j, A3 = N c_i c_j c_k; a one-hot B counts rows."""
+    N, d = 37, 5
+    c = np.array([1, -2, 3, 0, 2], dtype=np.float32)
+    B = np.tile(c, (N, 1))
+    A2, _ = oracle.pr_a2(B)
+    A3, _ = oracle.pr_a3(B)
+    assert np.array_equal(A2, np.array([N * c[i] * c[j] for i in range(d) for j in range(i, d)], dtype=np.float32))
+    assert np.array_equal(A3, np.array([N * c[i] * c[j] * c[k] for i in range(d) for j in range(i, d)
+                                        for k in range(j, d)], dtype=np.float32))
+    H = np.zeros((N, d), dtype=np.float32)
+    H[np.arange(N), np.arange(N) % d] = 1  # every sample has exactly one feature set
+    A3, _ = oracle.pr_a3(H)
+    counts = np.bincount(np.arange(N) % d, minlength=d)
+    want = [counts[i] if i == j == k else 0 for i in range(d) for j in range(i, d) for k in range(j, d)]
+    assert np.array_equal(A3, np.asarray(want, dtype=np.float32))
