@@ -277,6 +277,17 @@ def main() -> int:
     mms = beside(lambda: d.symm_f32(n2, m2, g["trmm"][0], g["trmm"][1], m2, g["trmm"][2], m2))
     result["beside"]["symm"] = entry("SYMM n=%d m=%d on the packed upper triangle" % (n2, m2), mms,
                                      wl.accounting("symm", n=n2, m=m2), "mfma")
+    # polynomial-regression tensors (Table 1): dense samples in, packed hyper-triangles out
+    for which, Np, dp in ((2, 100000, 1024), (3, 10000, 256)):
+        pw = wl.pr_inputs(Np, dp, which)
+        name = "pr_a%d" % which
+        gBp = up(pw["B"])
+        gO = out(dp * (dp + 1) // 2 if which == 2 else dp * (dp + 1) * (dp + 2) // 6)
+        fn = d.pr_a2_f32 if which == 2 else d.pr_a3_f32
+        pms = beside(lambda: fn(Np, dp, gBp, dp, gO))
+        result["beside"][name] = entry("A^%d of Table 1's polynomial regression, N=%d d=%d, packed output"
+                                       % (which, Np, dp), pms, wl.accounting(name, N=Np, d=dp), "mfma")
+        del gBp, gO, pw
     bw = wl.sband_inputs()
     nb, wb, sb = bw["n"], bw["w"], bw["s"]
     gD, gx, gy = up(bw["D"]), up(bw["x"]), out(nb)

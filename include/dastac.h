@@ -208,6 +208,16 @@ int dastac_tet_mttkrp_f32(int64_t n, int64_t R, const float *Ap, const float *B,
 int dastac_ttm_ut_f32(int64_t n, int64_t Q, int64_t K, const float *Bp, const float *C, int64_t ldc, float *Ap,
                       void *stream);
 
+/* The polynomial-regression tensors of Table 1 ("Polynomial Regression Degree-D": A^k(i1..ik) := B(x,i1)*...*B(x,ik),
+ * summed over x), orders 2 and 3, written straight into their packed hyper-triangles:
+ *   pr_a2   A2(i,j)   := B(x,i) * B(x,j),          i<=j      A2p[tri_count(d)] at tri(d,i,j)
+ *   pr_a3   A3(i,j,k) := B(x,i) * B(x,j) * B(x,k), i<=j<=k   A3p[tet_count(d)] at tet(d,i,j,k)
+ * B is N x d row-major with row stride ldb >= d.  d == 0 is a no-op; N == 0 writes zeros.  d <= 65536 (a2),
+ * d <= 8192 (a3), N <= 2^31.  When the output has few tiles the sample range is split over workgroups that
+ * add into the zeroed output with floating-point atomics (last bits may then differ between calls). */
+int dastac_pr_a2_f32(int64_t N, int64_t d, const float *B, int64_t ldb, float *A2p, void *stream);
+int dastac_pr_a3_f32(int64_t N, int64_t d, const float *B, int64_t ldb, float *A3p, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -1,0 +1,314 @@
+// Polynomial-regression tensors (Table 1, "Polynomial Regression Degree-D") written straight
+// into packed hyper-triangles on the fp32 matrix cores:
+//
+//   A2(i,j)   := B(x,i) * B(x,j)            i<=j        packed upper triangle,   tri(d,i,j)
+//   A3(i,j,k) := B(x,i) * B(x,j) * B(x,k)   i<=j<=k     packed upper tetrahedron, tet(d,i,j,k)
+//
+// B is the dense N x d sample matrix; both outputs are symmetric under any permutation of their
+// indices and only the unique elements are computed and stored (the output inherits the structure,
+// Section 3).  Slice i of A3 is a weighted Gram matrix, sum_x w(x) B(x,j) B(x,k) with w = B(.,i),
+// restricted to j,k >= i, whose upper triangle of order d-i is stored contiguously at
+// tet_slice_start(d,i); A2 is the same with w = 1 and a single slice.  One kernel serves both.
+//
+// A workgroup (8 wavefronts) owns a 64 (j) x 128 (k) tile of one slice and a range of samples x,
+// which is the reduction index: per step of 32 samples, the 32x64 tile of B columns j (multiplied
+// by w on the way in) and the 32x128 tile of B columns k are staged in LDS, double-buffered
+// against the global loads of the next step, and each wavefront runs v_mfma_f32_32x32x2_f32 on a
+// 32x32 sub-tile.  Tiles that lie wholly below the diagonal are never launched; tiles on the diagonal
+// stage their full rectangle, wavefronts whose sub-tile lies below it skip their matrix instructions,
+// and only j<=k is stored.  When the tile
+// count alone cannot fill the chip the sample range is split over several workgroups, which then
+// add into a pre-zeroed output with floating-point atomics.
+#include "common.h"
+
+using namespace dastac;
+
+namespace {
+
+constexpr int kBJ = 64;    // j extent of a workgroup tile
+constexpr int kBK = 128;   // k extent of a workgroup tile
+constexpr int kXT = 32;    // samples per step
+constexpr int kJP = kBJ + 4;  // LDS pitch of the j tile [x][j]
+constexpr int kBlock = 512;
+constexpr int64_t kMaxD2 = 1 << 16;  // A2: tile grid and tri(d) stay small
+constexpr int64_t kMaxD3 = 1 << 13;  // A3: the tile count stays inside gridDim.x
+constexpr int64_t kMaxN = (int64_t)1 << 31;
+
+typedef float f16v __attribute__((ext_vector_type(16)));
+
+struct Stage {
+  f4a a;     // j tile: sample row tk, four columns
+  f4a b[2];  // k tile: sample rows bk and bk+16, four columns each
+};
+
+// Tiles with work.  A slice of order q has m = ceil(q/64) blocks of rows j and ceil(m/2) blocks of columns k;
+// tile (J,K) holds an element with j<=k exactly when K >= J/2 (integer division), so row block J has
+// ceil(m/2) - J/2 tiles and the slice has tiles_of(m) in all.  Tiles are numbered densely, slice after slice,
+// row block after row block, so that consecutive workgroup ids (which the hardware deals out to the XCDs in
+// turn) all carry work: numbering the whole J x K rectangle and letting the empty tiles exit would leave
+// the XCDs with very different loads, because the id modulo 8 would select the column block.
+DASTAC_HD int64_t tiles_of(int64_t m) {
+  const int64_t p = m / 2;
+  return (m & 1) ? p * p + 3 * p + 1 : p * (p + 1);
+}
+
+DASTAC_HD int64_t total_tiles(int64_t d, bool cube) {
+  const int64_t m0 = ceil_div(d, kBJ);
+  if (!cube) return tiles_of(m0);
+  int64_t total = (d - kBJ * (m0 - 1)) * tiles_of(m0);  // slices whose order needs m0 row blocks
+  for (int64_t m = m0 - 1; m >= 1; --m) total += kBJ * tiles_of(m);
+  return total;
+}
+
+// Dense tile number -> slice i and tile (J,K).
+__device__ inline void decode_tile(int64_t d, bool cube, int64_t t, int64_t &i, int &J, int &K) {
+  int64_t m = ceil_div(d, kBJ);
+  i = 0;
+  if (cube) {
+    int64_t first = 0, count = d - kBJ * (m - 1);  // slices first .. first+count-1 need m row blocks
+    while (t >= count * tiles_of(m)) {
+      t -= count * tiles_of(m);
+      first += count;
+      count = kBJ;
+      --m;
+    }
+    i = first + t / tiles_of(m);
+    t = t % tiles_of(m);
+  }
+  const int64_t nK = (m + 1) / 2;
+  int64_t Jr = 0;
+  while (t >= nK - Jr / 2) {
+    t -= nK - Jr / 2;
+    ++Jr;
+  }
+  J = (int)Jr;
+  K = (int)(Jr / 2 + t);
+}
+
+template <bool CUBE, bool ATOMIC>
+__global__ __launch_bounds__(kBlock) void pr_mfma_kernel(int64_t N, int64_t d, const float *__restrict__ B,
+                                                         int64_t ldb, float *__restrict__ out, int64_t chunk) {
+  __shared__ __attribute__((aligned(16))) float As[2][kXT * kJP];
+  __shared__ __attribute__((aligned(16))) float Bs[2][kXT * kBK];
+
+  int64_t i;  // slice: every column index of this workgroup is >= i
+  int J, K;
+  decode_tile(d, CUBE, uniform64((int64_t)blockIdx.x), i, J, K);
+  const int64_t q = d - i;  // order of the slice's triangle
+  const int64_t xbeg = (int64_t)blockIdx.y * chunk;
+  const int64_t xend = xbeg + chunk < N ? xbeg + chunk : N;
+  if (xbeg >= xend) return;
+  const int nk = (int)ceil_div(xend - xbeg, kXT);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wr = wave >> 2, wc = wave & 3;  // 2x4 wavefronts: 32 (j) x 32 (k) each
+  const int l32 = lane & 31, h = lane >> 5;
+  // A wavefront whose 32x32 sub-tile lies wholly below the diagonal (largest k < smallest j) still helps
+  // to stage the tiles but issues no matrix instructions, which leaves the SIMD's matrix pipe to the
+  // wavefronts of the other workgroups resident on it.
+  const bool live = uniform32(K * kBK + wc * 32 + 31 >= J * kBJ + wr * 32) != 0;
+
+  const int tk = tid >> 4, ti = (tid & 15) * 4;   // j tile: sample row tk, column offset ti
+  const int bk = tid >> 5, bc = (tid & 31) * 4;   // k tile: sample row bk (+16), column offset bc
+  const int64_t j0 = i + (int64_t)J * kBJ, k0 = i + (int64_t)K * kBK;  // absolute first columns
+  const bool j_full = j0 + kBJ <= d, k_full = k0 + kBK <= d;
+
+  // Columns c..c+3 of one row of B, zero from column d on, with one vector load whose address is pulled
+  // back inside the row (needs d >= 4): a lane that straddles the end shifts what it fetched.
+  auto load4_clamped = [&](const float *row, int64_t c) -> f4a {
+    const int64_t cc = c + 4 <= d ? c : d - 4;
+    const f4a v = *reinterpret_cast<const f4u *>(row + cc);
+    const int64_t sh = c - cc;  // 0: all four inside; 1..3: that many beyond the end; >= 4: all beyond
+    f4a r;
+    r.x = sh == 0 ? v.x : sh == 1 ? v.y : sh == 2 ? v.z : sh == 3 ? v.w : 0.0f;
+    r.y = sh == 0 ? v.y : sh == 1 ? v.z : sh == 2 ? v.w : 0.0f;
+    r.z = sh == 0 ? v.z : sh == 1 ? v.w : 0.0f;
+    r.w = sh == 0 ? v.w : 0.0f;
+    return r;
+  };
+  const bool wide = d >= 4;
+
+  auto load_stage = [&](int kt, Stage &s) {
+    const int64_t x0 = xbeg + (int64_t)kt * kXT;
+    const bool x_full = x0 + kXT <= xend;
+    const int64_t xa = x0 + tk;
+    if (x_full && j_full) {
+      s.a = *reinterpret_cast<const f4u *>(B + xa * ldb + j0 + ti);
+    } else if (x_full && wide) {
+      s.a = load4_clamped(B + xa * ldb, j0 + ti);
+    } else {
+      float v[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = (xa < xend && j0 + ti + e < d) ? B[xa * ldb + j0 + ti + e] : 0.0f;
+      s.a = f4a{v[0], v[1], v[2], v[3]};
+    }
+    if (CUBE) {
+      const float w = xa < xend ? B[xa * ldb + i] : 0.0f;
+      s.a *= w;
+    }
+    if (x_full && k_full) {
+#pragma unroll
+      for (int r = 0; r < 2; ++r) s.b[r] = *reinterpret_cast<const f4u *>(B + (x0 + bk + 16 * r) * ldb + k0 + bc);
+    } else if (x_full && wide) {
+#pragma unroll
+      for (int r = 0; r < 2; ++r) s.b[r] = load4_clamped(B + (x0 + bk + 16 * r) * ldb, k0 + bc);
+    } else {
+#pragma unroll
+      for (int r = 0; r < 2; ++r) {
+        const int64_t x = x0 + bk + 16 * r;
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = (x < xend && k0 + bc + e < d) ? B[x * ldb + k0 + bc + e] : 0.0f;
+        s.b[r] = f4a{v[0], v[1], v[2], v[3]};
+      }
+    }
+  };
+  auto store_stage = [&](int buf, const Stage &s) {
+    *reinterpret_cast<f4a *>(&As[buf][tk * kJP + ti]) = s.a;
+#pragma unroll
+    for (int r = 0; r < 2; ++r) *reinterpret_cast<f4a *>(&Bs[buf][(bk + 16 * r) * kBK + bc]) = s.b[r];
+  };
+
+  f16v acc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+
+  // Operands of one group of eight samples: lane half h takes samples 8t+4h .. 8t+4h+3 (the sum over x
+  // may be taken in any order), four MFMA steps on the wavefront's 32x32 sub-tile.
+  struct Ops {
+    float a[4];
+    float b[4];
+  };
+  auto read_ops = [&](int buf, int t, Ops &o) {
+    if (!live) return;
+    const float *as = &As[buf][(4 * h) * kJP + wr * 32 + l32];
+    const float *bs = &Bs[buf][(4 * h) * kBK + wc * 32 + l32];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      o.a[r] = as[(8 * t + r) * kJP];
+      o.b[r] = bs[(8 * t + r) * kBK];
+    }
+  };
+  auto mma = [&](const Ops &o) {
+    if (!live) return;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(o.a[r], o.b[r], acc, 0, 0, 0);
+  };
+
+  Stage st;
+  Ops oa = {}, ob = {};
+  load_stage(0, st);
+  store_stage(0, st);
+  __syncthreads();
+  read_ops(0, 0, oa);
+
+  // One step on LDS buffer `buf`: the next step's global loads are in flight throughout; its LDS
+  // stores and the barrier sit before the last group's matrix instructions.
+  auto step = [&](int kt, int buf) {
+    const bool more = kt + 1 < nk;
+    if (more) load_stage(kt + 1, st);
+    read_ops(buf, 1, ob);
+    mma(oa);
+    read_ops(buf, 2, oa);
+    mma(ob);
+    read_ops(buf, 3, ob);
+    mma(oa);
+    if (more) store_stage(buf ^ 1, st);
+    __syncthreads();
+    if (more) read_ops(buf ^ 1, 0, oa);
+    mma(ob);
+  };
+  for (int kt = 0; kt < nk; kt += 2) {
+    step(kt, 0);
+    if (kt + 1 < nk) step(kt + 1, 1);
+  }
+
+  // D layout of the 32x32 tile: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32.
+  // Rows are j, columns are k; both relative to the slice's first column i.
+  float *slice = out + (CUBE ? tet_slice_start(d, i) : 0);
+  const int64_t kr = (int64_t)K * kBK + wc * 32 + l32;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int64_t jr = (int64_t)J * kBJ + wr * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+    if (jr <= kr && kr < q) {
+      float *p = slice + tri_offset(q, jr, kr);
+      if (ATOMIC)
+        unsafeAtomicAdd(p, acc[v]);
+      else
+        *p = acc[v];
+    }
+  }
+}
+
+__global__ void fill_zero_kernel(float *__restrict__ y, int64_t count) {
+  for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < count; t += (int64_t)gridDim.x * blockDim.x)
+    y[t] = 0.0f;
+}
+
+template <bool CUBE>
+int run(int64_t N, int64_t d, const float *B, int64_t ldb, float *out, void *stream) {
+  if (N < 0 || d < 0 || ldb < d) return DASTAC_EINVAL;
+  if (d > (CUBE ? kMaxD3 : kMaxD2) || N > kMaxN) return DASTAC_EOVERFLOW;
+  if (d == 0) return DASTAC_OK;
+  if (!out || (N > 0 && !B)) return DASTAC_ENULL;
+  const int64_t count = CUBE ? tet(d) : tri(d);
+  if (overlaps(out, count * 4, B, N * ldb * 4)) return DASTAC_EALIAS;
+  hipStream_t st = (hipStream_t)stream;
+
+  const int64_t tiles = total_tiles(d, CUBE);
+  if (tiles > 0x7fffffff) return DASTAC_EOVERFLOW;
+  // Split the samples when the tiles alone cannot fill the chip.  All workgroups cost the same, so the
+  // launch runs in rounds of `slots` resident workgroups: take the smallest split that fills its last
+  // round to 90 %, or else the best one found; every share is a multiple of a step and at least 8 steps.
+  int64_t split = 1, chunk = kXT;
+  if (N > 0) {
+    int dev = 0, per_cu = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, pr_mfma_kernel<CUBE, true>, kBlock, 0) != hipSuccess)
+      return DASTAC_EHIP;
+    const int64_t slots = (int64_t)(per_cu > 0 ? per_cu : 1) * (cus > 0 ? cus : 1);
+    const int64_t max_split = N / (8 * kXT) > 1 ? N / (8 * kXT) : 1;
+    double best = -1.0;
+    for (int64_t s = 1; s <= max_split && s <= 4096; ++s) {
+      const int64_t blocks = tiles * s, rounds = ceil_div(blocks, slots);
+      const double fill = (double)blocks / (double)(rounds * slots);
+      if (fill > best + 1e-9) best = fill, split = s;
+      if (fill >= 0.9 || blocks >= 16 * slots) {
+        split = s;
+        break;
+      }
+    }
+    chunk = ceil_div(ceil_div(N, split), kXT) * kXT;
+    split = ceil_div(N, chunk);
+  }
+  if (split > 65535) return DASTAC_EOVERFLOW;
+
+  const bool atomic = split > 1;
+  if (atomic || N == 0) {
+    const int64_t zb = ceil_div(count, 256);
+    fill_zero_kernel<<<(unsigned)(zb < 8192 ? zb : 8192), 256, 0, st>>>(out, count);
+    if (hipGetLastError() != hipSuccess) return DASTAC_EHIP;
+    if (N == 0) return DASTAC_OK;
+  }
+  const dim3 grid((unsigned)tiles, (unsigned)split);
+  if (atomic)
+    pr_mfma_kernel<CUBE, true><<<grid, kBlock, 0, st>>>(N, d, B, ldb, out, chunk);
+  else
+    pr_mfma_kernel<CUBE, false><<<grid, kBlock, 0, st>>>(N, d, B, ldb, out, chunk);
+  return launch_status();
+}
+
+}  // namespace
+
+extern "C" {
+
+int dastac_pr_a2_f32(int64_t N, int64_t d, const float *B, int64_t ldb, float *A2p, void *stream) {
+  return run<false>(N, d, B, ldb, A2p, stream);
+}
+
+int dastac_pr_a3_f32(int64_t N, int64_t d, const float *B, int64_t ldb, float *A3p, void *stream) {
+  return run<true>(N, d, B, ldb, A3p, stream);
+}
+
+}  // extern "C"

@@ -57,6 +57,8 @@ SIGNATURES = {
     "dastac_unpack_uhc_f32": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp]),
     "dastac_ttm_ut_f32": (ctypes.c_int, [_i64, _i64, _i64, _vp, _vp, _i64, _vp, _vp]),
     "dastac_symm_f32": (ctypes.c_int, [_i64, _i64, _vp, _vp, _i64, _vp, _i64, _vp]),
+    "dastac_pr_a2_f32": (ctypes.c_int, [_i64, _i64, _vp, _i64, _vp, _vp]),
+    "dastac_pr_a3_f32": (ctypes.c_int, [_i64, _i64, _vp, _i64, _vp, _vp]),
     "dastac_subtri_offset": (_i64, [_i64, _i64, _i64, _i64]),
     "dastac_pack_sband_f32": (ctypes.c_int, [_i64, _i64, _i64, _vp, _i64, _vp, _vp]),
     "dastac_unpack_sband_f32": (ctypes.c_int, [_i64, _i64, _i64, _vp, _vp, _i64, _vp]),
@@ -286,3 +288,11 @@ def leslie_spmv_f32(n, R, S, x, y, stream=None):
 
 def symm_f32(n, m, Up, B, ldb, C, ldc, stream=None):
     _check(lib().dastac_symm_f32(n, m, _ptr(Up), _ptr(B), ldb, _ptr(C), ldc, _stream(stream)), "symm_f32")
+
+
+def pr_a2_f32(N, d, B, ldb, A2p, stream=None):
+    _check(lib().dastac_pr_a2_f32(N, d, _ptr(B), ldb, _ptr(A2p), _stream(stream)), "pr_a2_f32")
+
+
+def pr_a3_f32(N, d, B, ldb, A3p, stream=None):
+    _check(lib().dastac_pr_a3_f32(N, d, _ptr(B), ldb, _ptr(A3p), _stream(stream)), "pr_a3_f32")

@@ -78,6 +78,12 @@ def leslie_inputs(n: int = 1 << 24):
             "x": inputs.uniform(_seed(10, 2), n)}
 
 
+def pr_inputs(N: int, d: int, which: int):
+    """Table 1's polynomial-regression kernels: a dense N x d sample matrix (first dimension 100000 for
+    the second-order tensor, 10000 for the third-order one); stream seeds of "config 11" and "config 12"."""
+    return {"N": N, "d": d, "B": inputs.normal(_seed(9 + which, 0), N, d)}
+
+
 def accounting(name: str, **kw) -> dict:
     """Useful FLOPs and algorithmic bytes of one launch."""
     if name == "trmv":
@@ -100,6 +106,13 @@ def accounting(name: str, **kw) -> dict:
     if name == "symv":  # every unique element is used twice, the diagonal once
         n = kw["n"]
         return {"flops": 2 * n * n, "bytes": 4 * (_tri(n) + 2 * n)}
+    if name == "pr_a2":  # one multiply-add per sample and unique output
+        N, d = kw["N"], kw["d"]
+        return {"flops": 2 * N * _tri(d), "bytes": 4 * (N * d + _tri(d))}
+    if name == "pr_a3":  # factored as the kernel executes it: one scaling per (x, i, j>=i), one multiply-add per unique output
+        N, d = kw["N"], kw["d"]
+        return {"flops": 2 * N * _tet(d) + N * _tri(d), "flops_paper_convention": 3 * N * _tet(d),
+                "bytes": 4 * (N * d + _tet(d))}
     if name == "symm":  # every unique element is used twice per column of B, the diagonal once
         n, m = kw["n"], kw["m"]
         return {"flops": 2 * n * n * m, "bytes": 4 * (_tri(n) + 2 * n * m)}

@@ -40,6 +40,10 @@ def tri(n):
     return n * (n + 1) // 2
 
 
+def tet(n):
+    return n * (n + 1) * (n + 2) // 6
+
+
 def assert_within(got, want, scale, what):
     got = np.asarray(got, dtype=np.float64).ravel()
     want = np.asarray(want, dtype=np.float64).ravel()
@@ -176,3 +180,47 @@ def test_leslie_spmv_exact_on_integers_and_repeatable_call(gpu, oracle):
     for _ in range(2):  # the second call must not add onto the first call's y(0)
         gpu.d.leslie_spmv_f32(n, dR, dS, dx, y)
         assert gpu.down(y).tobytes() == want.tobytes()
+
+
+# ------------------------------------------ polynomial-regression tensors ----
+
+@pytest.mark.parametrize("N,d,ld", [(1, 1, 1), (5, 3, 3), (100, 64, 64), (333, 65, 70), (40, 200, 200), (1000, 130, 130),
+                                    (20000, 64, 64), (5000, 257, 260), (31, 129, 129)])
+def test_pr_a2_parity(gpu, oracle, N, d, ld):
+    B = inputs.normal(1800 + N + d, N, ld)
+    want, scale = oracle.pr_a2(np.ascontiguousarray(B[:, :d]))
+    out = gpu.empty(tri(d))
+    gpu.d.pr_a2_f32(N, d, gpu.up(B), ld, out)
+    assert_within(gpu.down(out), want, scale, "pr_a2 N=%d d=%d" % (N, d))
+
+
+@pytest.mark.parametrize("N,d,ld", [(1, 1, 1), (5, 3, 3), (100, 33, 33), (300, 64, 64), (333, 65, 70), (2000, 70, 70),
+                                    (40, 130, 130), (600, 129, 129)])
+def test_pr_a3_parity(gpu, oracle, N, d, ld):
+    B = inputs.normal(1810 + N + d, N, ld)
+    want, scale = oracle.pr_a3(np.ascontiguousarray(B[:, :d]))
+    out = gpu.empty(tet(d))
+    gpu.d.pr_a3_f32(N, d, gpu.up(B), ld, out)
+    assert_within(gpu.down(out), want, scale, "pr_a3 N=%d d=%d" % (N, d))
+
+
+@pytest.mark.parametrize("N,d", [(300, 150), (3000, 40)])  # one share of the samples / several shares with atomics
+def test_pr_tensors_exact_on_integers(gpu, oracle, N, d):
+    B = inputs.small_int(1820 + N, -2, 2, N, d)
+    dB = gpu.up(B)
+    w2, _ = oracle.pr_a2(B)
+    w3, _ = oracle.pr_a3(B)
+    o2, o3 = gpu.empty(tri(d)), gpu.empty(tet(d))
+    for _ in range(2):  # a second call must overwrite, not add onto, the first call's result
+        gpu.d.pr_a2_f32(N, d, dB, d, o2)
+        gpu.d.pr_a3_f32(N, d, dB, d, o3)
+        assert gpu.down(o2).tobytes() == w2.tobytes()
+        assert gpu.down(o3).tobytes() == w3.tobytes()
+
+
+def test_pr_tensors_without_samples_are_zero(gpu):
+    d = 37
+    o2, o3 = gpu.empty(tri(d)), gpu.empty(tet(d))
+    gpu.d.pr_a2_f32(0, d, None, d, o2)
+    gpu.d.pr_a3_f32(0, d, None, d, o3)
+    assert not gpu.down(o2).any() and not gpu.down(o3).any()

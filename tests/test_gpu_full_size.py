@@ -140,3 +140,21 @@ def test_symm_16384_sampled_rows(gpu, oracle):
     for i in rows:
         want, scale = oracle.symm(n, m, w["Up"], w["B"], rows=(i, i + 1))
         check(got[i], want[i], scale[i], "symm row %d" % i)
+
+
+@pytest.mark.parametrize("which,N,d", [(2, 100000, 1024), (3, 10000, 256)])
+def test_pr_tensors_sampled_positions(gpu, oracle, which, N, d):
+    """The polynomial-regression tensors at the sizes bench.py reports beside the five configurations
+    (Table 1: first dimension 100000 for the second-order tensor, 10000 for the third-order one)."""
+    w = wl.pr_inputs(N, d, which)
+    count = d * (d + 1) // 2 if which == 2 else d * (d + 1) * (d + 2) // 6
+    out = gpu.empty(count)
+    (gpu.d.pr_a2_f32 if which == 2 else gpu.d.pr_a3_f32)(N, d, gpu.up(w["B"]), d, out)
+    got = gpu.down(out)
+    assert np.isfinite(got).all()
+    rng = np.random.default_rng(10 + which)
+    starts = sorted({0, 1, d - 2, d, count - 3} | {int(r) for r in rng.integers(0, count - 3, 24)})
+    fn = oracle.pr_a2 if which == 2 else oracle.pr_a3
+    for p in starts:
+        want, scale = fn(w["B"], window=(p, p + 3))
+        check(got[p:p + 3], want[p:p + 3], scale[p:p + 3], "pr_a%d position %d" % (which, p))

@@ -177,6 +177,16 @@ def test_new_domain_entry_points_reject_bad_arguments():
     assert L.dastac_symm_f32(4, 2, _p(A), None, 2, _p(C), 2, None) == dastac.ENULL
     assert L.dastac_symm_f32(4, 2, _p(A), _p(B), 2, _p(B + 8), 2, None) == dastac.EALIAS
     assert L.dastac_symm_f32(0, 2, None, None, 2, None, 2, None) == dastac.OK
+    for fn, dmax in ((L.dastac_pr_a2_f32, 65536), (L.dastac_pr_a3_f32, 8192)):
+        assert fn(-1, 4, _p(A), 4, _p(B), None) == dastac.EINVAL
+        assert fn(10, -1, _p(A), 4, _p(B), None) == dastac.EINVAL
+        assert fn(10, 4, _p(A), 3, _p(B), None) == dastac.EINVAL
+        assert fn(10, dmax + 1, _p(A), dmax + 1, _p(B), None) == dastac.EOVERFLOW
+        assert fn(2 ** 31 + 1, 4, _p(A), 4, _p(B), None) == dastac.EOVERFLOW
+        assert fn(10, 4, None, 4, _p(B), None) == dastac.ENULL
+        assert fn(10, 4, _p(A), 4, None, None) == dastac.ENULL
+        assert fn(10, 4, _p(A), 4, _p(A + 32), None) == dastac.EALIAS
+        assert fn(10, 0, None, 0, None, None) == dastac.OK
     assert L.dastac_sband_spmv_f32(-1, 1, 1, _p(A), _p(B), _p(C), None) == dastac.EINVAL
     assert L.dastac_sband_spmv_f32(4, 1, 0, _p(A), _p(B), _p(C), None) == dastac.EINVAL
     assert L.dastac_sband_spmv_f32(4, 65, 1, _p(A), _p(B), _p(C), None) == dastac.EINVAL
