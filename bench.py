@@ -55,6 +55,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--sweep", action="store_true",
                     help="also time TRMV, TTV and MTTKRP at larger sizes (reported under \"sweep\", never in value)")
+    ap.add_argument("--no-beside", action="store_true",
+                    help="skip the kernels that are measured beside the five-contraction step")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy first, so that a rocprofv3 --pmc run of "
                          "this command can scale FETCH_SIZE / WRITE_SIZE by a kernel of known traffic")
@@ -241,73 +243,74 @@ def main() -> int:
             del A3
         result["sweep"] = sweep
 
-    # Measured beside the step, never part of `value`: the paper's running example (TTM_UT), the
-    # symmetric product on a packed triangle, and the strided-band, sub-triangular and Leslie SpMVs,
-    # which are not among the five benchmark configurations.
-    def beside(fn):
-        for _ in range(args.warmup):
-            fn()
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
-        ev[0].record()
-        for s in range(args.steps):
-            fn()
-            ev[s + 1].record()
-        torch.cuda.synchronize()
-        return float(np.mean([ev[s].elapsed_time(ev[s + 1]) for s in range(args.steps)]))
+    if not args.no_beside:
+        # Measured beside the step, never part of `value`: the paper's running example (TTM_UT), the
+        # symmetric product on a packed triangle, and the strided-band, sub-triangular and Leslie SpMVs,
+        # which are not among the five benchmark configurations.
+        def beside(fn):
+            for _ in range(args.warmup):
+                fn()
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+            ev[0].record()
+            for s in range(args.steps):
+                fn()
+                ev[s + 1].record()
+            torch.cuda.synchronize()
+            return float(np.mean([ev[s].elapsed_time(ev[s + 1]) for s in range(args.steps)]))
 
-    def entry(workload, ms, a, bound):
-        frac = a["flops"] / ms / 1e9 / MFMA_F32_PEAK_TFLOPS if bound == "mfma" else a["bytes"] / ms / 1e6 / HBM_PEAK_GBPS
-        return {"workload": workload, "ms": ms, "gflops": a["flops"] / ms / 1e6, "gbps": a["bytes"] / ms / 1e6,
-                "bound": bound, "frac": frac}
+        def entry(workload, ms, a, bound):
+            frac = a["flops"] / ms / 1e9 / MFMA_F32_PEAK_TFLOPS if bound == "mfma" else a["bytes"] / ms / 1e6 / HBM_PEAK_GBPS
+            return {"workload": workload, "ms": ms, "gflops": a["flops"] / ms / 1e6, "gbps": a["bytes"] / ms / 1e6,
+                    "bound": bound, "frac": frac}
 
-    tw = wl.ttm_ut_inputs()
-    nt, Qt, Kt = tw["n"], tw["Q"], tw["K"]
-    gB, gC, gA = up(tw["Bp"]), up(tw["C"]), out(nt * (nt + 1) // 2 * Kt)
-    tms = beside(lambda: d.ttm_ut_f32(nt, Qt, Kt, gB, gC, Qt, gA))
-    result["beside"] = {"ttm_ut": entry("TTM_UT n=%d Q=%d K=%d, packed in and out" % (nt, Qt, Kt), tms,
-                                        wl.accounting("ttm_ut", n=nt, Q=Qt, K=Kt), "mfma")}
-    del gB, gA, tw
-    sw = wl.symv_inputs()
-    ns = sw["n"]
-    gU, gx, gy = up(sw["Up"]), up(sw["x"]), out(ns)
-    sms = beside(lambda: d.symv_f32(ns, gU, gx, gy))
-    result["beside"]["symv"] = entry("SYMV n=%d on the packed upper triangle" % ns, sms, wl.accounting("symv", n=ns), "hbm")
-    del gU, sw
-    # SYMM on the TRMM configuration's operands (still resident)
-    mms = beside(lambda: d.symm_f32(n2, m2, g["trmm"][0], g["trmm"][1], m2, g["trmm"][2], m2))
-    result["beside"]["symm"] = entry("SYMM n=%d m=%d on the packed upper triangle" % (n2, m2), mms,
-                                     wl.accounting("symm", n=n2, m=m2), "mfma")
-    # polynomial-regression tensors (Table 1): dense samples in, packed hyper-triangles out
-    for which, Np, dp in ((2, 100000, 1024), (3, 10000, 256)):
-        pw = wl.pr_inputs(Np, dp, which)
-        name = "pr_a%d" % which
-        gBp = up(pw["B"])
-        gO = out(dp * (dp + 1) // 2 if which == 2 else dp * (dp + 1) * (dp + 2) // 6)
-        fn = d.pr_a2_f32 if which == 2 else d.pr_a3_f32
-        pms = beside(lambda: fn(Np, dp, gBp, dp, gO))
-        result["beside"][name] = entry("A^%d of Table 1's polynomial regression, N=%d d=%d, packed output"
-                                       % (which, Np, dp), pms, wl.accounting(name, N=Np, d=dp), "mfma")
-        del gBp, gO, pw
-    bw = wl.sband_inputs()
-    nb, wb, sb = bw["n"], bw["w"], bw["s"]
-    gD, gx, gy = up(bw["D"]), up(bw["x"]), out(nb)
-    bms = beside(lambda: d.sband_spmv_f32(nb, wb, sb, gD, gx, gy))
-    result["beside"]["sband"] = entry("strided-band SpMV n=%d w=%d s=%d" % (nb, wb, sb), bms,
-                                      wl.accounting("sband", n=nb, w=wb, s=sb), "hbm")
-    del gD, bw
-    uw = wl.subtri_inputs()
-    Nu, ku = uw["N"], uw["k"]
-    gP, gx, gy = up(uw["Ap"]), up(uw["x"]), out(Nu)
-    ums = beside(lambda: d.subtri_spmv_f32(Nu, ku, gP, gx, gy))
-    result["beside"]["subtri"] = entry("sub-triangular SpMV N=%d k=%d" % (Nu, ku), ums,
-                                       wl.accounting("subtri", N=Nu, k=ku), "hbm")
-    del gP, uw
-    lw = wl.leslie_inputs()
-    nl = lw["n"]
-    gR, gS, gx, gy = up(lw["R"]), up(lw["S"]), up(lw["x"]), out(nl)
-    lms = beside(lambda: d.leslie_spmv_f32(nl, gR, gS, gx, gy))
-    result["beside"]["leslie"] = entry("Leslie SpMV n=%d" % nl, lms, wl.accounting("leslie", n=nl), "hbm")
-    del gR, gS, lw
+        tw = wl.ttm_ut_inputs()
+        nt, Qt, Kt = tw["n"], tw["Q"], tw["K"]
+        gB, gC, gA = up(tw["Bp"]), up(tw["C"]), out(nt * (nt + 1) // 2 * Kt)
+        tms = beside(lambda: d.ttm_ut_f32(nt, Qt, Kt, gB, gC, Qt, gA))
+        result["beside"] = {"ttm_ut": entry("TTM_UT n=%d Q=%d K=%d, packed in and out" % (nt, Qt, Kt), tms,
+                                            wl.accounting("ttm_ut", n=nt, Q=Qt, K=Kt), "mfma")}
+        del gB, gA, tw
+        sw = wl.symv_inputs()
+        ns = sw["n"]
+        gU, gx, gy = up(sw["Up"]), up(sw["x"]), out(ns)
+        sms = beside(lambda: d.symv_f32(ns, gU, gx, gy))
+        result["beside"]["symv"] = entry("SYMV n=%d on the packed upper triangle" % ns, sms, wl.accounting("symv", n=ns), "hbm")
+        del gU, sw
+        # SYMM on the TRMM configuration's operands (still resident)
+        mms = beside(lambda: d.symm_f32(n2, m2, g["trmm"][0], g["trmm"][1], m2, g["trmm"][2], m2))
+        result["beside"]["symm"] = entry("SYMM n=%d m=%d on the packed upper triangle" % (n2, m2), mms,
+                                         wl.accounting("symm", n=n2, m=m2), "mfma")
+        # polynomial-regression tensors (Table 1): dense samples in, packed hyper-triangles out
+        for which, Np, dp in ((2, 100000, 1024), (3, 10000, 256)):
+            pw = wl.pr_inputs(Np, dp, which)
+            name = "pr_a%d" % which
+            gBp = up(pw["B"])
+            gO = out(dp * (dp + 1) // 2 if which == 2 else dp * (dp + 1) * (dp + 2) // 6)
+            fn = d.pr_a2_f32 if which == 2 else d.pr_a3_f32
+            pms = beside(lambda: fn(Np, dp, gBp, dp, gO))
+            result["beside"][name] = entry("A^%d of Table 1's polynomial regression, N=%d d=%d, packed output"
+                                           % (which, Np, dp), pms, wl.accounting(name, N=Np, d=dp), "mfma")
+            del gBp, gO, pw
+        bw = wl.sband_inputs()
+        nb, wb, sb = bw["n"], bw["w"], bw["s"]
+        gD, gx, gy = up(bw["D"]), up(bw["x"]), out(nb)
+        bms = beside(lambda: d.sband_spmv_f32(nb, wb, sb, gD, gx, gy))
+        result["beside"]["sband"] = entry("strided-band SpMV n=%d w=%d s=%d" % (nb, wb, sb), bms,
+                                          wl.accounting("sband", n=nb, w=wb, s=sb), "hbm")
+        del gD, bw
+        uw = wl.subtri_inputs()
+        Nu, ku = uw["N"], uw["k"]
+        gP, gx, gy = up(uw["Ap"]), up(uw["x"]), out(Nu)
+        ums = beside(lambda: d.subtri_spmv_f32(Nu, ku, gP, gx, gy))
+        result["beside"]["subtri"] = entry("sub-triangular SpMV N=%d k=%d" % (Nu, ku), ums,
+                                           wl.accounting("subtri", N=Nu, k=ku), "hbm")
+        del gP, uw
+        lw = wl.leslie_inputs()
+        nl = lw["n"]
+        gR, gS, gx, gy = up(lw["R"]), up(lw["S"]), up(lw["x"]), out(nl)
+        lms = beside(lambda: d.leslie_spmv_f32(nl, gR, gS, gx, gy))
+        result["beside"]["leslie"] = entry("Leslie SpMV n=%d" % nl, lms, wl.accounting("leslie", n=nl), "hbm")
+        del gR, gS, lw
 
     if not args.no_cpu_baseline:
         import oracle
