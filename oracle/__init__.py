@@ -81,6 +81,15 @@ def lib() -> ctypes.CDLL:
         L.oracle_pack_tril_f32.argtypes = [_i64, _fp, _i64, _fp]
         L.oracle_unpack_tril_f32.argtypes = [_i64, _fp, _fp, _i64]
         L.oracle_ttm_ut_f32.argtypes = [_i64, _i64, _i64, _fp, _fp, _i64, _fp, _dp, _i64, _i64]
+        L.oracle_pack_triu_f64.argtypes = [_i64, _dp, _i64, _dp]
+        L.oracle_unpack_triu_f64.argtypes = [_i64, _dp, _dp, _i64]
+        L.oracle_pack_tet_f64.argtypes = [_i64, _dp, _dp]
+        L.oracle_unpack_tet_f64.argtypes = [_i64, _dp, _dp]
+        L.oracle_pack_band_f64.argtypes = [_i64, _i64, _dp, _i64, _dp]
+        L.oracle_unpack_band_f64.argtypes = [_i64, _i64, _dp, _dp, _i64]
+        L.oracle_trmv_f64.argtypes = [_i64, _dp, _dp, _dp, _dp, _i64, _i64]
+        L.oracle_band_spmv_f64.argtypes = [_i64, _i64, _dp, _dp, _dp, _dp, _i64, _i64]
+        L.oracle_tet_ttv_f64.argtypes = [_i64, _dp, _dp, _dp, _dp, _i64, _i64]
         L.oracle_pr_a2_f32.argtypes = [_i64, _i64, _fp, _i64, _fp, _dp, _i64, _i64]
         L.oracle_pr_a3_f32.argtypes = [_i64, _i64, _fp, _i64, _fp, _dp, _i64, _i64]
         L.oracle_symm_f32.argtypes = [_i64, _i64, _fp, _fp, _i64, _fp, _i64, _dp, _i64, _i64]
@@ -436,3 +445,82 @@ def pr_a3(B, window=None):
     """A3(i,j,k) = sum_x B(x,i) B(x,j) B(x,k), i<=j<=k, packed."""
     d = B.shape[1]
     return _pr(lib().oracle_pr_a3_f32, d * (d + 1) * (d + 2) // 6, B, window)
+
+
+# ---- double precision ---------------------------------------------------------
+
+def _f64(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def pack_triu_f64(dense):
+    dense = _f64(dense)
+    n = dense.shape[0]
+    out = np.empty(n * (n + 1) // 2, dtype=np.float64)
+    lib().oracle_pack_triu_f64(n, _d(dense), dense.shape[1], _d(out))
+    return out
+
+
+def unpack_triu_f64(n, packed):
+    packed = _f64(packed)
+    out = np.empty((n, n), dtype=np.float64)
+    lib().oracle_unpack_triu_f64(n, _d(packed), _d(out), n)
+    return out
+
+
+def pack_tet_f64(dense):
+    dense = _f64(dense)
+    n = dense.shape[0]
+    out = np.empty(n * (n + 1) * (n + 2) // 6, dtype=np.float64)
+    lib().oracle_pack_tet_f64(n, _d(dense), _d(out))
+    return out
+
+
+def unpack_tet_f64(n, packed):
+    packed = _f64(packed)
+    out = np.empty((n, n, n), dtype=np.float64)
+    lib().oracle_unpack_tet_f64(n, _d(packed), _d(out))
+    return out
+
+
+def pack_band_f64(dense, w):
+    dense = _f64(dense)
+    n = dense.shape[0]
+    out = np.empty((2 * w + 1) * n, dtype=np.float64)
+    lib().oracle_pack_band_f64(n, w, _d(dense), dense.shape[1], _d(out))
+    return out
+
+
+def unpack_band_f64(n, w, diag):
+    diag = _f64(diag)
+    out = np.empty((n, n), dtype=np.float64)
+    lib().oracle_unpack_band_f64(n, w, _d(diag), _d(out), n)
+    return out
+
+
+def trmv_f64(n, Up, x, rows=None):
+    Up, x = _f64(Up), _f64(x)
+    lo, hi = _window(n, rows)
+    y = np.full(n, np.nan, dtype=np.float64)
+    sc = np.full(n, np.nan, dtype=np.float64)
+    lib().oracle_trmv_f64(n, _d(Up), _d(x), _d(y), _d(sc), lo, hi)
+    return y, sc
+
+
+def band_spmv_f64(n, w, D, x, rows=None):
+    D, x = _f64(D), _f64(x)
+    lo, hi = _window(n, rows)
+    y = np.full(n, np.nan, dtype=np.float64)
+    sc = np.full(n, np.nan, dtype=np.float64)
+    lib().oracle_band_spmv_f64(n, w, _d(D), _d(x), _d(y), _d(sc), lo, hi)
+    return y, sc
+
+
+def tet_ttv_f64(n, Ap, v, rows=None):
+    Ap, v = _f64(Ap), _f64(v)
+    lo, hi = _window(n, rows)
+    cnt = n * (n + 1) // 2
+    M = np.full(cnt, np.nan, dtype=np.float64)
+    sc = np.full(cnt, np.nan, dtype=np.float64)
+    lib().oracle_tet_ttv_f64(n, _d(Ap), _d(v), _d(M), _d(sc), lo, hi)
+    return M, sc

@@ -700,3 +700,119 @@ void oracle_pr_a3_f32(int64_t N, int64_t d, const float *B, int64_t ldb, float *
         if (scale) scale[p] = mag;
       }
 }
+
+/* ---- double precision (the paper's own element type, Section 6.1) -------------------------
+ * The same definitions on double operands.  Accumulation is in long double (64-bit mantissa on
+ * this host), rounded to double once at the end, so that the reference stays well below the
+ * rounding error of any double-precision summation order it is compared with. */
+void oracle_pack_triu_f64(int64_t n, const double *dense, int64_t ld, double *packed) {
+  int64_t p = 0;
+  for (int64_t i = 0; i < n; ++i)
+    for (int64_t j = i; j < n; ++j) packed[p++] = dense[i * ld + j];
+}
+
+void oracle_unpack_triu_f64(int64_t n, const double *packed, double *dense, int64_t ld) {
+  for (int64_t i = 0; i < n; ++i)
+    for (int64_t j = 0; j < n; ++j) dense[i * ld + j] = 0.0;
+  int64_t p = 0;
+  for (int64_t i = 0; i < n; ++i)
+    for (int64_t j = i; j < n; ++j) dense[i * ld + j] = packed[p++];
+}
+
+void oracle_pack_tet_f64(int64_t n, const double *dense, double *packed) {
+  int64_t p = 0;
+  for (int64_t i = 0; i < n; ++i)
+    for (int64_t j = i; j < n; ++j)
+      for (int64_t k = j; k < n; ++k) packed[p++] = dense[(i * n + j) * n + k];
+}
+
+void oracle_unpack_tet_f64(int64_t n, const double *packed, double *dense) {
+  for (int64_t t = 0; t < n * n * n; ++t) dense[t] = 0.0;
+  int64_t p = 0;
+  for (int64_t i = 0; i < n; ++i)
+    for (int64_t j = i; j < n; ++j)
+      for (int64_t k = j; k < n; ++k) dense[(i * n + j) * n + k] = packed[p++];
+}
+
+void oracle_pack_band_f64(int64_t n, int64_t w, const double *dense, int64_t ld, double *diag) {
+  int64_t p = 0;
+  for (int64_t d = -w; d <= w; ++d)
+    for (int64_t i = 0; i < n; ++i) {
+      int64_t j = i + d;
+      diag[p++] = (j >= 0 && j < n) ? dense[i * ld + j] : 0.0;
+    }
+}
+
+void oracle_unpack_band_f64(int64_t n, int64_t w, const double *diag, double *dense, int64_t ld) {
+  for (int64_t i = 0; i < n; ++i)
+    for (int64_t j = 0; j < n; ++j) dense[i * ld + j] = 0.0;
+  int64_t p = 0;
+  for (int64_t d = -w; d <= w; ++d)
+    for (int64_t i = 0; i < n; ++i) {
+      int64_t j = i + d;
+      if (j >= 0 && j < n) dense[i * ld + j] = diag[p];
+      ++p;
+    }
+}
+
+void oracle_trmv_f64(int64_t n, const double *Up, const double *x, double *y, double *scale,
+                     int64_t r_lo, int64_t r_hi) {
+  int64_t p = 0;
+  for (int64_t i = 0; i < n; ++i) {
+    int on = (i >= r_lo && i < r_hi);
+    long double acc = 0.0L, mag = 0.0L;
+    for (int64_t j = i; j < n; ++j) {
+      if (on) {
+        long double t = (long double)Up[p] * (long double)x[j];
+        acc += t;
+        mag += fabsl(t);
+      }
+      ++p;
+    }
+    if (on) {
+      y[i] = (double)acc;
+      if (scale) scale[i] = (double)mag;
+    }
+  }
+}
+
+void oracle_band_spmv_f64(int64_t n, int64_t w, const double *D, const double *x, double *y,
+                          double *scale, int64_t r_lo, int64_t r_hi) {
+  for (int64_t i = r_lo; i < r_hi && i < n; ++i) {
+    if (i < 0) continue;
+    long double acc = 0.0L, mag = 0.0L;
+    for (int64_t d = -w; d <= w; ++d) {
+      int64_t j = i + d;
+      if (j < 0 || j >= n) continue;
+      long double t = (long double)D[(d + w) * n + i] * (long double)x[j];
+      acc += t;
+      mag += fabsl(t);
+    }
+    y[i] = (double)acc;
+    if (scale) scale[i] = (double)mag;
+  }
+}
+
+void oracle_tet_ttv_f64(int64_t n, const double *Ap, const double *v, double *Mp, double *scale,
+                        int64_t r_lo, int64_t r_hi) {
+  int64_t p = 0, q = 0;
+  for (int64_t i = 0; i < n; ++i) {
+    int on = (i >= r_lo && i < r_hi);
+    for (int64_t j = i; j < n; ++j) {
+      long double acc = 0.0L, mag = 0.0L;
+      for (int64_t k = j; k < n; ++k) {
+        if (on) {
+          long double t = (long double)Ap[p] * (long double)v[k];
+          acc += t;
+          mag += fabsl(t);
+        }
+        ++p;
+      }
+      if (on) {
+        Mp[q] = (double)acc;
+        if (scale) scale[q] = (double)mag;
+      }
+      ++q;
+    }
+  }
+}

@@ -10,6 +10,7 @@ Generator: the SplitMix64 output function (Steele, Lea, Flood 2014) applied to
 ``seed * 0x9E3779B97F4A7C15 + t``; the top 24 bits give ``u = k / 2**24``.
 
 * ``uniform``  : ``2u - 1``  in [-1, 1), exactly representable in fp32.
+* ``uniform64``: ``2 k53 / 2**53 - 1`` from the top 53 bits, an fp64 value with a full mantissa.
 * ``normal``   : Box-Muller on ``u1 = (k+1)/2**24`` and a second draw ``u2``
                  (the mix of the first word), evaluated in fp64, rounded to fp32.
 * ``small_int``: integers in [lo, hi] stored as fp32 (every partial sum of
@@ -62,6 +63,18 @@ def _fill(kind: str, seed: int, count: int, lo: int = 0, hi: int = 0) -> np.ndar
         else:
             raise ValueError(kind)
     return out
+
+
+def uniform64(seed: int, *shape: int) -> np.ndarray:
+    """fp64 values uniform on [-1, 1) with a full 53-bit mantissa: ``2 k / 2**53 - 1`` from the top
+    53 bits of the same stream (for the double-precision entry points)."""
+    count = int(np.prod(shape, dtype=np.int64))
+    out = np.empty(count, dtype=np.float64)
+    for s in range(0, count, _CHUNK):
+        c = min(_CHUNK, count - s)
+        k = (_words(seed, s, c) >> np.uint64(11)).astype(np.float64)
+        out[s:s + c] = k * (2.0 / (1 << 53)) - 1.0
+    return out.reshape(shape)
 
 
 def uniform(seed: int, *shape: int) -> np.ndarray:

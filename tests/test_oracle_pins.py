@@ -611,3 +611,54 @@ def test_pr_tensors_closed_forms(oracle):
     counts = np.bincount(np.arange(N) % d, minlength=d)
     want = [counts[i] if i == j == k else 0 for i in range(d) for j in range(i, d) for k in range(j, d)]
     assert np.array_equal(A3, np.asarray(want, dtype=np.float32))
+
+
+# ---------------------------------------------------------- double precision ----
+
+def _close64(got, want, scale, rel=1e-15):
+    return np.all(np.abs(got - want) <= rel * scale + 1e-300)
+
+
+@pytest.mark.parametrize("n", [1, 2, 7, 33])
+def test_f64_oracle_against_numpy_float64(oracle, n):
+    """The double-precision definitions against NumPy's float64 products on the dense, masked
+    operands, and the layouts against NumPy's own index orders."""
+    w = 3
+    D = inputs.uniform64(2000 + n, n, n)
+    T = inputs.uniform64(2001 + n, n, n, n)
+    x = inputs.uniform64(2002 + n, n)
+    Up = oracle.pack_triu_f64(D)
+    assert np.array_equal(Up, D[np.triu_indices(n)])
+    assert np.array_equal(oracle.unpack_triu_f64(n, Up), np.triu(D))
+    i, j, k = np.meshgrid(np.arange(n), np.arange(n), np.arange(n), indexing="ij")
+    mask = (i <= j) & (j <= k)
+    Tp = oracle.pack_tet_f64(T)
+    assert np.array_equal(Tp, T[mask])
+    assert np.array_equal(oracle.unpack_tet_f64(n, Tp), np.where(mask, T, 0.0))
+    Bp = oracle.pack_band_f64(D, w).reshape(2 * w + 1, n)
+    ii, jj = np.meshgrid(np.arange(n), np.arange(n), indexing="ij")
+    Bd = np.where(np.abs(jj - ii) <= w, D, 0.0)
+    assert np.array_equal(oracle.unpack_band_f64(n, w, Bp.ravel()), Bd)
+    y, sc = oracle.trmv_f64(n, Up, x)
+    assert _close64(y, np.triu(D) @ x, sc, rel=4e-16 * n)
+    assert np.allclose(sc, np.abs(np.triu(D)) @ np.abs(x), rtol=1e-13)
+    yb, scb = oracle.band_spmv_f64(n, w, Bp.ravel(), x)
+    assert _close64(yb, Bd @ x, scb, rel=4e-16 * n)
+    M, scm = oracle.tet_ttv_f64(n, Tp, x)
+    F = np.einsum("ijk,k->ij", np.where(mask, T, 0.0), x)
+    assert _close64(M, F[np.triu_indices(n)], scm, rel=4e-16 * n)
+
+
+def test_f64_oracle_keeps_what_fp32_would_lose(oracle):
+    """1 + 2^-40 survives in double and is exact in the long-double accumulator; the fp32 entry
+    points could not represent it.  Also: on fp32-representable inputs both oracles agree."""
+    n = 3
+    Up = np.array([1.0, 2.0 ** -40, 0.0, 0.0, 0.0, 0.0])
+    x = np.array([1.0, 1.0, 0.0])
+    y, _ = oracle.trmv_f64(n, Up, x)
+    assert y[0] == 1.0 + 2.0 ** -40 and y[0] != 1.0
+    n = 40
+    Uf, xf = inputs.uniform(2010, n * (n + 1) // 2), inputs.uniform(2011, n)
+    y32, _ = oracle.trmv(n, Uf, xf)
+    y64, _ = oracle.trmv_f64(n, Uf.astype(np.float64), xf.astype(np.float64))
+    assert np.array_equal(y64.astype(np.float32), y32)
