@@ -291,6 +291,27 @@ def main() -> int:
             result["beside"][name] = entry("A^%d of Table 1's polynomial regression, N=%d d=%d, packed output"
                                            % (which, Np, dp), pms, wl.accounting(name, N=Np, d=dp), "mfma")
             del gBp, gO, pw
+        # the streaming contractions in double precision (the paper's element type)
+        fw = wl.f64_inputs()
+        up64 = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+        out64 = lambda *shape: torch.empty(shape, dtype=torch.float64, device=dev)
+        nf = fw["trmv"]["n"]
+        gU, gx, gy = up64(fw["trmv"]["Up"]), up64(fw["trmv"]["x"]), out64(nf)
+        fms = beside(lambda: d.trmv_f64(nf, gU, gx, gy))
+        result["beside"]["trmv_f64"] = entry("TRMV n=%d, fp64" % nf, fms, wl.accounting("trmv_f64", n=nf), "hbm")
+        del gU
+        nf, wf = fw["band"]["n"], fw["band"]["w"]
+        gD, gx, gy = up64(fw["band"]["D"]), up64(fw["band"]["x"]), out64(nf)
+        fms = beside(lambda: d.band_spmv_f64(nf, wf, gD, gx, gy))
+        result["beside"]["band_f64"] = entry("band SpMV n=%d w=%d, fp64" % (nf, wf), fms,
+                                             wl.accounting("band_f64", n=nf, w=wf), "hbm")
+        del gD
+        nf = fw["ttv"]["n"]
+        gA, gx, gy = up64(fw["ttv"]["Ap"]), up64(fw["ttv"]["v"]), out64(nf * (nf + 1) // 2)
+        fms = beside(lambda: d.tet_ttv_f64(nf, gA, gx, gy))
+        result["beside"]["ttv_f64"] = entry("tet TTV n=%d, fp64 (operand stays in the memory-side cache between launches)"
+                                            % nf, fms, wl.accounting("ttv_f64", n=nf), "hbm")
+        del gA, fw
         bw = wl.sband_inputs()
         nb, wb, sb = bw["n"], bw["w"], bw["s"]
         gD, gx, gy = up(bw["D"]), up(bw["x"]), out(nb)

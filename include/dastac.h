@@ -218,6 +218,21 @@ int dastac_ttm_ut_f32(int64_t n, int64_t Q, int64_t K, const float *Bp, const fl
 int dastac_pr_a2_f32(int64_t N, int64_t d, const float *B, int64_t ldb, float *A2p, void *stream);
 int dastac_pr_a3_f32(int64_t N, int64_t d, const float *B, int64_t ldb, float *A3p, void *stream);
 
+/* ---- double precision (the paper's own element type, Section 6.1) ------------------------------
+ * The same layouts, index polynomials, argument rules and error codes as the _f32 entry points of the
+ * same name, on double operands (8-byte aligned).  Each output element is within 1e-12 * sum|products|
+ * of the exactly rounded result.  trmv_f64 and tet_ttv_f64 need n <= 8192 (the vector is kept in LDS),
+ * beyond that DASTAC_EOVERFLOW.  The matrix-core contractions have no double-precision version. */
+int dastac_pack_triu_f64(int64_t n, const double *dense, int64_t ld, double *packed, void *stream);
+int dastac_unpack_triu_f64(int64_t n, const double *packed, double *dense, int64_t ld, void *stream);
+int dastac_pack_tet_f64(int64_t n, const double *dense, double *packed, void *stream);
+int dastac_unpack_tet_f64(int64_t n, const double *packed, double *dense, void *stream);
+int dastac_pack_band_f64(int64_t n, int64_t w, const double *dense, int64_t ld, double *diag_major, void *stream);
+int dastac_unpack_band_f64(int64_t n, int64_t w, const double *diag_major, double *dense, int64_t ld, void *stream);
+int dastac_trmv_f64(int64_t n, const double *Up, const double *x, double *y, void *stream);
+int dastac_band_spmv_f64(int64_t n, int64_t w, const double *D, const double *x, double *y, void *stream);
+int dastac_tet_ttv_f64(int64_t n, const double *Ap, const double *v, double *Mp, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

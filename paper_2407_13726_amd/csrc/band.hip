@@ -24,16 +24,16 @@ namespace {
 constexpr int kBlock = 256;
 
 // W >= 0: half-width known at compile time (fully unrolled); W < 0: run-time half-width `w`.
-template <int W>
-__global__ __launch_bounds__(kBlock) void band_kernel(int64_t n, int w, const float *__restrict__ D,
-                                                      const float *__restrict__ x, float *__restrict__ y) {
+template <int W, typename T>
+__global__ __launch_bounds__(kBlock) void band_kernel(int64_t n, int w, const T *__restrict__ D,
+                                                      const T *__restrict__ x, T *__restrict__ y) {
   const int hw = W >= 0 ? W : w;
   const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i >= n) return;
-  const float *d = D + i;
-  float acc = 0.0f;
+  const T *d = D + i;
+  T acc = T(0);
   if (i >= hw && i + hw < n) {  // interior row: every column exists
-    const float *xw = x + (i - hw);
+    const T *xw = x + (i - hw);
     if (W >= 0) {
 #pragma unroll
       for (int dd = 0; dd <= 2 * (W >= 0 ? W : 0); ++dd)
@@ -50,24 +50,36 @@ __global__ __launch_bounds__(kBlock) void band_kernel(int64_t n, int w, const fl
   __builtin_nontemporal_store(acc, y + i);
 }
 
-}  // namespace
-
-extern "C" int dastac_band_spmv_f32(int64_t n, int64_t w, const float *D, const float *x, float *y, void *stream) {
+// Element type T: float, or double (the paper's element type; same kernel, eight bytes per slot).
+template <typename T>
+int run(int64_t n, int64_t w, const T *D, const T *x, T *y, void *stream) {
   if (n < 0 || w < 0 || w > 64) return DASTAC_EINVAL;
   if (n > ((int64_t)1 << 40) / (2 * w + 1)) return DASTAC_EOVERFLOW;
   if (n == 0) return DASTAC_OK;
   if (!D || !x || !y) return DASTAC_ENULL;
-  if (overlaps(y, n * 4, D, (2 * w + 1) * n * 4) || overlaps(y, n * 4, x, n * 4)) return DASTAC_EALIAS;
+  const int64_t sz = (int64_t)sizeof(T);
+  if (overlaps(y, n * sz, D, (2 * w + 1) * n * sz) || overlaps(y, n * sz, x, n * sz)) return DASTAC_EALIAS;
   hipStream_t st = (hipStream_t)stream;
   const unsigned blocks = (unsigned)ceil_div(n, kBlock);
   switch (w) {
-    case 16: band_kernel<16><<<blocks, kBlock, 0, st>>>(n, 16, D, x, y); break;
-    case 8: band_kernel<8><<<blocks, kBlock, 0, st>>>(n, 8, D, x, y); break;
-    case 4: band_kernel<4><<<blocks, kBlock, 0, st>>>(n, 4, D, x, y); break;
-    case 2: band_kernel<2><<<blocks, kBlock, 0, st>>>(n, 2, D, x, y); break;
-    case 1: band_kernel<1><<<blocks, kBlock, 0, st>>>(n, 1, D, x, y); break;
-    case 0: band_kernel<0><<<blocks, kBlock, 0, st>>>(n, 0, D, x, y); break;
-    default: band_kernel<-1><<<blocks, kBlock, 0, st>>>(n, (int)w, D, x, y);
+    case 16: band_kernel<16, T><<<blocks, kBlock, 0, st>>>(n, 16, D, x, y); break;
+    case 8: band_kernel<8, T><<<blocks, kBlock, 0, st>>>(n, 8, D, x, y); break;
+    case 4: band_kernel<4, T><<<blocks, kBlock, 0, st>>>(n, 4, D, x, y); break;
+    case 2: band_kernel<2, T><<<blocks, kBlock, 0, st>>>(n, 2, D, x, y); break;
+    case 1: band_kernel<1, T><<<blocks, kBlock, 0, st>>>(n, 1, D, x, y); break;
+    case 0: band_kernel<0, T><<<blocks, kBlock, 0, st>>>(n, 0, D, x, y); break;
+    default: band_kernel<-1, T><<<blocks, kBlock, 0, st>>>(n, (int)w, D, x, y);
   }
   return launch_status();
+}
+
+}  // namespace
+
+extern "C" int dastac_band_spmv_f32(int64_t n, int64_t w, const float *D, const float *x, float *y, void *stream) {
+  return run<float>(n, w, D, x, y, stream);
+}
+
+extern "C" int dastac_band_spmv_f64(int64_t n, int64_t w, const double *D, const double *x, double *y,
+                                    void *stream) {
+  return run<double>(n, w, D, x, y, stream);
 }

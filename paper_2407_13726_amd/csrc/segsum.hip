@@ -37,10 +37,19 @@ __device__ inline float dpp_add(float v) {
   return v + __builtin_bit_cast(float, t);
 }
 
+template <int CTRL>
+__device__ inline double dpp_add(double v) {  // the two halves of a double travel separately
+  const uint64_t b = __builtin_bit_cast(uint64_t, v);
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)b, CTRL, 0xf, 0xf, false);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(b >> 32), CTRL, 0xf, 0xf, false);
+  return v + __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+
 // Sum over aligned groups of 2^lg lanes; every lane of a group receives the total.
 // Strides 1,2 use quad permutes, 4 and 8 the half-row and row mirrors (all lanes of the mirrored
 // unit already hold equal values), 16 and 32 go through the LDS crossbar.
-__device__ inline float group_sum(float v, int lg) {
+template <typename T>
+__device__ inline T group_sum(T v, int lg) {
   if (lg >= 1) v = dpp_add<0xB1>(v);   // quad_perm [1,0,3,2]
   if (lg >= 2) v = dpp_add<0x4E>(v);   // quad_perm [2,3,0,1]
   if (lg >= 3) v = dpp_add<0x141>(v);  // row_half_mirror
@@ -92,7 +101,7 @@ __device__ inline void first_row_from(int64_t n, int64_t total, int64_t q, int64
 // (larger triangles go to the column-panel kernel of trimv.hip).
 //
 // x is staged once per workgroup, followed by kPad zeros.  A lane handles sixteen packed elements
-// per step (four 16-byte loads, each contiguous across the lanes of a row) without any bounds
+// (eight in double precision) per step (four 16-byte loads, each contiguous across the lanes of a row) without any bounds
 // test: elements past the end of its row meet a zero of the pad, and the product is formed with
 // v_mul_legacy_f32 (0 * anything = 0), so they contribute exactly nothing even if they are Inf or
 // NaN.  A load that would lie wholly past the row's end is aimed at the row's last piece instead,
@@ -103,8 +112,6 @@ __device__ inline void first_row_from(int64_t n, int64_t total, int64_t q, int64
 constexpr int kLdsBlock = 512;
 constexpr int kLdsWaves = kLdsBlock / 64;
 constexpr int kLdsMaxN = 8192;
-constexpr int kSpan = 1024;      // packed elements per step: 64 lanes x 4 loads x 4 floats
-constexpr int kPad = kSpan + 8;  // zeros after x: a lane may look up to kSpan+3 columns past the row end
 
 __device__ inline float mul0(float a, float b) {  // 0 * x == 0 for every x
   float r;
@@ -116,14 +123,40 @@ __device__ inline float dot0(f4a a, f4a x) {
   return (mul0(a.x, x.x) + mul0(a.y, x.y)) + (mul0(a.z, x.z) + mul0(a.w, x.w));
 }
 
-struct Piece16 {
-  f4a a[4], x[4];
+// Double precision has no multiply that returns 0 for 0 * Inf: a product with a zero of x is dropped by a
+// select instead (the same meaning: a zero of x contributes nothing, whatever it multiplies).
+typedef double d2u __attribute__((ext_vector_type(2), aligned(8)));
+typedef double d2a __attribute__((ext_vector_type(2)));
+__device__ inline double dot0(d2a a, d2a x) {
+  return (x.x == 0.0 ? 0.0 : a.x * x.x) + (x.y == 0.0 ? 0.0 : a.y * x.y);
+}
+
+// Per element type: a lane's load is one 16-byte piece of kPer elements, a lane takes four pieces per
+// step (2^kLg elements), a step spans kSpan elements.
+template <typename T>
+struct Elem;
+template <>
+struct Elem<float> {
+  static constexpr int kPer = 4, kLg = 4;
+  typedef f4a vec;
+  typedef f4u uvec;
+};
+template <>
+struct Elem<double> {
+  static constexpr int kPer = 2, kLg = 3;
+  typedef d2a vec;
+  typedef d2u uvec;
 };
 
-// lanes per row (log2) for rows of `len` elements at sixteen elements per lane
-__device__ inline int lanes_log2_16(int len) {
-  return len > 512 ? 6 : len > 256 ? 5 : len > 128 ? 4 : len > 64 ? 3 : len > 32 ? 2 : len > 16 ? 1 : 0;
-}
+template <typename T>
+constexpr int kSpanOf = 64 * 4 * Elem<T>::kPer;  // packed elements per step: 64 lanes x 4 loads x one piece
+template <typename T>
+constexpr int kPadOf = kSpanOf<T> + 8;  // zeros after x: a lane may look up to a span and a piece past the row end
+
+template <typename T>
+struct Piece16 {
+  typename Elem<T>::vec a[4], x[4];
+};
 
 // A step of the LDS variant in 32-bit arithmetic: positions are relative to the wavefront's first
 // row (packed position p0, output position s0), which keeps every per-step update to single
@@ -141,20 +174,24 @@ struct Step32 {
 // STREAM: the packed buffer is larger than the memory-side cache, so its loads are non-temporal
 // (measured 10 % faster there); a smaller buffer is read through the caches, where the lines
 // shared by two neighbouring rows are fetched once (measured 9 % faster at 90 MB).
-template <bool TET, bool STREAM>
-__global__ __launch_bounds__(kLdsBlock) void segsum_lds_kernel(int n, const float *__restrict__ A,
-                                                               const float *__restrict__ x,
-                                                               float *__restrict__ out, int64_t total,
+template <typename T, bool TET, bool STREAM>
+__global__ __launch_bounds__(kLdsBlock) void segsum_lds_kernel(int n, const T *__restrict__ A,
+                                                               const T *__restrict__ x,
+                                                               T *__restrict__ out, int64_t total,
                                                                int64_t total_a, int64_t share, int64_t waves_a,
                                                                int tail_order) {
-  extern __shared__ float xs[];  // x[0..n), then kPad zeros
+  constexpr int kPer = Elem<T>::kPer, kLg = Elem<T>::kLg, kSpan = kSpanOf<T>, kPad = kPadOf<T>;
+  typedef typename Elem<T>::vec vec;
+  typedef typename Elem<T>::uvec uvec;
+  extern __shared__ __attribute__((aligned(16))) unsigned char xs_bytes[];
+  T *xs = reinterpret_cast<T *>(xs_bytes);  // x[0..n), then kPad zeros
   // Request this thread's first four values of x right away; they arrive while the wavefront
   // works out which rows it owns.
-  float xr[4];
+  T xr[4];
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     const int t = threadIdx.x + q * kLdsBlock;
-    xr[q] = t < n ? x[t] : 0.0f;
+    xr[q] = t < n ? x[t] : T(0);
   }
   const int lane = threadIdx.x & 63;
   const int64_t wave = (int64_t)blockIdx.x * kLdsWaves + uniform32(threadIdx.x >> 6);
@@ -180,8 +217,8 @@ __global__ __launch_bounds__(kLdsBlock) void segsum_lds_kernel(int n, const floa
   slice = uniform32(slice);
   const int64_t p0 = uniform64(sp);
   const int64_t s0 = TET ? tri_offset(n, slice, uniform32((int)sj)) : uniform32((int)sj);
-  const float *__restrict__ A0 = A + p0;
-  float *__restrict__ out0 = out + s0;
+  const T *__restrict__ A0 = A + p0;
+  T *__restrict__ out0 = out + s0;
   const int64_t room_hi = uniform64(hi64) - p0, room_total = total - p0;
   const int hi = room_hi > 0x3fffffff ? 0x3fffffff : (int)room_hi;          // rows must start before hi
   const int end = room_total > 0x3fffffff ? 0x3fffffff : (int)room_total;    // one past the last element
@@ -198,14 +235,14 @@ __global__ __launch_bounds__(kLdsBlock) void segsum_lds_kernel(int n, const floa
   // per-lane geometry of a step: row g of the group, `used` rows taken by the step
   auto geometry = [&](const Step32 &d, int &g, int &used, bool &mine, int &off, int &sub4, int &lim, int &xi,
                       int &lw4) {
-    const int v = (d.len + 15) >> 4;                          // lanes a row of this length needs
+    const int v = (d.len + (1 << kLg) - 1) >> kLg;            // lanes a row of this length needs
     int lg = v <= 1 ? 0 : 32 - __builtin_clz(v - 1);         // ceil(log2(v))
     if (lg > 6) lg = 6;
-    lw4 = 4 << lg;  // elements between two consecutive loads of a lane
+    lw4 = kPer << lg;  // elements between two consecutive loads of a lane
     int rows = 64 >> lg;
     if (rows > d.len) rows = d.len;  // stay inside the slice
     g = lane >> lg;
-    sub4 = (lane & ((1 << lg) - 1)) * 4;
+    sub4 = (lane & ((1 << lg) - 1)) * kPer;
     const int goff = g * d.len - ((g * (g - 1)) >> 1);  // start of row g relative to d.p
     mine = g < rows && goff < hi - d.p;
     used = __popcll(__ballot(mine && sub4 == 0));
@@ -214,17 +251,17 @@ __global__ __launch_bounds__(kLdsBlock) void segsum_lds_kernel(int n, const floa
     off = d.p + (mine ? goff + d.t0 : 0);
     // last 4-element piece that still holds an element of my row (my row has len - g elements, of
     // which t0 are behind this step)
-    lim = mine ? (d.len - g - d.t0 - 1) & ~3 : 0;
+    lim = mine ? (d.len - g - d.t0 - 1) & ~(kPer - 1) : 0;
     // column of my first element; lanes without a row look at the zero pad
     xi = mine ? d.j + g + d.t0 + sub4 : n;
   };
   // every lane's loads of step d lie inside the buffer
-  auto fits = [&](const Step32 &d) -> bool { return d.p + d.t0 + kSpan + 4 <= end; };
+  auto fits = [&](const Step32 &d) -> bool { return d.p + d.t0 + kSpan + kPer <= end; };
 
   // Loads that would start past the end of the lane's row are pointed at the row's last piece
   // instead: the line is being fetched anyway, so they cost no memory traffic, and whatever they
   // return meets a zero of the pad.
-  auto issue_a = [&](const Step32 &d, int &g, int &used, int &xi, int &lw4, Piece16 &r) {
+  auto issue_a = [&](const Step32 &d, int &g, int &used, int &xi, int &lw4, Piece16<T> &r) {
     bool mine;
     int off, sub4, lim;
     geometry(d, g, used, mine, off, sub4, lim, xi, lw4);
@@ -232,27 +269,27 @@ __global__ __launch_bounds__(kLdsBlock) void segsum_lds_kernel(int n, const floa
     for (int q = 0; q < 4; ++q) {
       int e = sub4 + q * lw4;
       e = e < lim ? e : lim;
-      const f4u *src = reinterpret_cast<const f4u *>(A0 + off + e);
+      const uvec *src = reinterpret_cast<const uvec *>(A0 + off + e);
       r.a[q] = STREAM ? __builtin_nontemporal_load(src) : *src;
     }
   };
-  auto issue_x = [&](int xi, int lw4, Piece16 &r) {
+  auto issue_x = [&](int xi, int lw4, Piece16<T> &r) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) r.x[q] = *reinterpret_cast<const f4u *>(&xs[xi + q * lw4]);
+    for (int q = 0; q < 4; ++q) r.x[q] = *reinterpret_cast<const uvec *>(&xs[xi + q * lw4]);
   };
-  auto issue_guarded = [&](const Step32 &d, int &g, int &used, Piece16 &r) {
+  auto issue_guarded = [&](const Step32 &d, int &g, int &used, Piece16<T> &r) {
     bool mine;
     int off, sub4, lim, xi, lw4;
     geometry(d, g, used, mine, off, sub4, lim, xi, lw4);
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      float e[4];
+      vec e;
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
+      for (int c = 0; c < kPer; ++c) {
         const int o = off + sub4 + q * lw4 + c;
-        e[c] = (mine && o < end) ? A0[o] : 0.0f;
+        e[c] = (mine && o < end) ? A0[o] : T(0);
       }
-      r.a[q] = f4a{e[0], e[1], e[2], e[3]};
+      r.a[q] = e;
     }
     issue_x(xi, lw4, r);
   };
@@ -275,18 +312,18 @@ __global__ __launch_bounds__(kLdsBlock) void segsum_lds_kernel(int n, const floa
     return nx;
   };
 
-  float racc = 0.0f;  // running per-lane sum of a long row
-  auto consume = [&](const Step32 &d, const Piece16 &c, int g, int used) {
-    float v = (dot0(c.a[0], c.x[0]) + dot0(c.a[1], c.x[1])) + (dot0(c.a[2], c.x[2]) + dot0(c.a[3], c.x[3]));
+  T racc = T(0);  // running per-lane sum of a long row
+  auto consume = [&](const Step32 &d, const Piece16<T> &c, int g, int used) {
+    T v = (dot0(c.a[0], c.x[0]) + dot0(c.a[1], c.x[1])) + (dot0(c.a[2], c.x[2]) + dot0(c.a[3], c.x[3]));
     if (d.len > kSpan) {
       racc += v;
       if (d.t0 + kSpan >= d.len) {
         v = group_sum(racc, 6);
-        racc = 0.0f;
+        racc = T(0);
         if (lane == 0) out0[d.s] = v;
       }
     } else {
-      const int w = (d.len + 15) >> 4;
+      const int w = (d.len + (1 << kLg) - 1) >> kLg;
       int lg = w <= 1 ? 0 : 32 - __builtin_clz(w - 1);
       v = group_sum(v, lg);
       const int sub = lane & ((1 << lg) - 1);
@@ -295,7 +332,7 @@ __global__ __launch_bounds__(kLdsBlock) void segsum_lds_kernel(int n, const floa
   };
 
   // The packed loads of the first step do not depend on LDS: request them before x is staged.
-  Piece16 pa, pb;
+  Piece16<T> pa, pb;
   int ga = 0, ua = 0, gb = 0, ub = 0, xia = 0, lwa = 4, xib = 0, lwb = 4;
   const bool fast = st.valid && fits(st);
   if (fast) issue_a(st, ga, ua, xia, lwa, pa);
@@ -305,7 +342,7 @@ __global__ __launch_bounds__(kLdsBlock) void segsum_lds_kernel(int n, const floa
     const int t = threadIdx.x + q * kLdsBlock;
     if (t < n + kPad) xs[t] = xr[q];
   }
-  for (int t = threadIdx.x + 4 * kLdsBlock; t < n + kPad; t += kLdsBlock) xs[t] = t < n ? x[t] : 0.0f;
+  for (int t = threadIdx.x + 4 * kLdsBlock; t < n + kPad; t += kLdsBlock) xs[t] = t < n ? x[t] : T(0);
   __syncthreads();
 
   // Unguarded steps: two register sets alternate, and nothing but the reductions is branched
@@ -332,7 +369,7 @@ __global__ __launch_bounds__(kLdsBlock) void segsum_lds_kernel(int n, const floa
   }
   // Steps that reach into the last kSpan elements of the buffer.
   while (st.valid) {
-    Piece16 pc;
+    Piece16<T> pc;
     int gc, uc;
     issue_guarded(st, gc, uc, pc);
     consume(st, pc, gc, uc);
@@ -351,8 +388,8 @@ inline int64_t pick_share(int64_t total, int per_cu) {
 
 constexpr int64_t kStreamBytes = (int64_t)192 << 20;  // above this a buffer does not stay in the 256 MB memory-side cache
 
-template <bool TET>
-int launch_lds(int64_t n, const float *A, const float *x, float *out, int64_t total, void *stream) {
+template <typename T, bool TET>
+int launch_lds(int64_t n, const T *A, const T *x, T *out, int64_t total, void *stream) {
   int64_t tail_order = 0, total_a = total;
   if (TET) {  // slices whose triangle is below about half a share get a wavefront of their own
     int64_t m0 = (int64_t)sqrt((double)pick_share(total, 24));
@@ -363,12 +400,12 @@ int launch_lds(int64_t n, const float *A, const float *x, float *out, int64_t to
   const int64_t share = pick_share(total_a, 24);
   const int64_t waves_a = ceil_div(total_a, share);
   const int64_t blocks = ceil_div(waves_a + tail_order, kLdsWaves);
-  const size_t lds = (size_t)(n + kPad) * sizeof(float);
-  if (total * 4 > kStreamBytes)
-    segsum_lds_kernel<TET, true><<<(unsigned)blocks, kLdsBlock, lds, (hipStream_t)stream>>>(
+  const size_t lds = (size_t)(n + kPadOf<T>) * sizeof(T);
+  if (total * (int64_t)sizeof(T) > kStreamBytes)
+    segsum_lds_kernel<T, TET, true><<<(unsigned)blocks, kLdsBlock, lds, (hipStream_t)stream>>>(
         (int)n, A, x, out, total, total_a, share, waves_a, (int)tail_order);
   else
-    segsum_lds_kernel<TET, false><<<(unsigned)blocks, kLdsBlock, lds, (hipStream_t)stream>>>(
+    segsum_lds_kernel<T, TET, false><<<(unsigned)blocks, kLdsBlock, lds, (hipStream_t)stream>>>(
         (int)n, A, x, out, total, total_a, share, waves_a, (int)tail_order);
   return launch_status();
 }
@@ -383,7 +420,7 @@ int dastac_trmv_f32(int64_t n, const float *Up, const float *x, float *y, void *
   if (n == 0) return DASTAC_OK;
   if (!Up || !x || !y) return DASTAC_ENULL;
   if (overlaps(y, n * 4, Up, tri(n) * 4) || overlaps(y, n * 4, x, n * 4)) return DASTAC_EALIAS;
-  if (n <= kLdsMaxN) return launch_lds<false>(n, Up, x, y, tri(n), stream);
+  if (n <= kLdsMaxN) return launch_lds<float, false>(n, Up, x, y, tri(n), stream);
   // x no longer fits in LDS: the column-panel kernel keeps it in registers (n=16384: 4.7 TB/s)
   return trmv_upper_by_panels(n, Up, x, y, stream);
 }
@@ -395,7 +432,26 @@ int dastac_tet_ttv_f32(int64_t n, const float *Ap, const float *v, float *Mp, vo
   if (n == 0) return DASTAC_OK;
   if (!Ap || !v || !Mp) return DASTAC_ENULL;
   if (overlaps(Mp, tri(n) * 4, Ap, tet(n) * 4) || overlaps(Mp, tri(n) * 4, v, n * 4)) return DASTAC_EALIAS;
-  return launch_lds<true>(n, Ap, v, Mp, tet(n), stream);
+  return launch_lds<float, true>(n, Ap, v, Mp, tet(n), stream);
+}
+
+// Double precision (the paper's element type): the same kernel with 16-byte pieces of two elements.
+int dastac_trmv_f64(int64_t n, const double *Up, const double *x, double *y, void *stream) {
+  if (n < 0) return DASTAC_EINVAL;
+  if (n > kLdsMaxN) return DASTAC_EOVERFLOW;  // x must fit in LDS; there is no column-panel kernel in double
+  if (n == 0) return DASTAC_OK;
+  if (!Up || !x || !y) return DASTAC_ENULL;
+  if (overlaps(y, n * 8, Up, tri(n) * 8) || overlaps(y, n * 8, x, n * 8)) return DASTAC_EALIAS;
+  return launch_lds<double, false>(n, Up, x, y, tri(n), stream);
+}
+
+int dastac_tet_ttv_f64(int64_t n, const double *Ap, const double *v, double *Mp, void *stream) {
+  if (n < 0) return DASTAC_EINVAL;
+  if (n > kLdsMaxN) return DASTAC_EOVERFLOW;
+  if (n == 0) return DASTAC_OK;
+  if (!Ap || !v || !Mp) return DASTAC_ENULL;
+  if (overlaps(Mp, tri(n) * 8, Ap, tet(n) * 8) || overlaps(Mp, tri(n) * 8, v, n * 8)) return DASTAC_EALIAS;
+  return launch_lds<double, true>(n, Ap, v, Mp, tet(n), stream);
 }
 
 }  // extern "C"

@@ -59,6 +59,15 @@ SIGNATURES = {
     "dastac_symm_f32": (ctypes.c_int, [_i64, _i64, _vp, _vp, _i64, _vp, _i64, _vp]),
     "dastac_pr_a2_f32": (ctypes.c_int, [_i64, _i64, _vp, _i64, _vp, _vp]),
     "dastac_pr_a3_f32": (ctypes.c_int, [_i64, _i64, _vp, _i64, _vp, _vp]),
+    "dastac_pack_triu_f64": (ctypes.c_int, [_i64, _vp, _i64, _vp, _vp]),
+    "dastac_unpack_triu_f64": (ctypes.c_int, [_i64, _vp, _vp, _i64, _vp]),
+    "dastac_pack_tet_f64": (ctypes.c_int, [_i64, _vp, _vp, _vp]),
+    "dastac_unpack_tet_f64": (ctypes.c_int, [_i64, _vp, _vp, _vp]),
+    "dastac_pack_band_f64": (ctypes.c_int, [_i64, _i64, _vp, _i64, _vp, _vp]),
+    "dastac_unpack_band_f64": (ctypes.c_int, [_i64, _i64, _vp, _vp, _i64, _vp]),
+    "dastac_trmv_f64": (ctypes.c_int, [_i64, _vp, _vp, _vp, _vp]),
+    "dastac_band_spmv_f64": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp, _vp]),
+    "dastac_tet_ttv_f64": (ctypes.c_int, [_i64, _vp, _vp, _vp, _vp]),
     "dastac_subtri_offset": (_i64, [_i64, _i64, _i64, _i64]),
     "dastac_pack_sband_f32": (ctypes.c_int, [_i64, _i64, _i64, _vp, _i64, _vp, _vp]),
     "dastac_unpack_sband_f32": (ctypes.c_int, [_i64, _i64, _i64, _vp, _vp, _i64, _vp]),
@@ -114,6 +123,17 @@ def _ptr(t):
         raise ValueError("device tensor expected")
     if t.dtype.__str__() != "torch.float32":
         raise ValueError("float32 tensor expected")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _ptr64(t):
+    """Device address of a float64 tensor (None -> NULL)."""
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("device tensor expected")
+    if t.dtype.__str__() != "torch.float64":
+        raise ValueError("float64 tensor expected")
     return ctypes.c_void_p(t.data_ptr())
 
 
@@ -296,3 +316,42 @@ def pr_a2_f32(N, d, B, ldb, A2p, stream=None):
 
 def pr_a3_f32(N, d, B, ldb, A3p, stream=None):
     _check(lib().dastac_pr_a3_f32(N, d, _ptr(B), ldb, _ptr(A3p), _stream(stream)), "pr_a3_f32")
+
+
+# ---- double precision ---------------------------------------------------------
+
+def pack_triu_f64(n, dense, ld, packed, stream=None):
+    _check(lib().dastac_pack_triu_f64(n, _ptr64(dense), ld, _ptr64(packed), _stream(stream)), "pack_triu_f64")
+
+
+def unpack_triu_f64(n, packed, dense, ld, stream=None):
+    _check(lib().dastac_unpack_triu_f64(n, _ptr64(packed), _ptr64(dense), ld, _stream(stream)), "unpack_triu_f64")
+
+
+def pack_tet_f64(n, dense, packed, stream=None):
+    _check(lib().dastac_pack_tet_f64(n, _ptr64(dense), _ptr64(packed), _stream(stream)), "pack_tet_f64")
+
+
+def unpack_tet_f64(n, packed, dense, stream=None):
+    _check(lib().dastac_unpack_tet_f64(n, _ptr64(packed), _ptr64(dense), _stream(stream)), "unpack_tet_f64")
+
+
+def pack_band_f64(n, w, dense, ld, diag_major, stream=None):
+    _check(lib().dastac_pack_band_f64(n, w, _ptr64(dense), ld, _ptr64(diag_major), _stream(stream)), "pack_band_f64")
+
+
+def unpack_band_f64(n, w, diag_major, dense, ld, stream=None):
+    _check(lib().dastac_unpack_band_f64(n, w, _ptr64(diag_major), _ptr64(dense), ld, _stream(stream)),
+           "unpack_band_f64")
+
+
+def trmv_f64(n, Up, x, y, stream=None):
+    _check(lib().dastac_trmv_f64(n, _ptr64(Up), _ptr64(x), _ptr64(y), _stream(stream)), "trmv_f64")
+
+
+def band_spmv_f64(n, w, D, x, y, stream=None):
+    _check(lib().dastac_band_spmv_f64(n, w, _ptr64(D), _ptr64(x), _ptr64(y), _stream(stream)), "band_spmv_f64")
+
+
+def tet_ttv_f64(n, Ap, v, Mp, stream=None):
+    _check(lib().dastac_tet_ttv_f64(n, _ptr64(Ap), _ptr64(v), _ptr64(Mp), _stream(stream)), "tet_ttv_f64")

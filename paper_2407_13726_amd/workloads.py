@@ -84,8 +84,22 @@ def pr_inputs(N: int, d: int, which: int):
     return {"N": N, "d": d, "B": inputs.normal(_seed(9 + which, 0), N, d)}
 
 
+def f64_inputs():
+    """Double-precision operands (the paper's element type) for the three streaming contractions:
+    TRMV n=8192, band SpMV n=2097152 w=16, TTV n=512; stream seeds of "config 13"."""
+    n1, n3, w3, n4 = 8192, 1 << 21, 16, 512
+    return {"trmv": {"n": n1, "Up": inputs.uniform64(_seed(13, 0), _tri(n1)), "x": inputs.uniform64(_seed(13, 1), n1)},
+            "band": {"n": n3, "w": w3, "D": inputs.uniform64(_seed(13, 2), (2 * w3 + 1) * n3),
+                     "x": inputs.uniform64(_seed(13, 3), n3)},
+            "ttv": {"n": n4, "Ap": inputs.uniform64(_seed(13, 4), _tet(n4)), "v": inputs.uniform64(_seed(13, 5), n4)}}
+
+
 def accounting(name: str, **kw) -> dict:
     """Useful FLOPs and algorithmic bytes of one launch."""
+    if name.endswith("_f64"):  # same counts, eight bytes per element
+        a = dict(accounting(name[:-4], **kw))
+        a["bytes"] *= 2
+        return a
     if name == "trmv":
         n = kw["n"]
         return {"flops": 2 * _tri(n), "bytes": 4 * (_tri(n) + 2 * n)}

@@ -1,0 +1,160 @@
+"""GPU parity of the double-precision entry points (the paper's element type) against the
+double-precision oracle, which accumulates in long double.
+
+Bars: layouts and copied values bit-exact; floating outputs within 1e-12 * sum|products| per
+element (fp64 rounding is 1.1e-16 per operation; the longest sums here have a few thousand terms);
+bit-exact on small-integer inputs.
+"""
+import numpy as np
+import pytest
+
+from paper_2407_13726_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+TOL64 = 1e-12
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+
+    from paper_2407_13726_amd import dastac
+
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    dastac.lib()
+
+    class G:
+        pass
+
+    g = G()
+    g.d = dastac
+    g.dev = torch.device("cuda:0")
+    g.up = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float64)).to(g.dev)
+    g.empty = lambda *shape: torch.full(shape, float("nan"), dtype=torch.float64, device=g.dev)
+    g.down = lambda t: (torch.cuda.synchronize(), t.cpu().numpy())[1]
+    return g
+
+
+def tri(n):
+    return n * (n + 1) // 2
+
+
+def tet(n):
+    return n * (n + 1) * (n + 2) // 6
+
+
+def assert_within(got, want, scale, what):
+    got, want, scale = (np.asarray(a, dtype=np.float64).ravel() for a in (got, want, scale))
+    assert np.isfinite(got).all(), what + ": non-finite output"
+    err = np.abs(got - want)
+    bad = err > TOL64 * scale
+    assert not bad.any(), "%s: %d of %d outside tolerance, worst err/scale %.3g" % (
+        what, bad.sum(), bad.size, (err / np.maximum(scale, 1e-300)).max())
+
+
+@pytest.mark.parametrize("n,ld", [(1, 1), (17, 20), (256, 256), (257, 300)])
+def test_pack_unpack_triu_f64_bit_exact(gpu, oracle, n, ld):
+    D = inputs.uniform64(3000 + n, n, ld)
+    want = oracle.pack_triu_f64(np.ascontiguousarray(D[:, :n]))
+    dP = gpu.empty(tri(n))
+    gpu.d.pack_triu_f64(n, gpu.up(D), ld, dP)
+    assert gpu.down(dP).tobytes() == want.tobytes()
+    dU = gpu.empty(n, ld)
+    gpu.d.unpack_triu_f64(n, dP, dU, ld)
+    U = gpu.down(dU)
+    assert U[:, :n].tobytes() == oracle.unpack_triu_f64(n, want).tobytes()
+    assert np.isnan(U[:, n:]).all()
+
+
+@pytest.mark.parametrize("n", [1, 9, 40])
+def test_pack_unpack_tet_f64_bit_exact(gpu, oracle, n):
+    D = inputs.uniform64(3010 + n, n, n, n)
+    want = oracle.pack_tet_f64(D)
+    dP = gpu.empty(tet(n))
+    gpu.d.pack_tet_f64(n, gpu.up(D), dP)
+    assert gpu.down(dP).tobytes() == want.tobytes()
+    dU = gpu.empty(n, n, n)
+    gpu.d.unpack_tet_f64(n, dP, dU)
+    assert gpu.down(dU).tobytes() == oracle.unpack_tet_f64(n, want).tobytes()
+
+
+@pytest.mark.parametrize("n,w,ld", [(1, 2, 1), (300, 5, 310), (700, 16, 700)])
+def test_pack_unpack_band_f64_bit_exact(gpu, oracle, n, w, ld):
+    D = inputs.uniform64(3020 + n, n, ld)
+    want = oracle.pack_band_f64(np.ascontiguousarray(D[:, :n]), w)
+    dP = gpu.empty((2 * w + 1) * n)
+    gpu.d.pack_band_f64(n, w, gpu.up(D), ld, dP)
+    assert gpu.down(dP).tobytes() == want.tobytes()
+    dU = gpu.empty(n, ld)
+    gpu.d.unpack_band_f64(n, w, dP, dU, ld)
+    assert gpu.down(dU)[:, :n].tobytes() == oracle.unpack_band_f64(n, w, want).tobytes()
+
+
+TRMV_SIZES = [1, 2, 3, 7, 8, 9, 31, 63, 64, 65, 127, 129, 255, 256, 257, 511, 512, 513, 520, 1000, 1030, 2049, 4100,
+              8192]
+
+
+@pytest.mark.parametrize("n", TRMV_SIZES)
+def test_trmv_f64_parity(gpu, oracle, n):
+    Up, x = inputs.uniform64(3100 + n, tri(n)), inputs.uniform64(3101 + n, n)
+    want, scale = oracle.trmv_f64(n, Up, x)
+    y = gpu.empty(n)
+    gpu.d.trmv_f64(n, gpu.up(Up), gpu.up(x), y)
+    assert_within(gpu.down(y), want, scale, "trmv_f64 n=%d" % n)
+
+
+@pytest.mark.parametrize("n", [1, 2, 5, 8, 17, 33, 64, 65, 100, 130, 200, 257])
+def test_tet_ttv_f64_parity(gpu, oracle, n):
+    Ap, v = inputs.uniform64(3200 + n, tet(n)), inputs.uniform64(3201 + n, n)
+    want, scale = oracle.tet_ttv_f64(n, Ap, v)
+    M = gpu.empty(tri(n))
+    gpu.d.tet_ttv_f64(n, gpu.up(Ap), gpu.up(v), M)
+    assert_within(gpu.down(M), want, scale, "ttv_f64 n=%d" % n)
+
+
+@pytest.mark.parametrize("n,w", [(1, 0), (1, 3), (255, 16), (5000, 16), (3000, 5), (100, 40), (12, 30)])
+def test_band_spmv_f64_parity(gpu, oracle, n, w):
+    D, x = inputs.uniform64(3300 + n, 2 * w + 1, n), inputs.uniform64(3301 + n, n)
+    want, scale = oracle.band_spmv_f64(n, w, D.ravel(), x)
+    i = np.arange(n)
+    for d in range(-w, w + 1):  # poison every padding slot
+        D[d + w, (i + d < 0) | (i + d >= n)] = np.nan
+    y = gpu.empty(n)
+    gpu.d.band_spmv_f64(n, w, gpu.up(D.ravel()), gpu.up(x), y)
+    assert_within(gpu.down(y), want, scale, "band_f64 n=%d w=%d" % (n, w))
+
+
+def test_f64_exact_on_integers_and_ignores_nonfinite_neighbours(gpu, oracle):
+    """Integer inputs: bit-exact whatever the summation order.  And a row's result must not depend on
+    what the neighbouring rows hold: the lanes that read past a row's end meet a zero of the pad."""
+    n = 300
+    Up = inputs.small_int(3400, -3, 3, tri(n)).astype(np.float64)
+    x = inputs.small_int(3401, -3, 3, n).astype(np.float64)
+    want, _ = oracle.trmv_f64(n, Up, x)
+    y = gpu.empty(n)
+    gpu.d.trmv_f64(n, gpu.up(Up), gpu.up(x), y)
+    assert gpu.down(y).tobytes() == want.tobytes()
+    # row 100 holds Inf everywhere: only y(100) may be non-finite
+    r0 = 100 * n - 100 * 99 // 2
+    Up2 = Up.copy()
+    Up2[r0: r0 + (n - 100)] = np.inf
+    gpu.d.trmv_f64(n, gpu.up(Up2), gpu.up(x), y)
+    got = gpu.down(y)
+    assert np.array_equal(np.delete(got, 100), np.delete(want, 100))
+    m = 60
+    Ap = inputs.small_int(3402, -3, 3, tet(m)).astype(np.float64)
+    v = inputs.small_int(3403, -3, 3, m).astype(np.float64)
+    wantM, _ = oracle.tet_ttv_f64(m, Ap, v)
+    M = gpu.empty(tri(m))
+    gpu.d.tet_ttv_f64(m, gpu.up(Ap), gpu.up(v), M)
+    assert gpu.down(M).tobytes() == wantM.tobytes()
+
+
+def test_f64_keeps_what_fp32_would_lose(gpu):
+    n = 3
+    Up = np.array([1.0, 2.0 ** -40, 0.0, 0.0, 0.0, 0.0])
+    x = np.array([1.0, 1.0, 0.0])
+    y = gpu.empty(n)
+    gpu.d.trmv_f64(n, gpu.up(Up), gpu.up(x), y)
+    assert gpu.down(y)[0] == 1.0 + 2.0 ** -40

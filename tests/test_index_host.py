@@ -187,6 +187,19 @@ def test_new_domain_entry_points_reject_bad_arguments():
         assert fn(10, 4, _p(A), 4, None, None) == dastac.ENULL
         assert fn(10, 4, _p(A), 4, _p(A + 32), None) == dastac.EALIAS
         assert fn(10, 0, None, 0, None, None) == dastac.OK
+    for fn in (L.dastac_trmv_f64, L.dastac_tet_ttv_f64):
+        assert fn(-1, _p(A), _p(B), _p(C), None) == dastac.EINVAL
+        assert fn(8193, _p(A), _p(B), _p(C), None) == dastac.EOVERFLOW
+        assert fn(4, None, _p(B), _p(C), None) == dastac.ENULL
+        assert fn(4, _p(A), _p(B), _p(B + 16), None) == dastac.EALIAS
+        assert fn(0, None, None, None, None) == dastac.OK
+    assert L.dastac_band_spmv_f64(4, 65, _p(A), _p(B), _p(C), None) == dastac.EINVAL
+    assert L.dastac_band_spmv_f64(4, 1, _p(A), _p(B), _p(B + 24), None) == dastac.EALIAS
+    assert L.dastac_pack_triu_f64(8, _p(A), 7, _p(B), None) == dastac.EINVAL
+    assert L.dastac_unpack_tet_f64(4, _p(A), None, None) == dastac.ENULL
+    assert L.dastac_pack_band_f64(4, -1, _p(A), 4, _p(B), None) == dastac.EINVAL
+    # 8-byte elements: two 6-element double vectors 40 bytes apart overlap (two float vectors would not)
+    assert L.dastac_trmv_f64(6, _p(A), _p(B), _p(B + 40), None) == dastac.EALIAS
     assert L.dastac_sband_spmv_f32(-1, 1, 1, _p(A), _p(B), _p(C), None) == dastac.EINVAL
     assert L.dastac_sband_spmv_f32(4, 1, 0, _p(A), _p(B), _p(C), None) == dastac.EINVAL
     assert L.dastac_sband_spmv_f32(4, 65, 1, _p(A), _p(B), _p(C), None) == dastac.EINVAL
