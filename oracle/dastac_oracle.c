@@ -816,3 +816,34 @@ void oracle_tet_ttv_f64(int64_t n, const double *Ap, const double *v, double *Mp
     }
   }
 }
+
+/* C(i,c) := U(i,k) * B(k,c),  i<=k, on double operands (long-double accumulation). */
+void oracle_trmm_f64(int64_t n, int64_t m, const double *Up, const double *B, int64_t ldb, double *C,
+                     int64_t ldc, double *scale, int64_t r_lo, int64_t r_hi) {
+  long double *acc = (long double *)malloc(sizeof(long double) * (size_t)(m > 0 ? m : 1));
+  long double *mag = (long double *)malloc(sizeof(long double) * (size_t)(m > 0 ? m : 1));
+  int64_t p = 0;
+  for (int64_t i = 0; i < n; ++i) {
+    int on = (i >= r_lo && i < r_hi);
+    if (on)
+      for (int64_t c = 0; c < m; ++c) acc[c] = mag[c] = 0.0L;
+    for (int64_t k = i; k < n; ++k) {
+      if (on) {
+        long double u = (long double)Up[p];
+        for (int64_t c = 0; c < m; ++c) {
+          long double t = u * (long double)B[k * ldb + c];
+          acc[c] += t;
+          mag[c] += fabsl(t);
+        }
+      }
+      ++p;
+    }
+    if (on)
+      for (int64_t c = 0; c < m; ++c) {
+        C[i * ldc + c] = (double)acc[c];
+        if (scale) scale[i * m + c] = (double)mag[c];
+      }
+  }
+  free(acc);
+  free(mag);
+}

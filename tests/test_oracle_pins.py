@@ -662,3 +662,20 @@ def test_f64_oracle_keeps_what_fp32_would_lose(oracle):
     y32, _ = oracle.trmv(n, Uf, xf)
     y64, _ = oracle.trmv_f64(n, Uf.astype(np.float64), xf.astype(np.float64))
     assert np.array_equal(y64.astype(np.float32), y32)
+
+
+@pytest.mark.parametrize("n,m", [(1, 1), (6, 3), (33, 17)])
+def test_trmm_f64_against_numpy_and_blas(oracle, n, m):
+    """The double-precision triangular product against NumPy's float64 product with the masked matrix
+    and BLAS's own triangular product (dtrmm reads only the upper triangle), column 0 against TRMV."""
+    from scipy.linalg.blas import dtrmm
+    Up = inputs.uniform64(2100 + n, n * (n + 1) // 2)
+    B = inputs.uniform64(2101 + n, n, m)
+    U = np.zeros((n, n))
+    U[np.triu_indices(n)] = Up
+    C, sc = oracle.trmm_f64(n, m, Up, B)
+    assert _close64(C, U @ B, sc, rel=4e-16 * n)
+    G = U + np.tril(np.full((n, n), 555.0), k=-1)  # garbage below the diagonal must not be read
+    assert _close64(C, dtrmm(1.0, G, B, side=0, lower=0), sc, rel=4e-16 * n)
+    y, _ = oracle.trmv_f64(n, Up, np.ascontiguousarray(B[:, 0]))
+    assert np.array_equal(C[:, 0], y)
