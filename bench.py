@@ -26,6 +26,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E
 MFMA_F32_PEAK_TFLOPS = 157.3  # dense fp32 matrix peak
+MFMA_F64_PEAK_TFLOPS = 78.6   # dense fp64 matrix peak
 
 
 KERNEL_SOURCE = {"trmv": "segsum.hip", "ttv": "segsum.hip", "band": "band.hip", "trmm": "trmm.hip",
@@ -317,6 +318,16 @@ def main() -> int:
         result["beside"]["ttv_f64"] = entry("tet TTV n=%d, fp64 (operand stays in the memory-side cache between launches)"
                                             % nf, fms, wl.accounting("ttv_f64", n=nf), "hbm")
         del gA, fw
+        # TRMM in double precision on the fp64 matrix cores, at the benchmark configuration's shape
+        tf = wl.trmm_f64_inputs(n2, m2)
+        gU, gBd, gCd = up64(tf["Up"]), up64(tf["B"]), out64(n2, m2)
+        del tf
+        fms = beside(lambda: d.trmm_f64(n2, m2, gU, gBd, m2, gCd, m2))
+        ta = wl.accounting("trmm_f64", n=n2, m=m2)
+        result["beside"]["trmm_f64"] = {"workload": "TRMM n=%d m=%d, fp64" % (n2, m2), "ms": fms,
+                                        "gflops": ta["flops"] / fms / 1e6, "gbps": ta["bytes"] / fms / 1e6,
+                                        "bound": "mfma", "frac": ta["flops"] / fms / 1e9 / MFMA_F64_PEAK_TFLOPS}
+        del gU, gBd, gCd
         bw = wl.sband_inputs()
         nb, wb, sb = bw["n"], bw["w"], bw["s"]
         gD, gx, gy = up(bw["D"]), up(bw["x"]), out(nb)

@@ -222,7 +222,8 @@ int dastac_pr_a3_f32(int64_t N, int64_t d, const float *B, int64_t ldb, float *A
  * The same layouts, index polynomials, argument rules and error codes as the _f32 entry points of the
  * same name, on double operands (8-byte aligned).  Each output element is within 1e-12 * sum|products|
  * of the exactly rounded result.  trmv_f64 and tet_ttv_f64 need n <= 8192 (the vector is kept in LDS),
- * beyond that DASTAC_EOVERFLOW.  The matrix-core contractions have no double-precision version. */
+ * beyond that DASTAC_EOVERFLOW.  Of the matrix-core contractions only TRMM has a double-precision version
+ * (trmm_f64, on the fp64 matrix cores; shapes and limits as trmm_f32). */
 int dastac_pack_triu_f64(int64_t n, const double *dense, int64_t ld, double *packed, void *stream);
 int dastac_unpack_triu_f64(int64_t n, const double *packed, double *dense, int64_t ld, void *stream);
 int dastac_pack_tet_f64(int64_t n, const double *dense, double *packed, void *stream);
@@ -232,6 +233,8 @@ int dastac_unpack_band_f64(int64_t n, int64_t w, const double *diag_major, doubl
 int dastac_trmv_f64(int64_t n, const double *Up, const double *x, double *y, void *stream);
 int dastac_band_spmv_f64(int64_t n, int64_t w, const double *D, const double *x, double *y, void *stream);
 int dastac_tet_ttv_f64(int64_t n, const double *Ap, const double *v, double *Mp, void *stream);
+int dastac_trmm_f64(int64_t n, int64_t m, const double *Up, const double *B, int64_t ldb, double *C, int64_t ldc,
+                    void *stream);
 
 #ifdef __cplusplus
 }

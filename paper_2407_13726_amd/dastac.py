@@ -68,6 +68,7 @@ SIGNATURES = {
     "dastac_trmv_f64": (ctypes.c_int, [_i64, _vp, _vp, _vp, _vp]),
     "dastac_band_spmv_f64": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp, _vp]),
     "dastac_tet_ttv_f64": (ctypes.c_int, [_i64, _vp, _vp, _vp, _vp]),
+    "dastac_trmm_f64": (ctypes.c_int, [_i64, _i64, _vp, _vp, _i64, _vp, _i64, _vp]),
     "dastac_subtri_offset": (_i64, [_i64, _i64, _i64, _i64]),
     "dastac_pack_sband_f32": (ctypes.c_int, [_i64, _i64, _i64, _vp, _i64, _vp, _vp]),
     "dastac_unpack_sband_f32": (ctypes.c_int, [_i64, _i64, _i64, _vp, _vp, _i64, _vp]),
@@ -355,3 +356,7 @@ def band_spmv_f64(n, w, D, x, y, stream=None):
 
 def tet_ttv_f64(n, Ap, v, Mp, stream=None):
     _check(lib().dastac_tet_ttv_f64(n, _ptr64(Ap), _ptr64(v), _ptr64(Mp), _stream(stream)), "tet_ttv_f64")
+
+
+def trmm_f64(n, m, Up, B, ldb, C, ldc, stream=None):
+    _check(lib().dastac_trmm_f64(n, m, _ptr64(Up), _ptr64(B), ldb, _ptr64(C), ldc, _stream(stream)), "trmm_f64")

@@ -94,6 +94,11 @@ def f64_inputs():
             "ttv": {"n": n4, "Ap": inputs.uniform64(_seed(13, 4), _tet(n4)), "v": inputs.uniform64(_seed(13, 5), n4)}}
 
 
+def trmm_f64_inputs(n: int = 16384, m: int = 256):
+    """The TRMM configuration's shape with double operands; stream seeds of "config 14"."""
+    return {"n": n, "m": m, "Up": inputs.uniform64(_seed(14, 0), _tri(n)), "B": inputs.uniform64(_seed(14, 1), n, m)}
+
+
 def accounting(name: str, **kw) -> dict:
     """Useful FLOPs and algorithmic bytes of one launch."""
     if name.endswith("_f64"):  # same counts, eight bytes per element

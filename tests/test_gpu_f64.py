@@ -158,3 +158,37 @@ def test_f64_keeps_what_fp32_would_lose(gpu):
     y = gpu.empty(n)
     gpu.d.trmv_f64(n, gpu.up(Up), gpu.up(x), y)
     assert gpu.down(y)[0] == 1.0 + 2.0 ** -40
+
+
+@pytest.mark.parametrize("n,m", [(1, 1), (2, 3), (15, 5), (16, 16), (31, 7), (64, 64), (65, 33), (127, 128), (130, 129),
+                                 (200, 256), (300, 40), (515, 70)])
+def test_trmm_f64_parity(gpu, oracle, n, m):
+    Up, B = inputs.uniform64(3500 + n, tri(n)), inputs.uniform64(3501 + n, n, m)
+    want, scale = oracle.trmm_f64(n, m, Up, B)
+    C = gpu.empty(n, m)
+    gpu.d.trmm_f64(n, m, gpu.up(Up), gpu.up(B), m, C, m)
+    assert_within(gpu.down(C), want, scale, "trmm_f64 n=%d m=%d" % (n, m))
+
+
+def test_trmm_f64_leading_dimensions_and_integer_exactness(gpu, oracle):
+    n, m, ldb, ldc = 150, 37, 45, 41
+    Up = inputs.small_int(3510, -3, 3, tri(n)).astype(np.float64)
+    B = inputs.small_int(3511, -3, 3, n, ldb).astype(np.float64)
+    want, _ = oracle.trmm_f64(n, m, Up, np.ascontiguousarray(B[:, :m]))
+    C = gpu.empty(n, ldc)
+    gpu.d.trmm_f64(n, m, gpu.up(Up), gpu.up(B), ldb, C, ldc)
+    got = gpu.down(C)
+    assert got[:, :m].tobytes() == want.tobytes()
+    assert np.isnan(got[:, m:]).all()
+
+
+def test_trmm_f64_large_sampled_rows(gpu, oracle):
+    n, m = 4096, 256
+    Up, B = inputs.uniform64(3520, tri(n)), inputs.uniform64(3521, n, m)
+    C = gpu.empty(n, m)
+    gpu.d.trmm_f64(n, m, gpu.up(Up), gpu.up(B), m, C, m)
+    got = gpu.down(C)
+    assert np.isfinite(got).all()
+    for i in (0, 1, 63, 64, 2047, 2048, n - 65, n - 64, n - 17, n - 16, n - 1):
+        want, scale = oracle.trmm_f64(n, m, Up, B, rows=(i, i + 1))
+        assert_within(got[i], want[i], scale[i], "trmm_f64 row %d" % i)
