@@ -10,15 +10,15 @@
 // restricted to j,k >= i, whose upper triangle of order d-i is stored contiguously at
 // tet_slice_start(d,i); A2 is the same with w = 1 and a single slice.  One kernel serves both.
 //
-// A workgroup (8 wavefronts) owns a 64 (j) x 128 (k) tile of one slice and a range of samples x,
-// which is the reduction index: per step of 32 samples, the 32x64 tile of B columns j (multiplied
-// by w on the way in) and the 32x128 tile of B columns k are staged in LDS, double-buffered
-// against the global loads of the next step, and each wavefront runs v_mfma_f32_32x32x2_f32 on a
-// 32x32 sub-tile.  Tiles that lie wholly below the diagonal are never launched; tiles on the diagonal
-// stage their full rectangle, wavefronts whose sub-tile lies below it skip their matrix instructions,
-// and only j<=k is stored.  When the tile
-// count alone cannot fill the chip the sample range is split over several workgroups, which then
-// add into a pre-zeroed output with floating-point atomics.
+// A workgroup owns a 64 (j) x 128 (k) tile of one slice (eight wavefronts; for small d a 64 x 64 tile and
+// four wavefronts) and a range of samples x, which is the reduction index: per step of 32 samples, the
+// 32x64 tile of B columns j (multiplied by w on the way in) and the tile of B columns k are staged in
+// LDS, double-buffered against the global loads of the next step, and each wavefront runs
+// v_mfma_f32_32x32x2_f32 on a 32x32 sub-tile.  Tiles that lie wholly below the diagonal are never
+// launched; tiles on the diagonal stage their full rectangle, wavefronts whose sub-tile lies below it
+// skip their matrix instructions, and only j<=k is stored.  When the tile count alone cannot fill the
+// chip the sample range is split over several workgroups, which then add into a pre-zeroed output with
+// floating-point atomics.
 #include "common.h"
 
 using namespace dastac;
@@ -26,18 +26,21 @@ using namespace dastac;
 namespace {
 
 constexpr int kBJ = 64;    // j extent of a workgroup tile
-constexpr int kBK = 128;   // k extent of a workgroup tile
+// k extent of a workgroup tile: BK = 128 (eight wavefronts) or BK = 64 (four), a template parameter
 constexpr int kXT = 32;    // samples per step
 constexpr int kJP = kBJ + 4;  // LDS pitch of the j tile [x][j]
-constexpr int kBlock = 512;
 constexpr int64_t kMaxD2 = 1 << 16;  // A2: tile grid and tri(d) stay small
 constexpr int64_t kMaxD3 = 1 << 13;  // A3: the tile count stays inside gridDim.x
 constexpr int64_t kMaxN = (int64_t)1 << 31;
+// Up to these d the 64 x 64 tile is used: it wastes less on the diagonal and leaves more workgroups per CU,
+// which outweighs its lower operand reuse while diagonal tiles are a large share of all tiles (measured, N=100000
+// resp. 10000: A2 d=512 73 against 49 TFLOP/s, d=1024 91 against 103; A3 d=256 46 against 36, d=1024 78 against 72).
+constexpr int64_t kNarrowMaxD2 = 768, kNarrowMaxD3 = 2048;
 
 typedef float f16v __attribute__((ext_vector_type(16)));
 
 struct Stage {
-  f4a a;     // j tile: sample row tk, four columns
+  f4a a[2];  // j tile: one or two sample rows, four columns each
   f4a b[2];  // k tile: sample rows bk and bk+16, four columns each
 };
 
@@ -47,53 +50,56 @@ struct Stage {
 // row block after row block, so that consecutive workgroup ids (which the hardware deals out to the XCDs in
 // turn) all carry work: numbering the whole J x K rectangle and letting the empty tiles exit would leave
 // the XCDs with very different loads, because the id modulo 8 would select the column block.
-DASTAC_HD int64_t tiles_of(int64_t m) {
+// (With BK = 64 the condition is K >= J: row block J has m - J tiles, a slice m(m+1)/2.)
+DASTAC_HD int64_t tiles_of(int64_t m, int BK) {
+  if (BK == 64) return m * (m + 1) / 2;
   const int64_t p = m / 2;
   return (m & 1) ? p * p + 3 * p + 1 : p * (p + 1);
 }
 
-DASTAC_HD int64_t total_tiles(int64_t d, bool cube) {
+DASTAC_HD int64_t total_tiles(int64_t d, bool cube, int BK) {
   const int64_t m0 = ceil_div(d, kBJ);
-  if (!cube) return tiles_of(m0);
-  int64_t total = (d - kBJ * (m0 - 1)) * tiles_of(m0);  // slices whose order needs m0 row blocks
-  for (int64_t m = m0 - 1; m >= 1; --m) total += kBJ * tiles_of(m);
+  if (!cube) return tiles_of(m0, BK);
+  int64_t total = (d - kBJ * (m0 - 1)) * tiles_of(m0, BK);  // slices whose order needs m0 row blocks
+  for (int64_t m = m0 - 1; m >= 1; --m) total += kBJ * tiles_of(m, BK);
   return total;
 }
 
 // Dense tile number -> slice i and tile (J,K).
-__device__ inline void decode_tile(int64_t d, bool cube, int64_t t, int64_t &i, int &J, int &K) {
+__device__ inline void decode_tile(int64_t d, bool cube, int BK, int64_t t, int64_t &i, int &J, int &K) {
   int64_t m = ceil_div(d, kBJ);
   i = 0;
   if (cube) {
     int64_t first = 0, count = d - kBJ * (m - 1);  // slices first .. first+count-1 need m row blocks
-    while (t >= count * tiles_of(m)) {
-      t -= count * tiles_of(m);
+    while (t >= count * tiles_of(m, BK)) {
+      t -= count * tiles_of(m, BK);
       first += count;
       count = kBJ;
       --m;
     }
-    i = first + t / tiles_of(m);
-    t = t % tiles_of(m);
+    i = first + t / tiles_of(m, BK);
+    t = t % tiles_of(m, BK);
   }
-  const int64_t nK = (m + 1) / 2;
+  const int64_t nK = BK == 64 ? m : (m + 1) / 2;  // column blocks of the slice
   int64_t Jr = 0;
-  while (t >= nK - Jr / 2) {
-    t -= nK - Jr / 2;
+  while (t >= nK - Jr * kBJ / BK) {  // row block Jr has column blocks Jr*64/BK .. nK-1
+    t -= nK - Jr * kBJ / BK;
     ++Jr;
   }
   J = (int)Jr;
-  K = (int)(Jr / 2 + t);
+  K = (int)(Jr * kBJ / BK + t);
 }
 
-template <bool CUBE, bool ATOMIC>
-__global__ __launch_bounds__(kBlock) void pr_mfma_kernel(int64_t N, int64_t d, const float *__restrict__ B,
+template <bool CUBE, bool ATOMIC, int BK>
+__global__ __launch_bounds__(4 * BK) void pr_mfma_kernel(int64_t N, int64_t d, const float *__restrict__ B,
                                                          int64_t ldb, float *__restrict__ out, int64_t chunk) {
   __shared__ __attribute__((aligned(16))) float As[2][kXT * kJP];
-  __shared__ __attribute__((aligned(16))) float Bs[2][kXT * kBK];
+  __shared__ __attribute__((aligned(16))) float Bs[2][kXT * BK];
+  constexpr int kThreads = 4 * BK, kWC = BK / 32;  // wavefronts: 2 rows of kWC
 
   int64_t i;  // slice: every column index of this workgroup is >= i
   int J, K;
-  decode_tile(d, CUBE, uniform64((int64_t)blockIdx.x), i, J, K);
+  decode_tile(d, CUBE, BK, uniform64((int64_t)blockIdx.x), i, J, K);
   const int64_t q = d - i;  // order of the slice's triangle
   const int64_t xbeg = (int64_t)blockIdx.y * chunk;
   const int64_t xend = xbeg + chunk < N ? xbeg + chunk : N;
@@ -101,17 +107,19 @@ __global__ __launch_bounds__(kBlock) void pr_mfma_kernel(int64_t N, int64_t d, c
   const int nk = (int)ceil_div(xend - xbeg, kXT);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wr = wave >> 2, wc = wave & 3;  // 2x4 wavefronts: 32 (j) x 32 (k) each
+  const int wr = wave / kWC, wc = wave % kWC;  // 2 x kWC wavefronts: 32 (j) x 32 (k) each
   const int l32 = lane & 31, h = lane >> 5;
   // A wavefront whose 32x32 sub-tile lies wholly below the diagonal (largest k < smallest j) still helps
   // to stage the tiles but issues no matrix instructions, which leaves the SIMD's matrix pipe to the
   // wavefronts of the other workgroups resident on it.
-  const bool live = uniform32(K * kBK + wc * 32 + 31 >= J * kBJ + wr * 32) != 0;
+  const bool live = uniform32(K * BK + wc * 32 + 31 >= J * kBJ + wr * 32) != 0;
 
-  const int tk = tid >> 4, ti = (tid & 15) * 4;   // j tile: sample row tk, column offset ti
-  const int bk = tid >> 5, bc = (tid & 31) * 4;   // k tile: sample row bk (+16), column offset bc
-  const int64_t j0 = i + (int64_t)J * kBJ, k0 = i + (int64_t)K * kBK;  // absolute first columns
-  const bool j_full = j0 + kBJ <= d, k_full = k0 + kBK <= d;
+  // j tile: sample rows tk + kJRows*r (r < kJRep), column offset ti; k tile: sample rows bk and bk+16, column offset bc
+  constexpr int kJRows = kThreads / 16, kJRep = kXT / kJRows;
+  const int tk = tid >> 4, ti = (tid & 15) * 4;
+  const int bk = tid / (BK / 4), bc = (tid % (BK / 4)) * 4;
+  const int64_t j0 = i + (int64_t)J * kBJ, k0 = i + (int64_t)K * BK;  // absolute first columns
+  const bool j_full = j0 + kBJ <= d, k_full = k0 + BK <= d;
 
   // Columns c..c+3 of one row of B, zero from column d on, with one vector load whose address is pulled
   // back inside the row (needs d >= 4): a lane that straddles the end shifts what it fetched.
@@ -131,20 +139,23 @@ __global__ __launch_bounds__(kBlock) void pr_mfma_kernel(int64_t N, int64_t d, c
   auto load_stage = [&](int kt, Stage &s) {
     const int64_t x0 = xbeg + (int64_t)kt * kXT;
     const bool x_full = x0 + kXT <= xend;
-    const int64_t xa = x0 + tk;
-    if (x_full && j_full) {
-      s.a = *reinterpret_cast<const f4u *>(B + xa * ldb + j0 + ti);
-    } else if (x_full && wide) {
-      s.a = load4_clamped(B + xa * ldb, j0 + ti);
-    } else {
-      float v[4];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) v[e] = (xa < xend && j0 + ti + e < d) ? B[xa * ldb + j0 + ti + e] : 0.0f;
-      s.a = f4a{v[0], v[1], v[2], v[3]};
-    }
-    if (CUBE) {
-      const float w = xa < xend ? B[xa * ldb + i] : 0.0f;
-      s.a *= w;
+    for (int r = 0; r < kJRep; ++r) {
+      const int64_t xa = x0 + tk + kJRows * r;
+      if (x_full && j_full) {
+        s.a[r] = *reinterpret_cast<const f4u *>(B + xa * ldb + j0 + ti);
+      } else if (x_full && wide) {
+        s.a[r] = load4_clamped(B + xa * ldb, j0 + ti);
+      } else {
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = (xa < xend && j0 + ti + e < d) ? B[xa * ldb + j0 + ti + e] : 0.0f;
+        s.a[r] = f4a{v[0], v[1], v[2], v[3]};
+      }
+      if (CUBE) {
+        const float w = xa < xend ? B[xa * ldb + i] : 0.0f;
+        s.a[r] *= w;
+      }
     }
     if (x_full && k_full) {
 #pragma unroll
@@ -164,9 +175,10 @@ __global__ __launch_bounds__(kBlock) void pr_mfma_kernel(int64_t N, int64_t d, c
     }
   };
   auto store_stage = [&](int buf, const Stage &s) {
-    *reinterpret_cast<f4a *>(&As[buf][tk * kJP + ti]) = s.a;
 #pragma unroll
-    for (int r = 0; r < 2; ++r) *reinterpret_cast<f4a *>(&Bs[buf][(bk + 16 * r) * kBK + bc]) = s.b[r];
+    for (int r = 0; r < kJRep; ++r) *reinterpret_cast<f4a *>(&As[buf][(tk + kJRows * r) * kJP + ti]) = s.a[r];
+#pragma unroll
+    for (int r = 0; r < 2; ++r) *reinterpret_cast<f4a *>(&Bs[buf][(bk + 16 * r) * BK + bc]) = s.b[r];
   };
 
   f16v acc;
@@ -182,11 +194,11 @@ __global__ __launch_bounds__(kBlock) void pr_mfma_kernel(int64_t N, int64_t d, c
   auto read_ops = [&](int buf, int t, Ops &o) {
     if (!live) return;
     const float *as = &As[buf][(4 * h) * kJP + wr * 32 + l32];
-    const float *bs = &Bs[buf][(4 * h) * kBK + wc * 32 + l32];
+    const float *bs = &Bs[buf][(4 * h) * BK + wc * 32 + l32];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       o.a[r] = as[(8 * t + r) * kJP];
-      o.b[r] = bs[(8 * t + r) * kBK];
+      o.b[r] = bs[(8 * t + r) * BK];
     }
   };
   auto mma = [&](const Ops &o) {
@@ -226,7 +238,7 @@ __global__ __launch_bounds__(kBlock) void pr_mfma_kernel(int64_t N, int64_t d, c
   // D layout of the 32x32 tile: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32.
   // Rows are j, columns are k; both relative to the slice's first column i.
   float *slice = out + (CUBE ? tet_slice_start(d, i) : 0);
-  const int64_t kr = (int64_t)K * kBK + wc * 32 + l32;
+  const int64_t kr = (int64_t)K * BK + wc * 32 + l32;
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
     const int64_t jr = (int64_t)J * kBJ + wr * 32 + 8 * (v / 4) + 4 * h + (v % 4);
@@ -245,8 +257,9 @@ __global__ void fill_zero_kernel(float *__restrict__ y, int64_t count) {
     y[t] = 0.0f;
 }
 
-template <bool CUBE>
+template <bool CUBE, int BK>
 int run(int64_t N, int64_t d, const float *B, int64_t ldb, float *out, void *stream) {
+  constexpr int kBlock = 4 * BK;
   if (N < 0 || d < 0 || ldb < d) return DASTAC_EINVAL;
   if (d > (CUBE ? kMaxD3 : kMaxD2) || N > kMaxN) return DASTAC_EOVERFLOW;
   if (d == 0) return DASTAC_OK;
@@ -255,7 +268,7 @@ int run(int64_t N, int64_t d, const float *B, int64_t ldb, float *out, void *str
   if (overlaps(out, count * 4, B, N * ldb * 4)) return DASTAC_EALIAS;
   hipStream_t st = (hipStream_t)stream;
 
-  const int64_t tiles = total_tiles(d, CUBE);
+  const int64_t tiles = total_tiles(d, CUBE, BK);
   if (tiles > 0x7fffffff) return DASTAC_EOVERFLOW;
   // Split the samples when the tiles alone cannot fill the chip.  All workgroups cost the same, so the
   // launch runs in rounds of `slots` resident workgroups: take the smallest split that fills its last
@@ -265,7 +278,7 @@ int run(int64_t N, int64_t d, const float *B, int64_t ldb, float *out, void *str
     int dev = 0, per_cu = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess ||
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, pr_mfma_kernel<CUBE, true>, kBlock, 0) != hipSuccess)
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, pr_mfma_kernel<CUBE, true, BK>, kBlock, 0) != hipSuccess)
       return DASTAC_EHIP;
     const int64_t slots = (int64_t)(per_cu > 0 ? per_cu : 1) * (cus > 0 ? cus : 1);
     const int64_t max_split = N / (8 * kXT) > 1 ? N / (8 * kXT) : 1;
@@ -293,9 +306,9 @@ int run(int64_t N, int64_t d, const float *B, int64_t ldb, float *out, void *str
   }
   const dim3 grid((unsigned)tiles, (unsigned)split);
   if (atomic)
-    pr_mfma_kernel<CUBE, true><<<grid, kBlock, 0, st>>>(N, d, B, ldb, out, chunk);
+    pr_mfma_kernel<CUBE, true, BK><<<grid, kBlock, 0, st>>>(N, d, B, ldb, out, chunk);
   else
-    pr_mfma_kernel<CUBE, false><<<grid, kBlock, 0, st>>>(N, d, B, ldb, out, chunk);
+    pr_mfma_kernel<CUBE, false, BK><<<grid, kBlock, 0, st>>>(N, d, B, ldb, out, chunk);
   return launch_status();
 }
 
@@ -304,11 +317,11 @@ int run(int64_t N, int64_t d, const float *B, int64_t ldb, float *out, void *str
 extern "C" {
 
 int dastac_pr_a2_f32(int64_t N, int64_t d, const float *B, int64_t ldb, float *A2p, void *stream) {
-  return run<false>(N, d, B, ldb, A2p, stream);
+  return d <= kNarrowMaxD2 ? run<false, 64>(N, d, B, ldb, A2p, stream) : run<false, 128>(N, d, B, ldb, A2p, stream);
 }
 
 int dastac_pr_a3_f32(int64_t N, int64_t d, const float *B, int64_t ldb, float *A3p, void *stream) {
-  return run<true>(N, d, B, ldb, A3p, stream);
+  return d <= kNarrowMaxD3 ? run<true, 64>(N, d, B, ldb, A3p, stream) : run<true, 128>(N, d, B, ldb, A3p, stream);
 }
 
 }  // extern "C"
