@@ -18,3 +18,26 @@ def oracle():
 
     orc.lib()
     return orc
+
+
+@pytest.fixture(scope="session")
+def gpu():
+    """Device handle for the GPU tests: the binding, and helpers that move NumPy arrays to the MI355X and
+    back.  Output tensors start as NaN so that an element a kernel fails to write is caught."""
+    import numpy as np
+    import torch
+
+    from paper_2407_13726_amd import dastac
+
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    dastac.lib()
+
+    class G:
+        pass
+
+    g = G()
+    g.torch, g.d, g.dev = torch, dastac, torch.device("cuda:0")
+    g.up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(g.dev)
+    g.empty = lambda *shape: torch.full(shape, float("nan"), dtype=torch.float32, device=g.dev)
+    g.down = lambda t: (torch.cuda.synchronize(), t.cpu().numpy())[1]
+    return g

@@ -16,23 +16,15 @@ TOL64 = 1e-12
 
 
 @pytest.fixture(scope="module")
-def gpu():
+def gpu(gpu):
+    """The shared device handle with double-precision tensors."""
+    import copy
+
     import torch
 
-    from paper_2407_13726_amd import dastac
-
-    assert torch.cuda.is_available(), "these tests need the MI355X"
-    dastac.lib()
-
-    class G:
-        pass
-
-    g = G()
-    g.d = dastac
-    g.dev = torch.device("cuda:0")
+    g = copy.copy(gpu)
     g.up = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float64)).to(g.dev)
     g.empty = lambda *shape: torch.full(shape, float("nan"), dtype=torch.float64, device=g.dev)
-    g.down = lambda t: (torch.cuda.synchronize(), t.cpu().numpy())[1]
     return g
 
 

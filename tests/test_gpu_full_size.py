@@ -16,26 +16,6 @@ pytestmark = pytest.mark.gpu
 TOL = 1e-4
 
 
-@pytest.fixture(scope="module")
-def gpu():
-    import torch
-
-    from paper_2407_13726_amd import dastac
-
-    assert torch.cuda.is_available(), "these tests need the MI355X"
-    dastac.lib()
-
-    class G:
-        pass
-
-    g = G()
-    g.torch, g.d, g.dev = torch, dastac, torch.device("cuda:0")
-    g.up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(g.dev)
-    g.empty = lambda *shape: torch.full(shape, float("nan"), dtype=torch.float32, device=g.dev)
-    g.down = lambda t: (torch.cuda.synchronize(), t.cpu().numpy())[1]
-    return g
-
-
 def check(got, want, scale, what):
     got, want, scale = (np.asarray(a, dtype=np.float64).ravel() for a in (got, want, scale))
     assert np.isfinite(got).all(), what + ": non-finite output"

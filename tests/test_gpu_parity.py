@@ -17,28 +17,6 @@ pytestmark = pytest.mark.gpu
 TOL = 1e-4
 
 
-@pytest.fixture(scope="module")
-def gpu():
-    import torch
-
-    from paper_2407_13726_amd import dastac
-
-    assert torch.cuda.is_available(), "these tests need the MI355X"
-    dastac.lib()
-
-    class G:
-        pass
-
-    g = G()
-    g.torch = torch
-    g.d = dastac
-    g.dev = torch.device("cuda:0")
-    g.up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(g.dev)
-    g.empty = lambda *shape: torch.full(shape, float("nan"), dtype=torch.float32, device=g.dev)
-    g.down = lambda t: (torch.cuda.synchronize(), t.cpu().numpy())[1]
-    return g
-
-
 def tri(n):
     return n * (n + 1) // 2
 
