@@ -7,7 +7,7 @@
 // result is consumed at once and never leaves the registers.  A is read exactly once.
 //
 // One workgroup (8 wavefronts) per slice, heaviest slices first.  The workgroup walks k in panels of
-// 256; the panel's rows of C are staged in LDS (the reused dense operand).  Inside a panel the
+// 512; the panel's rows of C are staged in LDS (the reused dense operand).  Inside a panel the
 // work items are 32-row blocks of the slice; wavefronts draw them from an LDS counter, full blocks
 // first and the blocks cut by the diagonal (shorter) last, which balances the eight wavefronts.
 //
