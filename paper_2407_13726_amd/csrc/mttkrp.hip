@@ -71,27 +71,31 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
   for (int c = 0; c < npanels; ++c) {
     const int64_t kp0 = i + (int64_t)c * kPanel;
     __syncthreads();  // every wavefront is done with the previous panel
-    for (int t = tid; t < kPanel * 8; t += kBlock) {
-      const int row = t >> 3, c4 = (t & 7) * 4;
-      const int64_t k = kp0 + row;
-      f4a v = {0.0f, 0.0f, 0.0f, 0.0f};
-      if (k < n) {
-        if (R == 32) {
-          v = *reinterpret_cast<const f4u *>(Cm + k * ldc + c4);
-        } else {
-          if (c4 + 0 < R) v.x = Cm[k * ldc + c4 + 0];
-          if (c4 + 1 < R) v.y = Cm[k * ldc + c4 + 1];
-          if (c4 + 2 < R) v.z = Cm[k * ldc + c4 + 2];
-          if (c4 + 3 < R) v.w = Cm[k * ldc + c4 + 3];
-        }
+    // Layout [k/4][r][k%4]: the four k values a lane feeds to four consecutive matrix instructions
+    // are then one 16-byte read.  A thread stages the same column r of four consecutive rows k, so its
+    // LDS write is one 16-byte piece too and the lanes of a wavefront write consecutive pieces (free of
+    // bank conflicts); the global loads, 128 contiguous bytes per row and half-wavefront, are all
+    // requested before the first is used.
+    {
+      constexpr int kIter = kPanel * 8 / kBlock;
+      f4a v[kIter];
+      const int r = tid & 31;
+#pragma unroll
+      for (int it = 0; it < kIter; ++it) {
+        const int kg = (tid >> 5) + it * (kBlock / 32);
+        const int64_t k = kp0 + 4 * (int64_t)kg;
+        const float *src = Cm + k * ldc + r;
+        const bool col_ok = r < R;
+        v[it].x = (col_ok && k + 0 < n) ? src[0] : 0.0f;
+        v[it].y = (col_ok && k + 1 < n) ? src[ldc] : 0.0f;
+        v[it].z = (col_ok && k + 2 < n) ? src[2 * ldc] : 0.0f;
+        v[it].w = (col_ok && k + 3 < n) ? src[3 * ldc] : 0.0f;
       }
-      // Layout [k/4][r][k%4]: the four k values a lane feeds to four consecutive matrix
-      // instructions are then one 16-byte read.
-      float *cd = &Cs[((row >> 2) * 32 + c4) * 4 + (row & 3)];
-      cd[0] = v.x;
-      cd[4] = v.y;
-      cd[8] = v.z;
-      cd[12] = v.w;
+#pragma unroll
+      for (int it = 0; it < kIter; ++it) {
+        const int kg = (tid >> 5) + it * (kBlock / 32);
+        *reinterpret_cast<f4a *>(&Cs[(kg * 32 + r) * 4]) = v[it];
+      }
     }
     if (tid == 0) next_unit = 0;
     __syncthreads();
