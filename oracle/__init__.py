@@ -90,6 +90,7 @@ def lib() -> ctypes.CDLL:
         L.oracle_trmv_f64.argtypes = [_i64, _dp, _dp, _dp, _dp, _i64, _i64]
         L.oracle_band_spmv_f64.argtypes = [_i64, _i64, _dp, _dp, _dp, _dp, _i64, _i64]
         L.oracle_tet_ttv_f64.argtypes = [_i64, _dp, _dp, _dp, _dp, _i64, _i64]
+        L.oracle_symm_f64.argtypes = [_i64, _i64, _dp, _dp, _i64, _dp, _i64, _dp, _i64, _i64]
         L.oracle_trmm_f64.argtypes = [_i64, _i64, _dp, _dp, _i64, _dp, _i64, _dp, _i64, _i64]
         L.oracle_pr_a2_f32.argtypes = [_i64, _i64, _fp, _i64, _fp, _dp, _i64, _i64]
         L.oracle_pr_a3_f32.argtypes = [_i64, _i64, _fp, _i64, _fp, _dp, _i64, _i64]
@@ -533,4 +534,13 @@ def trmm_f64(n, m, Up, B, rows=None):
     C = np.full((n, m), np.nan, dtype=np.float64)
     sc = np.full((n, m), np.nan, dtype=np.float64)
     lib().oracle_trmm_f64(n, m, _d(Up), _d(B), B.shape[1] if B.ndim == 2 else m, _d(C), m, _d(sc), lo, hi)
+    return C, sc
+
+
+def symm_f64(n, m, Up, B, rows=None):
+    Up, B = _f64(Up), _f64(B)
+    lo, hi = _window(n, rows)
+    C = np.full((n, m), np.nan, dtype=np.float64)
+    sc = np.full((n, m), np.nan, dtype=np.float64)
+    lib().oracle_symm_f64(n, m, _d(Up), _d(B), B.shape[1] if B.ndim == 2 else m, _d(C), m, _d(sc), lo, hi)
     return C, sc

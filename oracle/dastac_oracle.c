@@ -847,3 +847,31 @@ void oracle_trmm_f64(int64_t n, int64_t m, const double *Up, const double *B, in
   free(acc);
   free(mag);
 }
+
+/* C(i,c) := S(i,j) * B(j,c), S symmetric with its unique elements packed as an upper triangle, on double
+ * operands (long-double accumulation). */
+void oracle_symm_f64(int64_t n, int64_t m, const double *Up, const double *B, int64_t ldb, double *C,
+                     int64_t ldc, double *scale, int64_t r_lo, int64_t r_hi) {
+  int64_t *start = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n + 1));
+  int64_t p = 0;
+  for (int64_t i = 0; i < n; ++i) {
+    start[i] = p;
+    p += n - i;
+  }
+  for (int64_t i = 0; i < n; ++i) {
+    if (i < r_lo || i >= r_hi) continue;
+    for (int64_t c = 0; c < m; ++c) {
+      long double acc = 0.0L, mag = 0.0L;
+      for (int64_t j = 0; j < n; ++j) {
+        int64_t a = i, b = j;
+        if (a > b) { int64_t t = a; a = b; b = t; } /* the redundancy map */
+        long double t = (long double)Up[start[a] + (b - a)] * (long double)B[j * ldb + c];
+        acc += t;
+        mag += fabsl(t);
+      }
+      C[i * ldc + c] = (double)acc;
+      if (scale) scale[i * m + c] = (double)mag;
+    }
+  }
+  free(start);
+}

@@ -679,3 +679,21 @@ def test_trmm_f64_against_numpy_and_blas(oracle, n, m):
     assert _close64(C, dtrmm(1.0, G, B, side=0, lower=0), sc, rel=4e-16 * n)
     y, _ = oracle.trmv_f64(n, Up, np.ascontiguousarray(B[:, 0]))
     assert np.array_equal(C[:, 0], y)
+
+
+@pytest.mark.parametrize("n,m", [(1, 1), (7, 3), (30, 11)])
+def test_symm_f64_against_numpy_and_blas(oracle, n, m):
+    from scipy.linalg.blas import dsymm
+    Up = inputs.uniform64(2200 + n, n * (n + 1) // 2)
+    B = inputs.uniform64(2201 + n, n, m)
+    U = np.zeros((n, n))
+    U[np.triu_indices(n)] = Up
+    S = U + U.T - np.diag(np.diag(U))
+    C, sc = oracle.symm_f64(n, m, Up, B)
+    assert _close64(C, S @ B, sc, rel=4e-16 * n)
+    assert _close64(C, dsymm(1.0, U + np.tril(np.full((n, n), 9.0), k=-1), B, side=0, lower=0), sc, rel=4e-16 * n)
+    # on fp32-representable inputs the two precisions' oracles agree
+    Uf, Bf = inputs.uniform(2202 + n, n * (n + 1) // 2), inputs.uniform(2203 + n, n, m)
+    C32, _ = oracle.symm(n, m, Uf, Bf)
+    C64, _ = oracle.symm_f64(n, m, Uf.astype(np.float64), Bf.astype(np.float64))
+    assert np.allclose(C64, C32, rtol=1e-6, atol=1e-6)
