@@ -354,6 +354,11 @@ def main() -> int:
         result["beside"]["trmm_f64"] = {"workload": "TRMM n=%d m=%d, fp64" % (n2, m2), "ms": fms,
                                         "gflops": ta["flops"] / fms / 1e6, "gbps": ta["bytes"] / fms / 1e6,
                                         "bound": "mfma", "frac": ta["flops"] / fms / 1e9 / MFMA_F64_PEAK_TFLOPS}
+        fms = beside(lambda: d.symm_f64(n2, m2, gU, gBd, m2, gCd, m2))
+        ta = wl.accounting("symm_f64", n=n2, m=m2)
+        result["beside"]["symm_f64"] = {"workload": "SYMM n=%d m=%d, fp64" % (n2, m2), "ms": fms,
+                                        "gflops": ta["flops"] / fms / 1e6, "gbps": ta["bytes"] / fms / 1e6,
+                                        "bound": "mfma", "frac": ta["flops"] / fms / 1e9 / MFMA_F64_PEAK_TFLOPS}
         del gU, gBd, gCd
         bw = wl.sband_inputs()
         nb, wb, sb = bw["n"], bw["w"], bw["s"]

@@ -69,6 +69,7 @@ SIGNATURES = {
     "dastac_band_spmv_f64": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp, _vp]),
     "dastac_tet_ttv_f64": (ctypes.c_int, [_i64, _vp, _vp, _vp, _vp]),
     "dastac_trmm_f64": (ctypes.c_int, [_i64, _i64, _vp, _vp, _i64, _vp, _i64, _vp]),
+    "dastac_symm_f64": (ctypes.c_int, [_i64, _i64, _vp, _vp, _i64, _vp, _i64, _vp]),
     "dastac_subtri_offset": (_i64, [_i64, _i64, _i64, _i64]),
     "dastac_pack_sband_f32": (ctypes.c_int, [_i64, _i64, _i64, _vp, _i64, _vp, _vp]),
     "dastac_unpack_sband_f32": (ctypes.c_int, [_i64, _i64, _i64, _vp, _vp, _i64, _vp]),
@@ -360,3 +361,7 @@ def tet_ttv_f64(n, Ap, v, Mp, stream=None):
 
 def trmm_f64(n, m, Up, B, ldb, C, ldc, stream=None):
     _check(lib().dastac_trmm_f64(n, m, _ptr64(Up), _ptr64(B), ldb, _ptr64(C), ldc, _stream(stream)), "trmm_f64")
+
+
+def symm_f64(n, m, Up, B, ldb, C, ldc, stream=None):
+    _check(lib().dastac_symm_f64(n, m, _ptr64(Up), _ptr64(B), ldb, _ptr64(C), ldc, _stream(stream)), "symm_f64")

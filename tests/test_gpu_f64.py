@@ -184,3 +184,25 @@ def test_trmm_f64_large_sampled_rows(gpu, oracle):
     for i in (0, 1, 63, 64, 2047, 2048, n - 65, n - 64, n - 17, n - 16, n - 1):
         want, scale = oracle.trmm_f64(n, m, Up, B, rows=(i, i + 1))
         assert_within(got[i], want[i], scale[i], "trmm_f64 row %d" % i)
+
+
+@pytest.mark.parametrize("n,m", [(1, 1), (2, 3), (15, 5), (16, 16), (33, 7), (64, 64), (65, 33), (127, 128), (130, 129),
+                                 (200, 256), (300, 40), (515, 70), (1030, 130)])
+def test_symm_f64_parity(gpu, oracle, n, m):
+    Up, B = inputs.uniform64(3600 + n, tri(n)), inputs.uniform64(3601 + n, n, m)
+    want, scale = oracle.symm_f64(n, m, Up, B)
+    C = gpu.empty(n, m)
+    gpu.d.symm_f64(n, m, gpu.up(Up), gpu.up(B), m, C, m)
+    assert_within(gpu.down(C), want, scale, "symm_f64 n=%d m=%d" % (n, m))
+
+
+def test_symm_f64_leading_dimensions_and_integer_exactness(gpu, oracle):
+    n, m, ldb, ldc = 330, 37, 45, 41
+    Up = inputs.small_int(3610, -3, 3, tri(n)).astype(np.float64)
+    B = inputs.small_int(3611, -3, 3, n, ldb).astype(np.float64)
+    want, _ = oracle.symm_f64(n, m, Up, np.ascontiguousarray(B[:, :m]))
+    C = gpu.empty(n, ldc)
+    gpu.d.symm_f64(n, m, gpu.up(Up), gpu.up(B), ldb, C, ldc)
+    got = gpu.down(C)
+    assert got[:, :m].tobytes() == want.tobytes()
+    assert np.isnan(got[:, m:]).all()
