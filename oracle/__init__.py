@@ -90,6 +90,9 @@ def lib() -> ctypes.CDLL:
         L.oracle_trmv_f64.argtypes = [_i64, _dp, _dp, _dp, _dp, _i64, _i64]
         L.oracle_band_spmv_f64.argtypes = [_i64, _i64, _dp, _dp, _dp, _dp, _i64, _i64]
         L.oracle_tet_ttv_f64.argtypes = [_i64, _dp, _dp, _dp, _dp, _i64, _i64]
+        L.oracle_pack_uhc_f64.argtypes = [_i64, _i64, _i64, _dp, _dp]
+        L.oracle_unpack_uhc_f64.argtypes = [_i64, _i64, _i64, _dp, _dp]
+        L.oracle_ttm_ut_f64.argtypes = [_i64, _i64, _i64, _dp, _dp, _i64, _dp, _dp, _i64, _i64]
         L.oracle_symm_f64.argtypes = [_i64, _i64, _dp, _dp, _i64, _dp, _i64, _dp, _i64, _i64]
         L.oracle_trmm_f64.argtypes = [_i64, _i64, _dp, _dp, _i64, _dp, _i64, _dp, _i64, _i64]
         L.oracle_pr_a2_f32.argtypes = [_i64, _i64, _fp, _i64, _fp, _dp, _i64, _i64]
@@ -544,3 +547,28 @@ def symm_f64(n, m, Up, B, rows=None):
     sc = np.full((n, m), np.nan, dtype=np.float64)
     lib().oracle_symm_f64(n, m, _d(Up), _d(B), B.shape[1] if B.ndim == 2 else m, _d(C), m, _d(sc), lo, hi)
     return C, sc
+
+
+def pack_uhc_f64(dense):
+    dense = _f64(dense)
+    M, N, Q = dense.shape
+    packed = np.empty(sum(N - i for i in range(min(M, N))) * Q, dtype=np.float64)
+    lib().oracle_pack_uhc_f64(M, N, Q, _d(dense), _d(packed))
+    return packed
+
+
+def unpack_uhc_f64(M, N, Q, packed):
+    packed = _f64(packed)
+    dense = np.empty((M, N, Q), dtype=np.float64)
+    lib().oracle_unpack_uhc_f64(M, N, Q, _d(packed), _d(dense))
+    return dense
+
+
+def ttm_ut_f64(n, Q, K, Bp, C, rows=None):
+    Bp, C = _f64(Bp), _f64(C)
+    pairs = n * (n + 1) // 2
+    lo, hi = (0, pairs) if rows is None else (int(rows[0]), int(rows[1]))
+    A = np.full(pairs * K, np.nan, dtype=np.float64)
+    sc = np.full(pairs * K, np.nan, dtype=np.float64)
+    lib().oracle_ttm_ut_f64(n, Q, K, _d(Bp), _d(C), C.shape[1] if C.ndim == 2 else Q, _d(A), _d(sc), lo, hi)
+    return A, sc

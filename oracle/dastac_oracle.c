@@ -875,3 +875,43 @@ void oracle_symm_f64(int64_t n, int64_t m, const double *Up, const double *B, in
   }
   free(start);
 }
+
+/* The running example on double operands: pack/unpack of the upper half cube and
+ * A(i,j,k) := B(i,j,l) * C(k,l), i<=j (long-double accumulation). */
+void oracle_pack_uhc_f64(int64_t M, int64_t N, int64_t Q, const double *dense, double *packed) {
+  int64_t p = 0;
+  for (int64_t i = 0; i < M; ++i)
+    for (int64_t j = i; j < N; ++j)
+      for (int64_t l = 0; l < Q; ++l) packed[p++] = dense[(i * N + j) * Q + l];
+}
+
+void oracle_unpack_uhc_f64(int64_t M, int64_t N, int64_t Q, const double *packed, double *dense) {
+  for (int64_t t = 0; t < M * N * Q; ++t) dense[t] = 0.0;
+  int64_t p = 0;
+  for (int64_t i = 0; i < M; ++i)
+    for (int64_t j = i; j < N; ++j)
+      for (int64_t l = 0; l < Q; ++l) dense[(i * N + j) * Q + l] = packed[p++];
+}
+
+void oracle_ttm_ut_f64(int64_t n, int64_t Q, int64_t K, const double *Bp, const double *C, int64_t ldc,
+                       double *Ap, double *scale, int64_t r_lo, int64_t r_hi) {
+  int64_t pb = 0, pa = 0, pair = 0;
+  for (int64_t i = 0; i < n; ++i)
+    for (int64_t j = i; j < n; ++j) {
+      if (pair >= r_lo && pair < r_hi) {
+        for (int64_t k = 0; k < K; ++k) {
+          long double acc = 0.0L, mag = 0.0L;
+          for (int64_t l = 0; l < Q; ++l) {
+            long double t = (long double)Bp[pb + l] * (long double)C[k * ldc + l];
+            acc += t;
+            mag += fabsl(t);
+          }
+          Ap[pa + k] = (double)acc;
+          if (scale) scale[pa + k] = (double)mag;
+        }
+      }
+      pb += Q;
+      pa += K;
+      ++pair;
+    }
+}

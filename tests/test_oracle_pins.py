@@ -697,3 +697,18 @@ def test_symm_f64_against_numpy_and_blas(oracle, n, m):
     C32, _ = oracle.symm(n, m, Uf, Bf)
     C64, _ = oracle.symm_f64(n, m, Uf.astype(np.float64), Bf.astype(np.float64))
     assert np.allclose(C64, C32, rtol=1e-6, atol=1e-6)
+
+
+@pytest.mark.parametrize("n,Q,K", [(1, 1, 1), (4, 3, 5), (9, 8, 6)])
+def test_ttm_ut_f64_against_einsum(oracle, n, Q, K):
+    """The running example in double: packed rows are NumPy's mask order, the product is einsum on the
+    masked dense tensor, restricted to i<=j."""
+    Bd = inputs.uniform64(2300 + n, n, n, Q)
+    C = inputs.uniform64(2301 + n, K, Q)
+    i, j = np.meshgrid(np.arange(n), np.arange(n), indexing="ij")
+    Bp = oracle.pack_uhc_f64(Bd)
+    assert np.array_equal(Bp, Bd[i <= j].ravel())
+    assert np.array_equal(oracle.unpack_uhc_f64(n, n, Q, Bp), np.where((i <= j)[:, :, None], Bd, 0.0))
+    A, sc = oracle.ttm_ut_f64(n, Q, K, Bp, C)
+    want = np.einsum("ijl,kl->ijk", Bd, C)[i <= j].ravel()
+    assert _close64(A, want, sc, rel=4e-16 * Q)
