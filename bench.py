@@ -74,6 +74,7 @@ def main() -> int:
     import torch
 
     from paper_2407_13726_amd import dastac as d
+    from paper_2407_13726_amd import inputs
     from paper_2407_13726_amd import workloads as wl
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
@@ -360,6 +361,15 @@ def main() -> int:
                                         "gflops": ta["flops"] / fms / 1e6, "gbps": ta["bytes"] / fms / 1e6,
                                         "bound": "mfma", "frac": ta["flops"] / fms / 1e9 / MFMA_F64_PEAK_TFLOPS}
         del gU, gBd, gCd
+        # the running example in double precision
+        gBq = up64(inputs.uniform64(20240713 * 15, nt * (nt + 1) // 2 * Qt))
+        gCq, gAq = up64(inputs.uniform64(20240713 * 15 + 1, Kt, Qt)), out64(nt * (nt + 1) // 2 * Kt)
+        fms = beside(lambda: d.ttm_ut_f64(nt, Qt, Kt, gBq, gCq, Qt, gAq))
+        ta = wl.accounting("ttm_ut_f64", n=nt, Q=Qt, K=Kt)
+        result["beside"]["ttm_ut_f64"] = {"workload": "TTM_UT n=%d Q=%d K=%d, fp64" % (nt, Qt, Kt), "ms": fms,
+                                          "gflops": ta["flops"] / fms / 1e6, "gbps": ta["bytes"] / fms / 1e6,
+                                          "bound": "mfma", "frac": ta["flops"] / fms / 1e9 / MFMA_F64_PEAK_TFLOPS}
+        del gBq, gAq
         bw = wl.sband_inputs()
         nb, wb, sb = bw["n"], bw["w"], bw["s"]
         gD, gx, gy = up(bw["D"]), up(bw["x"]), out(nb)

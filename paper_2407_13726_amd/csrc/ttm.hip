@@ -184,9 +184,9 @@ __global__ __launch_bounds__(kBlock) void ttm_mfma_kernel(int64_t rows, int64_t 
 // One workgroup per 256-element piece of one (i,j) row of the dense n x n x Q tensor.
 constexpr int kCopy = 256;
 
-template <bool PACK>
-__global__ __launch_bounds__(kCopy) void uhc_copy_kernel(int64_t n, int64_t Q, const float *__restrict__ src,
-                                                         float *__restrict__ dst, int64_t pieces,
+template <bool PACK, typename T>
+__global__ __launch_bounds__(kCopy) void uhc_copy_kernel(int64_t n, int64_t Q, const T *__restrict__ src,
+                                                         T *__restrict__ dst, int64_t pieces,
                                                          int64_t nblocks) {
   for (int64_t b = blockIdx.x; b < nblocks; b += gridDim.x) {
     const int64_t ij = b / pieces, l = (b - ij * pieces) * kCopy + threadIdx.x;
@@ -195,13 +195,28 @@ __global__ __launch_bounds__(kCopy) void uhc_copy_kernel(int64_t n, int64_t Q, c
     if (PACK) {
       if (j >= i) dst[tri_offset(n, i, j) * Q + l] = src[ij * Q + l];
     } else {
-      dst[ij * Q + l] = (j >= i) ? src[tri_offset(n, i, j) * Q + l] : 0.0f;
+      dst[ij * Q + l] = (j >= i) ? src[tri_offset(n, i, j) * Q + l] : T(0);
     }
   }
 }
 
 inline bool uhc_ok(int64_t n, int64_t Q) {
   return n >= 0 && Q >= 1 && n <= (1 << 20) && Q <= (1 << 24) && (n == 0 || tri(n) <= ((int64_t)1 << 40) / Q);
+}
+
+// pack (dense -> packed) or unpack (packed -> dense) of the upper half cube, float or double
+template <bool PACK, typename T>
+int uhc_copy(int64_t n, int64_t Q, const T *src, T *dst, void *stream) {
+  if (n < 0 || Q < 1) return DASTAC_EINVAL;
+  if (!uhc_ok(n, Q) || n * n > ((int64_t)1 << 40) / Q) return DASTAC_EOVERFLOW;
+  if (n == 0) return DASTAC_OK;
+  if (!src || !dst) return DASTAC_ENULL;
+  const int64_t sz = (int64_t)sizeof(T), nd = n * n * Q * sz, np = tri(n) * Q * sz;
+  if (overlaps(dst, PACK ? np : nd, src, PACK ? nd : np)) return DASTAC_EALIAS;
+  const int64_t pieces = ceil_div(Q, kCopy), nblocks = n * n * pieces;
+  const unsigned grid = (unsigned)(nblocks < (1 << 20) ? nblocks : (1 << 20));
+  uhc_copy_kernel<PACK, T><<<grid, kCopy, 0, (hipStream_t)stream>>>(n, Q, src, dst, pieces, nblocks);
+  return launch_status();
 }
 
 }  // namespace
@@ -219,27 +234,19 @@ int64_t dastac_uhc_offset(int64_t n, int64_t Q, int64_t i, int64_t j, int64_t l)
 }
 
 int dastac_pack_uhc_f32(int64_t n, int64_t Q, const float *dense, float *packed, void *stream) {
-  if (n < 0 || Q < 1) return DASTAC_EINVAL;
-  if (!uhc_ok(n, Q) || n * n > ((int64_t)1 << 40) / Q) return DASTAC_EOVERFLOW;
-  if (n == 0) return DASTAC_OK;
-  if (!dense || !packed) return DASTAC_ENULL;
-  if (overlaps(packed, tri(n) * Q * 4, dense, n * n * Q * 4)) return DASTAC_EALIAS;
-  const int64_t pieces = ceil_div(Q, kCopy), nblocks = n * n * pieces;
-  const unsigned grid = (unsigned)(nblocks < (1 << 20) ? nblocks : (1 << 20));
-  uhc_copy_kernel<true><<<grid, kCopy, 0, (hipStream_t)stream>>>(n, Q, dense, packed, pieces, nblocks);
-  return launch_status();
+  return uhc_copy<true, float>(n, Q, dense, packed, stream);
 }
 
 int dastac_unpack_uhc_f32(int64_t n, int64_t Q, const float *packed, float *dense, void *stream) {
-  if (n < 0 || Q < 1) return DASTAC_EINVAL;
-  if (!uhc_ok(n, Q) || n * n > ((int64_t)1 << 40) / Q) return DASTAC_EOVERFLOW;
-  if (n == 0) return DASTAC_OK;
-  if (!dense || !packed) return DASTAC_ENULL;
-  if (overlaps(dense, n * n * Q * 4, packed, tri(n) * Q * 4)) return DASTAC_EALIAS;
-  const int64_t pieces = ceil_div(Q, kCopy), nblocks = n * n * pieces;
-  const unsigned grid = (unsigned)(nblocks < (1 << 20) ? nblocks : (1 << 20));
-  uhc_copy_kernel<false><<<grid, kCopy, 0, (hipStream_t)stream>>>(n, Q, packed, dense, pieces, nblocks);
-  return launch_status();
+  return uhc_copy<false, float>(n, Q, packed, dense, stream);
+}
+
+int dastac_pack_uhc_f64(int64_t n, int64_t Q, const double *dense, double *packed, void *stream) {
+  return uhc_copy<true, double>(n, Q, dense, packed, stream);
+}
+
+int dastac_unpack_uhc_f64(int64_t n, int64_t Q, const double *packed, double *dense, void *stream) {
+  return uhc_copy<false, double>(n, Q, packed, dense, stream);
 }
 
 int dastac_ttm_ut_f32(int64_t n, int64_t Q, int64_t K, const float *Bp, const float *C, int64_t ldc, float *Ap,

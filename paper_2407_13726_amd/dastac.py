@@ -70,6 +70,9 @@ SIGNATURES = {
     "dastac_tet_ttv_f64": (ctypes.c_int, [_i64, _vp, _vp, _vp, _vp]),
     "dastac_trmm_f64": (ctypes.c_int, [_i64, _i64, _vp, _vp, _i64, _vp, _i64, _vp]),
     "dastac_symm_f64": (ctypes.c_int, [_i64, _i64, _vp, _vp, _i64, _vp, _i64, _vp]),
+    "dastac_pack_uhc_f64": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp]),
+    "dastac_unpack_uhc_f64": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp]),
+    "dastac_ttm_ut_f64": (ctypes.c_int, [_i64, _i64, _i64, _vp, _vp, _i64, _vp, _vp]),
     "dastac_subtri_offset": (_i64, [_i64, _i64, _i64, _i64]),
     "dastac_pack_sband_f32": (ctypes.c_int, [_i64, _i64, _i64, _vp, _i64, _vp, _vp]),
     "dastac_unpack_sband_f32": (ctypes.c_int, [_i64, _i64, _i64, _vp, _vp, _i64, _vp]),
@@ -365,3 +368,15 @@ def trmm_f64(n, m, Up, B, ldb, C, ldc, stream=None):
 
 def symm_f64(n, m, Up, B, ldb, C, ldc, stream=None):
     _check(lib().dastac_symm_f64(n, m, _ptr64(Up), _ptr64(B), ldb, _ptr64(C), ldc, _stream(stream)), "symm_f64")
+
+
+def pack_uhc_f64(n, Q, dense, packed, stream=None):
+    _check(lib().dastac_pack_uhc_f64(n, Q, _ptr64(dense), _ptr64(packed), _stream(stream)), "pack_uhc_f64")
+
+
+def unpack_uhc_f64(n, Q, packed, dense, stream=None):
+    _check(lib().dastac_unpack_uhc_f64(n, Q, _ptr64(packed), _ptr64(dense), _stream(stream)), "unpack_uhc_f64")
+
+
+def ttm_ut_f64(n, Q, K, Bp, C, ldc, Ap, stream=None):
+    _check(lib().dastac_ttm_ut_f64(n, Q, K, _ptr64(Bp), _ptr64(C), ldc, _ptr64(Ap), _stream(stream)), "ttm_ut_f64")

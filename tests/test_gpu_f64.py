@@ -206,3 +206,41 @@ def test_symm_f64_leading_dimensions_and_integer_exactness(gpu, oracle):
     got = gpu.down(C)
     assert got[:, :m].tobytes() == want.tobytes()
     assert np.isnan(got[:, m:]).all()
+
+
+@pytest.mark.parametrize("n,Q", [(1, 1), (5, 3), (17, 40), (30, 257)])
+def test_pack_unpack_uhc_f64_bit_exact(gpu, oracle, n, Q):
+    D = inputs.uniform64(3700 + n, n, n, Q)
+    want = oracle.pack_uhc_f64(D)
+    dP = gpu.empty(tri(n) * Q)
+    gpu.d.pack_uhc_f64(n, Q, gpu.up(D), dP)
+    assert gpu.down(dP).tobytes() == want.tobytes()
+    dU = gpu.empty(n, n, Q)
+    gpu.d.unpack_uhc_f64(n, Q, dP, dU)
+    assert gpu.down(dU).tobytes() == oracle.unpack_uhc_f64(n, n, Q, want).tobytes()
+
+
+@pytest.mark.parametrize("n,Q,K", [(1, 1, 1), (2, 3, 5), (12, 16, 128), (13, 17, 129), (40, 48, 72), (33, 100, 200),
+                                   (24, 256, 64), (50, 15, 300)])
+def test_ttm_ut_f64_parity(gpu, oracle, n, Q, K):
+    Bp, C = inputs.uniform64(3710 + n, tri(n) * Q), inputs.uniform64(3711 + n, K, Q)
+    want, scale = oracle.ttm_ut_f64(n, Q, K, Bp, C)
+    A = gpu.empty(tri(n) * K)
+    gpu.d.ttm_ut_f64(n, Q, K, gpu.up(Bp), gpu.up(C), Q, A)
+    assert_within(gpu.down(A), want, scale, "ttm_ut_f64 n=%d Q=%d K=%d" % (n, Q, K))
+
+
+def test_ttm_ut_f64_integer_exact_and_identity(gpu, oracle):
+    n, Q, K = 45, 33, 70
+    Bp = inputs.small_int(3720, -3, 3, tri(n) * Q).astype(np.float64)
+    C = inputs.small_int(3721, -3, 3, K, Q).astype(np.float64)
+    want, _ = oracle.ttm_ut_f64(n, Q, K, Bp, C)
+    A = gpu.empty(tri(n) * K)
+    gpu.d.ttm_ut_f64(n, Q, K, gpu.up(Bp), gpu.up(C), Q, A)
+    assert gpu.down(A).tobytes() == want.tobytes()
+    # C = I copies the packed operand
+    n, Q = 20, 64
+    Bq = inputs.uniform64(3722, tri(n) * Q)
+    A = gpu.empty(tri(n) * Q)
+    gpu.d.ttm_ut_f64(n, Q, Q, gpu.up(Bq), gpu.up(np.eye(Q)), Q, A)
+    assert gpu.down(A).tobytes() == Bq.tobytes()
