@@ -93,6 +93,8 @@ def lib() -> ctypes.CDLL:
         L.oracle_pack_uhc_f64.argtypes = [_i64, _i64, _i64, _dp, _dp]
         L.oracle_unpack_uhc_f64.argtypes = [_i64, _i64, _i64, _dp, _dp]
         L.oracle_ttm_ut_f64.argtypes = [_i64, _i64, _i64, _dp, _dp, _i64, _dp, _dp, _i64, _i64]
+        L.oracle_pr_a2_f64.argtypes = [_i64, _i64, _dp, _i64, _dp, _dp, _i64, _i64]
+        L.oracle_pr_a3_f64.argtypes = [_i64, _i64, _dp, _i64, _dp, _dp, _i64, _i64]
         L.oracle_symm_f64.argtypes = [_i64, _i64, _dp, _dp, _i64, _dp, _i64, _dp, _i64, _i64]
         L.oracle_trmm_f64.argtypes = [_i64, _i64, _dp, _dp, _i64, _dp, _i64, _dp, _i64, _i64]
         L.oracle_pr_a2_f32.argtypes = [_i64, _i64, _fp, _i64, _fp, _dp, _i64, _i64]
@@ -572,3 +574,23 @@ def ttm_ut_f64(n, Q, K, Bp, C, rows=None):
     sc = np.full(pairs * K, np.nan, dtype=np.float64)
     lib().oracle_ttm_ut_f64(n, Q, K, _d(Bp), _d(C), C.shape[1] if C.ndim == 2 else Q, _d(A), _d(sc), lo, hi)
     return A, sc
+
+
+def _pr64(fn, count, B, window):
+    B = _f64(B)
+    N, d = B.shape
+    lo, hi = (0, count) if window is None else (int(window[0]), int(window[1]))
+    out = np.full(count, np.nan, dtype=np.float64)
+    sc = np.full(count, np.nan, dtype=np.float64)
+    fn(N, d, _d(B), d, _d(out), _d(sc), lo, hi)
+    return out, sc
+
+
+def pr_a2_f64(B, window=None):
+    d = B.shape[1]
+    return _pr64(lib().oracle_pr_a2_f64, d * (d + 1) // 2, B, window)
+
+
+def pr_a3_f64(B, window=None):
+    d = B.shape[1]
+    return _pr64(lib().oracle_pr_a3_f64, d * (d + 1) * (d + 2) // 6, B, window)

@@ -915,3 +915,39 @@ void oracle_ttm_ut_f64(int64_t n, int64_t Q, int64_t K, const double *Bp, const 
       ++pair;
     }
 }
+
+/* The polynomial-regression tensors on double operands (long-double accumulation). */
+void oracle_pr_a2_f64(int64_t N, int64_t d, const double *B, int64_t ldb, double *A2p, double *scale,
+                      int64_t p_lo, int64_t p_hi) {
+  int64_t p = 0;
+  for (int64_t i = 0; i < d; ++i)
+    for (int64_t j = i; j < d; ++j, ++p) {
+      if (p < p_lo || p >= p_hi) continue;
+      long double acc = 0.0L, mag = 0.0L;
+      for (int64_t x = 0; x < N; ++x) {
+        long double t = (long double)B[x * ldb + i] * (long double)B[x * ldb + j];
+        acc += t;
+        mag += fabsl(t);
+      }
+      A2p[p] = (double)acc;
+      if (scale) scale[p] = (double)mag;
+    }
+}
+
+void oracle_pr_a3_f64(int64_t N, int64_t d, const double *B, int64_t ldb, double *A3p, double *scale,
+                      int64_t p_lo, int64_t p_hi) {
+  int64_t p = 0;
+  for (int64_t i = 0; i < d; ++i)
+    for (int64_t j = i; j < d; ++j)
+      for (int64_t k = j; k < d; ++k, ++p) {
+        if (p < p_lo || p >= p_hi) continue;
+        long double acc = 0.0L, mag = 0.0L;
+        for (int64_t x = 0; x < N; ++x) {
+          long double t = (long double)B[x * ldb + i] * (long double)B[x * ldb + j] * (long double)B[x * ldb + k];
+          acc += t;
+          mag += fabsl(t);
+        }
+        A3p[p] = (double)acc;
+        if (scale) scale[p] = (double)mag;
+      }
+}

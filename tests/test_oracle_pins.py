@@ -712,3 +712,14 @@ def test_ttm_ut_f64_against_einsum(oracle, n, Q, K):
     A, sc = oracle.ttm_ut_f64(n, Q, K, Bp, C)
     want = np.einsum("ijl,kl->ijk", Bd, C)[i <= j].ravel()
     assert _close64(A, want, sc, rel=4e-16 * Q)
+
+
+@pytest.mark.parametrize("N,d", [(1, 1), (30, 5), (200, 9)])
+def test_pr_tensors_f64_against_einsum(oracle, N, d):
+    B = inputs.uniform64(2400 + N + d, N, d)
+    i, j = np.meshgrid(np.arange(d), np.arange(d), indexing="ij")
+    A2, s2 = oracle.pr_a2_f64(B)
+    assert _close64(A2, np.einsum("xi,xj->ij", B, B)[i <= j], s2, rel=4e-16 * N)
+    i, j, k = np.meshgrid(np.arange(d), np.arange(d), np.arange(d), indexing="ij")
+    A3, s3 = oracle.pr_a3_f64(B)
+    assert _close64(A3, np.einsum("xi,xj,xk->ijk", B, B, B)[(i <= j) & (j <= k)], s3, rel=8e-16 * N)
