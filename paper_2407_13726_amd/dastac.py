@@ -73,6 +73,8 @@ SIGNATURES = {
     "dastac_pack_uhc_f64": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp]),
     "dastac_unpack_uhc_f64": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp]),
     "dastac_ttm_ut_f64": (ctypes.c_int, [_i64, _i64, _i64, _vp, _vp, _i64, _vp, _vp]),
+    "dastac_pr_a2_f64": (ctypes.c_int, [_i64, _i64, _vp, _i64, _vp, _vp]),
+    "dastac_pr_a3_f64": (ctypes.c_int, [_i64, _i64, _vp, _i64, _vp, _vp]),
     "dastac_subtri_offset": (_i64, [_i64, _i64, _i64, _i64]),
     "dastac_pack_sband_f32": (ctypes.c_int, [_i64, _i64, _i64, _vp, _i64, _vp, _vp]),
     "dastac_unpack_sband_f32": (ctypes.c_int, [_i64, _i64, _i64, _vp, _vp, _i64, _vp]),
@@ -380,3 +382,11 @@ def unpack_uhc_f64(n, Q, packed, dense, stream=None):
 
 def ttm_ut_f64(n, Q, K, Bp, C, ldc, Ap, stream=None):
     _check(lib().dastac_ttm_ut_f64(n, Q, K, _ptr64(Bp), _ptr64(C), ldc, _ptr64(Ap), _stream(stream)), "ttm_ut_f64")
+
+
+def pr_a2_f64(N, d, B, ldb, A2p, stream=None):
+    _check(lib().dastac_pr_a2_f64(N, d, _ptr64(B), ldb, _ptr64(A2p), _stream(stream)), "pr_a2_f64")
+
+
+def pr_a3_f64(N, d, B, ldb, A3p, stream=None):
+    _check(lib().dastac_pr_a3_f64(N, d, _ptr64(B), ldb, _ptr64(A3p), _stream(stream)), "pr_a3_f64")

@@ -244,3 +244,37 @@ def test_ttm_ut_f64_integer_exact_and_identity(gpu, oracle):
     A = gpu.empty(tri(n) * Q)
     gpu.d.ttm_ut_f64(n, Q, Q, gpu.up(Bq), gpu.up(np.eye(Q)), Q, A)
     assert gpu.down(A).tobytes() == Bq.tobytes()
+
+
+@pytest.mark.parametrize("N,d,ld", [(1, 1, 1), (5, 3, 3), (100, 64, 64), (333, 65, 70), (40, 200, 200), (1000, 130, 130),
+                                    (20000, 64, 64), (3000, 257, 260), (31, 129, 129), (900, 800, 800)])
+def test_pr_a2_f64_parity(gpu, oracle, N, d, ld):
+    B = inputs.uniform64(3800 + N + d, N, ld)
+    want, scale = oracle.pr_a2_f64(np.ascontiguousarray(B[:, :d]))
+    out = gpu.empty(tri(d))
+    gpu.d.pr_a2_f64(N, d, gpu.up(B), ld, out)
+    assert_within(gpu.down(out), want, scale, "pr_a2_f64 N=%d d=%d" % (N, d))
+
+
+@pytest.mark.parametrize("N,d,ld", [(1, 1, 1), (5, 3, 3), (100, 33, 33), (300, 64, 64), (333, 65, 70), (2000, 70, 70),
+                                    (40, 130, 130), (600, 129, 129)])
+def test_pr_a3_f64_parity(gpu, oracle, N, d, ld):
+    B = inputs.uniform64(3810 + N + d, N, ld)
+    want, scale = oracle.pr_a3_f64(np.ascontiguousarray(B[:, :d]))
+    out = gpu.empty(tet(d))
+    gpu.d.pr_a3_f64(N, d, gpu.up(B), ld, out)
+    assert_within(gpu.down(out), want, scale, "pr_a3_f64 N=%d d=%d" % (N, d))
+
+
+@pytest.mark.parametrize("N,d", [(300, 150), (3000, 40)])  # one share of the samples / several shares with atomics
+def test_pr_tensors_f64_exact_on_integers(gpu, oracle, N, d):
+    B = inputs.small_int(3820 + N, -2, 2, N, d).astype(np.float64)
+    dB = gpu.up(B)
+    w2, _ = oracle.pr_a2_f64(B)
+    w3, _ = oracle.pr_a3_f64(B)
+    o2, o3 = gpu.empty(tri(d)), gpu.empty(tet(d))
+    for _ in range(2):  # a second call must overwrite, not add onto, the first call's result
+        gpu.d.pr_a2_f64(N, d, dB, d, o2)
+        gpu.d.pr_a3_f64(N, d, dB, d, o3)
+        assert gpu.down(o2).tobytes() == w2.tobytes()
+        assert gpu.down(o3).tobytes() == w3.tobytes()

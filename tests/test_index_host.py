@@ -177,7 +177,8 @@ def test_new_domain_entry_points_reject_bad_arguments():
     assert L.dastac_symm_f32(4, 2, _p(A), None, 2, _p(C), 2, None) == dastac.ENULL
     assert L.dastac_symm_f32(4, 2, _p(A), _p(B), 2, _p(B + 8), 2, None) == dastac.EALIAS
     assert L.dastac_symm_f32(0, 2, None, None, 2, None, 2, None) == dastac.OK
-    for fn, dmax in ((L.dastac_pr_a2_f32, 65536), (L.dastac_pr_a3_f32, 8192)):
+    for fn, dmax in ((L.dastac_pr_a2_f32, 65536), (L.dastac_pr_a3_f32, 8192), (L.dastac_pr_a2_f64, 65536),
+                     (L.dastac_pr_a3_f64, 8192)):
         assert fn(-1, 4, _p(A), 4, _p(B), None) == dastac.EINVAL
         assert fn(10, -1, _p(A), 4, _p(B), None) == dastac.EINVAL
         assert fn(10, 4, _p(A), 3, _p(B), None) == dastac.EINVAL
