@@ -95,6 +95,7 @@ def lib() -> ctypes.CDLL:
         L.oracle_ttm_ut_f64.argtypes = [_i64, _i64, _i64, _dp, _dp, _i64, _dp, _dp, _i64, _i64]
         L.oracle_pr_a2_f64.argtypes = [_i64, _i64, _dp, _i64, _dp, _dp, _i64, _i64]
         L.oracle_pr_a3_f64.argtypes = [_i64, _i64, _dp, _i64, _dp, _dp, _i64, _i64]
+        L.oracle_tet_mttkrp_f64.argtypes = [_i64, _i64, _dp, _dp, _i64, _dp, _i64, _dp, _i64, _dp, _i64, _i64]
         L.oracle_symm_f64.argtypes = [_i64, _i64, _dp, _dp, _i64, _dp, _i64, _dp, _i64, _i64]
         L.oracle_trmm_f64.argtypes = [_i64, _i64, _dp, _dp, _i64, _dp, _i64, _dp, _i64, _i64]
         L.oracle_pr_a2_f32.argtypes = [_i64, _i64, _fp, _i64, _fp, _dp, _i64, _i64]
@@ -594,3 +595,12 @@ def pr_a2_f64(B, window=None):
 def pr_a3_f64(B, window=None):
     d = B.shape[1]
     return _pr64(lib().oracle_pr_a3_f64, d * (d + 1) * (d + 2) // 6, B, window)
+
+
+def tet_mttkrp_f64(n, R, Ap, B, C, rows=None):
+    Ap, B, C = _f64(Ap), _f64(B), _f64(C)
+    lo, hi = _window(n, rows)
+    M = np.full((n, R), np.nan, dtype=np.float64)
+    sc = np.full((n, R), np.nan, dtype=np.float64)
+    lib().oracle_tet_mttkrp_f64(n, R, _d(Ap), _d(B), B.shape[1], _d(C), C.shape[1], _d(M), R, _d(sc), lo, hi)
+    return M, sc

@@ -951,3 +951,36 @@ void oracle_pr_a3_f64(int64_t N, int64_t d, const double *B, int64_t ldb, double
         if (scale) scale[p] = (double)mag;
       }
 }
+
+/* M(i,r) := A(i,j,k) * B(j,r) * C(k,r),  i<=j<=k, on double operands (long-double accumulation). */
+void oracle_tet_mttkrp_f64(int64_t n, int64_t R, const double *Ap, const double *B, int64_t ldb,
+                           const double *C, int64_t ldc, double *M, int64_t ldm, double *scale,
+                           int64_t r_lo, int64_t r_hi) {
+  long double *acc = (long double *)malloc(sizeof(long double) * (size_t)(R > 0 ? R : 1));
+  long double *mag = (long double *)malloc(sizeof(long double) * (size_t)(R > 0 ? R : 1));
+  int64_t p = 0;
+  for (int64_t i = 0; i < n; ++i) {
+    int on = (i >= r_lo && i < r_hi);
+    if (on)
+      for (int64_t r = 0; r < R; ++r) acc[r] = mag[r] = 0.0L;
+    for (int64_t j = i; j < n; ++j)
+      for (int64_t k = j; k < n; ++k) {
+        if (on) {
+          long double a = (long double)Ap[p];
+          for (int64_t r = 0; r < R; ++r) {
+            long double t = a * (long double)B[j * ldb + r] * (long double)C[k * ldc + r];
+            acc[r] += t;
+            mag[r] += fabsl(t);
+          }
+        }
+        ++p;
+      }
+    if (on)
+      for (int64_t r = 0; r < R; ++r) {
+        M[i * ldm + r] = (double)acc[r];
+        if (scale) scale[i * R + r] = (double)mag[r];
+      }
+  }
+  free(acc);
+  free(mag);
+}

@@ -723,3 +723,14 @@ def test_pr_tensors_f64_against_einsum(oracle, N, d):
     i, j, k = np.meshgrid(np.arange(d), np.arange(d), np.arange(d), indexing="ij")
     A3, s3 = oracle.pr_a3_f64(B)
     assert _close64(A3, np.einsum("xi,xj,xk->ijk", B, B, B)[(i <= j) & (j <= k)], s3, rel=8e-16 * N)
+
+
+@pytest.mark.parametrize("n,R", [(1, 1), (6, 3), (13, 32)])
+def test_tet_mttkrp_f64_against_einsum(oracle, n, R):
+    T = inputs.uniform64(2500 + n, n, n, n)
+    B, C = inputs.uniform64(2501 + n, n, R), inputs.uniform64(2502 + n, n, R)
+    i, j, k = np.meshgrid(np.arange(n), np.arange(n), np.arange(n), indexing="ij")
+    mask = (i <= j) & (j <= k)
+    M, sc = oracle.tet_mttkrp_f64(n, R, T[mask], B, C)
+    want = np.einsum("ijk,jr,kr->ir", np.where(mask, T, 0.0), B, C)
+    assert _close64(M, want, sc, rel=8e-16 * n * n)
