@@ -222,8 +222,8 @@ int dastac_pr_a3_f32(int64_t N, int64_t d, const float *B, int64_t ldb, float *A
  * The same layouts, index polynomials, argument rules and error codes as the _f32 entry points of the
  * same name, on double operands (8-byte aligned).  Each output element is within 1e-12 * sum|products|
  * of the exactly rounded result.  trmv_f64 and tet_ttv_f64 need n <= 8192 (the vector is kept in LDS),
- * beyond that DASTAC_EOVERFLOW.  The matrix-core contractions TRMM, SYMM, TTM_UT and the polynomial-regression
- * tensors run on the fp64 matrix cores (shapes and limits as their _f32 namesakes); MTTKRP has no double version. */
+ * beyond that DASTAC_EOVERFLOW.  The matrix-core contractions (TRMM, SYMM, MTTKRP, TTM_UT, the
+ * polynomial-regression tensors) run on the fp64 matrix cores; shapes and limits as their _f32 namesakes. */
 int dastac_pack_triu_f64(int64_t n, const double *dense, int64_t ld, double *packed, void *stream);
 int dastac_unpack_triu_f64(int64_t n, const double *packed, double *dense, int64_t ld, void *stream);
 int dastac_pack_tet_f64(int64_t n, const double *dense, double *packed, void *stream);
@@ -241,6 +241,8 @@ int dastac_pack_uhc_f64(int64_t n, int64_t Q, const double *dense, double *packe
 int dastac_unpack_uhc_f64(int64_t n, int64_t Q, const double *packed, double *dense, void *stream);
 int dastac_ttm_ut_f64(int64_t n, int64_t Q, int64_t K, const double *Bp, const double *C, int64_t ldc, double *Ap,
                       void *stream);
+int dastac_tet_mttkrp_f64(int64_t n, int64_t R, const double *Ap, const double *B, int64_t ldb, const double *C,
+                          int64_t ldc, double *M, int64_t ldm, void *stream);
 int dastac_pr_a2_f64(int64_t N, int64_t d, const double *B, int64_t ldb, double *A2p, void *stream);
 int dastac_pr_a3_f64(int64_t N, int64_t d, const double *B, int64_t ldb, double *A3p, void *stream);
 

@@ -43,7 +43,9 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
                                                              const float *__restrict__ Bm, int64_t ldb,
                                                              const float *__restrict__ Cm, int64_t ldc,
                                                              float *__restrict__ M, int64_t ldm, int64_t total) {
-  __shared__ __attribute__((aligned(16))) float Cs[kPanel * 32];
+  // one tile of zero rows follows the panel: the last tile of a row block may reach past the panel's last row
+  // (there its elements of A are masked to zero, and must not meet anything but zeros)
+  __shared__ __attribute__((aligned(16))) float Cs[(kPanel + 32) * 32];
   __shared__ __attribute__((aligned(16))) float At[kWaves][32 * kTP];
   __shared__ float Mred[kWaves][32];
   __shared__ int next_unit;
@@ -77,7 +79,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     // bank conflicts); the global loads, 128 contiguous bytes per row and half-wavefront, are all
     // requested before the first is used.
     {
-      constexpr int kIter = kPanel * 8 / kBlock;
+      constexpr int kGroups = (kPanel + 32) / 4, kIter = (kGroups * 32 + kBlock - 1) / kBlock;
       f4a v[kIter];
       const int r = tid & 31;
 #pragma unroll
@@ -85,16 +87,16 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
         const int kg = (tid >> 5) + it * (kBlock / 32);
         const int64_t k = kp0 + 4 * (int64_t)kg;
         const float *src = Cm + k * ldc + r;
-        const bool col_ok = r < R;
-        v[it].x = (col_ok && k + 0 < n) ? src[0] : 0.0f;
-        v[it].y = (col_ok && k + 1 < n) ? src[ldc] : 0.0f;
-        v[it].z = (col_ok && k + 2 < n) ? src[2 * ldc] : 0.0f;
-        v[it].w = (col_ok && k + 3 < n) ? src[3 * ldc] : 0.0f;
+        const bool ok = r < R && kg < kPanel / 4;
+        v[it].x = (ok && k + 0 < n) ? src[0] : 0.0f;
+        v[it].y = (ok && k + 1 < n) ? src[ldc] : 0.0f;
+        v[it].z = (ok && k + 2 < n) ? src[2 * ldc] : 0.0f;
+        v[it].w = (ok && k + 3 < n) ? src[3 * ldc] : 0.0f;
       }
 #pragma unroll
       for (int it = 0; it < kIter; ++it) {
         const int kg = (tid >> 5) + it * (kBlock / 32);
-        *reinterpret_cast<f4a *>(&Cs[(kg * 32 + r) * 4]) = v[it];
+        if (kg < kGroups) *reinterpret_cast<f4a *>(&Cs[(kg * 32 + r) * 4]) = v[it];
       }
     }
     if (tid == 0) next_unit = 0;

@@ -75,6 +75,7 @@ SIGNATURES = {
     "dastac_ttm_ut_f64": (ctypes.c_int, [_i64, _i64, _i64, _vp, _vp, _i64, _vp, _vp]),
     "dastac_pr_a2_f64": (ctypes.c_int, [_i64, _i64, _vp, _i64, _vp, _vp]),
     "dastac_pr_a3_f64": (ctypes.c_int, [_i64, _i64, _vp, _i64, _vp, _vp]),
+    "dastac_tet_mttkrp_f64": (ctypes.c_int, [_i64, _i64, _vp, _vp, _i64, _vp, _i64, _vp, _i64, _vp]),
     "dastac_subtri_offset": (_i64, [_i64, _i64, _i64, _i64]),
     "dastac_pack_sband_f32": (ctypes.c_int, [_i64, _i64, _i64, _vp, _i64, _vp, _vp]),
     "dastac_unpack_sband_f32": (ctypes.c_int, [_i64, _i64, _i64, _vp, _vp, _i64, _vp]),
@@ -390,3 +391,8 @@ def pr_a2_f64(N, d, B, ldb, A2p, stream=None):
 
 def pr_a3_f64(N, d, B, ldb, A3p, stream=None):
     _check(lib().dastac_pr_a3_f64(N, d, _ptr64(B), ldb, _ptr64(A3p), _stream(stream)), "pr_a3_f64")
+
+
+def tet_mttkrp_f64(n, R, Ap, B, ldb, C, ldc, M, ldm, stream=None):
+    _check(lib().dastac_tet_mttkrp_f64(n, R, _ptr64(Ap), _ptr64(B), ldb, _ptr64(C), ldc, _ptr64(M), ldm,
+                                       _stream(stream)), "tet_mttkrp_f64")

@@ -278,3 +278,40 @@ def test_pr_tensors_f64_exact_on_integers(gpu, oracle, N, d):
         gpu.d.pr_a3_f64(N, d, dB, d, o3)
         assert gpu.down(o2).tobytes() == w2.tobytes()
         assert gpu.down(o3).tobytes() == w3.tobytes()
+
+
+@pytest.mark.parametrize("n,R", [(1, 1), (2, 32), (5, 3), (16, 32), (17, 7), (33, 32), (40, 16), (64, 32), (65, 31), (100, 32),
+                                 (130, 5), (270, 32), (300, 32)])
+def test_tet_mttkrp_f64_parity(gpu, oracle, n, R):
+    Ap = inputs.uniform64(3900 + n, tet(n))
+    B, C = inputs.uniform64(3901 + n, n, R), inputs.uniform64(3902 + n, n, R)
+    want, scale = oracle.tet_mttkrp_f64(n, R, Ap, B, C)
+    M = gpu.empty(n, R)
+    gpu.d.tet_mttkrp_f64(n, R, gpu.up(Ap), gpu.up(B), R, gpu.up(C), R, M, R)
+    assert_within(gpu.down(M), want, scale, "mttkrp_f64 n=%d R=%d" % (n, R))
+
+
+def test_tet_mttkrp_f64_leading_dimensions_and_integer_exactness(gpu, oracle):
+    n, R, ldb, ldc, ldm = 90, 20, 24, 33, 21
+    Ap = inputs.small_int(3910, -2, 2, tet(n)).astype(np.float64)
+    B = inputs.small_int(3911, -2, 2, n, ldb).astype(np.float64)
+    C = inputs.small_int(3912, -2, 2, n, ldc).astype(np.float64)
+    want, _ = oracle.tet_mttkrp_f64(n, R, Ap, np.ascontiguousarray(B[:, :R]), np.ascontiguousarray(C[:, :R]))
+    M = gpu.empty(n, ldm)
+    gpu.d.tet_mttkrp_f64(n, R, gpu.up(Ap), gpu.up(B), ldb, gpu.up(C), ldc, M, ldm)
+    got = gpu.down(M)
+    assert got[:, :R].tobytes() == want.tobytes()
+    assert np.isnan(got[:, R:]).all()
+
+
+def test_tet_mttkrp_f64_sampled_slices_at_a_larger_size(gpu, oracle):
+    n, R = 400, 32
+    Ap = inputs.uniform64(3920, tet(n))
+    B, C = inputs.uniform64(3921, n, R), inputs.uniform64(3922, n, R)
+    M = gpu.empty(n, R)
+    gpu.d.tet_mttkrp_f64(n, R, gpu.up(Ap), gpu.up(B), R, gpu.up(C), R, M, R)
+    got = gpu.down(M)
+    assert np.isfinite(got).all()
+    for i in (0, 1, 143, 144, 145, 200, n - 33, n - 32, n - 2, n - 1):
+        want, scale = oracle.tet_mttkrp_f64(n, R, Ap, B, C, rows=(i, i + 1))
+        assert_within(got[i], want[i], scale[i], "mttkrp_f64 slice %d" % i)

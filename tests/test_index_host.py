@@ -210,6 +210,11 @@ def test_new_domain_entry_points_reject_bad_arguments():
     assert L.dastac_ttm_ut_f64(0, 4, 4, None, None, 4, None, None) == dastac.OK
     assert L.dastac_pack_uhc_f64(4, 0, _p(A), _p(B), None) == dastac.EINVAL
     assert L.dastac_unpack_uhc_f64(4, 2, _p(A), None, None) == dastac.ENULL
+    assert L.dastac_tet_mttkrp_f64(4, 0, _p(A), _p(B), 4, _p(C), 4, _p(D), 4, None) == dastac.EINVAL
+    assert L.dastac_tet_mttkrp_f64(4, 33, _p(A), _p(B), 33, _p(C), 33, _p(D), 33, None) == dastac.EINVAL
+    assert L.dastac_tet_mttkrp_f64(4, 8, _p(A), _p(B), 8, _p(C), 8, _p(D), 7, None) == dastac.EINVAL
+    assert L.dastac_tet_mttkrp_f64(4, 2, _p(A), _p(B), 2, None, 2, _p(D), 2, None) == dastac.ENULL
+    assert L.dastac_tet_mttkrp_f64(0, 2, None, None, 2, None, 2, None, 2, None) == dastac.OK
     assert L.dastac_band_spmv_f64(4, 65, _p(A), _p(B), _p(C), None) == dastac.EINVAL
     assert L.dastac_band_spmv_f64(4, 1, _p(A), _p(B), _p(B + 24), None) == dastac.EALIAS
     assert L.dastac_pack_triu_f64(8, _p(A), 7, _p(B), None) == dastac.EINVAL
