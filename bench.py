@@ -370,6 +370,15 @@ def main() -> int:
                                           "gflops": ta["flops"] / fms / 1e6, "gbps": ta["bytes"] / fms / 1e6,
                                           "bound": "mfma", "frac": ta["flops"] / fms / 1e9 / MFMA_F64_PEAK_TFLOPS}
         del gBq, gAq
+        # tetrahedral MTTKRP in double precision (a smaller order than the fp32 configuration: 0.6 GB)
+        nm, Rm = 768, 32
+        gAm = up64(inputs.uniform64(20240713 * 16, nm * (nm + 1) * (nm + 2) // 6))
+        gBm, gCm = up64(inputs.uniform64(20240713 * 16 + 1, nm, Rm)), up64(inputs.uniform64(20240713 * 16 + 2, nm, Rm))
+        gMm = out64(nm, Rm)
+        fms = beside(lambda: d.tet_mttkrp_f64(nm, Rm, gAm, gBm, Rm, gCm, Rm, gMm, Rm))
+        result["beside"]["mttkrp_f64"] = entry("tet MTTKRP n=%d R=%d, fp64" % (nm, Rm), fms,
+                                               wl.accounting("mttkrp_f64", n=nm, R=Rm), "hbm")
+        del gAm
         bw = wl.sband_inputs()
         nb, wb, sb = bw["n"], bw["w"], bw["s"]
         gD, gx, gy = up(bw["D"]), up(bw["x"]), out(nb)
