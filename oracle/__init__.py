@@ -110,6 +110,18 @@ def lib() -> ctypes.CDLL:
         L.oracle_pack_leslie_f32.argtypes = [_i64, _fp, _i64, _fp, _fp]
         L.oracle_unpack_leslie_f32.argtypes = [_i64, _fp, _fp, _fp, _i64]
         L.oracle_leslie_spmv_f32.argtypes = [_i64, _fp, _fp, _fp, _fp, _dp]
+        L.oracle_trimv_f64.argtypes = [_i64, ctypes.c_int, ctypes.c_int, _dp, _dp, _dp, _dp, _i64, _i64]
+        L.oracle_pack_tril_f64.argtypes = [_i64, _dp, _i64, _dp]
+        L.oracle_unpack_tril_f64.argtypes = [_i64, _dp, _dp, _i64]
+        L.oracle_pack_sband_f64.argtypes = [_i64, _i64, _i64, _dp, _i64, _dp]
+        L.oracle_unpack_sband_f64.argtypes = [_i64, _i64, _i64, _dp, _dp, _i64]
+        L.oracle_sband_spmv_f64.argtypes = [_i64, _i64, _i64, _dp, _dp, _dp, _dp, _i64, _i64]
+        L.oracle_pack_subtri_f64.argtypes = [_i64, _i64, _dp, _i64, _dp]
+        L.oracle_unpack_subtri_f64.argtypes = [_i64, _i64, _dp, _dp, _i64]
+        L.oracle_subtri_spmv_f64.argtypes = [_i64, _i64, _dp, _dp, _dp, _dp, _i64, _i64]
+        L.oracle_pack_leslie_f64.argtypes = [_i64, _dp, _i64, _dp, _dp]
+        L.oracle_unpack_leslie_f64.argtypes = [_i64, _dp, _dp, _dp, _i64]
+        L.oracle_leslie_spmv_f64.argtypes = [_i64, _dp, _dp, _dp, _dp, _dp]
         for name in ("pack_triu", "unpack_triu", "pack_tet", "unpack_tet", "pack_band", "unpack_band",
                      "trmv", "trmm", "band_spmv", "tet_ttv", "tet_mttkrp"):
             getattr(L, "oracle_%s_f32" % name).restype = None
@@ -604,3 +616,100 @@ def tet_mttkrp_f64(n, R, Ap, B, C, rows=None):
     sc = np.full((n, R), np.nan, dtype=np.float64)
     lib().oracle_tet_mttkrp_f64(n, R, _d(Ap), _d(B), B.shape[1], _d(C), C.shape[1], _d(M), R, _d(sc), lo, hi)
     return M, sc
+
+
+def trimv_f64(n, Tp, x, lower=False, mode=0, rows=None):
+    """mode 0: T x; 1: T^T x; 2: S x with S symmetric and T its unique triangle (upper, or lower)."""
+    Tp, x = _f64(Tp), _f64(x)
+    lo, hi = _window(n, rows)
+    y = np.full(n, np.nan, dtype=np.float64)
+    sc = np.full(n, np.nan, dtype=np.float64)
+    lib().oracle_trimv_f64(n, int(bool(lower)), int(mode), _d(Tp), _d(x), _d(y), _d(sc), lo, hi)
+    return y, sc
+
+
+def pack_tril_f64(dense):
+    dense = _f64(dense)
+    n = dense.shape[0]
+    out = np.empty(n * (n + 1) // 2, dtype=np.float64)
+    lib().oracle_pack_tril_f64(n, _d(dense), dense.shape[1], _d(out))
+    return out
+
+
+def unpack_tril_f64(n, packed):
+    packed = _f64(packed)
+    out = np.empty((n, n), dtype=np.float64)
+    lib().oracle_unpack_tril_f64(n, _d(packed), _d(out), n)
+    return out
+
+
+def pack_sband_f64(dense, w, s):
+    dense = _f64(dense)
+    n = dense.shape[0]
+    out = np.empty((2 * w + 1) * n, dtype=np.float64)
+    lib().oracle_pack_sband_f64(n, w, s, _d(dense), dense.shape[1], _d(out))
+    return out
+
+
+def unpack_sband_f64(n, w, s, diag):
+    diag = _f64(diag)
+    out = np.empty((n, n), dtype=np.float64)
+    lib().oracle_unpack_sband_f64(n, w, s, _d(diag), _d(out), n)
+    return out
+
+
+def sband_spmv_f64(n, w, s, D, x, rows=None):
+    D, x = _f64(D), _f64(x)
+    lo, hi = _window(n, rows)
+    y = np.full(n, np.nan, dtype=np.float64)
+    sc = np.full(n, np.nan, dtype=np.float64)
+    lib().oracle_sband_spmv_f64(n, w, s, _d(D), _d(x), _d(y), _d(sc), lo, hi)
+    return y, sc
+
+
+def pack_subtri_f64(dense, k):
+    dense = _f64(dense)
+    N = dense.shape[0]
+    out = np.empty(k * (k + 1) // 2, dtype=np.float64)
+    lib().oracle_pack_subtri_f64(N, k, _d(dense), dense.shape[1], _d(out))
+    return out
+
+
+def unpack_subtri_f64(N, k, packed):
+    packed = _f64(packed)
+    out = np.empty((N, N), dtype=np.float64)
+    lib().oracle_unpack_subtri_f64(N, k, _d(packed), _d(out), N)
+    return out
+
+
+def subtri_spmv_f64(N, k, Ap, x, rows=None):
+    Ap, x = _f64(Ap), _f64(x)
+    lo, hi = _window(N, rows)
+    y = np.full(N, np.nan, dtype=np.float64)
+    sc = np.full(N, np.nan, dtype=np.float64)
+    lib().oracle_subtri_spmv_f64(N, k, _d(Ap), _d(x), _d(y), _d(sc), lo, hi)
+    return y, sc
+
+
+def pack_leslie_f64(dense):
+    dense = _f64(dense)
+    n = dense.shape[0]
+    R = np.empty(n, dtype=np.float64)
+    S = np.empty(max(n - 1, 0), dtype=np.float64)
+    lib().oracle_pack_leslie_f64(n, _d(dense), dense.shape[1], _d(R), _d(S))
+    return R, S
+
+
+def unpack_leslie_f64(n, R, S):
+    R, S = _f64(R), _f64(S)
+    out = np.empty((n, n), dtype=np.float64)
+    lib().oracle_unpack_leslie_f64(n, _d(R), _d(S), _d(out), n)
+    return out
+
+
+def leslie_spmv_f64(n, R, S, x):
+    R, S, x = _f64(R), _f64(S), _f64(x)
+    y = np.full(n, np.nan, dtype=np.float64)
+    sc = np.full(n, np.nan, dtype=np.float64)
+    lib().oracle_leslie_spmv_f64(n, _d(R), _d(S), _d(x), _d(y), _d(sc))
+    return y, sc

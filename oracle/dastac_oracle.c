@@ -984,3 +984,149 @@ void oracle_tet_mttkrp_f64(int64_t n, int64_t R, const double *Ap, const double 
   free(acc);
   free(mag);
 }
+
+/* ---- double precision: the remaining products of one packed triangle and the further domains ---
+ * Same definitions as their single-precision namesakes above; long double accumulation, one
+ * rounding to double. */
+void oracle_pack_tril_f64(int64_t n, const double *dense, int64_t ld, double *packed) {
+  int64_t p = 0;
+  for (int64_t i = 0; i < n; ++i)
+    for (int64_t j = 0; j <= i; ++j) packed[p++] = dense[i * ld + j];
+}
+
+void oracle_unpack_tril_f64(int64_t n, const double *packed, double *dense, int64_t ld) {
+  for (int64_t i = 0; i < n; ++i)
+    for (int64_t j = 0; j < n; ++j) dense[i * ld + j] = 0.0;
+  int64_t p = 0;
+  for (int64_t i = 0; i < n; ++i)
+    for (int64_t j = 0; j <= i; ++j) dense[i * ld + j] = packed[p++];
+}
+
+/* mode 0: y(i) := T(i,j) x(j); mode 1: y(j) := T(i,j) x(i); mode 2: the symmetric matrix whose
+ * unique elements are T (Section 3, "Redundancy map"). */
+void oracle_trimv_f64(int64_t n, int lower, int mode, const double *Tp, const double *x, double *y,
+                      double *scale, int64_t r_lo, int64_t r_hi) {
+  int64_t *start = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n + 1));
+  int64_t p = 0;
+  for (int64_t i = 0; i < n; ++i) {
+    start[i] = p;
+    p += lower ? i + 1 : n - i;
+  }
+  for (int64_t i = 0; i < n; ++i) {
+    if (i < r_lo || i >= r_hi) continue;
+    long double acc = 0.0L, mag = 0.0L;
+    for (int64_t j = 0; j < n; ++j) {
+      int64_t a = i, b = j;
+      if (mode == 1) { a = j; b = i; }
+      int inside = lower ? (b <= a) : (a <= b);
+      if (mode == 2 && !inside) { int64_t t = a; a = b; b = t; inside = 1; }
+      if (!inside) continue;
+      long double t = (long double)Tp[start[a] + (lower ? b : b - a)] * (long double)x[j];
+      acc += t;
+      mag += fabsl(t);
+    }
+    y[i] = (double)acc;
+    if (scale) scale[i] = (double)mag;
+  }
+  free(start);
+}
+
+void oracle_pack_sband_f64(int64_t n, int64_t w, int64_t s, const double *dense, int64_t ld, double *diag) {
+  int64_t p = 0;
+  for (int64_t d = -w; d <= w; ++d)
+    for (int64_t i = 0; i < n; ++i) {
+      int64_t j = i + d * s;
+      diag[p++] = (j >= 0 && j < n) ? dense[i * ld + j] : 0.0;
+    }
+}
+
+void oracle_unpack_sband_f64(int64_t n, int64_t w, int64_t s, const double *diag, double *dense, int64_t ld) {
+  for (int64_t i = 0; i < n; ++i)
+    for (int64_t j = 0; j < n; ++j) dense[i * ld + j] = 0.0;
+  int64_t p = 0;
+  for (int64_t d = -w; d <= w; ++d)
+    for (int64_t i = 0; i < n; ++i) {
+      int64_t j = i + d * s;
+      if (j >= 0 && j < n) dense[i * ld + j] = diag[p];
+      ++p;
+    }
+}
+
+void oracle_sband_spmv_f64(int64_t n, int64_t w, int64_t s, const double *D, const double *x, double *y,
+                           double *scale, int64_t r_lo, int64_t r_hi) {
+  for (int64_t i = 0; i < n; ++i) {
+    if (i < r_lo || i >= r_hi) continue;
+    long double acc = 0.0L, mag = 0.0L;
+    for (int64_t d = -w; d <= w; ++d) {
+      int64_t j = i + d * s;
+      if (j < 0 || j >= n) continue;
+      long double t = (long double)D[(d + w) * n + i] * (long double)x[j];
+      acc += t;
+      mag += fabsl(t);
+    }
+    y[i] = (double)acc;
+    if (scale) scale[i] = (double)mag;
+  }
+}
+
+void oracle_pack_subtri_f64(int64_t N, int64_t k, const double *dense, int64_t ld, double *packed) {
+  int64_t p = 0;
+  for (int64_t i = 0; i < N; ++i)
+    for (int64_t j = 0; j < N; ++j)
+      if (j - i >= N - k) packed[p++] = dense[i * ld + j];
+}
+
+void oracle_unpack_subtri_f64(int64_t N, int64_t k, const double *packed, double *dense, int64_t ld) {
+  int64_t p = 0;
+  for (int64_t i = 0; i < N; ++i)
+    for (int64_t j = 0; j < N; ++j) dense[i * ld + j] = (j - i >= N - k) ? packed[p++] : 0.0;
+}
+
+void oracle_subtri_spmv_f64(int64_t N, int64_t k, const double *Ap, const double *x, double *y, double *scale,
+                            int64_t r_lo, int64_t r_hi) {
+  int64_t p = 0;
+  for (int64_t i = 0; i < N; ++i) {
+    long double acc = 0.0L, mag = 0.0L;
+    for (int64_t j = 0; j < N; ++j) {
+      if (j - i < N - k) continue;
+      long double t = (long double)Ap[p++] * (long double)x[j];
+      acc += t;
+      mag += fabsl(t);
+    }
+    if (i >= r_lo && i < r_hi) {
+      y[i] = (double)acc;
+      if (scale) scale[i] = (double)mag;
+    }
+  }
+}
+
+void oracle_pack_leslie_f64(int64_t n, const double *dense, int64_t ld, double *R, double *S) {
+  int64_t p = 0;
+  for (int64_t j = 0; j < n; ++j) R[p++] = dense[j];
+  p = 0;
+  for (int64_t i = 1; i < n; ++i) S[p++] = dense[i * ld + (i - 1)];
+}
+
+void oracle_unpack_leslie_f64(int64_t n, const double *R, const double *S, double *dense, int64_t ld) {
+  for (int64_t i = 0; i < n; ++i)
+    for (int64_t j = 0; j < n; ++j) dense[i * ld + j] = 0.0;
+  for (int64_t j = 0; j < n; ++j) dense[j] = R[j];
+  for (int64_t i = 1; i < n; ++i) dense[i * ld + (i - 1)] = S[i - 1];
+}
+
+void oracle_leslie_spmv_f64(int64_t n, const double *R, const double *S, const double *x, double *y, double *scale) {
+  if (n <= 0) return;
+  long double acc = 0.0L, mag = 0.0L;
+  for (int64_t j = 0; j < n; ++j) {
+    long double t = (long double)R[j] * (long double)x[j];
+    acc += t;
+    mag += fabsl(t);
+  }
+  y[0] = (double)acc;
+  if (scale) scale[0] = (double)mag;
+  for (int64_t i = 1; i < n; ++i) {
+    double t = S[i - 1] * x[i - 1]; /* one product: correctly rounded in double already */
+    y[i] = t;
+    if (scale) scale[i] = fabs(t);
+  }
+}

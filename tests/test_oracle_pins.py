@@ -734,3 +734,87 @@ def test_tet_mttkrp_f64_against_einsum(oracle, n, R):
     M, sc = oracle.tet_mttkrp_f64(n, R, T[mask], B, C)
     want = np.einsum("ijk,jr,kr->ir", np.where(mask, T, 0.0), B, C)
     assert _close64(M, want, sc, rel=8e-16 * n * n)
+
+
+@pytest.mark.parametrize("n", [1, 2, 9, 34])
+def test_trimv_f64_against_numpy_float64(oracle, n):
+    """Every product of one packed triangle in double precision against NumPy on the dense
+    matrices that the packed buffer stands for (triangle, its transpose, its symmetric closure)."""
+    D = inputs.uniform64(2600 + n, n, n)
+    x = inputs.uniform64(2601 + n, n)
+    Up, Lp = D[np.triu_indices(n)], D[np.tril_indices(n)]
+    assert np.array_equal(oracle.pack_tril_f64(D), Lp)
+    assert np.array_equal(oracle.unpack_tril_f64(n, Lp), np.tril(D))
+    U, L = np.triu(D), np.tril(D)
+    SU, SL = U + U.T - np.diag(np.diag(D)), L + L.T - np.diag(np.diag(D))
+    for lower, Tp, mats in ((False, Up, (U, U.T, SU)), (True, Lp, (L, L.T, SL))):
+        for mode, Mx in enumerate(mats):
+            y, sc = oracle.trimv_f64(n, Tp, x, lower=lower, mode=mode)
+            assert _close64(y, Mx @ x, sc, rel=4e-16 * n), (lower, mode)
+            assert np.allclose(sc, np.abs(Mx) @ np.abs(x), rtol=1e-13)
+    # rows outside the window stay untouched
+    y, sc = oracle.trimv_f64(n, Up, x, mode=2, rows=(0, n // 2))
+    assert np.isnan(y[n // 2:]).all() and not np.isnan(y[: n // 2]).any()
+    # fp32-representable inputs: both oracles agree after one rounding
+    Uf, xf = inputs.uniform(2602 + n, n * (n + 1) // 2), inputs.uniform(2603 + n, n)
+    for mode in range(3):
+        y32, _ = oracle.trimv(n, Uf, xf, mode=mode)
+        y64, _ = oracle.trimv_f64(n, Uf.astype(np.float64), xf.astype(np.float64), mode=mode)
+        assert np.array_equal(y64.astype(np.float32), y32)
+
+
+@pytest.mark.parametrize("n,w,s", [(1, 1, 1), (7, 1, 3), (20, 2, 4), (20, 1, 25), (33, 0, 2)])
+def test_sband_f64_against_numpy_float64(oracle, n, w, s):
+    D = inputs.uniform64(2610 + n + s, n, n)
+    x = inputs.uniform64(2611 + n, n)
+    i, j = np.meshgrid(np.arange(n), np.arange(n), indexing="ij")
+    mask = np.zeros((n, n), dtype=bool)
+    for d in range(-w, w + 1):
+        mask |= (j - i) == d * s
+    P = oracle.pack_sband_f64(D, w, s)
+    Pm = P.reshape(2 * w + 1, n)
+    for d in range(-w, w + 1):
+        for r in range(n):
+            c = r + d * s
+            assert Pm[d + w, r] == (D[r, c] if 0 <= c < n else 0.0)
+    assert np.array_equal(oracle.unpack_sband_f64(n, w, s, P), np.where(mask, D, 0.0))
+    y, sc = oracle.sband_spmv_f64(n, w, s, P, x)
+    # a stride of 0 would stack summands; strides here are >= 1, so the structure is a plain mask
+    assert _close64(y, np.where(mask, D, 0.0) @ x, sc, rel=4e-16 * (2 * w + 1))
+    Pn = P.copy()
+    for d in range(-w, w + 1):
+        r = np.arange(n)
+        Pn.reshape(2 * w + 1, n)[d + w, (r + d * s < 0) | (r + d * s >= n)] = np.nan
+    y2, _ = oracle.sband_spmv_f64(n, w, s, Pn, x)
+    assert np.array_equal(y2, y)  # padding slots are never read
+
+
+@pytest.mark.parametrize("N,k", [(1, 0), (1, 1), (9, 4), (21, 21), (30, 7)])
+def test_subtri_f64_against_numpy_float64(oracle, N, k):
+    D = inputs.uniform64(2620 + N + k, N, N)
+    x = inputs.uniform64(2621 + N, N)
+    i, j = np.meshgrid(np.arange(N), np.arange(N), indexing="ij")
+    mask = (j - i) >= N - k
+    P = oracle.pack_subtri_f64(D, k)
+    assert P.size == k * (k + 1) // 2 and np.array_equal(P, D[mask])
+    assert np.array_equal(oracle.unpack_subtri_f64(N, k, P), np.where(mask, D, 0.0))
+    y, sc = oracle.subtri_spmv_f64(N, k, P, x)
+    assert _close64(y, np.where(mask, D, 0.0) @ x, sc, rel=4e-16 * N)
+    assert not y[k:].any()
+    # the structure is the packed upper triangle of order k acting on the last k entries of x
+    yt, _ = oracle.trmv_f64(k, P, x[N - k:]) if k else (np.zeros(0), None)
+    assert np.array_equal(y[:k], yt)
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 40])
+def test_leslie_f64_against_numpy_float64(oracle, n):
+    D = inputs.uniform64(2630 + n, n, n)
+    x = inputs.uniform64(2631 + n, n)
+    i, j = np.meshgrid(np.arange(n), np.arange(n), indexing="ij")
+    mask = (i == 0) | (j == i - 1)
+    R, S = oracle.pack_leslie_f64(D)
+    assert np.array_equal(R, D[0]) and np.array_equal(S, np.diag(D, -1))
+    assert np.array_equal(oracle.unpack_leslie_f64(n, R, S), np.where(mask, D, 0.0))
+    y, sc = oracle.leslie_spmv_f64(n, R, S, x)
+    assert _close64(y, np.where(mask, D, 0.0) @ x, sc, rel=4e-16 * n)
+    assert np.array_equal(y[1:], S * x[:-1])
