@@ -399,6 +399,31 @@ def main() -> int:
         lms = beside(lambda: d.leslie_spmv_f32(nl, gR, gS, gx, gy))
         result["beside"]["leslie"] = entry("Leslie SpMV n=%d" % nl, lms, wl.accounting("leslie", n=nl), "hbm")
         del gR, gS, lw
+        # the same four products in double precision
+        dw = wl.domains_f64_inputs()
+        w_ = dw["symv"]
+        gU, gx, gy = up64(w_["Up"]), up64(w_["x"]), out64(w_["n"])
+        fms = beside(lambda: d.symv_f64(w_["n"], gU, gx, gy))
+        result["beside"]["symv_f64"] = entry("SYMV n=%d, fp64" % w_["n"], fms, wl.accounting("symv_f64", n=w_["n"]), "hbm")
+        del gU
+        w_ = dw["sband"]
+        gD, gx, gy = up64(w_["D"]), up64(w_["x"]), out64(w_["n"])
+        fms = beside(lambda: d.sband_spmv_f64(w_["n"], w_["w"], w_["s"], gD, gx, gy))
+        result["beside"]["sband_f64"] = entry("strided-band SpMV n=%d w=%d s=%d, fp64" % (w_["n"], w_["w"], w_["s"]), fms,
+                                              wl.accounting("sband_f64", n=w_["n"], w=w_["w"], s=w_["s"]), "hbm")
+        del gD
+        w_ = dw["subtri"]
+        gP, gx, gy = up64(w_["Ap"]), up64(w_["x"]), out64(w_["N"])
+        fms = beside(lambda: d.subtri_spmv_f64(w_["N"], w_["k"], gP, gx, gy))
+        result["beside"]["subtri_f64"] = entry("sub-triangular SpMV N=%d k=%d, fp64" % (w_["N"], w_["k"]), fms,
+                                               wl.accounting("subtri_f64", N=w_["N"], k=w_["k"]), "hbm")
+        del gP
+        w_ = dw["leslie"]
+        gR, gS, gx, gy = up64(w_["R"]), up64(w_["S"]), up64(w_["x"]), out64(w_["n"])
+        fms = beside(lambda: d.leslie_spmv_f64(w_["n"], gR, gS, gx, gy))
+        result["beside"]["leslie_f64"] = entry("Leslie SpMV n=%d, fp64" % w_["n"], fms,
+                                               wl.accounting("leslie_f64", n=w_["n"]), "hbm")
+        del gR, gS, dw
 
     if not args.no_cpu_baseline:
         import oracle

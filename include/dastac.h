@@ -221,8 +221,8 @@ int dastac_pr_a3_f32(int64_t N, int64_t d, const float *B, int64_t ldb, float *A
 /* ---- double precision (the paper's own element type, Section 6.1) ------------------------------
  * The same layouts, index polynomials, argument rules and error codes as the _f32 entry points of the
  * same name, on double operands (8-byte aligned).  Each output element is within 1e-12 * sum|products|
- * of the exactly rounded result.  trmv_f64 and tet_ttv_f64 need n <= 8192 (the vector is kept in LDS),
- * beyond that DASTAC_EOVERFLOW.  The matrix-core contractions (TRMM, SYMM, MTTKRP, TTM_UT, the
+ * of the exactly rounded result.  tet_ttv_f64 needs n <= 8192 (the vector is kept in LDS), beyond that
+ * DASTAC_EOVERFLOW; the products of one packed triangle take n <= 262144.  The matrix-core contractions (TRMM, SYMM, MTTKRP, TTM_UT, the
  * polynomial-regression tensors) run on the fp64 matrix cores; shapes and limits as their _f32 namesakes. */
 int dastac_pack_triu_f64(int64_t n, const double *dense, int64_t ld, double *packed, void *stream);
 int dastac_unpack_triu_f64(int64_t n, const double *packed, double *dense, int64_t ld, void *stream);
@@ -245,6 +245,24 @@ int dastac_tet_mttkrp_f64(int64_t n, int64_t R, const double *Ap, const double *
                           int64_t ldc, double *M, int64_t ldm, void *stream);
 int dastac_pr_a2_f64(int64_t N, int64_t d, const double *B, int64_t ldb, double *A2p, void *stream);
 int dastac_pr_a3_f64(int64_t N, int64_t d, const double *B, int64_t ldb, double *A3p, void *stream);
+int dastac_pack_tril_f64(int64_t n, const double *dense, int64_t ld, double *packed, void *stream);
+int dastac_unpack_tril_f64(int64_t n, const double *packed, double *dense, int64_t ld, void *stream);
+int dastac_symv_f64(int64_t n, const double *Up, const double *x, double *y, void *stream);
+int dastac_trmv_t_f64(int64_t n, const double *Up, const double *x, double *y, void *stream);
+int dastac_symv_lower_f64(int64_t n, const double *Lp, const double *x, double *y, void *stream);
+int dastac_trmv_lower_f64(int64_t n, const double *Lp, const double *x, double *y, void *stream);
+int dastac_trmv_lower_t_f64(int64_t n, const double *Lp, const double *x, double *y, void *stream);
+int dastac_pack_sband_f64(int64_t n, int64_t w, int64_t s, const double *dense, int64_t ld, double *diag_major,
+                          void *stream);
+int dastac_unpack_sband_f64(int64_t n, int64_t w, int64_t s, const double *diag_major, double *dense, int64_t ld,
+                            void *stream);
+int dastac_sband_spmv_f64(int64_t n, int64_t w, int64_t s, const double *D, const double *x, double *y, void *stream);
+int dastac_pack_subtri_f64(int64_t N, int64_t k, const double *dense, int64_t ld, double *packed, void *stream);
+int dastac_unpack_subtri_f64(int64_t N, int64_t k, const double *packed, double *dense, int64_t ld, void *stream);
+int dastac_subtri_spmv_f64(int64_t N, int64_t k, const double *Ap, const double *x, double *y, void *stream);
+int dastac_pack_leslie_f64(int64_t n, const double *dense, int64_t ld, double *R, double *S, void *stream);
+int dastac_unpack_leslie_f64(int64_t n, const double *R, const double *S, double *dense, int64_t ld, void *stream);
+int dastac_leslie_spmv_f64(int64_t n, const double *R, const double *S, const double *x, double *y, void *stream);
 
 #ifdef __cplusplus
 }

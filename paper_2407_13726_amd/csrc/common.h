@@ -23,6 +23,7 @@ DASTAC_HD int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // defined in trimv.hip
 int trmv_upper_by_panels(int64_t n, const float *Up, const float *x, float *y, void *stream);
+int trmv_upper_by_panels(int64_t n, const double *Up, const double *x, double *y, void *stream);
 
 #if defined(__HIPCC__)
 // 16-byte vector of floats that only promises 4-byte alignment: packed rows start at arbitrary

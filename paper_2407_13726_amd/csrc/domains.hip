@@ -28,17 +28,17 @@ inline unsigned grid_for(int64_t nblocks) { return (unsigned)(nblocks < (1 << 22
 // ---- strided band ---------------------------------------------------------------------------
 
 // W >= 0: half-width known at compile time; W < 0: run-time half-width `w`.  One row per lane.
-template <int W>
-__global__ __launch_bounds__(kBlock) void sband_kernel(int64_t n, int w, int64_t s, const float *__restrict__ D,
-                                                       const float *__restrict__ x, float *__restrict__ y) {
+template <int W, typename T>
+__global__ __launch_bounds__(kBlock) void sband_kernel(int64_t n, int w, int64_t s, const T *__restrict__ D,
+                                                       const T *__restrict__ x, T *__restrict__ y) {
   const int hw = W >= 0 ? W : w;
   const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i >= n) return;
-  const float *d = D + i;
+  const T *d = D + i;
   const int64_t reach = (int64_t)hw * s;
-  float acc = 0.0f;
+  T acc = T(0);
   if (i >= reach && i + reach < n) {  // interior row: every column exists
-    const float *xw = x + (i - reach);
+    const T *xw = x + (i - reach);
     if (W >= 0) {
 #pragma unroll
       for (int dd = 0; dd <= 2 * (W >= 0 ? W : 0); ++dd)
@@ -56,22 +56,24 @@ __global__ __launch_bounds__(kBlock) void sband_kernel(int64_t n, int w, int64_t
   __builtin_nontemporal_store(acc, y + i);
 }
 
+template <typename T>
 __global__ __launch_bounds__(kBlock) void pack_sband_kernel(int64_t n, int64_t w, int64_t s,
-                                                            const float *__restrict__ dense, int64_t ld,
-                                                            float *__restrict__ diag, int64_t pieces,
+                                                            const T *__restrict__ dense, int64_t ld,
+                                                            T *__restrict__ diag, int64_t pieces,
                                                             int64_t nblocks) {
   for (int64_t b = blockIdx.x; b < nblocks; b += gridDim.x) {
     const int64_t dw = b / pieces;  // d + w
     const int64_t i = (b - dw * pieces) * kBlock + threadIdx.x;
     if (i >= n) continue;
     const int64_t j = i + (dw - w) * s;
-    diag[dw * n + i] = (j >= 0 && j < n) ? dense[i * ld + j] : 0.0f;
+    diag[dw * n + i] = (j >= 0 && j < n) ? dense[i * ld + j] : T(0);
   }
 }
 
+template <typename T>
 __global__ __launch_bounds__(kBlock) void unpack_sband_kernel(int64_t n, int64_t w, int64_t s,
-                                                              const float *__restrict__ diag,
-                                                              float *__restrict__ dense, int64_t ld,
+                                                              const T *__restrict__ diag,
+                                                              T *__restrict__ dense, int64_t ld,
                                                               int64_t pieces, int64_t nblocks) {
   for (int64_t b = blockIdx.x; b < nblocks; b += gridDim.x) {
     const int64_t i = b / pieces;
@@ -79,40 +81,43 @@ __global__ __launch_bounds__(kBlock) void unpack_sband_kernel(int64_t n, int64_t
     if (j >= n) continue;
     const int64_t dj = j - i, d = dj / s;  // exact only on a stored diagonal
     const bool stored = d * s == dj && d >= -w && d <= w;
-    dense[i * ld + j] = stored ? diag[(d + w) * n + i] : 0.0f;
+    dense[i * ld + j] = stored ? diag[(d + w) * n + i] : T(0);
   }
 }
 
 // ---- sub-triangular -------------------------------------------------------------------------
 
-__global__ __launch_bounds__(kBlock) void unpack_subtri_kernel(int64_t N, int64_t k, const float *__restrict__ packed,
-                                                               float *__restrict__ dense, int64_t ld,
+template <typename T>
+__global__ __launch_bounds__(kBlock) void unpack_subtri_kernel(int64_t N, int64_t k, const T *__restrict__ packed,
+                                                               T *__restrict__ dense, int64_t ld,
                                                                int64_t pieces, int64_t nblocks) {
   for (int64_t b = blockIdx.x; b < nblocks; b += gridDim.x) {
     const int64_t i = b / pieces;
     const int64_t j = (b - i * pieces) * kBlock + threadIdx.x;
     if (j >= N) continue;
     const int64_t c = j - (N - k);  // column inside the k x k corner block
-    dense[i * ld + j] = (i < k && c >= i) ? packed[tri_offset(k, i, c)] : 0.0f;
+    dense[i * ld + j] = (i < k && c >= i) ? packed[tri_offset(k, i, c)] : T(0);
   }
 }
 
-__global__ __launch_bounds__(kBlock) void zero_tail_kernel(float *__restrict__ y, int64_t count) {
+template <typename T>
+__global__ __launch_bounds__(kBlock) void zero_tail_kernel(T *__restrict__ y, int64_t count) {
   const int64_t t = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (t < count) y[t] = 0.0f;
+  if (t < count) y[t] = T(0);
 }
 
 // ---- Leslie ---------------------------------------------------------------------------------
 
-__global__ __launch_bounds__(kBlock) void leslie_kernel(int64_t n, const float *__restrict__ R,
-                                                        const float *__restrict__ S, const float *__restrict__ x,
-                                                        float *__restrict__ y) {
-  __shared__ float part[kBlock / 64];
+template <typename T>
+__global__ __launch_bounds__(kBlock) void leslie_kernel(int64_t n, const T *__restrict__ R,
+                                                        const T *__restrict__ S, const T *__restrict__ x,
+                                                        T *__restrict__ y) {
+  __shared__ T part[kBlock / 64];
   const int64_t stride = (int64_t)gridDim.x * kBlock;
-  float acc = 0.0f;
+  T acc = T(0);
   int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   for (; j + 3 * stride < n; j += 4 * stride) {  // four independent rows in flight per lane
-    float xv[4], rv[4], sv[4];
+    T xv[4], rv[4], sv[4];
     const bool last = j + 3 * stride + 1 < n;  // only the fourth can be the row without a successor
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -121,7 +126,7 @@ __global__ __launch_bounds__(kBlock) void leslie_kernel(int64_t n, const float *
     }
 #pragma unroll
     for (int q = 0; q < 3; ++q) sv[q] = __builtin_nontemporal_load(S + j + q * stride);
-    sv[3] = last ? __builtin_nontemporal_load(S + j + 3 * stride) : 0.0f;
+    sv[3] = last ? __builtin_nontemporal_load(S + j + 3 * stride) : T(0);
 #pragma unroll
     for (int q = 0; q < 4; ++q) acc += rv[q] * xv[q];
 #pragma unroll
@@ -129,7 +134,7 @@ __global__ __launch_bounds__(kBlock) void leslie_kernel(int64_t n, const float *
     if (last) __builtin_nontemporal_store(sv[3] * xv[3], y + j + 3 * stride + 1);
   }
   for (; j < n; j += stride) {
-    const float xj = x[j];
+    const T xj = x[j];
     acc += __builtin_nontemporal_load(R + j) * xj;
     if (j + 1 < n) __builtin_nontemporal_store(__builtin_nontemporal_load(S + j) * xj, y + j + 1);
   }
@@ -137,29 +142,31 @@ __global__ __launch_bounds__(kBlock) void leslie_kernel(int64_t n, const float *
   if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
   __syncthreads();
   if (threadIdx.x == 0) {
-    float t = 0.0f;
+    T t = T(0);
     for (int v = 0; v < kBlock / 64; ++v) t += part[v];
     atomicAdd(y, t);  // y(0) was cleared by the launch before this one
   }
 }
 
-__global__ __launch_bounds__(kBlock) void pack_leslie_kernel(int64_t n, const float *__restrict__ dense, int64_t ld,
-                                                             float *__restrict__ R, float *__restrict__ S) {
+template <typename T>
+__global__ __launch_bounds__(kBlock) void pack_leslie_kernel(int64_t n, const T *__restrict__ dense, int64_t ld,
+                                                             T *__restrict__ R, T *__restrict__ S) {
   const int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (j >= n) return;
   R[j] = dense[j];
   if (j + 1 < n) S[j] = dense[(j + 1) * ld + j];
 }
 
-__global__ __launch_bounds__(kBlock) void unpack_leslie_kernel(int64_t n, const float *__restrict__ R,
-                                                               const float *__restrict__ S,
-                                                               float *__restrict__ dense, int64_t ld, int64_t pieces,
+template <typename T>
+__global__ __launch_bounds__(kBlock) void unpack_leslie_kernel(int64_t n, const T *__restrict__ R,
+                                                               const T *__restrict__ S,
+                                                               T *__restrict__ dense, int64_t ld, int64_t pieces,
                                                                int64_t nblocks) {
   for (int64_t b = blockIdx.x; b < nblocks; b += gridDim.x) {
     const int64_t i = b / pieces;
     const int64_t j = (b - i * pieces) * kBlock + threadIdx.x;
     if (j >= n) continue;
-    dense[i * ld + j] = i == 0 ? R[j] : (j == i - 1 ? S[j] : 0.0f);
+    dense[i * ld + j] = i == 0 ? R[j] : (j == i - 1 ? S[j] : T(0));
   }
 }
 
@@ -168,6 +175,158 @@ int check_sband(int64_t n, int64_t w, int64_t s) {
   if (s > ((int64_t)1 << 40)) return DASTAC_EOVERFLOW;
   return DASTAC_OK;
 }
+// the packed upper-triangular entry points of either precision
+inline int pack_triu(int64_t n, const float *d, int64_t ld, float *p, void *st) {
+  return dastac_pack_triu_f32(n, d, ld, p, st);
+}
+inline int pack_triu(int64_t n, const double *d, int64_t ld, double *p, void *st) {
+  return dastac_pack_triu_f64(n, d, ld, p, st);
+}
+inline int trmv(int64_t n, const float *U, const float *x, float *y, void *st) {
+  return dastac_trmv_f32(n, U, x, y, st);
+}
+inline int trmv(int64_t n, const double *U, const double *x, double *y, void *st) {
+  return dastac_trmv_f64(n, U, x, y, st);
+}
+
+template <typename T>
+int pack_sband(int64_t n, int64_t w, int64_t s, const T *dense, int64_t ld, T *diag_major, void *stream) {
+  constexpr int64_t kB = (int64_t)sizeof(T);
+  if (int rc = check_sband(n, w, s)) return rc;
+  if (ld < n) return DASTAC_EINVAL;
+  if (n > kDenseMaxN || w > kDenseMaxN) return DASTAC_EOVERFLOW;
+  if (n == 0) return DASTAC_OK;
+  if (!dense || !diag_major) return DASTAC_ENULL;
+  if (overlaps(dense, n * ld * kB, diag_major, (2 * w + 1) * n * kB)) return DASTAC_EALIAS;
+  const int64_t pieces = ceil_div(n, kBlock), nblocks = (2 * w + 1) * pieces;
+  pack_sband_kernel<T><<<grid_for(nblocks), kBlock, 0, (hipStream_t)stream>>>(n, w, s, dense, ld, diag_major, pieces,
+                                                                           nblocks);
+  return launch_status();
+}
+
+template <typename T>
+int unpack_sband(int64_t n, int64_t w, int64_t s, const T *diag_major, T *dense, int64_t ld, void *stream) {
+  constexpr int64_t kB = (int64_t)sizeof(T);
+  if (int rc = check_sband(n, w, s)) return rc;
+  if (ld < n) return DASTAC_EINVAL;
+  if (n > kDenseMaxN || w > kDenseMaxN) return DASTAC_EOVERFLOW;
+  if (n == 0) return DASTAC_OK;
+  if (!dense || !diag_major) return DASTAC_ENULL;
+  if (overlaps(dense, n * ld * kB, diag_major, (2 * w + 1) * n * kB)) return DASTAC_EALIAS;
+  const int64_t pieces = ceil_div(n, kBlock), nblocks = n * pieces;
+  unpack_sband_kernel<T><<<grid_for(nblocks), kBlock, 0, (hipStream_t)stream>>>(n, w, s, diag_major, dense, ld, pieces,
+                                                                             nblocks);
+  return launch_status();
+}
+
+template <typename T>
+int sband_spmv(int64_t n, int64_t w, int64_t s, const T *D, const T *x, T *y, void *stream) {
+  constexpr int64_t kB = (int64_t)sizeof(T);
+  if (int rc = check_sband(n, w, s)) return rc;
+  if (w > 64) return DASTAC_EINVAL;
+  if (n > ((int64_t)1 << 40) / (2 * w + 1)) return DASTAC_EOVERFLOW;
+  if (n == 0) return DASTAC_OK;
+  if (!D || !x || !y) return DASTAC_ENULL;
+  if (overlaps(y, n * kB, D, (2 * w + 1) * n * kB) || overlaps(y, n * kB, x, n * kB)) return DASTAC_EALIAS;
+  hipStream_t st = (hipStream_t)stream;
+  const unsigned blocks = (unsigned)ceil_div(n, kBlock);
+  if (w == 1)
+    sband_kernel<1, T><<<blocks, kBlock, 0, st>>>(n, 1, s, D, x, y);
+  else
+    sband_kernel<-1, T><<<blocks, kBlock, 0, st>>>(n, (int)w, s, D, x, y);
+  return launch_status();
+}
+
+template <typename T>
+int pack_subtri(int64_t N, int64_t k, const T *dense, int64_t ld, T *packed, void *stream) {
+  constexpr int64_t kB = (int64_t)sizeof(T);
+  if (N < 0 || k < 0 || k > N || ld < N) return DASTAC_EINVAL;
+  if (N > kDenseMaxN) return DASTAC_EOVERFLOW;
+  if (k == 0) return DASTAC_OK;
+  if (!dense || !packed) return DASTAC_ENULL;
+  if (overlaps(dense, N * ld * kB, packed, tri(k) * kB)) return DASTAC_EALIAS;
+  // the unique set is the upper triangle of the k x k block whose first column is N-k
+  return pack_triu(k, dense + (N - k), ld, packed, stream);
+}
+
+template <typename T>
+int unpack_subtri(int64_t N, int64_t k, const T *packed, T *dense, int64_t ld, void *stream) {
+  constexpr int64_t kB = (int64_t)sizeof(T);
+  if (N < 0 || k < 0 || k > N || ld < N) return DASTAC_EINVAL;
+  if (N > kDenseMaxN) return DASTAC_EOVERFLOW;
+  if (N == 0) return DASTAC_OK;
+  if (!dense || (k > 0 && !packed)) return DASTAC_ENULL;
+  if (overlaps(dense, N * ld * kB, packed, tri(k) * kB)) return DASTAC_EALIAS;
+  const int64_t pieces = ceil_div(N, kBlock), nblocks = N * pieces;
+  unpack_subtri_kernel<T><<<grid_for(nblocks), kBlock, 0, (hipStream_t)stream>>>(N, k, packed, dense, ld, pieces,
+                                                                              nblocks);
+  return launch_status();
+}
+
+template <typename T>
+int subtri_spmv(int64_t N, int64_t k, const T *Ap, const T *x, T *y, void *stream) {
+  constexpr int64_t kB = (int64_t)sizeof(T);
+  if (N < 0 || k < 0 || k > N) return DASTAC_EINVAL;
+  if (N > ((int64_t)1 << 40)) return DASTAC_EOVERFLOW;
+  if (N == 0) return DASTAC_OK;
+  if (!x || !y || (k > 0 && !Ap)) return DASTAC_ENULL;
+  if (overlaps(y, N * kB, x, N * kB) || overlaps(y, N * kB, Ap, tri(k) * kB)) return DASTAC_EALIAS;
+  if (k > 0) {
+    const int rc = trmv(k, Ap, x + (N - k), y, stream);  // also bounds k
+    if (rc != DASTAC_OK) return rc;
+  }
+  if (k < N) {
+    zero_tail_kernel<T><<<(unsigned)ceil_div(N - k, kBlock), kBlock, 0, (hipStream_t)stream>>>(y + k, N - k);
+    return launch_status();
+  }
+  return DASTAC_OK;
+}
+
+template <typename T>
+int pack_leslie(int64_t n, const T *dense, int64_t ld, T *R, T *S, void *stream) {
+  constexpr int64_t kB = (int64_t)sizeof(T);
+  if (n < 0 || ld < n) return DASTAC_EINVAL;
+  if (n > kDenseMaxN) return DASTAC_EOVERFLOW;
+  if (n == 0) return DASTAC_OK;
+  if (!dense || !R || (n > 1 && !S)) return DASTAC_ENULL;
+  if (overlaps(dense, n * ld * kB, R, n * kB) || overlaps(dense, n * ld * kB, S, (n - 1) * kB) ||
+      overlaps(R, n * kB, S, (n - 1) * kB))
+    return DASTAC_EALIAS;
+  pack_leslie_kernel<T><<<(unsigned)ceil_div(n, kBlock), kBlock, 0, (hipStream_t)stream>>>(n, dense, ld, R, S);
+  return launch_status();
+}
+
+template <typename T>
+int unpack_leslie(int64_t n, const T *R, const T *S, T *dense, int64_t ld, void *stream) {
+  constexpr int64_t kB = (int64_t)sizeof(T);
+  if (n < 0 || ld < n) return DASTAC_EINVAL;
+  if (n > kDenseMaxN) return DASTAC_EOVERFLOW;
+  if (n == 0) return DASTAC_OK;
+  if (!dense || !R || (n > 1 && !S)) return DASTAC_ENULL;
+  if (overlaps(dense, n * ld * kB, R, n * kB) || overlaps(dense, n * ld * kB, S, (n - 1) * kB)) return DASTAC_EALIAS;
+  const int64_t pieces = ceil_div(n, kBlock), nblocks = n * pieces;
+  unpack_leslie_kernel<T><<<grid_for(nblocks), kBlock, 0, (hipStream_t)stream>>>(n, R, S, dense, ld, pieces, nblocks);
+  return launch_status();
+}
+
+template <typename T>
+int leslie_spmv(int64_t n, const T *R, const T *S, const T *x, T *y, void *stream) {
+  constexpr int64_t kB = (int64_t)sizeof(T);
+  if (n < 0) return DASTAC_EINVAL;
+  if (n > ((int64_t)1 << 40)) return DASTAC_EOVERFLOW;
+  if (n == 0) return DASTAC_OK;
+  if (!R || !x || !y || (n > 1 && !S)) return DASTAC_ENULL;
+  if (overlaps(y, n * kB, x, n * kB) || overlaps(y, n * kB, R, n * kB) || overlaps(y, n * kB, S, (n - 1) * kB))
+    return DASTAC_EALIAS;
+  hipStream_t st = (hipStream_t)stream;
+  zero_tail_kernel<T><<<1, kBlock, 0, st>>>(y, 1);
+  if (hipGetLastError() != hipSuccess) return DASTAC_EHIP;
+  const int64_t want = ceil_div(n, 4 * kBlock);  // about four rows per lane before the cap
+  const unsigned blocks = (unsigned)(want < 1 ? 1 : want > kLeslieMaxBlocks ? kLeslieMaxBlocks : want);
+  leslie_kernel<T><<<blocks, kBlock, 0, st>>>(n, R, S, x, y);
+  return launch_status();
+}
+
 
 }  // namespace
 
@@ -180,124 +339,62 @@ int64_t dastac_subtri_offset(int64_t N, int64_t k, int64_t i, int64_t j) {
 
 int dastac_pack_sband_f32(int64_t n, int64_t w, int64_t s, const float *dense, int64_t ld, float *diag_major,
                           void *stream) {
-  if (int rc = check_sband(n, w, s)) return rc;
-  if (ld < n) return DASTAC_EINVAL;
-  if (n > kDenseMaxN || w > kDenseMaxN) return DASTAC_EOVERFLOW;
-  if (n == 0) return DASTAC_OK;
-  if (!dense || !diag_major) return DASTAC_ENULL;
-  if (overlaps(dense, n * ld * 4, diag_major, (2 * w + 1) * n * 4)) return DASTAC_EALIAS;
-  const int64_t pieces = ceil_div(n, kBlock), nblocks = (2 * w + 1) * pieces;
-  pack_sband_kernel<<<grid_for(nblocks), kBlock, 0, (hipStream_t)stream>>>(n, w, s, dense, ld, diag_major, pieces,
-                                                                           nblocks);
-  return launch_status();
+  return pack_sband<float>(n, w, s, dense, ld, diag_major, stream);
 }
-
 int dastac_unpack_sband_f32(int64_t n, int64_t w, int64_t s, const float *diag_major, float *dense, int64_t ld,
                             void *stream) {
-  if (int rc = check_sband(n, w, s)) return rc;
-  if (ld < n) return DASTAC_EINVAL;
-  if (n > kDenseMaxN || w > kDenseMaxN) return DASTAC_EOVERFLOW;
-  if (n == 0) return DASTAC_OK;
-  if (!dense || !diag_major) return DASTAC_ENULL;
-  if (overlaps(dense, n * ld * 4, diag_major, (2 * w + 1) * n * 4)) return DASTAC_EALIAS;
-  const int64_t pieces = ceil_div(n, kBlock), nblocks = n * pieces;
-  unpack_sband_kernel<<<grid_for(nblocks), kBlock, 0, (hipStream_t)stream>>>(n, w, s, diag_major, dense, ld, pieces,
-                                                                             nblocks);
-  return launch_status();
+  return unpack_sband<float>(n, w, s, diag_major, dense, ld, stream);
 }
-
 int dastac_sband_spmv_f32(int64_t n, int64_t w, int64_t s, const float *D, const float *x, float *y, void *stream) {
-  if (int rc = check_sband(n, w, s)) return rc;
-  if (w > 64) return DASTAC_EINVAL;
-  if (n > ((int64_t)1 << 40) / (2 * w + 1)) return DASTAC_EOVERFLOW;
-  if (n == 0) return DASTAC_OK;
-  if (!D || !x || !y) return DASTAC_ENULL;
-  if (overlaps(y, n * 4, D, (2 * w + 1) * n * 4) || overlaps(y, n * 4, x, n * 4)) return DASTAC_EALIAS;
-  hipStream_t st = (hipStream_t)stream;
-  const unsigned blocks = (unsigned)ceil_div(n, kBlock);
-  if (w == 1)
-    sband_kernel<1><<<blocks, kBlock, 0, st>>>(n, 1, s, D, x, y);
-  else
-    sband_kernel<-1><<<blocks, kBlock, 0, st>>>(n, (int)w, s, D, x, y);
-  return launch_status();
+  return sband_spmv<float>(n, w, s, D, x, y, stream);
 }
-
 int dastac_pack_subtri_f32(int64_t N, int64_t k, const float *dense, int64_t ld, float *packed, void *stream) {
-  if (N < 0 || k < 0 || k > N || ld < N) return DASTAC_EINVAL;
-  if (N > kDenseMaxN) return DASTAC_EOVERFLOW;
-  if (k == 0) return DASTAC_OK;
-  if (!dense || !packed) return DASTAC_ENULL;
-  if (overlaps(dense, N * ld * 4, packed, tri(k) * 4)) return DASTAC_EALIAS;
-  // the unique set is the upper triangle of the k x k block whose first column is N-k
-  return dastac_pack_triu_f32(k, dense + (N - k), ld, packed, stream);
+  return pack_subtri<float>(N, k, dense, ld, packed, stream);
 }
-
 int dastac_unpack_subtri_f32(int64_t N, int64_t k, const float *packed, float *dense, int64_t ld, void *stream) {
-  if (N < 0 || k < 0 || k > N || ld < N) return DASTAC_EINVAL;
-  if (N > kDenseMaxN) return DASTAC_EOVERFLOW;
-  if (N == 0) return DASTAC_OK;
-  if (!dense || (k > 0 && !packed)) return DASTAC_ENULL;
-  if (overlaps(dense, N * ld * 4, packed, tri(k) * 4)) return DASTAC_EALIAS;
-  const int64_t pieces = ceil_div(N, kBlock), nblocks = N * pieces;
-  unpack_subtri_kernel<<<grid_for(nblocks), kBlock, 0, (hipStream_t)stream>>>(N, k, packed, dense, ld, pieces,
-                                                                              nblocks);
-  return launch_status();
+  return unpack_subtri<float>(N, k, packed, dense, ld, stream);
 }
-
 int dastac_subtri_spmv_f32(int64_t N, int64_t k, const float *Ap, const float *x, float *y, void *stream) {
-  if (N < 0 || k < 0 || k > N) return DASTAC_EINVAL;
-  if (N > ((int64_t)1 << 40)) return DASTAC_EOVERFLOW;
-  if (N == 0) return DASTAC_OK;
-  if (!x || !y || (k > 0 && !Ap)) return DASTAC_ENULL;
-  if (overlaps(y, N * 4, x, N * 4) || overlaps(y, N * 4, Ap, tri(k) * 4)) return DASTAC_EALIAS;
-  if (k > 0) {
-    const int rc = dastac_trmv_f32(k, Ap, x + (N - k), y, stream);  // also bounds k
-    if (rc != DASTAC_OK) return rc;
-  }
-  if (k < N) {
-    zero_tail_kernel<<<(unsigned)ceil_div(N - k, kBlock), kBlock, 0, (hipStream_t)stream>>>(y + k, N - k);
-    return launch_status();
-  }
-  return DASTAC_OK;
+  return subtri_spmv<float>(N, k, Ap, x, y, stream);
 }
-
 int dastac_pack_leslie_f32(int64_t n, const float *dense, int64_t ld, float *R, float *S, void *stream) {
-  if (n < 0 || ld < n) return DASTAC_EINVAL;
-  if (n > kDenseMaxN) return DASTAC_EOVERFLOW;
-  if (n == 0) return DASTAC_OK;
-  if (!dense || !R || (n > 1 && !S)) return DASTAC_ENULL;
-  if (overlaps(dense, n * ld * 4, R, n * 4) || overlaps(dense, n * ld * 4, S, (n - 1) * 4) ||
-      overlaps(R, n * 4, S, (n - 1) * 4))
-    return DASTAC_EALIAS;
-  pack_leslie_kernel<<<(unsigned)ceil_div(n, kBlock), kBlock, 0, (hipStream_t)stream>>>(n, dense, ld, R, S);
-  return launch_status();
+  return pack_leslie<float>(n, dense, ld, R, S, stream);
 }
-
 int dastac_unpack_leslie_f32(int64_t n, const float *R, const float *S, float *dense, int64_t ld, void *stream) {
-  if (n < 0 || ld < n) return DASTAC_EINVAL;
-  if (n > kDenseMaxN) return DASTAC_EOVERFLOW;
-  if (n == 0) return DASTAC_OK;
-  if (!dense || !R || (n > 1 && !S)) return DASTAC_ENULL;
-  if (overlaps(dense, n * ld * 4, R, n * 4) || overlaps(dense, n * ld * 4, S, (n - 1) * 4)) return DASTAC_EALIAS;
-  const int64_t pieces = ceil_div(n, kBlock), nblocks = n * pieces;
-  unpack_leslie_kernel<<<grid_for(nblocks), kBlock, 0, (hipStream_t)stream>>>(n, R, S, dense, ld, pieces, nblocks);
-  return launch_status();
+  return unpack_leslie<float>(n, R, S, dense, ld, stream);
+}
+int dastac_leslie_spmv_f32(int64_t n, const float *R, const float *S, const float *x, float *y, void *stream) {
+  return leslie_spmv<float>(n, R, S, x, y, stream);
 }
 
-int dastac_leslie_spmv_f32(int64_t n, const float *R, const float *S, const float *x, float *y, void *stream) {
-  if (n < 0) return DASTAC_EINVAL;
-  if (n > ((int64_t)1 << 40)) return DASTAC_EOVERFLOW;
-  if (n == 0) return DASTAC_OK;
-  if (!R || !x || !y || (n > 1 && !S)) return DASTAC_ENULL;
-  if (overlaps(y, n * 4, x, n * 4) || overlaps(y, n * 4, R, n * 4) || overlaps(y, n * 4, S, (n - 1) * 4))
-    return DASTAC_EALIAS;
-  hipStream_t st = (hipStream_t)stream;
-  zero_tail_kernel<<<1, kBlock, 0, st>>>(y, 1);
-  if (hipGetLastError() != hipSuccess) return DASTAC_EHIP;
-  const int64_t want = ceil_div(n, 4 * kBlock);  // about four rows per lane before the cap
-  const unsigned blocks = (unsigned)(want < 1 ? 1 : want > kLeslieMaxBlocks ? kLeslieMaxBlocks : want);
-  leslie_kernel<<<blocks, kBlock, 0, st>>>(n, R, S, x, y);
-  return launch_status();
+int dastac_pack_sband_f64(int64_t n, int64_t w, int64_t s, const double *dense, int64_t ld, double *diag_major,
+                          void *stream) {
+  return pack_sband<double>(n, w, s, dense, ld, diag_major, stream);
+}
+int dastac_unpack_sband_f64(int64_t n, int64_t w, int64_t s, const double *diag_major, double *dense, int64_t ld,
+                            void *stream) {
+  return unpack_sband<double>(n, w, s, diag_major, dense, ld, stream);
+}
+int dastac_sband_spmv_f64(int64_t n, int64_t w, int64_t s, const double *D, const double *x, double *y, void *stream) {
+  return sband_spmv<double>(n, w, s, D, x, y, stream);
+}
+int dastac_pack_subtri_f64(int64_t N, int64_t k, const double *dense, int64_t ld, double *packed, void *stream) {
+  return pack_subtri<double>(N, k, dense, ld, packed, stream);
+}
+int dastac_unpack_subtri_f64(int64_t N, int64_t k, const double *packed, double *dense, int64_t ld, void *stream) {
+  return unpack_subtri<double>(N, k, packed, dense, ld, stream);
+}
+int dastac_subtri_spmv_f64(int64_t N, int64_t k, const double *Ap, const double *x, double *y, void *stream) {
+  return subtri_spmv<double>(N, k, Ap, x, y, stream);
+}
+int dastac_pack_leslie_f64(int64_t n, const double *dense, int64_t ld, double *R, double *S, void *stream) {
+  return pack_leslie<double>(n, dense, ld, R, S, stream);
+}
+int dastac_unpack_leslie_f64(int64_t n, const double *R, const double *S, double *dense, int64_t ld, void *stream) {
+  return unpack_leslie<double>(n, R, S, dense, ld, stream);
+}
+int dastac_leslie_spmv_f64(int64_t n, const double *R, const double *S, const double *x, double *y, void *stream) {
+  return leslie_spmv<double>(n, R, S, x, y, stream);
 }
 
 }  // extern "C"

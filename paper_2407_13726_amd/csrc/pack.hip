@@ -44,9 +44,9 @@ __global__ __launch_bounds__(kBlock) void unpack_triu_kernel(int64_t n, const T 
 }
 
 // lower triangle: row i holds columns 0..i, starting at i(i+1)/2 (Section 4, worked example)
-template <bool PACK>
-__global__ __launch_bounds__(kBlock) void tril_copy_kernel(int64_t n, const float *__restrict__ src,
-                                                           float *__restrict__ dst, int64_t ld, int64_t pieces,
+template <bool PACK, typename T>
+__global__ __launch_bounds__(kBlock) void tril_copy_kernel(int64_t n, const T *__restrict__ src,
+                                                           T *__restrict__ dst, int64_t ld, int64_t pieces,
                                                            int64_t nblocks) {
   for (int64_t b = blockIdx.x; b < nblocks; b += gridDim.x) {
     int64_t i, c0;
@@ -57,7 +57,7 @@ __global__ __launch_bounds__(kBlock) void tril_copy_kernel(int64_t n, const floa
     if (PACK) {
       if (j <= i) dst[at] = src[i * ld + j];
     } else {
-      dst[i * ld + j] = (j <= i) ? src[at] : 0.0f;
+      dst[i * ld + j] = (j <= i) ? src[at] : T(0);
     }
   }
 }
@@ -202,6 +202,20 @@ int unpack_band(int64_t n, int64_t w, const T *diag_major, T *dense, int64_t ld,
   return launch_status();
 }
 
+// PACK: src is the dense matrix (row stride ld), dst the packed lower triangle; else the reverse
+template <bool PACK, typename T>
+int tril_copy(int64_t n, const T *src, T *dst, int64_t ld, void *stream) {
+  if (n < 0 || ld < n) return DASTAC_EINVAL;
+  if (n > kDenseMaxN) return DASTAC_EOVERFLOW;
+  if (n == 0) return DASTAC_OK;
+  if (!src || !dst) return DASTAC_ENULL;
+  const int64_t dense_bytes = n * ld * (int64_t)sizeof(T), packed_bytes = tri(n) * (int64_t)sizeof(T);
+  if (overlaps(src, PACK ? dense_bytes : packed_bytes, dst, PACK ? packed_bytes : dense_bytes)) return DASTAC_EALIAS;
+  int64_t pieces = ceil_div(n, kBlock), nblocks = n * pieces;
+  tril_copy_kernel<PACK, T><<<grid_for(nblocks), kBlock, 0, (hipStream_t)stream>>>(n, src, dst, ld, pieces, nblocks);
+  return launch_status();
+}
+
 }  // namespace
 
 extern "C" {
@@ -255,25 +269,19 @@ int dastac_unpack_band_f64(int64_t n, int64_t w, const double *diag_major, doubl
 }
 
 int dastac_pack_tril_f32(int64_t n, const float *dense, int64_t ld, float *packed, void *stream) {
-  if (n < 0 || ld < n) return DASTAC_EINVAL;
-  if (n > kDenseMaxN) return DASTAC_EOVERFLOW;
-  if (n == 0) return DASTAC_OK;
-  if (!dense || !packed) return DASTAC_ENULL;
-  if (overlaps(packed, tri(n) * 4, dense, n * ld * 4)) return DASTAC_EALIAS;
-  int64_t pieces = ceil_div(n, kBlock), nblocks = n * pieces;
-  tril_copy_kernel<true><<<grid_for(nblocks), kBlock, 0, (hipStream_t)stream>>>(n, dense, packed, ld, pieces, nblocks);
-  return launch_status();
+  return tril_copy<true, float>(n, dense, packed, ld, stream);
+}
+
+int dastac_pack_tril_f64(int64_t n, const double *dense, int64_t ld, double *packed, void *stream) {
+  return tril_copy<true, double>(n, dense, packed, ld, stream);
 }
 
 int dastac_unpack_tril_f32(int64_t n, const float *packed, float *dense, int64_t ld, void *stream) {
-  if (n < 0 || ld < n) return DASTAC_EINVAL;
-  if (n > kDenseMaxN) return DASTAC_EOVERFLOW;
-  if (n == 0) return DASTAC_OK;
-  if (!dense || !packed) return DASTAC_ENULL;
-  if (overlaps(dense, n * ld * 4, packed, tri(n) * 4)) return DASTAC_EALIAS;
-  int64_t pieces = ceil_div(n, kBlock), nblocks = n * pieces;
-  tril_copy_kernel<false><<<grid_for(nblocks), kBlock, 0, (hipStream_t)stream>>>(n, packed, dense, ld, pieces, nblocks);
-  return launch_status();
+  return tril_copy<false, float>(n, packed, dense, ld, stream);
+}
+
+int dastac_unpack_tril_f64(int64_t n, const double *packed, double *dense, int64_t ld, void *stream) {
+  return tril_copy<false, double>(n, packed, dense, ld, stream);
 }
 
 }  // extern "C"

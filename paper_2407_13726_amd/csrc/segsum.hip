@@ -438,11 +438,12 @@ int dastac_tet_ttv_f32(int64_t n, const float *Ap, const float *v, float *Mp, vo
 // Double precision (the paper's element type): the same kernel with 16-byte pieces of two elements.
 int dastac_trmv_f64(int64_t n, const double *Up, const double *x, double *y, void *stream) {
   if (n < 0) return DASTAC_EINVAL;
-  if (n > kLdsMaxN) return DASTAC_EOVERFLOW;  // x must fit in LDS; there is no column-panel kernel in double
+  if (n > DASTAC_TRI_MAX_N || tri(n) > ((int64_t)1 << 40)) return DASTAC_EOVERFLOW;
   if (n == 0) return DASTAC_OK;
   if (!Up || !x || !y) return DASTAC_ENULL;
   if (overlaps(y, n * 8, Up, tri(n) * 8) || overlaps(y, n * 8, x, n * 8)) return DASTAC_EALIAS;
-  return launch_lds<double, false>(n, Up, x, y, tri(n), stream);
+  if (n <= kLdsMaxN) return launch_lds<double, false>(n, Up, x, y, tri(n), stream);
+  return trmv_upper_by_panels(n, Up, x, y, stream);  // x no longer fits in LDS
 }
 
 int dastac_tet_ttv_f64(int64_t n, const double *Ap, const double *v, double *Mp, void *stream) {

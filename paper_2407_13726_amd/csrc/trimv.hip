@@ -12,10 +12,11 @@
 // i/2 + i^2/2 + j is the row base used here).  The packed buffer is read once; an element U(i,j)
 // gives U x(j) to the row sum of i and U x(i) to the column sum of j from the same registers.
 //
-// Work split.  The triangle is cut into column panels of kW = 256*NQ columns, and the rows that
+// Work split.  A lane's load is one 16-byte piece: P = 4 single-precision or 2 double-precision
+// elements.  The triangle is cut into column panels of kW = 64*P*NQ columns, and the rows that
 // reach a panel into chunks of R consecutive rows; a wavefront owns one (panel, chunk) pair, and the
 // four wavefronts of a workgroup own four consecutive chunks of one panel.  Lane l is tied to the same
-// 4*NQ columns of the panel for the whole chunk (columns c0+4l+256q .. +3), so
+// P*NQ columns of the panel for the whole chunk (columns c0+P*l+64*P*q .. +P-1), so
 //   * the x values of its columns sit in registers (no LDS, no per-row lookup),
 //   * the column sums  sum_i T(i,c) x(i)  accumulate in registers; at the end the four wavefronts add
 //     theirs up through LDS and the workgroup issues ONE atomic add per column (atomics on one
@@ -43,13 +44,41 @@ constexpr int kMaxN = 524288;  // 512 panels of 1024 columns; such a triangle is
 
 enum { MODE_ROWS = 0, MODE_COLS = 1, MODE_SYM = 2 };
 
+typedef double d2u __attribute__((ext_vector_type(2), aligned(8)));
+typedef double d2a __attribute__((ext_vector_type(2)));
+
+// Per element type: elements in a 16-byte piece, and the piece as a register vector and as a
+// load type that only promises the element's own alignment.
+template <typename T>
+struct Piece;
+template <>
+struct Piece<float> {
+  static constexpr int kPer = 4;
+  typedef f4a vec;
+  typedef f4u uvec;
+};
+template <>
+struct Piece<double> {
+  static constexpr int kPer = 2;
+  typedef d2a vec;
+  typedef d2u uvec;
+};
+
 template <int CTRL>
 __device__ inline float dpp_add(float v) {
   int t = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false);
   return v + __builtin_bit_cast(float, t);
 }
+template <int CTRL>
+__device__ inline double dpp_add(double v) {  // the two halves of a double travel separately
+  const uint64_t b = __builtin_bit_cast(uint64_t, v);
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)b, CTRL, 0xf, 0xf, false);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(b >> 32), CTRL, 0xf, 0xf, false);
+  return v + __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
 // sum over the 64 lanes; every lane receives the total
-__device__ inline float wave_sum(float v) {
+template <typename T>
+__device__ inline T wave_sum(T v) {
   v = dpp_add<0xB1>(v);   // quad_perm [1,0,3,2]
   v = dpp_add<0x4E>(v);   // quad_perm [2,3,0,1]
   v = dpp_add<0x141>(v);  // row_half_mirror
@@ -75,13 +104,16 @@ DASTAC_HD void panel_rows(int64_t n, int64_t c0, int64_t kW, int64_t &lo, int64_
   }
 }
 
-template <int NQ, bool LOWER, int MODE>
-__global__ __launch_bounds__(kBlock) void trimv_kernel(int n, const float *__restrict__ T,
-                                                       const float *__restrict__ x, float *__restrict__ y,
+template <typename E, int NQ, bool LOWER, int MODE>
+__global__ __launch_bounds__(kBlock) void trimv_kernel(int n, const E *__restrict__ T,
+                                                       const E *__restrict__ x, E *__restrict__ y,
                                                        int R, int npanels, Panels pn) {
-  constexpr int kW = 256 * NQ;
+  constexpr int P = Piece<E>::kPer;
+  typedef typename Piece<E>::vec vec;
+  typedef typename Piece<E>::uvec uvec;
+  constexpr int kW = 64 * P * NQ;
   constexpr bool ROWS = MODE != MODE_COLS, COLS = MODE != MODE_ROWS;
-  __shared__ float cs[kWavesPerBlock][kW];  // the wavefronts' column sums
+  __shared__ E cs[kWavesPerBlock][kW];  // the wavefronts' column sums
   const int lane = threadIdx.x & 63, wave = uniform32(threadIdx.x >> 6);
   int p = 0;
   while ((int)blockIdx.x >= pn.first[p + 1]) ++p;  // wave-uniform, at most kMaxPanels steps
@@ -97,28 +129,28 @@ __global__ __launch_bounds__(kBlock) void trimv_kernel(int n, const float *__res
   // column every row has -- n-1 in an upper triangle, 0 in a lower one -- and masked)
   int col[NQ];
   unsigned voff[NQ];
-  f4a xv[NQ], acc[NQ];
+  vec xv[NQ], acc[NQ];
 #pragma unroll
   for (int q = 0; q < NQ; ++q) {
-    col[q] = c0 + 4 * lane + 256 * q;
-    voff[q] = 4u * (unsigned)(col[q] < n ? col[q] : LOWER ? 0 : n - 1);
-    float e[4];
+    col[q] = c0 + P * lane + 64 * P * q;
+    voff[q] = (unsigned)sizeof(E) * (unsigned)(col[q] < n ? col[q] : LOWER ? 0 : n - 1);
 #pragma unroll
-    for (int t = 0; t < 4; ++t) e[t] = col[q] + t < n ? x[col[q] + t] : 0.0f;
-    xv[q] = f4a{e[0], e[1], e[2], e[3]};
-    acc[q] = f4a{0.0f, 0.0f, 0.0f, 0.0f};
+    for (int t = 0; t < P; ++t) {
+      xv[q][t] = col[q] + t < n ? x[col[q] + t] : E(0);
+      acc[q][t] = E(0);
+    }
   }
 
   struct Row {
-    f4a a[NQ];
-    float xi;
+    vec a[NQ];
+    E xi;
   };
   // element (i,c) of the triangle is at T[row_base(i) + c]
   auto row_base = [&](int i) -> int64_t {
     return LOWER ? ((int64_t)i * (i + 1)) / 2 : tri_row_start((int64_t)n, (int64_t)i) - i;
   };
-  // A 16-byte load may start on the last elements of a row and run up to three elements past its
-  // end, into the next rows.  Only the last two rows of the buffer have fewer than three elements
+  // A 16-byte load may start on the last elements of a row and run up to P-1 <= 3 elements past its
+  // end, into the next rows.  Only the last two rows of the buffer can have fewer than three elements
   // behind them: they take bounds-tested scalar loads.
   auto load_row = [&](int i, Row &r) {
     const int ii = i < r1 ? i : r1 - 1;  // past the end of the chunk: a repeat that is never used
@@ -126,29 +158,27 @@ __global__ __launch_bounds__(kBlock) void trimv_kernel(int n, const float *__res
     r.xi = x[ii];
     if (ii + 2 < n) {
 #pragma unroll
-      for (int q = 0; q < NQ; ++q) r.a[q] = *reinterpret_cast<const f4u *>(base + voff[q]);
+      for (int q = 0; q < NQ; ++q) r.a[q] = *reinterpret_cast<const uvec *>(base + voff[q]);
     } else {
-      const float *rp = T + row_base(ii);
+      const E *rp = T + row_base(ii);
 #pragma unroll
       for (int q = 0; q < NQ; ++q) {
-        float e[4];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
+        for (int t = 0; t < P; ++t) {
           const int c = col[q] + t;
-          e[t] = (LOWER ? c <= ii : (c >= ii && c < n)) ? rp[c] : 0.0f;
+          r.a[q][t] = (LOWER ? c <= ii : (c >= ii && c < n)) ? rp[c] : E(0);
         }
-        r.a[q] = f4a{e[0], e[1], e[2], e[3]};
       }
     }
   };
 
-  float rowacc = 0.0f;  // lane (i - r0) % 64 parks the sum of row i
+  E rowacc = E(0);  // lane (i - r0) % 64 parks the sum of row i
   auto flush_rows = [&](int first, int count) {
     if (lane < count) unsafeAtomicAdd(&y[first + lane], rowacc);
-    rowacc = 0.0f;
+    rowacc = E(0);
   };
   auto consume = [&](int i, Row &r) {
-    f4a ac[NQ];  // what enters the column sums
+    vec ac[NQ];  // what enters the column sums
     const bool crosses = LOWER ? i >= c0 + kW : (panel_full && i < c0);
     if (crosses) {  // the row crosses the whole panel: every element exists, none is diagonal
 #pragma unroll
@@ -159,15 +189,11 @@ __global__ __launch_bounds__(kBlock) void trimv_kernel(int n, const float *__res
         const int dg = i - col[q];                        // element dg is the diagonal one
         const int lo = LOWER ? -0x40000000 : dg;          // first element inside
         const int hi = LOWER ? dg + 1 : n - col[q];       // one past the last element inside
-        r.a[q].x = (0 >= lo && 0 < hi) ? r.a[q].x : 0.0f;
-        r.a[q].y = (1 >= lo && 1 < hi) ? r.a[q].y : 0.0f;
-        r.a[q].z = (2 >= lo && 2 < hi) ? r.a[q].z : 0.0f;
-        r.a[q].w = (3 >= lo && 3 < hi) ? r.a[q].w : 0.0f;
+#pragma unroll
+        for (int t = 0; t < P; ++t) r.a[q][t] = (t >= lo && t < hi) ? r.a[q][t] : E(0);
         if (MODE == MODE_SYM) {  // the diagonal element is used once: the row sum has it
-          ac[q].x = dg == 0 ? 0.0f : r.a[q].x;
-          ac[q].y = dg == 1 ? 0.0f : r.a[q].y;
-          ac[q].z = dg == 2 ? 0.0f : r.a[q].z;
-          ac[q].w = dg == 3 ? 0.0f : r.a[q].w;
+#pragma unroll
+          for (int t = 0; t < P; ++t) ac[q][t] = dg == t ? E(0) : r.a[q][t];
         } else {
           ac[q] = r.a[q];
         }
@@ -178,10 +204,12 @@ __global__ __launch_bounds__(kBlock) void trimv_kernel(int n, const float *__res
       for (int q = 0; q < NQ; ++q) acc[q] += ac[q] * r.xi;
     }
     if (ROWS) {
-      float rs = 0.0f;
+      E rs = E(0);
 #pragma unroll
-      for (int q = 0; q < NQ; ++q)
-        rs += r.a[q].x * xv[q].x + r.a[q].y * xv[q].y + r.a[q].z * xv[q].z + r.a[q].w * xv[q].w;
+      for (int q = 0; q < NQ; ++q) {
+#pragma unroll
+        for (int t = 0; t < P; ++t) rs += r.a[q][t] * xv[q][t];
+      }
       rs = wave_sum(rs);
       const int slot = (i - r0) & 63;
       if (lane == slot) rowacc = rs;
@@ -208,25 +236,26 @@ __global__ __launch_bounds__(kBlock) void trimv_kernel(int n, const float *__res
 
   if (COLS) {  // column sums: add the wavefronts' up, then one atomic per column
 #pragma unroll
-    for (int q = 0; q < NQ; ++q) *reinterpret_cast<f4a *>(&cs[wave][4 * lane + 256 * q]) = acc[q];
+    for (int q = 0; q < NQ; ++q) *reinterpret_cast<vec *>(&cs[wave][P * lane + 64 * P * q]) = acc[q];
     __syncthreads();
     for (int c = threadIdx.x; c < kW; c += kBlock) {
-      float v = 0.0f;
+      E v = E(0);
 #pragma unroll
       for (int w = 0; w < kWavesPerBlock; ++w) v += cs[w][c];
-      if (c0 + c < n && v != 0.0f) unsafeAtomicAdd(&y[c0 + c], v);
+      if (c0 + c < n && v != E(0)) unsafeAtomicAdd(&y[c0 + c], v);
     }
   }
 }
 
-__global__ void zero_kernel(float *__restrict__ y, int64_t n) {
+template <typename E>
+__global__ void zero_kernel(E *__restrict__ y, int64_t n) {
   const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (t < n) y[t] = 0.0f;
+  if (t < n) y[t] = E(0);
 }
 
-template <int NQ, bool LOWER, int MODE>
-int launch(int64_t n, const float *Tp, const float *x, float *y, hipStream_t st) {
-  constexpr int kW = 256 * NQ;
+template <typename E, int NQ, bool LOWER, int MODE>
+int launch(int64_t n, const E *Tp, const E *x, E *y, hipStream_t st) {
+  constexpr int kW = 64 * Piece<E>::kPer * NQ;
   const int npanels = (int)ceil_div(n, kW);
   if (npanels > kMaxPanels) return DASTAC_EOVERFLOW;
   int64_t steps = 0, lo, hi;
@@ -246,20 +275,22 @@ int launch(int64_t n, const float *Tp, const float *x, float *y, hipStream_t st)
     blocks += (int)ceil_div(hi - lo, R * kWavesPerBlock);
   }
   pn.first[npanels] = blocks;
-  zero_kernel<<<(unsigned)ceil_div(n, 256), 256, 0, st>>>(y, n);
-  trimv_kernel<NQ, LOWER, MODE><<<(unsigned)blocks, kBlock, 0, st>>>((int)n, Tp, x, y, (int)R, npanels, pn);
+  zero_kernel<E><<<(unsigned)ceil_div(n, 256), 256, 0, st>>>(y, n);
+  trimv_kernel<E, NQ, LOWER, MODE><<<(unsigned)blocks, kBlock, 0, st>>>((int)n, Tp, x, y, (int)R, npanels, pn);
   return launch_status();
 }
 
-template <bool LOWER, int MODE>
-int run(int64_t n, const float *Tp, const float *x, float *y, void *stream) {
+template <typename E, bool LOWER, int MODE>
+int run(int64_t n, const E *Tp, const E *x, E *y, void *stream) {
+  constexpr int64_t kB = (int64_t)sizeof(E);
   if (n < 0) return DASTAC_EINVAL;
-  if (n > kMaxN) return DASTAC_EOVERFLOW;
+  // 512 panels of the widest kind; double-precision panels are half as wide
+  if (n > kMaxN / (kB / 4)) return DASTAC_EOVERFLOW;
   if (n == 0) return DASTAC_OK;
   if (!Tp || !x || !y) return DASTAC_ENULL;
-  if (overlaps(y, n * 4, Tp, tri(n) * 4) || overlaps(y, n * 4, x, n * 4)) return DASTAC_EALIAS;
-  if (n <= 2048) return launch<1, LOWER, MODE>(n, Tp, x, y, (hipStream_t)stream);
-  return launch<4, LOWER, MODE>(n, Tp, x, y, (hipStream_t)stream);
+  if (overlaps(y, n * kB, Tp, tri(n) * kB) || overlaps(y, n * kB, x, n * kB)) return DASTAC_EALIAS;
+  if (n <= 2048) return launch<E, 1, LOWER, MODE>(n, Tp, x, y, (hipStream_t)stream);
+  return launch<E, 4, LOWER, MODE>(n, Tp, x, y, (hipStream_t)stream);
 }
 
 }  // namespace
@@ -267,25 +298,44 @@ int run(int64_t n, const float *Tp, const float *x, float *y, void *stream) {
 // y := U x over the packed upper triangle with this file's kernel (no limit on n below kMaxN);
 // used by dastac_trmv_f32 for triangles whose vector does not fit in LDS.
 int dastac::trmv_upper_by_panels(int64_t n, const float *Up, const float *x, float *y, void *stream) {
-  return run<false, MODE_ROWS>(n, Up, x, y, stream);
+  return run<float, false, MODE_ROWS>(n, Up, x, y, stream);
+}
+int dastac::trmv_upper_by_panels(int64_t n, const double *Up, const double *x, double *y, void *stream) {
+  return run<double, false, MODE_ROWS>(n, Up, x, y, stream);
 }
 
 extern "C" {
 
 int dastac_symv_f32(int64_t n, const float *Up, const float *x, float *y, void *stream) {
-  return run<false, MODE_SYM>(n, Up, x, y, stream);
+  return run<float, false, MODE_SYM>(n, Up, x, y, stream);
 }
 int dastac_trmv_t_f32(int64_t n, const float *Up, const float *x, float *y, void *stream) {
-  return run<false, MODE_COLS>(n, Up, x, y, stream);
+  return run<float, false, MODE_COLS>(n, Up, x, y, stream);
 }
 int dastac_symv_lower_f32(int64_t n, const float *Lp, const float *x, float *y, void *stream) {
-  return run<true, MODE_SYM>(n, Lp, x, y, stream);
+  return run<float, true, MODE_SYM>(n, Lp, x, y, stream);
 }
 int dastac_trmv_lower_f32(int64_t n, const float *Lp, const float *x, float *y, void *stream) {
-  return run<true, MODE_ROWS>(n, Lp, x, y, stream);
+  return run<float, true, MODE_ROWS>(n, Lp, x, y, stream);
 }
 int dastac_trmv_lower_t_f32(int64_t n, const float *Lp, const float *x, float *y, void *stream) {
-  return run<true, MODE_COLS>(n, Lp, x, y, stream);
+  return run<float, true, MODE_COLS>(n, Lp, x, y, stream);
+}
+
+int dastac_symv_f64(int64_t n, const double *Up, const double *x, double *y, void *stream) {
+  return run<double, false, MODE_SYM>(n, Up, x, y, stream);
+}
+int dastac_trmv_t_f64(int64_t n, const double *Up, const double *x, double *y, void *stream) {
+  return run<double, false, MODE_COLS>(n, Up, x, y, stream);
+}
+int dastac_symv_lower_f64(int64_t n, const double *Lp, const double *x, double *y, void *stream) {
+  return run<double, true, MODE_SYM>(n, Lp, x, y, stream);
+}
+int dastac_trmv_lower_f64(int64_t n, const double *Lp, const double *x, double *y, void *stream) {
+  return run<double, true, MODE_ROWS>(n, Lp, x, y, stream);
+}
+int dastac_trmv_lower_t_f64(int64_t n, const double *Lp, const double *x, double *y, void *stream) {
+  return run<double, true, MODE_COLS>(n, Lp, x, y, stream);
 }
 
 }  // extern "C"

@@ -76,6 +76,22 @@ SIGNATURES = {
     "dastac_pr_a2_f64": (ctypes.c_int, [_i64, _i64, _vp, _i64, _vp, _vp]),
     "dastac_pr_a3_f64": (ctypes.c_int, [_i64, _i64, _vp, _i64, _vp, _vp]),
     "dastac_tet_mttkrp_f64": (ctypes.c_int, [_i64, _i64, _vp, _vp, _i64, _vp, _i64, _vp, _i64, _vp]),
+    "dastac_pack_tril_f64": (ctypes.c_int, [_i64, _vp, _i64, _vp, _vp]),
+    "dastac_unpack_tril_f64": (ctypes.c_int, [_i64, _vp, _vp, _i64, _vp]),
+    "dastac_symv_f64": (ctypes.c_int, [_i64, _vp, _vp, _vp, _vp]),
+    "dastac_trmv_t_f64": (ctypes.c_int, [_i64, _vp, _vp, _vp, _vp]),
+    "dastac_symv_lower_f64": (ctypes.c_int, [_i64, _vp, _vp, _vp, _vp]),
+    "dastac_trmv_lower_f64": (ctypes.c_int, [_i64, _vp, _vp, _vp, _vp]),
+    "dastac_trmv_lower_t_f64": (ctypes.c_int, [_i64, _vp, _vp, _vp, _vp]),
+    "dastac_pack_sband_f64": (ctypes.c_int, [_i64, _i64, _i64, _vp, _i64, _vp, _vp]),
+    "dastac_unpack_sband_f64": (ctypes.c_int, [_i64, _i64, _i64, _vp, _vp, _i64, _vp]),
+    "dastac_sband_spmv_f64": (ctypes.c_int, [_i64, _i64, _i64, _vp, _vp, _vp, _vp]),
+    "dastac_pack_subtri_f64": (ctypes.c_int, [_i64, _i64, _vp, _i64, _vp, _vp]),
+    "dastac_unpack_subtri_f64": (ctypes.c_int, [_i64, _i64, _vp, _vp, _i64, _vp]),
+    "dastac_subtri_spmv_f64": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp, _vp]),
+    "dastac_pack_leslie_f64": (ctypes.c_int, [_i64, _vp, _i64, _vp, _vp, _vp]),
+    "dastac_unpack_leslie_f64": (ctypes.c_int, [_i64, _vp, _vp, _vp, _i64, _vp]),
+    "dastac_leslie_spmv_f64": (ctypes.c_int, [_i64, _vp, _vp, _vp, _vp, _vp]),
     "dastac_subtri_offset": (_i64, [_i64, _i64, _i64, _i64]),
     "dastac_pack_sband_f32": (ctypes.c_int, [_i64, _i64, _i64, _vp, _i64, _vp, _vp]),
     "dastac_unpack_sband_f32": (ctypes.c_int, [_i64, _i64, _i64, _vp, _vp, _i64, _vp]),
@@ -396,3 +412,73 @@ def pr_a3_f64(N, d, B, ldb, A3p, stream=None):
 def tet_mttkrp_f64(n, R, Ap, B, ldb, C, ldc, M, ldm, stream=None):
     _check(lib().dastac_tet_mttkrp_f64(n, R, _ptr64(Ap), _ptr64(B), ldb, _ptr64(C), ldc, _ptr64(M), ldm,
                                        _stream(stream)), "tet_mttkrp_f64")
+
+
+def pack_tril_f64(n, dense, ld, packed, stream=None):
+    _check(lib().dastac_pack_tril_f64(n, _ptr64(dense), ld, _ptr64(packed), _stream(stream)), "pack_tril_f64")
+
+
+def unpack_tril_f64(n, packed, dense, ld, stream=None):
+    _check(lib().dastac_unpack_tril_f64(n, _ptr64(packed), _ptr64(dense), ld, _stream(stream)), "unpack_tril_f64")
+
+
+def symv_f64(n, Up, x, y, stream=None):
+    _check(lib().dastac_symv_f64(n, _ptr64(Up), _ptr64(x), _ptr64(y), _stream(stream)), "symv_f64")
+
+
+def trmv_t_f64(n, Up, x, y, stream=None):
+    _check(lib().dastac_trmv_t_f64(n, _ptr64(Up), _ptr64(x), _ptr64(y), _stream(stream)), "trmv_t_f64")
+
+
+def symv_lower_f64(n, Lp, x, y, stream=None):
+    _check(lib().dastac_symv_lower_f64(n, _ptr64(Lp), _ptr64(x), _ptr64(y), _stream(stream)), "symv_lower_f64")
+
+
+def trmv_lower_f64(n, Lp, x, y, stream=None):
+    _check(lib().dastac_trmv_lower_f64(n, _ptr64(Lp), _ptr64(x), _ptr64(y), _stream(stream)), "trmv_lower_f64")
+
+
+def trmv_lower_t_f64(n, Lp, x, y, stream=None):
+    _check(lib().dastac_trmv_lower_t_f64(n, _ptr64(Lp), _ptr64(x), _ptr64(y), _stream(stream)), "trmv_lower_t_f64")
+
+
+def pack_sband_f64(n, w, s, dense, ld, diag_major, stream=None):
+    _check(lib().dastac_pack_sband_f64(n, w, s, _ptr64(dense), ld, _ptr64(diag_major), _stream(stream)),
+           "pack_sband_f64")
+
+
+def unpack_sband_f64(n, w, s, diag_major, dense, ld, stream=None):
+    _check(lib().dastac_unpack_sband_f64(n, w, s, _ptr64(diag_major), _ptr64(dense), ld, _stream(stream)),
+           "unpack_sband_f64")
+
+
+def sband_spmv_f64(n, w, s, D, x, y, stream=None):
+    _check(lib().dastac_sband_spmv_f64(n, w, s, _ptr64(D), _ptr64(x), _ptr64(y), _stream(stream)), "sband_spmv_f64")
+
+
+def pack_subtri_f64(N, k, dense, ld, packed, stream=None):
+    _check(lib().dastac_pack_subtri_f64(N, k, _ptr64(dense), ld, _ptr64(packed), _stream(stream)), "pack_subtri_f64")
+
+
+def unpack_subtri_f64(N, k, packed, dense, ld, stream=None):
+    _check(lib().dastac_unpack_subtri_f64(N, k, _ptr64(packed), _ptr64(dense), ld, _stream(stream)),
+           "unpack_subtri_f64")
+
+
+def subtri_spmv_f64(N, k, Ap, x, y, stream=None):
+    _check(lib().dastac_subtri_spmv_f64(N, k, _ptr64(Ap), _ptr64(x), _ptr64(y), _stream(stream)), "subtri_spmv_f64")
+
+
+def pack_leslie_f64(n, dense, ld, R, S, stream=None):
+    _check(lib().dastac_pack_leslie_f64(n, _ptr64(dense), ld, _ptr64(R), _ptr64(S), _stream(stream)),
+           "pack_leslie_f64")
+
+
+def unpack_leslie_f64(n, R, S, dense, ld, stream=None):
+    _check(lib().dastac_unpack_leslie_f64(n, _ptr64(R), _ptr64(S), _ptr64(dense), ld, _stream(stream)),
+           "unpack_leslie_f64")
+
+
+def leslie_spmv_f64(n, R, S, x, y, stream=None):
+    _check(lib().dastac_leslie_spmv_f64(n, _ptr64(R), _ptr64(S), _ptr64(x), _ptr64(y), _stream(stream)),
+           "leslie_spmv_f64")

@@ -94,6 +94,20 @@ def f64_inputs():
             "ttv": {"n": n4, "Ap": inputs.uniform64(_seed(13, 4), _tet(n4)), "v": inputs.uniform64(_seed(13, 5), n4)}}
 
 
+def domains_f64_inputs():
+    """Double-precision operands for the symmetric product (n=8192) and for the strided-band
+    (n=2^23, w=1, s=4096), sub-triangular (N=2^14, k=2^13) and Leslie (n=2^23) products; stream
+    seeds of "config 15"."""
+    ns, nb, sb, Nu, ku, nl = 8192, 1 << 23, 4096, 1 << 14, 1 << 13, 1 << 23
+    return {"symv": {"n": ns, "Up": inputs.uniform64(_seed(15, 0), _tri(ns)), "x": inputs.uniform64(_seed(15, 1), ns)},
+            "sband": {"n": nb, "w": 1, "s": sb, "D": inputs.uniform64(_seed(15, 2), 3 * nb),
+                      "x": inputs.uniform64(_seed(15, 3), nb)},
+            "subtri": {"N": Nu, "k": ku, "Ap": inputs.uniform64(_seed(15, 4), _tri(ku)),
+                       "x": inputs.uniform64(_seed(15, 5), Nu)},
+            "leslie": {"n": nl, "R": inputs.uniform64(_seed(15, 6), nl), "S": inputs.uniform64(_seed(15, 7), nl - 1),
+                       "x": inputs.uniform64(_seed(15, 8), nl)}}
+
+
 def trmm_f64_inputs(n: int = 16384, m: int = 256):
     """The TRMM configuration's shape with double operands; stream seeds of "config 14"."""
     return {"n": n, "m": m, "Up": inputs.uniform64(_seed(14, 0), _tri(n)), "B": inputs.uniform64(_seed(14, 1), n, m)}

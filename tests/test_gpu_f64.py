@@ -315,3 +315,156 @@ def test_tet_mttkrp_f64_sampled_slices_at_a_larger_size(gpu, oracle):
     for i in (0, 1, 143, 144, 145, 200, n - 33, n - 32, n - 2, n - 1):
         want, scale = oracle.tet_mttkrp_f64(n, R, Ap, B, C, rows=(i, i + 1))
         assert_within(got[i], want[i], scale[i], "mttkrp_f64 slice %d" % i)
+
+
+# ----------------------- every product of one packed triangle, double precision ----
+
+TRIMV64 = [("symv_f64", False, 2), ("trmv_t_f64", False, 1), ("symv_lower_f64", True, 2), ("trmv_lower_f64", True, 0),
+           ("trmv_lower_t_f64", True, 1)]
+
+
+@pytest.mark.parametrize("n,ld", [(1, 1), (17, 20), (256, 256), (257, 300)])
+def test_pack_unpack_tril_f64_bit_exact(gpu, oracle, n, ld):
+    D = inputs.uniform64(3500 + n, n, ld)
+    want = oracle.pack_tril_f64(np.ascontiguousarray(D[:, :n]))
+    dP = gpu.empty(tri(n))
+    gpu.d.pack_tril_f64(n, gpu.up(D), ld, dP)
+    assert gpu.down(dP).tobytes() == want.tobytes()
+    dU = gpu.empty(n, ld)
+    gpu.d.unpack_tril_f64(n, dP, dU, ld)
+    U = gpu.down(dU)
+    assert U[:, :n].tobytes() == oracle.unpack_tril_f64(n, want).tobytes()
+    assert np.isnan(U[:, n:]).all()
+
+
+@pytest.mark.parametrize("name,lower,mode", TRIMV64)
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 63, 64, 65, 127, 128, 129, 255, 257, 500, 513, 1030, 2048, 2049, 2600])
+def test_trimv_f64_parity(gpu, oracle, name, lower, mode, n):
+    Tp, x = inputs.uniform64(3510 + n, tri(n)), inputs.uniform64(3511 + n, n)
+    want, scale = oracle.trimv_f64(n, Tp, x, lower=lower, mode=mode)
+    y = gpu.empty(n)
+    getattr(gpu.d, name)(n, gpu.up(Tp), gpu.up(x), y)
+    assert_within(gpu.down(y), want, scale, "%s n=%d" % (name, n))
+
+
+@pytest.mark.parametrize("name,lower,mode", TRIMV64)
+def test_trimv_f64_exact_on_integers(gpu, oracle, name, lower, mode):
+    n = 777
+    Tp = inputs.small_int(3520, -3, 3, tri(n)).astype(np.float64)
+    x = inputs.small_int(3521, -3, 3, n).astype(np.float64)
+    want, _ = oracle.trimv_f64(n, Tp, x, lower=lower, mode=mode)
+    y = gpu.empty(n)
+    dT, dx = gpu.up(Tp), gpu.up(x)
+    for _ in range(2):  # the output is zeroed by every call: a second call must not add onto the first
+        getattr(gpu.d, name)(n, dT, dx, y)
+        assert gpu.down(y).tobytes() == want.tobytes()
+
+
+def test_trimv_f64_wide_panels_sampled_rows(gpu, oracle):
+    """n above 2048 takes the four-piece panels (512 columns in double precision); n above 8192 also
+    sends the plain upper-triangular product to the panel kernel."""
+    n = 9000
+    Tp, x = inputs.uniform64(3530, tri(n)), inputs.uniform64(3531, n)
+    dT, dx = gpu.up(Tp), gpu.up(x)
+    windows = [(0, 40), (2040, 2060), (4590, 4620), (n - 40, n)]
+    for name, lower, mode in TRIMV64 + [("trmv_f64", False, 0)]:
+        y = gpu.empty(n)
+        getattr(gpu.d, name)(n, dT, dx, y)
+        got = gpu.down(y)
+        assert np.isfinite(got).all()
+        for lo, hi in windows:
+            want, scale = oracle.trimv_f64(n, Tp, x, lower=lower, mode=mode, rows=(lo, hi))
+            assert_within(got[lo:hi], want[lo:hi], scale[lo:hi], "%s n=%d rows %d..%d" % (name, n, lo, hi))
+
+
+def test_symv_f64_keeps_what_fp32_would_lose(gpu):
+    n = 3
+    Up = np.array([1.0, 2.0 ** -40, 0.0, 1.0, 0.0, 1.0])  # rows (0,0..2), (1,1..2), (2,2)
+    x = np.array([1.0, 1.0, 0.0])
+    y = gpu.empty(n)
+    gpu.d.symv_f64(n, gpu.up(Up), gpu.up(x), y)
+    got = gpu.down(y)
+    assert got[0] == 1.0 + 2.0 ** -40 and got[1] == 1.0 + 2.0 ** -40 and got[2] == 0.0
+
+
+# ----------------------- strided band, sub-triangle, Leslie: double precision ----
+
+@pytest.mark.parametrize("n,w,s,ld", [(1, 1, 1, 1), (9, 1, 3, 12), (300, 1, 64, 300), (513, 2, 100, 520), (64, 0, 5, 64)])
+def test_pack_unpack_sband_f64_bit_exact(gpu, oracle, n, w, s, ld):
+    D = inputs.uniform64(3600 + n + s, n, ld)
+    want = oracle.pack_sband_f64(np.ascontiguousarray(D[:, :n]), w, s)
+    dP = gpu.empty((2 * w + 1) * n)
+    gpu.d.pack_sband_f64(n, w, s, gpu.up(D), ld, dP)
+    assert gpu.down(dP).tobytes() == want.tobytes()
+    dU = gpu.empty(n, ld)
+    gpu.d.unpack_sband_f64(n, w, s, dP, dU, ld)
+    U = gpu.down(dU)
+    assert U[:, :n].tobytes() == oracle.unpack_sband_f64(n, w, s, want).tobytes()
+    assert np.isnan(U[:, n:]).all()
+
+
+@pytest.mark.parametrize("n,w,s", [(1, 1, 1), (2, 1, 1), (255, 1, 1), (1000, 1, 7), (4099, 1, 4096), (4099, 1, 5000),
+                                   (65536, 1, 256), (3000, 3, 17), (3000, 0, 9), (777, 16, 40)])
+def test_sband_spmv_f64_parity_and_padding_never_read(gpu, oracle, n, w, s):
+    D, x = inputs.uniform64(3610 + n + s, 2 * w + 1, n), inputs.uniform64(3611 + n, n)
+    want, scale = oracle.sband_spmv_f64(n, w, s, D.ravel(), x)
+    i = np.arange(n)
+    for d in range(-w, w + 1):  # poison every padding slot
+        D[d + w, (i + d * s < 0) | (i + d * s >= n)] = np.nan
+    y = gpu.empty(n)
+    gpu.d.sband_spmv_f64(n, w, s, gpu.up(D.ravel()), gpu.up(x), y)
+    assert_within(gpu.down(y), want, scale, "sband_f64 n=%d w=%d s=%d" % (n, w, s))
+
+
+@pytest.mark.parametrize("N,k,ld", [(1, 0, 1), (1, 1, 1), (40, 13, 48), (300, 300, 300), (700, 257, 704)])
+def test_pack_unpack_subtri_f64_bit_exact(gpu, oracle, N, k, ld):
+    D = inputs.uniform64(3620 + N + k, N, ld)
+    want = oracle.pack_subtri_f64(np.ascontiguousarray(D[:, :N]), k)
+    dP = gpu.empty(max(tri(k), 1))
+    gpu.d.pack_subtri_f64(N, k, gpu.up(D), ld, dP)
+    assert gpu.down(dP)[: tri(k)].tobytes() == want.tobytes()
+    dU = gpu.empty(N, ld)
+    gpu.d.unpack_subtri_f64(N, k, dP, dU, ld)
+    U = gpu.down(dU)
+    assert U[:, :N].tobytes() == oracle.unpack_subtri_f64(N, k, want).tobytes()
+    assert np.isnan(U[:, N:]).all()
+
+
+@pytest.mark.parametrize("N,k", [(1, 0), (1, 1), (50, 0), (50, 1), (333, 100), (1000, 1000), (2048, 511), (4099, 4097),
+                                 (9000, 8500)])
+def test_subtri_spmv_f64_parity(gpu, oracle, N, k):
+    Ap, x = inputs.uniform64(3630 + N + k, max(tri(k), 1)), inputs.uniform64(3631 + N, N)
+    want, scale = oracle.subtri_spmv_f64(N, k, Ap[: tri(k)], x)
+    y = gpu.empty(N)
+    gpu.d.subtri_spmv_f64(N, k, gpu.up(Ap), gpu.up(x), y)
+    got = gpu.down(y)
+    assert_within(got, want, scale, "subtri_f64 N=%d k=%d" % (N, k))
+    assert np.all(got[k:] == 0)
+
+
+@pytest.mark.parametrize("n,ld", [(1, 1), (2, 2), (33, 40), (1025, 1030)])
+def test_pack_unpack_leslie_f64_bit_exact(gpu, oracle, n, ld):
+    D = inputs.uniform64(3640 + n, n, ld)
+    R, S = oracle.pack_leslie_f64(np.ascontiguousarray(D[:, :n]))
+    dR, dS = gpu.empty(n), gpu.empty(max(n - 1, 1))
+    gpu.d.pack_leslie_f64(n, gpu.up(D), ld, dR, dS)
+    assert gpu.down(dR).tobytes() == R.tobytes()
+    assert gpu.down(dS)[: n - 1].tobytes() == S.tobytes()
+    dU = gpu.empty(n, ld)
+    gpu.d.unpack_leslie_f64(n, dR, dS, dU, ld)
+    U = gpu.down(dU)
+    assert U[:, :n].tobytes() == oracle.unpack_leslie_f64(n, R, S).tobytes()
+    assert np.isnan(U[:, n:]).all()
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 255, 256, 257, 1024, 4097, 100000, 1048577])
+def test_leslie_spmv_f64_parity(gpu, oracle, n):
+    R, S, x = inputs.uniform64(3650 + n, n), inputs.uniform64(3651 + n, max(n - 1, 1)), inputs.uniform64(3652 + n, n)
+    want, scale = oracle.leslie_spmv_f64(n, R, S[: n - 1], x)
+    y = gpu.empty(n)
+    dR, dS, dx = gpu.up(R), gpu.up(S), gpu.up(x)
+    for _ in range(2):  # the second call must not add onto the first call's y(0)
+        gpu.d.leslie_spmv_f64(n, dR, dS, dx, y)
+        got = gpu.down(y)
+        assert_within(got, want, scale, "leslie_f64 n=%d" % n)
+        assert got[1:].tobytes() == want[1:].tobytes()  # single products: exactly rounded

@@ -36,7 +36,7 @@ def test_random_sizes_match_the_oracle(gpu, oracle, seed0):
     reps = 6
     seed = 7000 + 1000 * seed0
     for it in range(reps):
-        seed += 30
+        seed += 40
         n = rng.choice([rng.randint(1, 70), rng.randint(70, 700), rng.randint(700, 2600)])
         Up, x = inputs.uniform(seed, tri(n)), inputs.normal(seed+1, n)
         dU, dx = up(Up), up(x)
@@ -47,6 +47,10 @@ def test_random_sizes_match_the_oracle(gpu, oracle, seed0):
         y = nan(N); d.subtri_spmv_f32(N, n, dU, up(xN), y); check("subtri", (N, n), down(y), *oracle.subtri_spmv(N, n, Up, xN))
         U64, x64 = inputs.uniform64(seed+3, tri(n)), inputs.uniform64(seed+4, n)
         y = nan64(n); d.trmv_f64(n, up(U64), up(x64), y); check("trmv_f64", n, down(y), *oracle.trmv_f64(n, U64, x64), tol=1e-12)
+        for name, lower, mode in (("symv", 0, 2), ("trmv_t", 0, 1), ("trmv_lower", 1, 0), ("trmv_lower_t", 1, 1), ("symv_lower", 1, 2)):
+            y = nan64(n); getattr(d, name + "_f64")(n, up(U64), up(x64), y); check(name + "_f64", n, down(y), *oracle.trimv_f64(n, U64, x64, lower=bool(lower), mode=mode), tol=1e-12)
+        xN64 = inputs.uniform64(seed+25, N)
+        y = nan64(N); d.subtri_spmv_f64(N, n, up(U64), up(xN64), y); check("subtri_f64", (N, n), down(y), *oracle.subtri_spmv_f64(N, n, U64, xN64), tol=1e-12)
         # matrix right-hand sides
         n2 = rng.choice([rng.randint(1, 100), rng.randint(100, 600)]); m = rng.choice([1, rng.randint(2, 40), rng.randint(40, 300)])
         Up2, B = inputs.uniform(seed+5, tri(n2)), inputs.uniform(seed+6, n2, m)
@@ -61,9 +65,12 @@ def test_random_sizes_match_the_oracle(gpu, oracle, seed0):
         y = nan(nb); d.sband_spmv_f32(nb, w, s, up(D.ravel()), up(xb), y); check("sband", (nb, w, s), down(y), *oracle.sband_spmv(nb, w, s, D.ravel(), xb))
         D64 = inputs.uniform64(seed+11, 2*w+1, nb); xb64 = inputs.uniform64(seed+12, nb)
         y = nan64(nb); d.band_spmv_f64(nb, w, up(D64.ravel()), up(xb64), y); check("band_f64", (nb, w), down(y), *oracle.band_spmv_f64(nb, w, D64.ravel(), xb64), tol=1e-12)
+        y = nan64(nb); d.sband_spmv_f64(nb, w, s, up(D64.ravel()), up(xb64), y); check("sband_f64", (nb, w, s), down(y), *oracle.sband_spmv_f64(nb, w, s, D64.ravel(), xb64), tol=1e-12)
         nl = rng.choice([rng.randint(1, 600), rng.randint(600, 300000)])
         R_, S_, xl = inputs.normal(seed+13, nl), inputs.uniform(seed+14, max(nl-1, 1)), inputs.normal(seed+15, nl)
         y = nan(nl); d.leslie_spmv_f32(nl, up(R_), up(S_), up(xl), y); check("leslie", nl, down(y), *oracle.leslie_spmv(nl, R_, S_[:nl-1], xl))
+        R64, S64, xl64 = inputs.uniform64(seed+26, nl), inputs.uniform64(seed+27, max(nl-1, 1)), inputs.uniform64(seed+28, nl)
+        y = nan64(nl); d.leslie_spmv_f64(nl, up(R64), up(S64), up(xl64), y); check("leslie_f64", nl, down(y), *oracle.leslie_spmv_f64(nl, R64, S64[:nl-1], xl64), tol=1e-12)
         # tetrahedron
         nt = rng.choice([rng.randint(1, 40), rng.randint(40, 150)]); R = rng.choice([1, 5, 16, 31, 32, rng.randint(1, 32)])
         Ap, v = inputs.uniform(seed+16, tet(nt)), inputs.normal(seed+17, nt)

@@ -188,9 +188,11 @@ def test_new_domain_entry_points_reject_bad_arguments():
         assert fn(10, 4, _p(A), 4, None, None) == dastac.ENULL
         assert fn(10, 4, _p(A), 4, _p(A + 32), None) == dastac.EALIAS
         assert fn(10, 0, None, 0, None, None) == dastac.OK
-    for fn in (L.dastac_trmv_f64, L.dastac_tet_ttv_f64):
+    for fn, nmax in ((L.dastac_trmv_f64, 2 ** 31 - 1), (L.dastac_tet_ttv_f64, 8192), (L.dastac_symv_f64, 262144),
+                     (L.dastac_trmv_t_f64, 262144), (L.dastac_symv_lower_f64, 262144),
+                     (L.dastac_trmv_lower_f64, 262144), (L.dastac_trmv_lower_t_f64, 262144)):
         assert fn(-1, _p(A), _p(B), _p(C), None) == dastac.EINVAL
-        assert fn(8193, _p(A), _p(B), _p(C), None) == dastac.EOVERFLOW
+        assert fn(nmax + 1, _p(A), _p(B), _p(C), None) == dastac.EOVERFLOW
         assert fn(4, None, _p(B), _p(C), None) == dastac.ENULL
         assert fn(4, _p(A), _p(B), _p(B + 16), None) == dastac.EALIAS
         assert fn(0, None, None, None, None) == dastac.OK
@@ -222,6 +224,28 @@ def test_new_domain_entry_points_reject_bad_arguments():
     assert L.dastac_pack_band_f64(4, -1, _p(A), 4, _p(B), None) == dastac.EINVAL
     # 8-byte elements: two 6-element double vectors 40 bytes apart overlap (two float vectors would not)
     assert L.dastac_trmv_f64(6, _p(A), _p(B), _p(B + 40), None) == dastac.EALIAS
+    assert L.dastac_pack_tril_f64(8, _p(A), 7, _p(B), None) == dastac.EINVAL
+    assert L.dastac_unpack_tril_f64(4, None, _p(B), 4, None) == dastac.ENULL
+    assert L.dastac_pack_tril_f64(4, _p(A), 4, _p(A + 120), None) == dastac.EALIAS  # 16 doubles reach byte 128
+    assert L.dastac_sband_spmv_f64(4, 1, 0, _p(A), _p(B), _p(C), None) == dastac.EINVAL
+    assert L.dastac_sband_spmv_f64(4, 65, 1, _p(A), _p(B), _p(C), None) == dastac.EINVAL
+    assert L.dastac_sband_spmv_f64(4, 1, 2, None, _p(B), _p(C), None) == dastac.ENULL
+    assert L.dastac_sband_spmv_f64(4, 1, 2, _p(A), _p(B), _p(B + 24), None) == dastac.EALIAS
+    assert L.dastac_sband_spmv_f64(0, 1, 2, None, None, None, None) == dastac.OK
+    assert L.dastac_pack_sband_f64(8, 1, 2, _p(A), 7, _p(B), None) == dastac.EINVAL
+    assert L.dastac_unpack_sband_f64(8, 1, 2, None, _p(B), 8, None) == dastac.ENULL
+    assert L.dastac_subtri_spmv_f64(4, 5, _p(A), _p(B), _p(C), None) == dastac.EINVAL
+    assert L.dastac_subtri_spmv_f64(4, 2, None, _p(B), _p(C), None) == dastac.ENULL
+    assert L.dastac_subtri_spmv_f64(4, 2, _p(A), _p(B), _p(B + 24), None) == dastac.EALIAS
+    assert L.dastac_subtri_spmv_f64(0, 0, None, None, None, None) == dastac.OK
+    assert L.dastac_pack_subtri_f64(8, 9, _p(A), 8, _p(B), None) == dastac.EINVAL
+    assert L.dastac_unpack_subtri_f64(8, 4, _p(A), None, 8, None) == dastac.ENULL
+    assert L.dastac_leslie_spmv_f64(-1, _p(A), _p(B), _p(C), _p(D), None) == dastac.EINVAL
+    assert L.dastac_leslie_spmv_f64(4, _p(A), None, _p(C), _p(D), None) == dastac.ENULL
+    assert L.dastac_leslie_spmv_f64(4, _p(A), _p(B), _p(C), _p(A + 24), None) == dastac.EALIAS
+    assert L.dastac_leslie_spmv_f64(0, None, None, None, None, None) == dastac.OK
+    assert L.dastac_pack_leslie_f64(4, _p(A), 3, _p(B), _p(C), None) == dastac.EINVAL
+    assert L.dastac_unpack_leslie_f64(4, None, _p(B), _p(C), 4, None) == dastac.ENULL
     assert L.dastac_sband_spmv_f32(-1, 1, 1, _p(A), _p(B), _p(C), None) == dastac.EINVAL
     assert L.dastac_sband_spmv_f32(4, 1, 0, _p(A), _p(B), _p(C), None) == dastac.EINVAL
     assert L.dastac_sband_spmv_f32(4, 65, 1, _p(A), _p(B), _p(C), None) == dastac.EINVAL
