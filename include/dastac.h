@@ -172,12 +172,13 @@ int dastac_symm_f32(int64_t n, int64_t m, const float *Up, const float *B, int64
 
 /* y(i) := sum_{d=-w..w, 0<=i+d<n} D(d,i) * x(i+d)   (Section 6.4 strided-band rule, unit stride,
  * 2w+1 summands; w=0 is Table 2's SpMV_D).  D[(2w+1)*n] diagonal-major as described above; padding
- * slots are never used for their value.  0 <= w <= 64. */
+ * slots are never used for their value.  0 <= w <= 2^20 (beyond: DASTAC_EOVERFLOW); the half-widths
+ * 0, 1, 2, 4, 8 and 16 have unrolled kernels. */
 int dastac_band_spmv_f32(int64_t n, int64_t w, const float *D, const float *x, float *y, void *stream);
 
 /* y(i) := sum_{d=-w..w, 0<=i+d*s<n} D(d,i) * x(i+d*s)   (Section 6.4, strided band; the paper's experiment
  * is w=1 with s from 1, tridiagonal, to n, diagonal).  D[(2w+1)*n] as for band_spmv with slot (d,i)
- * holding A[i][i+d*s]; 0 <= w <= 64, 1 <= s <= 2^40 (s >= n leaves the main diagonal). */
+ * holding A[i][i+d*s]; 0 <= w <= 2^20, 1 <= s <= 2^40 (s >= n leaves the main diagonal). */
 int dastac_sband_spmv_f32(int64_t n, int64_t w, int64_t s, const float *D, const float *x, float *y, void *stream);
 
 /* y(i) := A(i,j) * x(j), j-i >= N-k   (Section 6.4, sub-triangular structure; k = N is SpMV_UT).
@@ -197,7 +198,8 @@ int dastac_tet_ttv_f32(int64_t n, const float *Ap, const float *v, float *Mp, vo
 
 /* M(i,r) := A(i,j,k) * B(j,r) * C(k,r), i<=j<=k, 0<=r<R  (Table 1 MTTKRP rule on the upper tetrahedron).
  * B, C are n x R row-major with row strides ldb, ldc >= R; M is n x R with row stride ldm >= R.
- * 1 <= R <= 32. */
+ * 1 <= R <= 2^20.  The kernel takes 32 columns of the factor matrices at a time: R > 32 runs block by block,
+ * each block reading the packed tetrahedron once. */
 int dastac_tet_mttkrp_f32(int64_t n, int64_t R, const float *Ap, const float *B, int64_t ldb, const float *C,
                           int64_t ldc, float *M, int64_t ldm, void *stream);
 

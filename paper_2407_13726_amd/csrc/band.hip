@@ -53,7 +53,8 @@ __global__ __launch_bounds__(kBlock) void band_kernel(int64_t n, int w, const T 
 // Element type T: float, or double (the paper's element type; same kernel, eight bytes per slot).
 template <typename T>
 int run(int64_t n, int64_t w, const T *D, const T *x, T *y, void *stream) {
-  if (n < 0 || w < 0 || w > 64) return DASTAC_EINVAL;
+  if (n < 0 || w < 0) return DASTAC_EINVAL;
+  if (w > (1 << 20)) return DASTAC_EOVERFLOW;
   if (n > ((int64_t)1 << 40) / (2 * w + 1)) return DASTAC_EOVERFLOW;
   if (n == 0) return DASTAC_OK;
   if (!D || !x || !y) return DASTAC_ENULL;

@@ -223,7 +223,7 @@ template <typename T>
 int sband_spmv(int64_t n, int64_t w, int64_t s, const T *D, const T *x, T *y, void *stream) {
   constexpr int64_t kB = (int64_t)sizeof(T);
   if (int rc = check_sband(n, w, s)) return rc;
-  if (w > 64) return DASTAC_EINVAL;
+  if (w > (1 << 20)) return DASTAC_EOVERFLOW;
   if (n > ((int64_t)1 << 40) / (2 * w + 1)) return DASTAC_EOVERFLOW;
   if (n == 0) return DASTAC_OK;
   if (!D || !x || !y) return DASTAC_ENULL;

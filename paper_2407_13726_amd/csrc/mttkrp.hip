@@ -1,6 +1,6 @@
 // MTTKRP over a packed upper tetrahedron on the fp32 matrix cores:
 //
-//   M(i,r) := A(i,j,k) * B(j,r) * C(k,r),   i<=j<=k, 0<=r<R<=32     (Table 1, MTTKRP rule)
+//   M(i,r) := A(i,j,k) * B(j,r) * C(k,r),   i<=j<=k, 0<=r<R (32 columns r per launch)     (Table 1, MTTKRP rule)
 //
 // Factored evaluation.  Slice i of the packed tetrahedron is a packed upper triangle U_i of order
 // n-i, so   M(i,:) = sum_j B(j,:) .* T_i(j,:)   with   T_i = U_i * C[i:, :]   -- a TRMM whose
@@ -275,13 +275,19 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
 
 extern "C" int dastac_tet_mttkrp_f32(int64_t n, int64_t R, const float *Ap, const float *B, int64_t ldb,
                                      const float *C, int64_t ldc, float *M, int64_t ldm, void *stream) {
-  if (n < 0 || R < 1 || R > 32 || ldb < R || ldc < R || ldm < R) return DASTAC_EINVAL;
+  if (n < 0 || R < 1 || R > (1 << 20) || ldb < R || ldc < R || ldm < R) return DASTAC_EINVAL;
   if (n > DASTAC_TET_MAX_N || tet(n) > ((int64_t)1 << 40)) return DASTAC_EOVERFLOW;
   if (n == 0) return DASTAC_OK;
   if (!Ap || !B || !C || !M) return DASTAC_ENULL;
   if (overlaps(M, n * ldm * 4, Ap, tet(n) * 4) || overlaps(M, n * ldm * 4, B, n * ldb * 4) ||
       overlaps(M, n * ldm * 4, C, n * ldc * 4))
     return DASTAC_EALIAS;
-  mttkrp_mfma_kernel<<<(unsigned)n, kBlock, 0, (hipStream_t)stream>>>(n, (int)R, Ap, B, ldb, C, ldc, M, ldm, tet(n));
-  return launch_status();
+  // the kernel takes up to 32 columns of the factor matrices; wider ones go block by block (each
+  // block reads the packed tetrahedron once)
+  for (int64_t c0 = 0; c0 < R; c0 += 32) {
+    const int Rb = (int)(R - c0 < 32 ? R - c0 : 32);
+    mttkrp_mfma_kernel<<<(unsigned)n, kBlock, 0, (hipStream_t)stream>>>(n, Rb, Ap, B + c0, ldb, C + c0, ldc, M + c0, ldm, tet(n));
+    if (hipGetLastError() != hipSuccess) return DASTAC_EHIP;
+  }
+  return DASTAC_OK;
 }

@@ -1,6 +1,6 @@
 // MTTKRP over a packed upper tetrahedron in double precision, on the fp64 matrix cores:
 //
-//   M(i,r) := A(i,j,k) * B(j,r) * C(k,r),   i<=j<=k, 0<=r<R<=32,   all double     (Table 1, MTTKRP rule)
+//   M(i,r) := A(i,j,k) * B(j,r) * C(k,r),   i<=j<=k, 0<=r<R (32 columns r per launch),   all double     (Table 1, MTTKRP rule)
 //
 // The plan is the fp32 kernel's.  Slice i of the packed tetrahedron is a packed upper triangle U_i of
 // order n-i, so  M(i,:) = sum_j B(j,:) .* T_i(j,:)  with  T_i = U_i * C[i:, :]  -- a TRMM whose result is
@@ -266,7 +266,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
 
 extern "C" int dastac_tet_mttkrp_f64(int64_t n, int64_t R, const double *Ap, const double *B, int64_t ldb,
                                      const double *C, int64_t ldc, double *M, int64_t ldm, void *stream) {
-  if (n < 0 || R < 1 || R > 32 || ldb < R || ldc < R || ldm < R) return DASTAC_EINVAL;
+  if (n < 0 || R < 1 || R > (1 << 20) || ldb < R || ldc < R || ldm < R) return DASTAC_EINVAL;
   if (n > DASTAC_TET_MAX_N || tet(n) > ((int64_t)1 << 40)) return DASTAC_EOVERFLOW;
   // packed row bases inside a slice are kept as 32-bit element offsets
   if (tri(n) > ((int64_t)1 << 28)) return DASTAC_EOVERFLOW;
@@ -275,6 +275,12 @@ extern "C" int dastac_tet_mttkrp_f64(int64_t n, int64_t R, const double *Ap, con
   if (overlaps(M, n * ldm * 8, Ap, tet(n) * 8) || overlaps(M, n * ldm * 8, B, n * ldb * 8) ||
       overlaps(M, n * ldm * 8, C, n * ldc * 8))
     return DASTAC_EALIAS;
-  mttkrp_f64_kernel<<<(unsigned)n, kBlock, 0, (hipStream_t)stream>>>(n, (int)R, Ap, B, ldb, C, ldc, M, ldm, tet(n));
-  return launch_status();
+  // the kernel takes up to 32 columns of the factor matrices; wider ones go block by block (each
+  // block reads the packed tetrahedron once)
+  for (int64_t c0 = 0; c0 < R; c0 += 32) {
+    const int Rb = (int)(R - c0 < 32 ? R - c0 : 32);
+    mttkrp_f64_kernel<<<(unsigned)n, kBlock, 0, (hipStream_t)stream>>>(n, Rb, Ap, B + c0, ldb, C + c0, ldc, M + c0, ldm, tet(n));
+    if (hipGetLastError() != hipSuccess) return DASTAC_EHIP;
+  }
+  return DASTAC_OK;
 }

@@ -52,7 +52,7 @@ def test_pack_unpack_sband_bit_exact(gpu, oracle, n, w, s, ld):
 
 @pytest.mark.parametrize("n,w,s", [(1, 1, 1), (2, 1, 1), (255, 1, 1), (1000, 1, 7), (4099, 1, 4096), (4099, 1, 5000),
                                    (65536, 1, 1), (65536, 1, 256), (65536, 1, 65536), (3000, 3, 17), (3000, 0, 9),
-                                   (777, 16, 40)])
+                                   (777, 16, 40), (900, 70, 3)])
 def test_sband_spmv_parity(gpu, oracle, n, w, s):
     D, x = inputs.band_normal(1210 + n + s, n, w), inputs.normal(1211 + n, n)
     want, scale = oracle.sband_spmv(n, w, s, D.ravel(), x)

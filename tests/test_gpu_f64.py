@@ -105,7 +105,7 @@ def test_tet_ttv_f64_parity(gpu, oracle, n):
     assert_within(gpu.down(M), want, scale, "ttv_f64 n=%d" % n)
 
 
-@pytest.mark.parametrize("n,w", [(1, 0), (1, 3), (255, 16), (5000, 16), (3000, 5), (100, 40), (12, 30)])
+@pytest.mark.parametrize("n,w", [(1, 0), (1, 3), (255, 16), (5000, 16), (3000, 5), (100, 40), (12, 30), (600, 70)])
 def test_band_spmv_f64_parity(gpu, oracle, n, w):
     D, x = inputs.uniform64(3300 + n, 2 * w + 1, n), inputs.uniform64(3301 + n, n)
     want, scale = oracle.band_spmv_f64(n, w, D.ravel(), x)
@@ -281,7 +281,7 @@ def test_pr_tensors_f64_exact_on_integers(gpu, oracle, N, d):
 
 
 @pytest.mark.parametrize("n,R", [(1, 1), (2, 32), (5, 3), (16, 32), (17, 7), (33, 32), (40, 16), (64, 32), (65, 31), (100, 32),
-                                 (130, 5), (270, 32), (300, 32)])
+                                 (130, 5), (270, 32), (300, 32), (40, 33), (50, 64)])
 def test_tet_mttkrp_f64_parity(gpu, oracle, n, R):
     Ap = inputs.uniform64(3900 + n, tet(n))
     B, C = inputs.uniform64(3901 + n, n, R), inputs.uniform64(3902 + n, n, R)

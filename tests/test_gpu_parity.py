@@ -138,7 +138,7 @@ def test_tet_ttv_integer_inputs_bit_exact(gpu, oracle, n):
 
 @pytest.mark.parametrize("n,w", [(1, 0), (1, 16), (5, 16), (31, 16), (33, 16), (1023, 16), (1024, 16), (1025, 16),
                                  (5000, 16), (4099, 0), (3000, 2), (3001, 4), (2500, 8), (2000, 1), (1500, 7),
-                                 (900, 64), (10, 40)])
+                                 (900, 64), (10, 40), (700, 65), (2300, 200), (50, 1000)])
 def test_band_spmv_parity(gpu, oracle, n, w):
     D, x = inputs.band_normal(90 + n, n, w), inputs.normal(91 + n, n)
     want, scale = oracle.band_spmv(n, w, D.ravel(), x)
@@ -291,7 +291,7 @@ def test_ttm_ut_leading_dimension_integer_exactness_and_identity(gpu, oracle):
 # ------------------------------------------------------------------- MTTKRP ----
 
 @pytest.mark.parametrize("n,R", [(1, 1), (2, 32), (5, 3), (31, 32), (33, 32), (64, 32), (70, 17), (100, 32),
-                                 (130, 8)])
+                                 (130, 8), (40, 33), (70, 64), (45, 100)])
 def test_tet_mttkrp_parity(gpu, oracle, n, R):
     Ap = inputs.uniform(130 + n, tet(n))
     B, C = inputs.normal(131 + n, n, R), inputs.normal(132 + n, n, R)
@@ -305,6 +305,20 @@ def test_tet_mttkrp_leading_dimensions_and_integer_exactness(gpu, oracle):
     n, R, ldb, ldc, ldm = 75, 20, 24, 32, 21
     Ap = inputs.small_int(140, -2, 2, tet(n))
     B, C = inputs.small_int(141, -2, 2, n, ldb), inputs.small_int(142, -2, 2, n, ldc)
+    want, _ = oracle.tet_mttkrp(n, R, Ap, np.ascontiguousarray(B[:, :R]), np.ascontiguousarray(C[:, :R]))
+    M = gpu.empty(n, ldm)
+    gpu.d.tet_mttkrp_f32(n, R, gpu.up(Ap), gpu.up(B), ldb, gpu.up(C), ldc, M, ldm)
+    out = gpu.down(M)
+    assert out[:, :R].tobytes() == want.tobytes()
+    assert np.isnan(out[:, R:]).all()
+
+
+def test_tet_mttkrp_wide_factors_block_by_block_exact_on_integers(gpu, oracle):
+    """More than 32 columns: every block of 32 is its own launch on shifted factor pointers; the padding
+    of M beyond column R stays untouched."""
+    n, R, ldb, ldc, ldm = 66, 70, 72, 70, 75
+    Ap = inputs.small_int(143, -2, 2, tet(n))
+    B, C = inputs.small_int(144, -2, 2, n, ldb), inputs.small_int(145, -2, 2, n, ldc)
     want, _ = oracle.tet_mttkrp(n, R, Ap, np.ascontiguousarray(B[:, :R]), np.ascontiguousarray(C[:, :R]))
     M = gpu.empty(n, ldm)
     gpu.d.tet_mttkrp_f32(n, R, gpu.up(Ap), gpu.up(B), ldb, gpu.up(C), ldc, M, ldm)

@@ -59,7 +59,7 @@ def test_random_sizes_match_the_oracle(gpu, oracle, seed0):
         U642, B64 = inputs.uniform64(seed+7, tri(n2)), inputs.uniform64(seed+8, n2, m)
         C = nan64(n2, m); d.trmm_f64(n2, m, up(U642), up(B64), m, C, m); check("trmm_f64", (n2, m), down(C), *oracle.trmm_f64(n2, m, U642, B64), tol=1e-12)
         # band family
-        nb = rng.choice([rng.randint(1, 300), rng.randint(300, 20000)]); w = rng.choice([0, 1, 2, 4, 8, 16, rng.randint(0, 64)]); s = rng.choice([1, 2, rng.randint(1, max(1, nb)), nb + 5])
+        nb = rng.choice([rng.randint(1, 300), rng.randint(300, 20000)]); w = rng.choice([0, 1, 2, 4, 8, 16, rng.randint(0, 64), rng.randint(65, 150)]); s = rng.choice([1, 2, rng.randint(1, max(1, nb)), nb + 5])
         D, xb = inputs.band_normal(seed+9, nb, w), inputs.normal(seed+10, nb)
         y = nan(nb); d.band_spmv_f32(nb, w, up(D.ravel()), up(xb), y); check("band", (nb, w), down(y), *oracle.band_spmv(nb, w, D.ravel(), xb))
         y = nan(nb); d.sband_spmv_f32(nb, w, s, up(D.ravel()), up(xb), y); check("sband", (nb, w, s), down(y), *oracle.sband_spmv(nb, w, s, D.ravel(), xb))
@@ -72,7 +72,7 @@ def test_random_sizes_match_the_oracle(gpu, oracle, seed0):
         R64, S64, xl64 = inputs.uniform64(seed+26, nl), inputs.uniform64(seed+27, max(nl-1, 1)), inputs.uniform64(seed+28, nl)
         y = nan64(nl); d.leslie_spmv_f64(nl, up(R64), up(S64), up(xl64), y); check("leslie_f64", nl, down(y), *oracle.leslie_spmv_f64(nl, R64, S64[:nl-1], xl64), tol=1e-12)
         # tetrahedron
-        nt = rng.choice([rng.randint(1, 40), rng.randint(40, 150)]); R = rng.choice([1, 5, 16, 31, 32, rng.randint(1, 32)])
+        nt = rng.choice([rng.randint(1, 40), rng.randint(40, 150)]); R = rng.choice([1, 5, 16, 31, 32, rng.randint(1, 32), rng.randint(33, 80)])
         Ap, v = inputs.uniform(seed+16, tet(nt)), inputs.normal(seed+17, nt)
         M = nan(tri(nt)); d.tet_ttv_f32(nt, up(Ap), up(v), M); check("ttv", nt, down(M), *oracle.tet_ttv(nt, Ap, v))
         A64, v64 = inputs.uniform64(seed+18, tet(nt)), inputs.uniform64(seed+19, nt)

@@ -213,11 +213,11 @@ def test_new_domain_entry_points_reject_bad_arguments():
     assert L.dastac_pack_uhc_f64(4, 0, _p(A), _p(B), None) == dastac.EINVAL
     assert L.dastac_unpack_uhc_f64(4, 2, _p(A), None, None) == dastac.ENULL
     assert L.dastac_tet_mttkrp_f64(4, 0, _p(A), _p(B), 4, _p(C), 4, _p(D), 4, None) == dastac.EINVAL
-    assert L.dastac_tet_mttkrp_f64(4, 33, _p(A), _p(B), 33, _p(C), 33, _p(D), 33, None) == dastac.EINVAL
+    assert L.dastac_tet_mttkrp_f64(4, 2 ** 20 + 1, _p(A), _p(B), 2 ** 21, _p(C), 2 ** 21, _p(D), 2 ** 21, None) == dastac.EINVAL
     assert L.dastac_tet_mttkrp_f64(4, 8, _p(A), _p(B), 8, _p(C), 8, _p(D), 7, None) == dastac.EINVAL
     assert L.dastac_tet_mttkrp_f64(4, 2, _p(A), _p(B), 2, None, 2, _p(D), 2, None) == dastac.ENULL
     assert L.dastac_tet_mttkrp_f64(0, 2, None, None, 2, None, 2, None, 2, None) == dastac.OK
-    assert L.dastac_band_spmv_f64(4, 65, _p(A), _p(B), _p(C), None) == dastac.EINVAL
+    assert L.dastac_band_spmv_f64(4, 2 ** 20 + 1, _p(A), _p(B), _p(C), None) == dastac.EOVERFLOW
     assert L.dastac_band_spmv_f64(4, 1, _p(A), _p(B), _p(B + 24), None) == dastac.EALIAS
     assert L.dastac_pack_triu_f64(8, _p(A), 7, _p(B), None) == dastac.EINVAL
     assert L.dastac_unpack_tet_f64(4, _p(A), None, None) == dastac.ENULL
@@ -228,7 +228,7 @@ def test_new_domain_entry_points_reject_bad_arguments():
     assert L.dastac_unpack_tril_f64(4, None, _p(B), 4, None) == dastac.ENULL
     assert L.dastac_pack_tril_f64(4, _p(A), 4, _p(A + 120), None) == dastac.EALIAS  # 16 doubles reach byte 128
     assert L.dastac_sband_spmv_f64(4, 1, 0, _p(A), _p(B), _p(C), None) == dastac.EINVAL
-    assert L.dastac_sband_spmv_f64(4, 65, 1, _p(A), _p(B), _p(C), None) == dastac.EINVAL
+    assert L.dastac_sband_spmv_f64(4, 2 ** 20 + 1, 1, _p(A), _p(B), _p(C), None) == dastac.EOVERFLOW
     assert L.dastac_sband_spmv_f64(4, 1, 2, None, _p(B), _p(C), None) == dastac.ENULL
     assert L.dastac_sband_spmv_f64(4, 1, 2, _p(A), _p(B), _p(B + 24), None) == dastac.EALIAS
     assert L.dastac_sband_spmv_f64(0, 1, 2, None, None, None, None) == dastac.OK
@@ -248,7 +248,7 @@ def test_new_domain_entry_points_reject_bad_arguments():
     assert L.dastac_unpack_leslie_f64(4, None, _p(B), _p(C), 4, None) == dastac.ENULL
     assert L.dastac_sband_spmv_f32(-1, 1, 1, _p(A), _p(B), _p(C), None) == dastac.EINVAL
     assert L.dastac_sband_spmv_f32(4, 1, 0, _p(A), _p(B), _p(C), None) == dastac.EINVAL
-    assert L.dastac_sband_spmv_f32(4, 65, 1, _p(A), _p(B), _p(C), None) == dastac.EINVAL
+    assert L.dastac_sband_spmv_f32(4, 2 ** 20 + 1, 1, _p(A), _p(B), _p(C), None) == dastac.EOVERFLOW
     assert L.dastac_sband_spmv_f32(4, 1, 2 ** 41, _p(A), _p(B), _p(C), None) == dastac.EOVERFLOW
     assert L.dastac_sband_spmv_f32(4, 1, 2, None, _p(B), _p(C), None) == dastac.ENULL
     assert L.dastac_sband_spmv_f32(4, 1, 2, _p(A), _p(B), _p(B + 4), None) == dastac.EALIAS
@@ -289,10 +289,10 @@ def test_device_entry_points_reject_bad_arguments():
     assert L.dastac_trmm_f32(4, 0, _p(A), _p(B), 4, _p(C), 4, None) == dastac.EINVAL
     assert L.dastac_trmm_f32(4, 8, _p(A), _p(B), 7, _p(C), 8, None) == dastac.EINVAL
     assert L.dastac_band_spmv_f32(4, -1, _p(A), _p(B), _p(C), None) == dastac.EINVAL
-    assert L.dastac_band_spmv_f32(4, 65, _p(A), _p(B), _p(C), None) == dastac.EINVAL
+    assert L.dastac_band_spmv_f32(4, 2 ** 20 + 1, _p(A), _p(B), _p(C), None) == dastac.EOVERFLOW
     assert L.dastac_tet_ttv_f32(-1, _p(A), _p(B), _p(C), None) == dastac.EINVAL
     assert L.dastac_tet_mttkrp_f32(4, 0, _p(A), _p(B), 4, _p(C), 4, _p(D), 4, None) == dastac.EINVAL
-    assert L.dastac_tet_mttkrp_f32(4, 33, _p(A), _p(B), 33, _p(C), 33, _p(D), 33, None) == dastac.EINVAL
+    assert L.dastac_tet_mttkrp_f32(4, 2 ** 20 + 1, _p(A), _p(B), 2 ** 21, _p(C), 2 ** 21, _p(D), 2 ** 21, None) == dastac.EINVAL
     assert L.dastac_tet_mttkrp_f32(4, 8, _p(A), _p(B), 8, _p(C), 8, _p(D), 7, None) == dastac.EINVAL
     for fn in (L.dastac_trmv_t_f32, L.dastac_trmv_lower_f32, L.dastac_trmv_lower_t_f32, L.dastac_symv_lower_f32):
         assert fn(-1, _p(A), _p(B), _p(C), None) == dastac.EINVAL
