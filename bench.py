@@ -429,7 +429,7 @@ def main() -> int:
         import oracle
 
         oracle.lib()
-        rows2, rows5 = 4096, 256
+        rows2, rows5 = 6144, 320
         sample_flops = (acct["trmv"]["flops"] + acct["band"]["flops"] + acct["ttv"]["flops"]
                         + sum(2 * (n2 - i) * m2 for i in range(rows2))
                         + sum(3 * R5 * ((n5 - i) * (n5 - i + 1) // 2) for i in range(rows5)))
