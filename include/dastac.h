@@ -43,7 +43,9 @@
  *     retains memory.  "HOST" pointers are ordinary host memory.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Device
  *     operations are enqueued on it and return without synchronising.  A launch
- *     failure is reported as DASTAC_EHIP.
+ *     failure is reported as DASTAC_EHIP.  Every device operation consists of kernel
+ *     launches only (outputs that must start at zero are cleared by a fill kernel),
+ *     so the calls may be recorded into a HIP graph by stream capture.
  *   - Outputs are overwritten, not accumulated into (the paper's statement adds into
  *     a zero-initialised output, Section 5.2; the result is the same).
  *   - An output buffer that overlaps an input buffer is rejected with DASTAC_EALIAS.
