@@ -1,0 +1,169 @@
+"""Operands that are only element-aligned: every device pointer is a view that starts one or three
+elements into its allocation (4-byte aligned in single, 8-byte aligned in double precision, never 16), with
+odd leading dimensions where there are any.  The boundary promises nothing more than element alignment;
+results must still meet the usual bars against the oracle, and nothing outside the views may be written."""
+import numpy as np
+import pytest
+
+from paper_2407_13726_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+
+def tri(n):
+    return n * (n + 1) // 2
+
+
+def tet(n):
+    return n * (n + 1) * (n + 2) // 6
+
+
+class Shifted:
+    """Device copies of host arrays at an element offset inside a NaN-filled allocation."""
+
+    def __init__(self, gpu, dtype):
+        self.g, self.dtype, self.outs = gpu, dtype, []
+
+    def inp(self, a, off):
+        t = self.g.torch
+        a = np.ascontiguousarray(a, dtype=self.dtype).ravel()
+        buf = t.full((a.size + off + 5,), float("nan"), dtype=t.float32 if self.dtype == np.float32 else t.float64,
+                     device=self.g.dev)
+        buf[off:off + a.size] = t.from_numpy(a).to(self.g.dev)
+        return buf[off:off + a.size]
+
+    def out(self, count, off):
+        t = self.g.torch
+        buf = t.full((count + off + 5,), float("nan"), dtype=t.float32 if self.dtype == np.float32 else t.float64,
+                     device=self.g.dev)
+        self.outs.append((buf, off, count))
+        return buf[off:off + count]
+
+    def check_guards(self):
+        for buf, off, count in self.outs:
+            h = self.g.down(buf)
+            assert np.isnan(h[:off]).all() and np.isnan(h[off + count:]).all(), "wrote outside the output view"
+
+
+def within(got, want, scale, tol, what):
+    got, want, scale = (np.asarray(a, dtype=np.float64).ravel() for a in (got, want, scale))
+    assert np.isfinite(got).all(), what + ": non-finite"
+    assert (np.abs(got - want) <= tol * scale + 1e-300).all(), what
+
+
+@pytest.mark.parametrize("prec", ["f32", "f64"])
+def test_every_contraction_on_element_aligned_views(gpu, oracle, prec):
+    f64 = prec == "f64"
+    dt, tol, sfx = (np.float64, 1e-12, "_f64") if f64 else (np.float32, 1e-4, "_f32")
+    gen = inputs.uniform64 if f64 else inputs.uniform
+    osfx = "_f64" if f64 else ""
+    d, down = gpu.d, gpu.down
+    S = Shifted(gpu, dt)
+    fn = lambda name: getattr(d, name + sfx)
+    orc = lambda name: getattr(oracle, name + osfx)
+
+    # TRMV, TTV, the other products of one packed triangle
+    n = 1300
+    Up, x = gen(9300, tri(n)), gen(9301, n)
+    gU, gx = S.inp(Up, 1), S.inp(x, 3)
+    y = S.out(n, 1); fn("trmv")(n, gU, gx, y); within(down(y), *orc("trmv")(n, Up, x), tol, "trmv")
+    for name, lower, mode in (("symv", False, 2), ("trmv_t", False, 1), ("trmv_lower", True, 0), ("trmv_lower_t", True, 1),
+                              ("symv_lower", True, 2)):
+        y = S.out(n, 3); fn(name)(n, gU, gx, y)
+        within(down(y), *orc("trimv")(n, Up, x, lower=lower, mode=mode), tol, name)
+    N = n + 77
+    xN = gen(9302, N)
+    y = S.out(N, 1); fn("subtri_spmv")(N, n, gU, S.inp(xN, 1), y); within(down(y), *orc("subtri_spmv")(N, n, Up, xN), tol, "subtri")
+    nt = 70
+    Ap, v = gen(9303, tet(nt)), gen(9304, nt)
+    gA = S.inp(Ap, 3 if not f64 else 1)
+    M = S.out(tri(nt), 1); fn("tet_ttv")(nt, gA, S.inp(v, 1), M); within(down(M), *orc("tet_ttv")(nt, Ap, v), tol, "ttv")
+
+    # matrix right-hand sides with odd leading dimensions
+    n2, m, ldb, ldc = 200, 37, 39, 41
+    U2, B = gen(9305, tri(n2)), gen(9306, n2, ldb)
+    Bc = np.ascontiguousarray(B[:, :m])
+    gU2, gB = S.inp(U2, 1), S.inp(B, 1)
+    for name in ("trmm", "symm"):
+        C = S.out(n2 * ldc, 3 if not f64 else 1)
+        C.fill_(0.0)  # the padding columns of C are never written: keep the comparison finite
+        fn(name)(n2, m, gU2, gB, ldb, C, ldc)
+        want, scale = orc(name)(n2, m, U2, Bc)
+        within(down(C).reshape(n2, ldc)[:, :m], want, scale, tol, name)
+        assert not down(C).reshape(n2, ldc)[:, m:].any(), name + ": wrote into the padding of C"
+    R, ldm = 21, 23
+    Bf, Cf = gen(9307, nt, ldb), gen(9308, nt, ldc)
+    Mo = S.out(nt * ldm, 1); Mo.fill_(0.0)
+    fn("tet_mttkrp")(nt, R, gA, S.inp(Bf, 1), ldb, S.inp(Cf, 3 if not f64 else 1), ldc, Mo, ldm)
+    want, scale = orc("tet_mttkrp")(nt, R, Ap, np.ascontiguousarray(Bf[:, :R]), np.ascontiguousarray(Cf[:, :R]))
+    within(down(Mo).reshape(nt, ldm)[:, :R], want, scale, tol, "mttkrp")
+    nq, Q, K, ldq = 18, 33, 45, 35
+    Bq, Cq = gen(9309, tri(nq) * Q), gen(9310, K, ldq)
+    Aq = S.out(tri(nq) * K, 1); fn("ttm_ut")(nq, Q, K, S.inp(Bq, 1), S.inp(Cq, 1), ldq, Aq)
+    within(down(Aq), *orc("ttm_ut")(nq, Q, K, Bq, np.ascontiguousarray(Cq[:, :Q])), tol, "ttm_ut")
+    Np, dp, ldp = 500, 45, 47
+    Bp = gen(9311, Np, ldp)
+    gBp = S.inp(Bp, 1)
+    Bpc = np.ascontiguousarray(Bp[:, :dp])
+    o2 = S.out(tri(dp), 1); fn("pr_a2")(Np, dp, gBp, ldp, o2); within(down(o2), *orc("pr_a2")(Bpc), tol, "pr_a2")
+    o3 = S.out(tet(dp), 3 if not f64 else 1); fn("pr_a3")(Np, dp, gBp, ldp, o3); within(down(o3), *orc("pr_a3")(Bpc), tol, "pr_a3")
+
+    # band family and Leslie
+    nb, w, s = 3001, 5, 17
+    D, xb = gen(9312, 2 * w + 1, nb), gen(9313, nb)
+    gD, gxb = S.inp(D, 1), S.inp(xb, 3 if not f64 else 1)
+    y = S.out(nb, 1); fn("band_spmv")(nb, w, gD, gxb, y); within(down(y), *orc("band_spmv")(nb, w, D.ravel(), xb), tol, "band")
+    y = S.out(nb, 1); fn("sband_spmv")(nb, w, s, gD, gxb, y); within(down(y), *orc("sband_spmv")(nb, w, s, D.ravel(), xb), tol, "sband")
+    nl = 5003
+    Rl, Sl, xl = gen(9314, nl), gen(9315, nl - 1), gen(9316, nl)
+    y = S.out(nl, 1); fn("leslie_spmv")(nl, S.inp(Rl, 1), S.inp(Sl, 3 if not f64 else 1), S.inp(xl, 1), y)
+    within(down(y), *orc("leslie_spmv")(nl, Rl, Sl, xl), tol, "leslie")
+
+    S.check_guards()
+
+
+@pytest.mark.parametrize("prec", ["f32", "f64"])
+def test_pack_unpack_on_element_aligned_views(gpu, oracle, prec):
+    f64 = prec == "f64"
+    dt, sfx, osfx = (np.float64, "_f64", "_f64") if f64 else (np.float32, "_f32", "")
+    gen = inputs.uniform64 if f64 else inputs.uniform
+    d, down = gpu.d, gpu.down
+    S = Shifted(gpu, dt)
+    fn = lambda name: getattr(d, name + sfx)
+    orc = lambda name: getattr(oracle, name + osfx)
+    n, ld = 131, 135
+    D = gen(9400, n, ld)
+    Dc = np.ascontiguousarray(D[:, :n])
+    gD = S.inp(D, 1)
+    for kind, count in (("triu", tri(n)), ("tril", tri(n))):
+        P = S.out(count, 1); fn("pack_" + kind)(n, gD, ld, P)
+        want = orc("pack_" + kind)(Dc)
+        assert down(P).tobytes() == want.tobytes(), kind
+        U = S.out(n * ld, 1); U.fill_(7.0); fn("unpack_" + kind)(n, P, U, ld)
+        got = down(U).reshape(n, ld)
+        assert got[:, :n].tobytes() == orc("unpack_" + kind)(n, want).tobytes() and (got[:, n:] == 7.0).all(), kind
+    w, s, k = 4, 9, 50
+    P = S.out((2 * w + 1) * n, 1); fn("pack_band")(n, w, gD, ld, P)
+    assert down(P).tobytes() == orc("pack_band")(Dc, w).tobytes()
+    P = S.out((2 * w + 1) * n, 1); fn("pack_sband")(n, w, s, gD, ld, P)
+    assert down(P).tobytes() == orc("pack_sband")(Dc, w, s).tobytes()
+    P = S.out(tri(k), 1); fn("pack_subtri")(n, k, gD, ld, P)
+    assert down(P).tobytes() == orc("pack_subtri")(Dc, k).tobytes()
+    R, Sd = S.out(n, 1), S.out(n - 1, 1); fn("pack_leslie")(n, gD, ld, R, Sd)
+    wr, ws = orc("pack_leslie")(Dc)
+    assert down(R).tobytes() == wr.tobytes() and down(Sd).tobytes() == ws.tobytes()
+    nt = 23
+    T = gen(9401, nt, nt, nt)
+    P = S.out(tet(nt), 1); fn("pack_tet")(nt, S.inp(T, 1), P)
+    want = orc("pack_tet")(T)
+    assert down(P).tobytes() == want.tobytes()
+    Ud = S.out(nt ** 3, 1); fn("unpack_tet")(nt, P, Ud)
+    assert down(Ud).tobytes() == orc("unpack_tet")(nt, want).tobytes()
+    nq, Q = 15, 7
+    H = gen(9402, nq, nq, Q)
+    P = S.out(tri(nq) * Q, 1); fn("pack_uhc")(nq, Q, S.inp(H, 1), P)
+    want = orc("pack_uhc")(H)
+    assert down(P).tobytes() == want.tobytes()
+    Ud = S.out(nq * nq * Q, 1); fn("unpack_uhc")(nq, Q, P, Ud)
+    assert down(Ud).tobytes() == orc("unpack_uhc")(nq, nq, Q, want).tobytes()
+    S.check_guards()
