@@ -49,8 +49,9 @@
  *   - Outputs are overwritten, not accumulated into (the paper's statement adds into
  *     a zero-initialised output, Section 5.2; the result is the same).
  *   - An output buffer that overlaps an input buffer is rejected with DASTAC_EALIAS.
- *   - The library keeps no mutable global state and may be called from several
- *     host threads.
+ *   - The library may be called from several host threads: the only state it keeps is
+ *     what it asks of the runtime once per device (how many workgroups of a kernel
+ *     the device holds at once).
  */
 #ifndef DASTAC_H
 #define DASTAC_H

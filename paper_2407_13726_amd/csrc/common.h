@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "../../include/dastac.h"
 #include "index_poly.h"
 
@@ -20,6 +22,40 @@ inline bool overlaps(const void *a, int64_t na, const void *b, int64_t nb) {
 inline int launch_status() { return hipGetLastError() == hipSuccess ? DASTAC_OK : DASTAC_EHIP; }
 
 DASTAC_HD int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+#if defined(__HIPCC__)
+// Workgroups of `block` threads of `kernel` (no dynamic LDS) that the current device holds at once:
+// occupancy per compute unit x compute units.  Asked of the runtime on the first call per (kernel,
+// device) and remembered afterwards in a small table; 0 on a runtime error.
+template <typename Kernel>
+inline int64_t resident_blocks(Kernel kernel, int block) {
+  struct Entry {
+    const void *fn;
+    int dev;
+    int64_t blocks;
+  };
+  constexpr int kEntries = 256;
+  static Entry table[kEntries];
+  static int used = 0;
+  static std::mutex guard;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  const void *fn = reinterpret_cast<const void *>(kernel);
+  {
+    std::lock_guard<std::mutex> lock(guard);
+    for (int e = 0; e < used; ++e)
+      if (table[e].fn == fn && table[e].dev == dev) return table[e].blocks;
+  }
+  int per_cu = 0, cus = 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+      hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, block, 0) != hipSuccess)
+    return 0;
+  const int64_t v = (int64_t)(per_cu > 0 ? per_cu : 1) * (cus > 0 ? cus : 1);
+  std::lock_guard<std::mutex> lock(guard);
+  if (used < kEntries) table[used++] = Entry{fn, dev, v};  // a full table only means asking again
+  return v;
+}
+#endif
 
 // defined in trimv.hip
 int trmv_upper_by_panels(int64_t n, const float *Up, const float *x, float *y, void *stream);

@@ -275,12 +275,8 @@ int run(int64_t N, int64_t d, const float *B, int64_t ldb, float *out, void *str
   // round to 90 %, or else the best one found; every share is a multiple of a step and at least 8 steps.
   int64_t split = 1, chunk = kXT;
   if (N > 0) {
-    int dev = 0, per_cu = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, pr_mfma_kernel<CUBE, true, BK>, kBlock, 0) != hipSuccess)
-      return DASTAC_EHIP;
-    const int64_t slots = (int64_t)(per_cu > 0 ? per_cu : 1) * (cus > 0 ? cus : 1);
+    const int64_t slots = resident_blocks(pr_mfma_kernel<CUBE, true, BK>, kBlock);
+    if (slots <= 0) return DASTAC_EHIP;
     const int64_t max_split = N / (8 * kXT) > 1 ? N / (8 * kXT) : 1;
     double best = -1.0;
     for (int64_t s = 1; s <= max_split && s <= 4096; ++s) {

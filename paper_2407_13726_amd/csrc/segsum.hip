@@ -421,7 +421,7 @@ int dastac_trmv_f32(int64_t n, const float *Up, const float *x, float *y, void *
   if (!Up || !x || !y) return DASTAC_ENULL;
   if (overlaps(y, n * 4, Up, tri(n) * 4) || overlaps(y, n * 4, x, n * 4)) return DASTAC_EALIAS;
   if (n <= kLdsMaxN) return launch_lds<float, false>(n, Up, x, y, tri(n), stream);
-  // x no longer fits in LDS: the column-panel kernel keeps it in registers (n=16384: 4.7 TB/s)
+  // x no longer fits in LDS: the column-panel kernel keeps it in registers
   return trmv_upper_by_panels(n, Up, x, y, stream);
 }
 

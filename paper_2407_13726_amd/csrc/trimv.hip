@@ -263,16 +263,25 @@ int launch(int64_t n, const E *Tp, const E *x, E *y, hipStream_t st) {
     panel_rows<LOWER>(n, (int64_t)p * kW, kW, lo, hi);
     steps += hi - lo;
   }
-  // about 16 wavefronts per compute unit (256 of them), at least 4 rows per wavefront; measured for
-  // the symmetric product at n=8192: 256-thread workgroups 37 us, 512 42 us, 1024 67 us
-  int64_t R = ceil_div(steps, 256 * 16);
+  // One round of resident workgroups: as many as the device holds at once (occupancy x compute units,
+  // asked of the runtime once per device), never more -- a grid a little larger than that leaves most of
+  // the chip idle while the stragglers of a second round run (measured for the symmetric product at
+  // n=8192, where three workgroups fit a compute unit: 768 workgroups 34 us, 1024 38 us, 2048 46 us).
+  // At least 4 rows per wavefront.  Workgroups of 256 threads: 512 measured 42 us, 1024 67 us.
+  const int64_t slots = resident_blocks(trimv_kernel<E, NQ, LOWER, MODE>, kBlock);
+  if (slots <= 0) return DASTAC_EHIP;
+  int64_t R = ceil_div(steps, slots * kWavesPerBlock);
   if (R < 4) R = 4;
   Panels pn;
-  int blocks = 0;
-  for (int p = 0; p < npanels; ++p) {
-    pn.first[p] = blocks;
-    panel_rows<LOWER>(n, (int64_t)p * kW, kW, lo, hi);
-    blocks += (int)ceil_div(hi - lo, R * kWavesPerBlock);
+  int blocks;
+  for (;; ++R) {  // the per-panel round-up can push the count past the slots: a few more rows each
+    blocks = 0;
+    for (int p = 0; p < npanels; ++p) {
+      pn.first[p] = blocks;
+      panel_rows<LOWER>(n, (int64_t)p * kW, kW, lo, hi);
+      blocks += (int)ceil_div(hi - lo, R * kWavesPerBlock);
+    }
+    if (blocks <= slots || R >= n) break;
   }
   pn.first[npanels] = blocks;
   zero_kernel<E><<<(unsigned)ceil_div(n, 256), 256, 0, st>>>(y, n);
