@@ -163,7 +163,10 @@ int dastac_trmv_lower_t_f32(int64_t n, const float *Lp, const float *x, float *y
 int dastac_symv_lower_f32(int64_t n, const float *Lp, const float *x, float *y, void *stream);
 
 /* C(i,c) := U(i,k) * B(k,c), i<=k, 0<=c<m  (the SpMV_UT rule with a matrix right-hand side).
- * B is n x m row-major with row stride ldb >= m, C is n x m with row stride ldc >= m; m >= 1. */
+ * B is n x m row-major with row stride ldb >= m, C is n x m with row stride ldc >= m; m >= 1.
+ * Only columns 0..m-1 of every row of C are written.  When m is small against n the reduction range is
+ * shared out over several workgroups that add into a cleared C with floating-point atomics (the last
+ * bits may then differ between calls); at shapes with enough columns every element of C has one writer. */
 int dastac_trmm_f32(int64_t n, int64_t m, const float *Up, const float *B, int64_t ldb, float *C, int64_t ldc,
                     void *stream);
 

@@ -16,10 +16,16 @@
 // Only the two k-steps that touch the diagonal (and the ragged last step / last row block) take
 // the masked loader, which writes zeros for k<i; every other tile is loaded without predicates.
 //
-// Load balance without atomics: row block b needs (n - 64 b)/32 k-steps, so a workgroup processes
-// the pair (b, nb-1-b), and every workgroup does the same amount of work.  Workgroups that share
-// a row-block pair (different column blocks) get ids that are equal modulo 8, i.e. land on the
+// Load balance: row block b needs (n - 64 b)/32 k-steps, so a workgroup processes the pair
+// (b, nb-1-b), and every workgroup does the same amount of work.  Workgroups that share a
+// row-block pair (different column blocks) get ids that are equal modulo 8, i.e. land on the
 // same XCD, so the packed U rows they both read are fetched from HBM once and hit in that XCD's L2.
+//
+// Few columns give few workgroups (m = 256: one per compute unit), and a compute unit whose only
+// workgroup waits at its barrier has nothing else to run.  Then the k-steps of a pair, taken as one
+// list (the long block's, then the short block's), are cut into S equal shares, one workgroup each;
+// a share covers pieces of at most two row blocks and adds each piece into a zeroed C with
+// floating-point atomics.  With S = 1 nothing changes: plain stores, no atomics, no fill.
 #include "common.h"
 
 using namespace dastac;
@@ -39,19 +45,27 @@ struct Stage {
   f4a b[2];  // B: k rows bk and bk+16, four columns each
 };
 
+template <bool SPLIT>
 __global__ __launch_bounds__(kBlock) void trmm_mfma_kernel(int64_t n, int64_t m, const float *__restrict__ U,
                                                            const float *__restrict__ B, int64_t ldb,
                                                            float *__restrict__ C, int64_t ldc, int nb, int npairs,
-                                                           int ncb) {
+                                                           int ncb, int S) {
   __shared__ __attribute__((aligned(16))) float Us[2][kBM * kUP];
   __shared__ __attribute__((aligned(16))) float Bs[2][kKT * kBN];
 
   // workgroup id -> (row-block pair, column block); ids equal mod 8 share an XCD
   const int L = blockIdx.x;
   const int xcd = L & 7, slot = L >> 3;
-  const int pair = xcd + 8 * (slot / ncb);
-  const int cb = slot % ncb;
+  const int per_pair = SPLIT ? ncb * S : ncb;
+  const int pair = xcd + 8 * (slot / per_pair);
+  const int cb = SPLIT ? (slot % per_pair) / S : slot % ncb;
+  const int share = SPLIT ? slot % S : 0;
   if (pair >= npairs) return;
+  // this workgroup's share [t_lo, t_hi) of the pair's k-steps, numbered through both row blocks
+  const int steps_a = (int)ceil_div(n - (int64_t)pair * kBM, kKT);
+  const int steps_b = (nb - 1 - pair != pair) ? (int)ceil_div(n - (int64_t)(nb - 1 - pair) * kBM, kKT) : 0;
+  const int t_lo = SPLIT ? (int)((int64_t)(steps_a + steps_b) * share / S) : 0;
+  const int t_hi = SPLIT ? (int)((int64_t)(steps_a + steps_b) * (share + 1) / S) : steps_a + steps_b;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave >> 2, wc = wave & 3;  // 2x4 wavefronts: 32 rows x 32 columns each
@@ -68,7 +82,13 @@ __global__ __launch_bounds__(kBlock) void trmm_mfma_kernel(int64_t n, int64_t m,
     if (which == 1 && blk == pair) break;  // odd number of row blocks: the middle one is alone
     const int64_t i0 = (int64_t)blk * kBM;
     const bool rows_full = i0 + kBM <= n;
-    const int nk = (int)ceil_div(n - i0, kKT);
+    // k-steps [kt_lo, nk) of this row block fall into the share
+    const int first = which == 0 ? 0 : steps_a;  // number of the block's step 0 in the pair's list
+    const int steps_blk = which == 0 ? steps_a : steps_b;
+    // (literal bounds without shares: the compiler then peels the two masked steps off the loop)
+    const int kt_lo = SPLIT ? (t_lo > first ? t_lo - first : 0) : 0;
+    const int nk = SPLIT ? (t_hi - first < steps_blk ? t_hi - first : steps_blk) : (int)ceil_div(n - i0, kKT);
+    if (SPLIT && kt_lo >= nk) continue;
 
     // per-thread packed row bases: element (i,k) of U is at ubase[i] + k
     const int64_t iu = i0 + ur;
@@ -135,7 +155,7 @@ __global__ __launch_bounds__(kBlock) void trmm_mfma_kernel(int64_t n, int64_t m,
 
     Stage st;
     Ops oa, ob;
-    load_stage(0, st);
+    load_stage(kt_lo, st);
     __syncthreads();  // the previous row block's last reads of buffer 0 are done
     store_stage(0, st);
     __syncthreads();
@@ -160,7 +180,7 @@ __global__ __launch_bounds__(kBlock) void trmm_mfma_kernel(int64_t n, int64_t m,
       if (more) read_ops(buf ^ 1, 0, oa);
       mma(ob);
     };
-    for (int kt = 0; kt < nk; kt += 2) {
+    for (int kt = kt_lo; kt < nk; kt += 2) {
       step(kt, 0);
       if (kt + 1 < nk) step(kt + 1, 1);
     }
@@ -171,8 +191,23 @@ __global__ __launch_bounds__(kBlock) void trmm_mfma_kernel(int64_t n, int64_t m,
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int64_t i = i0 + wr * 32 + 8 * (v / 4) + 4 * h + (v % 4);
-      if (i < n && col < m) C[i * ldc + col] = acc[v];
+      if (i < n && col < m) {
+        if (SPLIT)
+          unsafeAtomicAdd(&C[i * ldc + col], acc[v]);
+        else
+          C[i * ldc + col] = acc[v];
+      }
     }
+  }
+}
+
+// C(0..n-1, 0..m-1) := 0, leaving the padding columns of every row alone
+__global__ __launch_bounds__(256) void zero_rows_kernel(float *__restrict__ C, int64_t n, int64_t m, int64_t ldc) {
+  const int64_t quads = (m + 3) / 4, total = n * quads;
+  for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
+    const int64_t i = t / quads, c = (t - i * quads) * 4;
+    float *row = C + i * ldc;
+    for (int64_t e = c; e < c + 4 && e < m; ++e) row[e] = 0.0f;
   }
 }
 
@@ -188,8 +223,34 @@ extern "C" int dastac_trmm_f32(int64_t n, int64_t m, const float *Up, const floa
   const int nb = (int)ceil_div(n, kBM);
   const int npairs = (nb + 1) / 2;
   const int ncb = (int)ceil_div(m, kBN);
-  const int64_t grid = (int64_t)8 * ceil_div(npairs, 8) * ncb;
-  if (grid > 0x7fffffff) return DASTAC_EOVERFLOW;
-  trmm_mfma_kernel<<<(unsigned)grid, kBlock, 0, (hipStream_t)stream>>>(n, m, Up, B, ldb, C, ldc, nb, npairs, ncb);
+  const int64_t base = (int64_t)8 * ceil_div(npairs, 8) * ncb;
+  if (base > 0x7fffffff) return DASTAC_EOVERFLOW;
+  hipStream_t st = (hipStream_t)stream;
+  // Shares of the k range per pair.  One workgroup per compute unit already keeps the matrix pipes as busy
+  // as two do (m = 256 at n = 16384 runs in 0.60 ms either way), so what matters is that the workgroups
+  // come in whole layers over the compute units: take the smallest S <= 16, with at least 32 k-steps per
+  // share, whose last layer is at least 95 % full, else the fullest.  (n = 16384: m = 128 58 -> 102 TFLOP/s
+  // with two shares, m = 384 93 -> 118; n = 4096, m = 256 with four shares 82.)
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+    return DASTAC_EHIP;
+  const int64_t steps = ceil_div(n, kKT) + 2;  // k-steps of a pair, about
+  int64_t S = 1;
+  double best = 0.0;
+  for (int64_t s = 1; s <= 16 && (s == 1 || steps / s >= 32); ++s) {
+    const int64_t wgs = base * s;
+    const double fill = (double)wgs / (double)(ceil_div(wgs, cus) * cus);
+    if (fill > best + 0.02) best = fill, S = s;
+    if (fill >= 0.95) break;
+  }
+  if (S <= 1) {
+    trmm_mfma_kernel<false><<<(unsigned)base, kBlock, 0, st>>>(n, m, Up, B, ldb, C, ldc, nb, npairs, ncb, 1);
+    return launch_status();
+  }
+  const int64_t zb = ceil_div(n * ((m + 3) / 4), 256);
+  zero_rows_kernel<<<(unsigned)(zb < 4096 ? zb : 4096), 256, 0, st>>>(C, n, m, ldc);
+  if (hipGetLastError() != hipSuccess) return DASTAC_EHIP;
+  trmm_mfma_kernel<true><<<(unsigned)(base * S), kBlock, 0, st>>>(n, m, Up, B, ldb, C, ldc, nb, npairs, ncb, (int)S);
   return launch_status();
 }

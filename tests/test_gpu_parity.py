@@ -185,6 +185,36 @@ def test_trmm_leading_dimensions_and_integer_exactness(gpu, oracle):
     assert np.isnan(out[:, m:]).all()
 
 
+def test_trmm_shares_of_the_k_range_exact_on_integers(gpu, oracle):
+    """Few columns on a tall triangle: the k-steps of every row-block pair are cut into shares, one workgroup
+    each, which add into a zeroed C.  Integer inputs make the result independent of the order of those adds;
+    the padding columns of C must survive the clearing; a second call must not add onto the first."""
+    n, m, ldb, ldc = 2100, 40, 44, 43
+    Up = inputs.small_int(122, -2, 2, tri(n))
+    B = inputs.small_int(123, -2, 2, n, ldb)
+    want, _ = oracle.trmm(n, m, Up, np.ascontiguousarray(B[:, :m]))
+    C = gpu.empty(n, ldc)
+    dU, dB = gpu.up(Up), gpu.up(B)
+    for _ in range(2):
+        gpu.d.trmm_f32(n, m, dU, dB, ldb, C, ldc)
+        out = gpu.down(C)
+        assert out[:, :m].tobytes() == want.tobytes()
+        assert np.isnan(out[:, m:]).all()
+
+
+@pytest.mark.parametrize("n,m", [(4200, 130), (4096, 256), (2500, 1), (6000, 128)])
+def test_trmm_shares_of_the_k_range_sampled_rows(gpu, oracle, n, m):
+    Up, B = inputs.uniform(124 + n, tri(n)), inputs.uniform(125 + n, n, m)
+    C = gpu.empty(n, m)
+    gpu.d.trmm_f32(n, m, gpu.up(Up), gpu.up(B), m, C, m)
+    got = gpu.down(C)
+    assert np.isfinite(got).all()
+    for lo in (0, 63, n // 3, n // 2 - 30, n - 70):
+        hi = min(lo + 70, n)
+        want, scale = oracle.trmm(n, m, Up, B, rows=(lo, hi))
+        assert_within(got[lo:hi], want[lo:hi], scale[lo:hi], "trmm n=%d m=%d rows %d..%d" % (n, m, lo, hi))
+
+
 # ------------------------------------------------------ symmetric (SYMV) ----
 
 @pytest.mark.parametrize("n", [1, 2, 3, 5, 16, 17, 63, 64, 65, 130, 257, 512, 1000, 1025, 2050, 4100, 8192])
