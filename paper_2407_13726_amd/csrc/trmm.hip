@@ -226,23 +226,26 @@ extern "C" int dastac_trmm_f32(int64_t n, int64_t m, const float *Up, const floa
   const int64_t base = (int64_t)8 * ceil_div(npairs, 8) * ncb;
   if (base > 0x7fffffff) return DASTAC_EOVERFLOW;
   hipStream_t st = (hipStream_t)stream;
-  // Shares of the k range per pair.  One workgroup per compute unit already keeps the matrix pipes as busy
-  // as two do (m = 256 at n = 16384 runs in 0.60 ms either way), so what matters is that the workgroups
-  // come in whole layers over the compute units: take the smallest S <= 16, with at least 32 k-steps per
-  // share, whose last layer is at least 95 % full, else the fullest.  (n = 16384: m = 128 58 -> 102 TFLOP/s
-  // with two shares, m = 384 93 -> 118; n = 4096, m = 256 with four shares 82.)
+  // Shares of the k range per pair: the smallest S <= 16, with at least 32 k-steps per share, whose
+  // workgroups come in whole layers of two per compute unit (n = 16384: m = 128 58 -> 111 TFLOP/s, m = 384
+  // 93 -> 120; n = 8192, m = 256 114).  Where the column blocks alone give one full layer of one workgroup
+  // per compute unit (m = 256 at n = 16384) a second layer gains 1 % (0.589 -> 0.582 ms with the clearing
+  // of C): not worth giving up plain stores and one writer per element, so S = 1 there.
   int dev = 0, cus = 0;
   if (hipGetDevice(&dev) != hipSuccess ||
       hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
     return DASTAC_EHIP;
   const int64_t steps = ceil_div(n, kKT) + 2;  // k-steps of a pair, about
   int64_t S = 1;
-  double best = 0.0;
-  for (int64_t s = 1; s <= 16 && (s == 1 || steps / s >= 32); ++s) {
-    const int64_t wgs = base * s;
-    const double fill = (double)wgs / (double)(ceil_div(wgs, cus) * cus);
-    if (fill > best + 0.02) best = fill, S = s;
-    if (fill >= 0.95) break;
+  if ((double)base / (double)(ceil_div(base, cus) * cus) < 0.95) {
+    const int64_t layer = 2 * (int64_t)cus;
+    double best = 0.0;
+    for (int64_t s = 1; s <= 16 && (s == 1 || steps / s >= 32); ++s) {
+      const int64_t wgs = base * s;
+      const double fill = (double)wgs / (double)(ceil_div(wgs, layer) * layer);
+      if (fill > best + 0.02) best = fill, S = s;
+      if (fill >= 0.95) break;
+    }
   }
   if (S <= 1) {
     trmm_mfma_kernel<false><<<(unsigned)base, kBlock, 0, st>>>(n, m, Up, B, ldb, C, ldc, nb, npairs, ncb, 1);

@@ -36,19 +36,27 @@ struct Stage {
   d2a b[2];  // B: k rows bk and bk+8, two columns each
 };
 
+template <bool SPLIT>
 __global__ __launch_bounds__(kBlock) void trmm_f64_kernel(int64_t n, int64_t m, const double *__restrict__ U,
                                                           const double *__restrict__ B, int64_t ldb,
                                                           double *__restrict__ C, int64_t ldc, int nb, int npairs,
-                                                          int ncb) {
+                                                          int ncb, int S) {
   __shared__ __attribute__((aligned(16))) double Us[2][kBM * kUP];
   __shared__ __attribute__((aligned(16))) double Bs[2][kKT * kBN];
 
   // workgroup id -> (row-block pair, column block); ids equal mod 8 share an XCD
   const int L = blockIdx.x;
   const int xcd = L & 7, slot = L >> 3;
-  const int pair = xcd + 8 * (slot / ncb);
-  const int cb = slot % ncb;
+  const int per_pair = SPLIT ? ncb * S : ncb;
+  const int pair = xcd + 8 * (slot / per_pair);
+  const int cb = SPLIT ? (slot % per_pair) / S : slot % ncb;
+  const int share = SPLIT ? slot % S : 0;
   if (pair >= npairs) return;
+  // this workgroup's share [t_lo, t_hi) of the pair's k-steps, numbered through both row blocks
+  const int steps_a = (int)ceil_div(n - (int64_t)pair * kBM, kKT);
+  const int steps_b = (nb - 1 - pair != pair) ? (int)ceil_div(n - (int64_t)(nb - 1 - pair) * kBM, kKT) : 0;
+  const int t_lo = SPLIT ? (int)((int64_t)(steps_a + steps_b) * share / S) : 0;
+  const int t_hi = SPLIT ? (int)((int64_t)(steps_a + steps_b) * (share + 1) / S) : steps_a + steps_b;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave >> 2, wc = wave & 3;  // 2x4 wavefronts: 32 rows x 32 columns each
@@ -65,7 +73,13 @@ __global__ __launch_bounds__(kBlock) void trmm_f64_kernel(int64_t n, int64_t m, 
     if (which == 1 && blk == pair) break;  // odd number of row blocks: the middle one is alone
     const int64_t i0 = (int64_t)blk * kBM;
     const bool rows_full = i0 + kBM <= n;
-    const int nk = (int)ceil_div(n - i0, kKT);
+    // k-steps [kt_lo, nk) of this row block fall into the share (literal bounds without shares, so that
+    // the compiler peels the masked diagonal steps off the loop)
+    const int first = which == 0 ? 0 : steps_a;  // number of the block's step 0 in the pair's list
+    const int steps_blk = which == 0 ? steps_a : steps_b;
+    const int kt_lo = SPLIT ? (t_lo > first ? t_lo - first : 0) : 0;
+    const int nk = SPLIT ? (t_hi - first < steps_blk ? t_hi - first : steps_blk) : (int)ceil_div(n - i0, kKT);
+    if (SPLIT && kt_lo >= nk) continue;
 
     // element (i,k) of U is at ub + k for this thread's row i
     const int64_t iu = i0 + ur;
@@ -131,7 +145,7 @@ __global__ __launch_bounds__(kBlock) void trmm_f64_kernel(int64_t n, int64_t m, 
 
     Stage st;
     Ops oa, ob;
-    load_stage(0, st);
+    load_stage(kt_lo, st);
     __syncthreads();  // the previous row block's last reads of buffer 0 are done
     store_stage(0, st);
     __syncthreads();
@@ -154,7 +168,7 @@ __global__ __launch_bounds__(kBlock) void trmm_f64_kernel(int64_t n, int64_t m, 
       if (more) read_ops(buf ^ 1, 0, oa);
       mma(ob);
     };
-    for (int kt = 0; kt < nk; kt += 2) {
+    for (int kt = kt_lo; kt < nk; kt += 2) {
       step(kt, 0);
       if (kt + 1 < nk) step(kt + 1, 1);
     }
@@ -169,9 +183,24 @@ __global__ __launch_bounds__(kBlock) void trmm_f64_kernel(int64_t n, int64_t m, 
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
           const int64_t i = i0 + wr * 32 + 16 * ra + 4 * v + l4;
-          if (i < n && col < m) C[i * ldc + col] = acc[2 * ra + ca][v];
+          if (i < n && col < m) {
+            if (SPLIT)
+              unsafeAtomicAdd(&C[i * ldc + col], acc[2 * ra + ca][v]);
+            else
+              C[i * ldc + col] = acc[2 * ra + ca][v];
+          }
         }
       }
+  }
+}
+
+// C(0..n-1, 0..m-1) := 0, leaving the padding columns of every row alone
+__global__ __launch_bounds__(256) void zero_rows_kernel(double *__restrict__ C, int64_t n, int64_t m, int64_t ldc) {
+  const int64_t pairs = (m + 1) / 2, total = n * pairs;
+  for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < total; t += (int64_t)gridDim.x * 256) {
+    const int64_t i = t / pairs, c = (t - i * pairs) * 2;
+    double *row = C + i * ldc;
+    for (int64_t e = c; e < c + 2 && e < m; ++e) row[e] = 0.0;
   }
 }
 
@@ -187,8 +216,34 @@ extern "C" int dastac_trmm_f64(int64_t n, int64_t m, const double *Up, const dou
   const int nb = (int)ceil_div(n, kBM);
   const int npairs = (nb + 1) / 2;
   const int ncb = (int)ceil_div(m, kBN);
-  const int64_t grid = (int64_t)8 * ceil_div(npairs, 8) * ncb;
-  if (grid > 0x7fffffff) return DASTAC_EOVERFLOW;
-  trmm_f64_kernel<<<(unsigned)grid, kBlock, 0, (hipStream_t)stream>>>(n, m, Up, B, ldb, C, ldc, nb, npairs, ncb);
+  const int64_t base = (int64_t)8 * ceil_div(npairs, 8) * ncb;
+  if (base > 0x7fffffff) return DASTAC_EOVERFLOW;
+  hipStream_t st = (hipStream_t)stream;
+  // Shares of the k range per pair, as in the fp32 entry point: the smallest S <= 16, with at least 32
+  // k-steps per share, whose workgroups come in whole layers of two per compute unit.  Unlike fp32 the second
+  // layer pays at every shape measured (n = 16384: m = 256 1.19 -> 1.12 ms, m = 128 0.63 -> 0.59; n = 8192,
+  // m = 256 0.32 -> 0.29), so there is no single-layer exception; with two shares an element of C still gets
+  // at most two addends, whose sum does not depend on their order.
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+    return DASTAC_EHIP;
+  const int64_t layer = 2 * (int64_t)cus, steps = ceil_div(n, kKT) + 4;
+  int64_t S = 1;
+  double best = 0.0;
+  for (int64_t s = 1; s <= 16 && (s == 1 || steps / s >= 32); ++s) {
+    const int64_t wgs = base * s;
+    const double fill = (double)wgs / (double)(ceil_div(wgs, layer) * layer);
+    if (fill > best + 0.02) best = fill, S = s;
+    if (fill >= 0.95) break;
+  }
+  if (S <= 1) {
+    trmm_f64_kernel<false><<<(unsigned)base, kBlock, 0, st>>>(n, m, Up, B, ldb, C, ldc, nb, npairs, ncb, 1);
+    return launch_status();
+  }
+  const int64_t zb = ceil_div(n * ((m + 1) / 2), 256);
+  zero_rows_kernel<<<(unsigned)(zb < 4096 ? zb : 4096), 256, 0, st>>>(C, n, m, ldc);
+  if (hipGetLastError() != hipSuccess) return DASTAC_EHIP;
+  trmm_f64_kernel<true><<<(unsigned)(base * S), kBlock, 0, st>>>(n, m, Up, B, ldb, C, ldc, nb, npairs, ncb, (int)S);
   return launch_status();
 }

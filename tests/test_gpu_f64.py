@@ -186,6 +186,34 @@ def test_trmm_f64_large_sampled_rows(gpu, oracle):
         assert_within(got[i], want[i], scale[i], "trmm_f64 row %d" % i)
 
 
+def test_trmm_f64_shares_of_the_k_range_exact_on_integers(gpu, oracle):
+    """Few columns on a tall triangle: shares of the k range add into a zeroed C (see the fp32 test)."""
+    n, m, ldb, ldc = 1100, 40, 44, 43
+    Up = inputs.small_int(3522, -2, 2, tri(n)).astype(np.float64)
+    B = inputs.small_int(3523, -2, 2, n, ldb).astype(np.float64)
+    want, _ = oracle.trmm_f64(n, m, Up, np.ascontiguousarray(B[:, :m]))
+    C = gpu.empty(n, ldc)
+    dU, dB = gpu.up(Up), gpu.up(B)
+    for _ in range(2):
+        gpu.d.trmm_f64(n, m, dU, dB, ldb, C, ldc)
+        out = gpu.down(C)
+        assert out[:, :m].tobytes() == want.tobytes()
+        assert np.isnan(out[:, m:]).all()
+
+
+@pytest.mark.parametrize("n,m", [(2100, 130), (3000, 1), (5000, 128)])
+def test_trmm_f64_shares_of_the_k_range_sampled_rows(gpu, oracle, n, m):
+    Up, B = inputs.uniform64(3524 + n, tri(n)), inputs.uniform64(3525 + n, n, m)
+    C = gpu.empty(n, m)
+    gpu.d.trmm_f64(n, m, gpu.up(Up), gpu.up(B), m, C, m)
+    got = gpu.down(C)
+    assert np.isfinite(got).all()
+    for lo in (0, 63, n // 3, n // 2 - 30, n - 70):
+        hi = min(lo + 70, n)
+        want, scale = oracle.trmm_f64(n, m, Up, B, rows=(lo, hi))
+        assert_within(got[lo:hi], want[lo:hi], scale[lo:hi], "trmm_f64 n=%d m=%d rows %d..%d" % (n, m, lo, hi))
+
+
 @pytest.mark.parametrize("n,m", [(1, 1), (2, 3), (15, 5), (16, 16), (33, 7), (64, 64), (65, 33), (127, 128), (130, 129),
                                  (200, 256), (300, 40), (515, 70), (1030, 130)])
 def test_symm_f64_parity(gpu, oracle, n, m):
