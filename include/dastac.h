@@ -167,7 +167,7 @@ int dastac_symv_lower_f32(int64_t n, const float *Lp, const float *x, float *y, 
  * Only columns 0..m-1 of every row of C are written.  When m is small against n the reduction range is
  * shared out over several workgroups that add into a cleared C with floating-point atomics (the last
  * bits may then differ between calls); at shapes with enough columns every element of C has one writer.
- * (trmm_f64 always uses at least two shares when n >= 2048.) */
+ * (trmm_f64 shares more readily than trmm_f32: also where one workgroup per compute unit is available.) */
 int dastac_trmm_f32(int64_t n, int64_t m, const float *Up, const float *B, int64_t ldb, float *C, int64_t ldc,
                     void *stream);
 
