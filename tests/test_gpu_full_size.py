@@ -138,3 +138,21 @@ def test_pr_tensors_sampled_positions(gpu, oracle, which, N, d):
     for p in starts:
         want, scale = fn(w["B"], window=(p, p + 3))
         check(got[p:p + 3], want[p:p + 3], scale[p:p + 3], "pr_a%d position %d" % (which, p))
+
+
+def test_trmm_f64_16384_sampled_rows(gpu, oracle):
+    """The double-precision TRMM at the shape bench.py reports beside the step (two shares of the k range per
+    row-block pair): sampled rows against the long-double oracle, 1e-12 * sum|products|."""
+    w = wl.trmm_f64_inputs()
+    n, m = w["n"], w["m"]
+    t = gpu.torch
+    C = t.full((n, m), float("nan"), dtype=t.float64, device=gpu.dev)
+    gpu.d.trmm_f64(n, m, gpu.up(w["Up"]), gpu.up(w["B"]), m, C, m)
+    got = gpu.down(C)
+    assert np.isfinite(got).all()
+    rng = np.random.default_rng(3)
+    rows = sorted({0, 1, 63, 64, 8191, 8192, n - 65, n - 64, n - 17, n - 16, n - 1} | {int(r) for r in rng.integers(0, n, 8)})
+    for i in rows:
+        want, scale = oracle.trmm_f64(n, m, w["Up"], w["B"], rows=(i, i + 1))
+        err = np.abs(got[i] - want[i])
+        assert (err <= 1e-12 * scale[i]).all(), "trmm_f64 row %d: worst err/scale %.3g" % (i, (err / scale[i]).max())
