@@ -174,6 +174,9 @@ def main() -> int:
             ent["frac"] = ent["gflops"] / 1e3 / MFMA_F32_PEAK_TFLOPS
         ent["hbm_frac"] = ent["gbps"] / HBM_PEAK_GBPS
         ent["mfma_f32_frac"] = ent["gflops"] / 1e3 / MFMA_F32_PEAK_TFLOPS
+        # measured bytes per launch past the L2 (committed counter runs; null once the kernel source changed)
+        ent["traffic"] = measured_traffic(k)
+        ent["traffic_over_algorithmic"] = ent["traffic"] / by if ent["traffic"] else None
         kernels[k] = ent
     kernels["mttkrp"]["gflops_paper_convention"] = acct["mttkrp"]["flops_paper_convention"] / kernels["mttkrp"]["ms"] / 1e6
 
