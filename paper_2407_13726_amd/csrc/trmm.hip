@@ -19,7 +19,8 @@
 // Load balance: row block b needs (n - 64 b)/32 k-steps, so a workgroup processes the pair
 // (b, nb-1-b), and every workgroup does the same amount of work.  Workgroups that share a
 // row-block pair (different column blocks) get ids that are equal modulo 8, i.e. land on the
-// same XCD, so the packed U rows they both read are fetched from HBM once and hit in that XCD's L2.
+// same XCD, so the packed U rows they both read are fetched from HBM once and hit in that XCD's L2;
+// an XCD is given a run of consecutive pairs, which lets its L2 serve the re-reads of B as well.
 //
 // Few columns give few workgroups (m = 256: one per compute unit), and a compute unit whose only
 // workgroup waits at its barrier has nothing else to run.  Then the k-steps of a pair, taken as one
@@ -53,14 +54,17 @@ __global__ __launch_bounds__(kBlock) void trmm_mfma_kernel(int64_t n, int64_t m,
   __shared__ __attribute__((aligned(16))) float Us[2][kBM * kUP];
   __shared__ __attribute__((aligned(16))) float Bs[2][kKT * kBN];
 
-  // workgroup id -> (row-block pair, column block); ids equal mod 8 share an XCD
+  // workgroup id -> (row-block pair, column block); ids equal mod 8 share an XCD.  An XCD gets a run of
+  // consecutive pairs: their sweeps over k start 64 rows apart and move at the same speed, so the rows
+  // of B one of them reads are read again by its neighbour two k-steps later, out of that XCD's L2.
   const int L = blockIdx.x;
   const int xcd = L & 7, slot = L >> 3;
   const int per_pair = SPLIT ? ncb * S : ncb;
-  const int pair = xcd + 8 * (slot / per_pair);
+  const int pair_lo = (int)((int64_t)npairs * xcd / 8), pair_hi = (int)((int64_t)npairs * (xcd + 1) / 8);
+  const int pair = pair_lo + slot / per_pair;
   const int cb = SPLIT ? (slot % per_pair) / S : slot % ncb;
   const int share = SPLIT ? slot % S : 0;
-  if (pair >= npairs) return;
+  if (pair >= pair_hi) return;
   // this workgroup's share [t_lo, t_hi) of the pair's k-steps, numbered through both row blocks
   const int steps_a = (int)ceil_div(n - (int64_t)pair * kBM, kKT);
   const int steps_b = (nb - 1 - pair != pair) ? (int)ceil_div(n - (int64_t)(nb - 1 - pair) * kBM, kKT) : 0;

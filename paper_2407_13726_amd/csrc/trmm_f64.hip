@@ -48,10 +48,13 @@ __global__ __launch_bounds__(kBlock) void trmm_f64_kernel(int64_t n, int64_t m, 
   const int L = blockIdx.x;
   const int xcd = L & 7, slot = L >> 3;
   const int per_pair = SPLIT ? ncb * S : ncb;
-  const int pair = xcd + 8 * (slot / per_pair);
+  // an XCD gets a run of consecutive pairs: neighbouring sweeps read the same rows of B four k-steps apart,
+  // out of that XCD's L2
+  const int pair_lo = (int)((int64_t)npairs * xcd / 8), pair_hi = (int)((int64_t)npairs * (xcd + 1) / 8);
+  const int pair = pair_lo + slot / per_pair;
   const int cb = SPLIT ? (slot % per_pair) / S : slot % ncb;
   const int share = SPLIT ? slot % S : 0;
-  if (pair >= npairs) return;
+  if (pair >= pair_hi) return;
   // this workgroup's share [t_lo, t_hi) of the pair's k-steps, numbered through both row blocks
   const int steps_a = (int)ceil_div(n - (int64_t)pair * kBM, kKT);
   const int steps_b = (nb - 1 - pair != pair) ? (int)ceil_div(n - (int64_t)(nb - 1 - pair) * kBM, kKT) : 0;
