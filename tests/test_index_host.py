@@ -24,6 +24,32 @@ def test_library_exports_every_declared_symbol():
         assert getattr(L, name) is not None
 
 
+def test_binding_signatures_follow_the_header():
+    """Every prototype in the header against the argument list the binding marshals: the same number of
+    parameters, 64-bit integers where the header says int64_t, pointers where it says pointer."""
+    hdr = open(os.path.join(ROOT, "include", "dastac.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", " ", hdr, flags=re.S)  # comments mention the entry points too
+    protos = re.findall(r"\b([a-z_0-9]+\s*\*?)\s*\b(dastac_[a-z0-9_]+)\s*\(([^)]*)\)\s*;", hdr)
+    assert {name for _, name, _ in protos} == set(dastac.SIGNATURES)
+    for ret, name, params in protos:
+        res, args = dastac.SIGNATURES[name]
+        params = [q.strip() for q in params.split(",") if q.strip() and q.strip() != "void"]
+        assert len(params) == len(args), name
+        for decl, ctype in zip(params, args):
+            if "*" in decl:
+                assert ctype in (ctypes.c_void_p,) or issubclass(ctype, ctypes._Pointer), (name, decl)
+            elif decl.startswith("int64_t"):
+                assert ctype is ctypes.c_int64, (name, decl)
+            else:
+                assert decl.startswith("int ") and ctype is ctypes.c_int, (name, decl)
+        if "char" in ret:
+            assert res is ctypes.c_char_p, name
+        elif ret.strip() == "int64_t":
+            assert res is ctypes.c_int64, name
+        else:
+            assert ret.strip() == "int" and res is ctypes.c_int, name
+
+
 def test_strerror_names_every_code():
     names = {dastac.strerror(c) for c in range(6)}
     assert len(names) == 6 and "unknown status" not in names
