@@ -164,9 +164,11 @@ int dastac_symv_lower_f32(int64_t n, const float *Lp, const float *x, float *y, 
 
 /* C(i,c) := U(i,k) * B(k,c), i<=k, 0<=c<m  (the SpMV_UT rule with a matrix right-hand side).
  * B is n x m row-major with row stride ldb >= m, C is n x m with row stride ldc >= m; m >= 1.
- * Only columns 0..m-1 of every row of C are written.  When m is small against n the reduction range is
- * shared out over several workgroups that add into a cleared C with floating-point atomics (the last
- * bits may then differ between calls); at shapes with enough columns every element of C has one writer.
+ * Only columns 0..m-1 of every row of C are written.  With m <= 64 on n >= 1024 the packed triangle is
+ * streamed once per 32 columns and the pieces of C are added with floating-point atomics; otherwise, when
+ * m is small against n, the reduction range is shared out over several workgroups that add into a cleared
+ * C the same way (in both cases the last bits may differ between calls); at shapes with enough columns
+ * every element of C has one writer.
  * (trmm_f64 shares more readily than trmm_f32: also where one workgroup per compute unit is available.) */
 int dastac_trmm_f32(int64_t n, int64_t m, const float *Up, const float *B, int64_t ldb, float *C, int64_t ldc,
                     void *stream);

@@ -215,6 +215,20 @@ def test_trmm_shares_of_the_k_range_sampled_rows(gpu, oracle, n, m):
         assert_within(got[lo:hi], want[lo:hi], scale[lo:hi], "trmm n=%d m=%d rows %d..%d" % (n, m, lo, hi))
 
 
+@pytest.mark.parametrize("n,m,ldb,ldc", [(1024, 1, 1, 1), (1024, 32, 32, 32), (1055, 7, 9, 8), (1500, 33, 40, 35),
+                                        (2049, 64, 64, 70), (3000, 20, 20, 20)])
+def test_trmm_few_columns_streaming_kernel(gpu, oracle, n, m, ldb, ldc):
+    """Tall triangle, at most 64 right-hand sides: the kernel that streams U once per 32 columns and adds
+    32x32 pieces into a zeroed C.  Whole result against the oracle; padding of C untouched."""
+    Up, B = inputs.uniform(126 + n, tri(n)), inputs.uniform(127 + n, n, ldb)
+    want, scale = oracle.trmm(n, m, Up, np.ascontiguousarray(B[:, :m]))
+    C = gpu.empty(n, ldc)
+    gpu.d.trmm_f32(n, m, gpu.up(Up), gpu.up(B), ldb, C, ldc)
+    out = gpu.down(C)
+    assert_within(out[:, :m], want, scale, "trmm n=%d m=%d" % (n, m))
+    assert np.isnan(out[:, m:]).all()
+
+
 # ------------------------------------------------------ symmetric (SYMV) ----
 
 @pytest.mark.parametrize("n", [1, 2, 3, 5, 16, 17, 63, 64, 65, 130, 257, 512, 1000, 1025, 2050, 4100, 8192])
