@@ -91,6 +91,15 @@ def test_every_contraction_on_element_aligned_views(gpu, oracle, prec):
         want, scale = orc(name)(n2, m, U2, Bc)
         within(down(C).reshape(n2, ldc)[:, :m], want, scale, tol, name)
         assert not down(C).reshape(n2, ldc)[:, m:].any(), name + ": wrote into the padding of C"
+    if not f64:  # the streaming kernel for few columns on a tall triangle
+        n3, m3 = 1100, 37
+        U3, B3 = gen(9317, tri(n3)), gen(9318, n3, ldb)
+        C3 = S.out(n3 * ldc, 3)
+        C3.fill_(0.0)
+        fn("trmm")(n3, m3, S.inp(U3, 3), S.inp(B3, 1), ldb, C3, ldc)
+        want, scale = orc("trmm")(n3, m3, U3, np.ascontiguousarray(B3[:, :m3]))
+        within(down(C3).reshape(n3, ldc)[:, :m3], want, scale, tol, "trmm, few columns")
+        assert not down(C3).reshape(n3, ldc)[:, m3:].any()
     R, ldm = 21, 23
     Bf, Cf = gen(9307, nt, ldb), gen(9308, nt, ldc)
     Mo = S.out(nt * ldm, 1); Mo.fill_(0.0)
