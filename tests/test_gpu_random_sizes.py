@@ -58,6 +58,15 @@ def test_random_sizes_match_the_oracle(gpu, oracle, seed0):
         C = nan(n2, m); d.symm_f32(n2, m, up(Up2), up(B), m, C, m); check("symm", (n2, m), down(C), *oracle.symm(n2, m, Up2, B))
         U642, B64 = inputs.uniform64(seed+7, tri(n2)), inputs.uniform64(seed+8, n2, m)
         C = nan64(n2, m); d.trmm_f64(n2, m, up(U642), up(B64), m, C, m); check("trmm_f64", (n2, m), down(C), *oracle.trmm_f64(n2, m, U642, B64), tol=1e-12)
+        # tall triangles with few or some columns: the streaming kernel, or shares of the k range
+        n3 = rng.randint(1024, 3300); m3 = rng.choice([1, rng.randint(2, 64), rng.randint(65, 140)])
+        Up3, B3 = inputs.uniform(seed+30, tri(n3)), inputs.uniform(seed+31, n3, m3)
+        C = nan(n3, m3); d.trmm_f32(n3, m3, up(Up3), up(B3), m3, C, m3); got3 = down(C)
+        if not np.isfinite(got3).all():
+            fails.append(("trmm tall: non-finite", (n3, m3)))
+        for lo in (0, rng.randint(0, n3 - 20), n3 - 20):
+            want, scale = oracle.trmm(n3, m3, Up3, B3, rows=(lo, lo + 20))
+            check("trmm tall", (n3, m3, lo), got3[lo:lo+20], want[lo:lo+20], scale[lo:lo+20])
         # band family
         nb = rng.choice([rng.randint(1, 300), rng.randint(300, 20000)]); w = rng.choice([0, 1, 2, 4, 8, 16, rng.randint(0, 64), rng.randint(65, 150)]); s = rng.choice([1, 2, rng.randint(1, max(1, nb)), nb + 5])
         D, xb = inputs.band_normal(seed+9, nb, w), inputs.normal(seed+10, nb)
