@@ -63,6 +63,9 @@ int trmv_upper_by_panels(int64_t n, const double *Up, const double *x, double *y
 // defined in trmm_skinny.hip: C := U B for few columns (arguments already validated)
 int trmm_few_columns(int64_t n, int64_t m, const float *Up, const float *B, int64_t ldb, float *C, int64_t ldc,
                      void *stream);
+// defined in trmm_skinny_f64.hip
+int trmm_few_columns(int64_t n, int64_t m, const double *Up, const double *B, int64_t ldb, double *C, int64_t ldc,
+                     void *stream);
 
 #if defined(__HIPCC__)
 // 16-byte vector of floats that only promises 4-byte alignment: packed rows start at arbitrary

@@ -216,6 +216,8 @@ extern "C" int dastac_trmm_f64(int64_t n, int64_t m, const double *Up, const dou
   if (n == 0) return DASTAC_OK;
   if (!Up || !B || !C) return DASTAC_ENULL;
   if (overlaps(C, n * ldc * 8, Up, tri(n) * 8) || overlaps(C, n * ldc * 8, B, n * ldb * 8)) return DASTAC_EALIAS;
+  // few right-hand sides on a tall triangle: the streaming kernel (one pass over U per 32 columns)
+  if (m <= 64 && n >= 1024) return trmm_few_columns(n, m, Up, B, ldb, C, ldc, stream);
   const int nb = (int)ceil_div(n, kBM);
   const int npairs = (nb + 1) / 2;
   const int ncb = (int)ceil_div(m, kBN);

@@ -201,6 +201,20 @@ def test_trmm_f64_shares_of_the_k_range_exact_on_integers(gpu, oracle):
         assert np.isnan(out[:, m:]).all()
 
 
+@pytest.mark.parametrize("n,m,ldb,ldc", [(1024, 1, 1, 1), (1024, 32, 32, 32), (1055, 7, 9, 8), (1500, 33, 40, 35),
+                                        (2049, 64, 64, 70)])
+def test_trmm_f64_few_columns_streaming_kernel(gpu, oracle, n, m, ldb, ldc):
+    """Tall triangle, at most 64 right-hand sides: U streamed once per 32 columns, 32x32 pieces added into a
+    zeroed C.  Whole result against the oracle; padding of C untouched."""
+    Up, B = inputs.uniform64(3526 + n, tri(n)), inputs.uniform64(3527 + n, n, ldb)
+    want, scale = oracle.trmm_f64(n, m, Up, np.ascontiguousarray(B[:, :m]))
+    C = gpu.empty(n, ldc)
+    gpu.d.trmm_f64(n, m, gpu.up(Up), gpu.up(B), ldb, C, ldc)
+    out = gpu.down(C)
+    assert_within(out[:, :m], want, scale, "trmm_f64 n=%d m=%d" % (n, m))
+    assert np.isnan(out[:, m:]).all()
+
+
 @pytest.mark.parametrize("n,m", [(2100, 130), (3000, 1), (5000, 128)])
 def test_trmm_f64_shares_of_the_k_range_sampled_rows(gpu, oracle, n, m):
     Up, B = inputs.uniform64(3524 + n, tri(n)), inputs.uniform64(3525 + n, n, m)
