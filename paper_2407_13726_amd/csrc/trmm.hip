@@ -224,6 +224,8 @@ extern "C" int dastac_trmm_f32(int64_t n, int64_t m, const float *Up, const floa
   if (n == 0) return DASTAC_OK;
   if (!Up || !B || !C) return DASTAC_ENULL;
   if (overlaps(C, n * ldc * 4, Up, tri(n) * 4) || overlaps(C, n * ldc * 4, B, n * ldb * 4)) return DASTAC_EALIAS;
+  // one contiguous right-hand side is the matrix-vector product
+  if (m == 1 && ldb == 1 && ldc == 1) return dastac_trmv_f32(n, Up, B, C, stream);
   // few right-hand sides on a tall triangle: the streaming kernel (one pass over U per 32 columns)
   if (m <= 64 && n >= 1024) return trmm_few_columns(n, m, Up, B, ldb, C, ldc, stream);
   const int nb = (int)ceil_div(n, kBM);

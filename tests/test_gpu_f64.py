@@ -201,7 +201,7 @@ def test_trmm_f64_shares_of_the_k_range_exact_on_integers(gpu, oracle):
         assert np.isnan(out[:, m:]).all()
 
 
-@pytest.mark.parametrize("n,m,ldb,ldc", [(1024, 1, 1, 1), (1024, 32, 32, 32), (1055, 7, 9, 8), (1500, 33, 40, 35),
+@pytest.mark.parametrize("n,m,ldb,ldc", [(1024, 1, 1, 1), (1200, 1, 3, 2), (1024, 32, 32, 32), (1055, 7, 9, 8), (1500, 33, 40, 35),
                                         (2049, 64, 64, 70)])
 def test_trmm_f64_few_columns_streaming_kernel(gpu, oracle, n, m, ldb, ldc):
     """Tall triangle, at most 64 right-hand sides: U streamed once per 32 columns, 32x32 pieces added into a

@@ -215,7 +215,7 @@ def test_trmm_shares_of_the_k_range_sampled_rows(gpu, oracle, n, m):
         assert_within(got[lo:hi], want[lo:hi], scale[lo:hi], "trmm n=%d m=%d rows %d..%d" % (n, m, lo, hi))
 
 
-@pytest.mark.parametrize("n,m,ldb,ldc", [(1024, 1, 1, 1), (1024, 32, 32, 32), (1055, 7, 9, 8), (1500, 33, 40, 35),
+@pytest.mark.parametrize("n,m,ldb,ldc", [(1024, 1, 1, 1), (1200, 1, 3, 2), (1024, 32, 32, 32), (1055, 7, 9, 8), (1500, 33, 40, 35),
                                         (2049, 64, 64, 70), (3000, 20, 20, 20)])
 def test_trmm_few_columns_streaming_kernel(gpu, oracle, n, m, ldb, ldc):
     """Tall triangle, at most 64 right-hand sides: the kernel that streams U once per 32 columns and adds
