@@ -207,8 +207,10 @@ int dastac_tet_ttv_f32(int64_t n, const float *Ap, const float *v, float *Mp, vo
 
 /* M(i,r) := A(i,j,k) * B(j,r) * C(k,r), i<=j<=k, 0<=r<R  (Table 1 MTTKRP rule on the upper tetrahedron).
  * B, C are n x R row-major with row strides ldb, ldc >= R; M is n x R with row stride ldm >= R.
- * 1 <= R <= 2^20.  The kernel takes 32 columns of the factor matrices at a time: R > 32 runs block by block,
- * each block reading the packed tetrahedron once. */
+ * 1 <= R <= 2^20; row strides above 2^32 give DASTAC_EOVERFLOW.  The kernel takes 32 columns of the factor
+ * matrices at a time: R > 32 runs block by block, each block reading the packed tetrahedron once.  M is
+ * cleared first and the blocks of a slice add their parts with floating-point atomics, so the last bits
+ * may differ between calls (integer-valued inputs whose partial sums are exact give identical results). */
 int dastac_tet_mttkrp_f32(int64_t n, int64_t R, const float *Ap, const float *B, int64_t ldb, const float *C,
                           int64_t ldc, float *M, int64_t ldm, void *stream);
 
