@@ -11,7 +11,15 @@ form the kernel executes).  Inside the timed steps the kernel that dominates the
 bracketed by HIP events on the launch stream (`roofline`); a second pass of the same steps
 brackets every launch, so each kernel's own duration, GFLOP/s, GB/s and roofline fraction
 are reported too (an event pair adds a few microseconds of dispatch gap).  The CPU oracle is
-timed on a bounded sample of the same inputs as a baseline (not a target).
+timed on a bounded sample of the same inputs as a baseline (not a target), and what it computes is
+compared with what the timed launches left in their output buffers: the run fails (exit status 1)
+when an element is further than 1e-4 * sum|products| from the oracle.
+
+Besides the K timed steps the line carries: `steady_state` (200 further steps, by which time the clocks
+have settled -- after an idle period the matrix-core kernels run about 10 % slower for the first ~15
+steps, so the figures of a short timed region depend on the warm-up), `stream_ref` (a plain read-only
+stream over the same byte count as each bandwidth-bound contraction, measured the same way), `sweep`
+(TRMV, TTV and MTTKRP at larger sizes) and `pack` (compression / decompression throughput).
 
 Prints ONE JSON line.
 """
@@ -57,8 +65,10 @@ def main() -> int:
                     help="untimed steps before the timed ones (default 20: after an idle period the matrix-core "
                          "kernels run about 10 %% slower for the first ~15 steps)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
-    ap.add_argument("--sweep", action="store_true",
-                    help="also time TRMV, TTV and MTTKRP at larger sizes (reported under \"sweep\", never in value)")
+    ap.add_argument("--no-sweep", action="store_true",
+                    help="skip the size sweep of TRMV, TTV and MTTKRP (reported under \"sweep\", never in value)")
+    ap.add_argument("--steady-steps", type=int, default=200,
+                    help="further steps timed after everything else as `steady_state` (0: skip)")
     ap.add_argument("--no-beside", action="store_true",
                     help="skip the kernels that are measured beside the five-contraction step")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -160,6 +170,8 @@ def main() -> int:
 
     # second pass, same K steps, every launch bracketed: per-kernel durations
     per_kernel = bracketed_steps(args.steps)
+    # what the launches left in their output buffers, for the comparison with the oracle further down
+    produced = {k: g[k][-1].cpu().numpy() for k in order}
 
     kernels = {}
     for q, k in enumerate(order):
@@ -218,24 +230,40 @@ def main() -> int:
                          "throughputs are only in plots (Section 6.1 and 6.2)",
     }
 
-    # A plain device-to-device copy of 1 GiB on the same stream: the measured streaming reference the
-    # HBM-bound kernels are also compared with (a copy moves two bytes per byte copied).
-    ref_src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
-    ref_dst = torch.empty_like(ref_src)
-    ref_dst.copy_(ref_src)
-    rev = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
-    rev[0].record()
-    for s in range(5):
-        ref_dst.copy_(ref_src)
-        rev[s + 1].record()
-    torch.cuda.synchronize()
-    ref_ms = float(np.median([rev[s].elapsed_time(rev[s + 1]) for s in range(5)]))
-    stream_ref = 2.0 * ref_src.numel() * 4 / ref_ms / 1e6
-    del ref_src, ref_dst
-    result["stream_ref_gbps"] = stream_ref
+    # The measured streaming reference: the library's read-only stream (non-temporal 16-byte loads, one
+    # partial sum per workgroup) over the same number of bytes as each bandwidth-bound contraction moves,
+    # bracketed by events like the contractions themselves and, like them inside the step, preceded by
+    # other kernels' streams (here a 1 GiB read) so that nothing of the buffer waits in the memory-side cache.
+    flush = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
+    other = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
+    fpart = torch.empty(1 << 15, dtype=torch.float32, device=dev)
+
+    def stream_ref(nbytes, reps=10):
+        cnt = min(nbytes // 4, flush.numel())
+        buf = flush[:cnt]
+        npart = max(256, min(1 << 15, cnt // 8192))
+        ts = []
+        for _ in range(reps + 2):
+            d.stream_sum_f32(other.numel(), other, fpart, 1 << 15)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            d.stream_sum_f32(cnt, buf, fpart, npart)
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        ms = float(np.median(ts[2:]))
+        return {"bytes": cnt * 4, "ms": ms, "gbps": cnt * 4 / ms / 1e6}
+
+    result["stream_ref"] = {}
     for k in order:
         if bound[k] == "hbm":
-            kernels[k]["frac_of_stream_ref"] = kernels[k]["gbps"] / stream_ref
+            ref = stream_ref(acct[k]["bytes"])
+            result["stream_ref"][k] = ref
+            kernels[k]["frac_of_stream_ref"] = kernels[k]["gbps"] / ref["gbps"]
+    big = stream_ref(1 << 30)
+    result["stream_ref"]["1GiB"] = big
+    result["stream_ref_gbps"] = big["gbps"]
+    del flush, other
 
     # The two small operands (0.5 MB and 90 MB) fit in the 256 MB memory-side cache: inside the step they
     # are evicted by the other kernels' streams (the figures above); launched back to back they stay
@@ -251,7 +279,7 @@ def main() -> int:
         kernels[k]["warm_ms"] = float(np.mean([wev[s].elapsed_time(wev[s + 1]) for s in range(args.steps)]))
         kernels[k]["warm_gbps"] = acct[k]["bytes"] / kernels[k]["warm_ms"] / 1e6
 
-    if args.sweep:
+    if not args.no_sweep:
         def timed(fn, reps=10):
             fn()
             e = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
@@ -430,6 +458,68 @@ def main() -> int:
                                                wl.accounting("leslie_f64", n=w_["n"]), "hbm")
         del gR, gS, dw
 
+    # Compression / decompression (Section 3, "Data layout compression"): pure copies, timed at the two
+    # packed benchmark shapes.  Bytes: pack reads and writes the packed count; unpack reads it and writes
+    # the whole dense tensor (zeros outside the domain).
+    if not args.no_beside:
+        def timed_copy(fn, reps=5):
+            fn()
+            e = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+            e[0].record()
+            for r in range(reps):
+                fn()
+                e[r + 1].record()
+            torch.cuda.synchronize()
+            return float(np.median([e[r].elapsed_time(e[r + 1]) for r in range(reps)]))
+
+        result["pack"] = {}
+        dense = torch.empty(n2 * n2, dtype=torch.float32, device=dev).uniform_(-1, 1)
+        packed = torch.empty(n2 * (n2 + 1) // 2, dtype=torch.float32, device=dev)
+        for name, fn, by in (("pack_triu", lambda: d.pack_triu_f32(n2, dense, n2, packed), 8 * packed.numel()),
+                             ("unpack_triu", lambda: d.unpack_triu_f32(n2, packed, dense, n2),
+                              4 * (packed.numel() + dense.numel()))):
+            ms = timed_copy(fn)
+            result["pack"][name] = {"workload": "n=%d" % n2, "ms": ms, "gbps": by / ms / 1e6,
+                                    "frac": by / ms / 1e6 / HBM_PEAK_GBPS,
+                                    "frac_of_stream_ref": by / ms / 1e6 / result["stream_ref_gbps"]}
+        del dense, packed
+        dense = torch.empty(n5 * n5 * n5, dtype=torch.float32, device=dev).uniform_(-1, 1)
+        packed = torch.empty(n5 * (n5 + 1) * (n5 + 2) // 6, dtype=torch.float32, device=dev)
+        for name, fn, by in (("pack_tet", lambda: d.pack_tet_f32(n5, dense, packed), 8 * packed.numel()),
+                             ("unpack_tet", lambda: d.unpack_tet_f32(n5, packed, dense),
+                              4 * (packed.numel() + dense.numel()))):
+            ms = timed_copy(fn)
+            result["pack"][name] = {"workload": "n=%d" % n5, "ms": ms, "gbps": by / ms / 1e6,
+                                    "frac": by / ms / 1e6 / HBM_PEAK_GBPS,
+                                    "frac_of_stream_ref": by / ms / 1e6 / result["stream_ref_gbps"]}
+        del dense, packed
+
+    # Steady state: the same step, many more times, after everything above has kept the device busy.
+    if args.steady_steps > 0:
+        S = args.steady_steps
+        for _ in range(20):
+            for k in order:
+                launch[k]()
+        sev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(S)]
+        torch.cuda.synchronize()
+        s0 = time.perf_counter()
+        for q in range(S):
+            for k in order:
+                if k == dom:
+                    sev[q][0].record()
+                    launch[k]()
+                    sev[q][1].record()
+                else:
+                    launch[k]()
+        torch.cuda.synchronize()
+        s1 = time.perf_counter()
+        sms = (s1 - s0) * 1e3 / S
+        dms = float(np.mean([a.elapsed_time(b) for a, b in sev]))
+        dfr = (acct[dom]["flops"] / dms / 1e9 / MFMA_F32_PEAK_TFLOPS if bound[dom] == "mfma"
+               else acct[dom]["bytes"] / dms / 1e6 / HBM_PEAK_GBPS)
+        result["steady_state"] = {"steps": S, "ms_per_step": sms, "value": total_flops / sms / 1e6, "unit": "GFLOP/s",
+                                  "kernel": dom, "kernel_ms": dms, "roofline_frac": dfr}
+
     if not args.no_cpu_baseline:
         import oracle
 
@@ -439,12 +529,31 @@ def main() -> int:
                         + sum(2 * (n2 - i) * m2 for i in range(rows2))
                         + sum(3 * R5 * ((n5 - i) * (n5 - i + 1) // 2) for i in range(rows5)))
         c0 = time.perf_counter()
-        oracle.trmv(n1, h["trmv"]["Up"], h["trmv"]["x"])
-        oracle.trmm(n2, m2, h["trmm"]["Up"], h["trmm"]["B"], rows=(0, rows2))
-        oracle.band_spmv(n3, w3, h["band"]["D"].ravel(), h["band"]["x"])
-        oracle.tet_ttv(n4, h["ttv"]["Ap"], h["ttv"]["v"])
-        oracle.tet_mttkrp(n5, R5, h["mttkrp"]["Ap"], h["mttkrp"]["B"], h["mttkrp"]["C"], rows=(0, rows5))
+        want = {"trmv": oracle.trmv(n1, h["trmv"]["Up"], h["trmv"]["x"]),
+                "trmm": oracle.trmm(n2, m2, h["trmm"]["Up"], h["trmm"]["B"], rows=(0, rows2)),
+                "band": oracle.band_spmv(n3, w3, h["band"]["D"].ravel(), h["band"]["x"]),
+                "ttv": oracle.tet_ttv(n4, h["ttv"]["Ap"], h["ttv"]["v"]),
+                "mttkrp": oracle.tet_mttkrp(n5, R5, h["mttkrp"]["Ap"], h["mttkrp"]["B"], h["mttkrp"]["C"],
+                                            rows=(0, rows5))}
         c1 = time.perf_counter()
+        # The outputs of the timed launches against what the oracle just computed: every element the
+        # sample covers, |gpu - oracle| <= 1e-4 * sum|products| (reported as the largest ratio
+        # |gpu - oracle| / sum|products| per kernel).
+        covered = {"trmv": slice(0, n1), "trmm": slice(0, rows2), "band": slice(0, n3), "ttv": slice(0, None),
+                   "mttkrp": slice(0, rows5)}
+        check = {}
+        for k in order:
+            ref, scale = (np.asarray(a, dtype=np.float64) for a in want[k])
+            got = produced[k].astype(np.float64).reshape(ref.shape)[covered[k]]
+            ref, scale = ref[covered[k]], scale[covered[k]]
+            err = np.abs(got - ref)
+            ratio = np.where(scale > 0, err / np.where(scale > 0, scale, 1.0), np.where(err > 0, np.inf, 0.0))
+            check[k] = float(ratio.max()) if np.isfinite(got).all() else float("inf")
+        result["max_scaled_err"] = check
+        result["max_scaled_err_bound"] = 1e-4
+        result["check"] = ("every output element of TRMV, band SpMV and TTV, TRMM rows 0..%d and MTTKRP slices 0..%d "
+                           "of the timed launches against the oracle" % (rows2 - 1, rows5 - 1))
+        check_failed = any(not (v <= 1e-4) for v in check.values())
         result["cpu_baseline"] = {
             "value": sample_flops / (c1 - c0) / 1e9, "unit": "GFLOP/s", "cores": 1, "kind": "oracle",
             "sample": "full TRMV, band SpMV and TTV; TRMM output rows 0..%d; MTTKRP slices 0..%d "
@@ -456,7 +565,10 @@ def main() -> int:
         # windows, one per thread; the C calls run outside the interpreter lock.
         from concurrent.futures import ThreadPoolExecutor
 
-        T = max(1, min(16, os.cpu_count() or 1))
+        # threads: the host's cores, at most the 16 that one GPU's share of the machine allows
+        nproc = os.cpu_count() or 1
+        usable = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else nproc
+        T = max(1, min(16, usable))
 
         def cuts(lo, hi):
             step = -(-(hi - lo) // T)
@@ -475,9 +587,17 @@ def main() -> int:
                 fut.result()
         p1 = time.perf_counter()
         result["cpu_baseline"]["all_cores"] = {"value": sample_flops / (p1 - p0) / 1e9, "unit": "GFLOP/s", "cores": T,
-                                               "seconds": p1 - p0}
+                                               "seconds": p1 - p0, "nproc": nproc, "usable": usable,
+                                               "note": "threads capped at 16, one GPU's share of the host"}
+    else:
+        check_failed = False
+        result["max_scaled_err"] = None  # the oracle leg was skipped, nothing was compared
 
     print(json.dumps(result))
+    if check_failed:
+        print("bench.py: an output of the timed launches is further than 1e-4 * sum|products| from the oracle: %r"
+              % (result["max_scaled_err"],), file=sys.stderr)
+        return 1
     return 0
 
 

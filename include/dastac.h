@@ -231,6 +231,14 @@ int dastac_ttm_ut_f32(int64_t n, int64_t Q, int64_t K, const float *Bp, const fl
 int dastac_pr_a2_f32(int64_t N, int64_t d, const float *B, int64_t ldb, float *A2p, void *stream);
 int dastac_pr_a3_f32(int64_t N, int64_t d, const float *B, int64_t ldb, float *A3p, void *stream);
 
+/* Measurement aid, not one of the paper's operations: reads src[count] once (non-temporal 16-byte loads)
+ * and writes npartial partial sums, partial[b] = sum of the b-th contiguous chunk of ceil(count/npartial)
+ * elements (rounded up to a multiple of 4; chunks past the end give 0).  It is the read-only stream that
+ * bench.py times over the same byte count as each bandwidth-bound contraction (Section 6.1 reports run times
+ * only; the yardstick is this implementation's).  1 <= npartial <= 2^24, count <= 2^40 (else DASTAC_EINVAL,
+ * DASTAC_EOVERFLOW); src and partial are device pointers owned by the caller, 4-byte aligned. */
+int dastac_stream_sum_f32(int64_t count, const float *src, float *partial, int64_t npartial, void *stream);
+
 /* ---- double precision (the paper's own element type, Section 6.1) ------------------------------
  * The same layouts, index polynomials, argument rules and error codes as the _f32 entry points of the
  * same name, on double operands (8-byte aligned).  Each output element is within 1e-12 * sum|products|

@@ -102,6 +102,7 @@ SIGNATURES = {
     "dastac_sband_spmv_f32": (ctypes.c_int, [_i64, _i64, _i64, _vp, _vp, _vp, _vp]),
     "dastac_subtri_spmv_f32": (ctypes.c_int, [_i64, _i64, _vp, _vp, _vp, _vp]),
     "dastac_leslie_spmv_f32": (ctypes.c_int, [_i64, _vp, _vp, _vp, _vp, _vp]),
+    "dastac_stream_sum_f32": (ctypes.c_int, [_i64, _vp, _vp, _i64, _vp]),
 }
 
 
@@ -328,6 +329,10 @@ def subtri_spmv_f32(N, k, Ap, x, y, stream=None):
 
 def leslie_spmv_f32(n, R, S, x, y, stream=None):
     _check(lib().dastac_leslie_spmv_f32(n, _ptr(R), _ptr(S), _ptr(x), _ptr(y), _stream(stream)), "leslie_spmv_f32")
+
+
+def stream_sum_f32(count, src, partial, npartial, stream=None):
+    _check(lib().dastac_stream_sum_f32(count, _ptr(src), _ptr(partial), npartial, _stream(stream)), "stream_sum_f32")
 
 
 def symm_f32(n, m, Up, B, ldb, C, ldc, stream=None):
