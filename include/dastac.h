@@ -48,7 +48,12 @@
  *     so the calls may be recorded into a HIP graph by stream capture.
  *   - Outputs are overwritten, not accumulated into (the paper's statement adds into
  *     a zero-initialised output, Section 5.2; the result is the same).
- *   - An output buffer that overlaps an input buffer is rejected with DASTAC_EALIAS.
+ *   - An output buffer that overlaps an input buffer is rejected with DASTAC_EALIAS.  A
+ *     matrix with row stride ld occupies the bytes from its first element to the last
+ *     used element of its last row, so two column ranges of one row-major buffer that
+ *     interleave row by row count as overlapping only if those byte ranges intersect.
+ *   - Row strides (ld, ldb, ldc, ldm) above DASTAC_MAX_LD elements are rejected with
+ *     DASTAC_EOVERFLOW (rows * ld * element size must stay inside int64).
  *   - The library may be called from several host threads: the only state it keeps is
  *     what it asks of the runtime once per device (how many workgroups of a kernel
  *     the device holds at once).
@@ -72,6 +77,7 @@ extern "C" {
 /* Largest sizes accepted: beyond these a count or an intermediate product could overflow int64. */
 #define DASTAC_TRI_MAX_N 2147483647LL /* 2*Tri(n) < 2^63 */
 #define DASTAC_TET_MAX_N 1048576LL    /* Tri(n)*(n+2) < 2^63 */
+#define DASTAC_MAX_LD 268435456LL     /* largest row stride, in elements */
 
 /* Human-readable name of a status code (static storage, never NULL). */
 const char *dastac_strerror(int status);
@@ -138,6 +144,13 @@ int dastac_unpack_leslie_f32(int64_t n, const float *R, const float *S, float *d
 /* ---- contractions: DEVICE, fp32 storage and arithmetic ---------------------------
  * Summation order is unspecified (the paper compiles with fast-math, Section 6.1);
  * each output element is within 1e-4 * sum|products| of the exactly rounded result.
+ *
+ * Non-finite inputs.  Every contraction propagates Inf and NaN of the elements it multiplies as
+ * IEEE arithmetic does, with one exception: in trmv (n <= 8192), tet_ttv and subtri_spmv (k <= 8192)
+ * a product with a ZERO factor contributes nothing even if the other factor is Inf or NaN, where
+ * IEEE arithmetic and the plain rule give NaN -- in fp32 when either factor is zero, in fp64 when the
+ * element of x (of v) is zero.  (These kernels let lanes read past the end of a packed row and pair
+ * such elements with zeros; the same multiply serves the elements inside the row.)
  */
 
 /* y(i) := U(i,j) * x(j), i<=j   (Table 1/2, SpMV_UT).  Up[tri_count(n)], x[n], y[n]; n <= 524288.
@@ -207,7 +220,7 @@ int dastac_tet_ttv_f32(int64_t n, const float *Ap, const float *v, float *Mp, vo
 
 /* M(i,r) := A(i,j,k) * B(j,r) * C(k,r), i<=j<=k, 0<=r<R  (Table 1 MTTKRP rule on the upper tetrahedron).
  * B, C are n x R row-major with row strides ldb, ldc >= R; M is n x R with row stride ldm >= R.
- * 1 <= R <= 2^20; row strides above 2^32 give DASTAC_EOVERFLOW.  The kernel takes 32 columns of the factor
+ * 1 <= R <= 2^20.  The kernel takes 32 columns of the factor
  * matrices at a time: R > 32 runs block by block, each block reading the packed tetrahedron once.  M is
  * cleared first and the blocks of a slice add their parts with floating-point atomics, so the last bits
  * may differ between calls (integer-valued inputs whose partial sums are exact give identical results). */

@@ -18,6 +18,17 @@ inline bool overlaps(const void *a, int64_t na, const void *b, int64_t nb) {
   return a0 < b0 + (uintptr_t)nb && b0 < a0 + (uintptr_t)na;
 }
 
+// Largest row stride (in elements) an entry point accepts; keeps rows * ld * sizeof(element) inside int64 for
+// every row count the entry points accept.  Above it: DASTAC_EOVERFLOW.
+constexpr int64_t kMaxLd = DASTAC_MAX_LD;
+inline bool ld_too_large(int64_t a, int64_t b = 0, int64_t c = 0) { return a > kMaxLd || b > kMaxLd || c > kMaxLd; }
+
+// Bytes from the first element to one past the last of a view of `rows` rows with row stride ld of which the
+// first `cols` columns are used (the tail of the last row is not part of the view).
+inline int64_t view_bytes(int64_t rows, int64_t ld, int64_t cols, int64_t elem) {
+  return rows <= 0 ? 0 : ((rows - 1) * ld + cols) * elem;
+}
+
 // Status of the launch that was just issued on this thread.
 inline int launch_status() { return hipGetLastError() == hipSuccess ? DASTAC_OK : DASTAC_EHIP; }
 

@@ -194,10 +194,10 @@ int pack_sband(int64_t n, int64_t w, int64_t s, const T *dense, int64_t ld, T *d
   constexpr int64_t kB = (int64_t)sizeof(T);
   if (int rc = check_sband(n, w, s)) return rc;
   if (ld < n) return DASTAC_EINVAL;
-  if (n > kDenseMaxN || w > kDenseMaxN) return DASTAC_EOVERFLOW;
+  if (n > kDenseMaxN || w > kDenseMaxN || ld_too_large(ld)) return DASTAC_EOVERFLOW;
   if (n == 0) return DASTAC_OK;
   if (!dense || !diag_major) return DASTAC_ENULL;
-  if (overlaps(dense, n * ld * kB, diag_major, (2 * w + 1) * n * kB)) return DASTAC_EALIAS;
+  if (overlaps(dense, view_bytes(n, ld, n, kB), diag_major, (2 * w + 1) * n * kB)) return DASTAC_EALIAS;
   const int64_t pieces = ceil_div(n, kBlock), nblocks = (2 * w + 1) * pieces;
   pack_sband_kernel<T><<<grid_for(nblocks), kBlock, 0, (hipStream_t)stream>>>(n, w, s, dense, ld, diag_major, pieces,
                                                                            nblocks);
@@ -209,10 +209,10 @@ int unpack_sband(int64_t n, int64_t w, int64_t s, const T *diag_major, T *dense,
   constexpr int64_t kB = (int64_t)sizeof(T);
   if (int rc = check_sband(n, w, s)) return rc;
   if (ld < n) return DASTAC_EINVAL;
-  if (n > kDenseMaxN || w > kDenseMaxN) return DASTAC_EOVERFLOW;
+  if (n > kDenseMaxN || w > kDenseMaxN || ld_too_large(ld)) return DASTAC_EOVERFLOW;
   if (n == 0) return DASTAC_OK;
   if (!dense || !diag_major) return DASTAC_ENULL;
-  if (overlaps(dense, n * ld * kB, diag_major, (2 * w + 1) * n * kB)) return DASTAC_EALIAS;
+  if (overlaps(dense, view_bytes(n, ld, n, kB), diag_major, (2 * w + 1) * n * kB)) return DASTAC_EALIAS;
   const int64_t pieces = ceil_div(n, kBlock), nblocks = n * pieces;
   unpack_sband_kernel<T><<<grid_for(nblocks), kBlock, 0, (hipStream_t)stream>>>(n, w, s, diag_major, dense, ld, pieces,
                                                                              nblocks);
@@ -241,10 +241,10 @@ template <typename T>
 int pack_subtri(int64_t N, int64_t k, const T *dense, int64_t ld, T *packed, void *stream) {
   constexpr int64_t kB = (int64_t)sizeof(T);
   if (N < 0 || k < 0 || k > N || ld < N) return DASTAC_EINVAL;
-  if (N > kDenseMaxN) return DASTAC_EOVERFLOW;
+  if (N > kDenseMaxN || ld_too_large(ld)) return DASTAC_EOVERFLOW;
   if (k == 0) return DASTAC_OK;
   if (!dense || !packed) return DASTAC_ENULL;
-  if (overlaps(dense, N * ld * kB, packed, tri(k) * kB)) return DASTAC_EALIAS;
+  if (overlaps(dense, view_bytes(N, ld, N, kB), packed, tri(k) * kB)) return DASTAC_EALIAS;
   // the unique set is the upper triangle of the k x k block whose first column is N-k
   return pack_triu(k, dense + (N - k), ld, packed, stream);
 }
@@ -253,10 +253,10 @@ template <typename T>
 int unpack_subtri(int64_t N, int64_t k, const T *packed, T *dense, int64_t ld, void *stream) {
   constexpr int64_t kB = (int64_t)sizeof(T);
   if (N < 0 || k < 0 || k > N || ld < N) return DASTAC_EINVAL;
-  if (N > kDenseMaxN) return DASTAC_EOVERFLOW;
+  if (N > kDenseMaxN || ld_too_large(ld)) return DASTAC_EOVERFLOW;
   if (N == 0) return DASTAC_OK;
   if (!dense || (k > 0 && !packed)) return DASTAC_ENULL;
-  if (overlaps(dense, N * ld * kB, packed, tri(k) * kB)) return DASTAC_EALIAS;
+  if (overlaps(dense, view_bytes(N, ld, N, kB), packed, tri(k) * kB)) return DASTAC_EALIAS;
   const int64_t pieces = ceil_div(N, kBlock), nblocks = N * pieces;
   unpack_subtri_kernel<T><<<grid_for(nblocks), kBlock, 0, (hipStream_t)stream>>>(N, k, packed, dense, ld, pieces,
                                                                               nblocks);
@@ -286,10 +286,10 @@ template <typename T>
 int pack_leslie(int64_t n, const T *dense, int64_t ld, T *R, T *S, void *stream) {
   constexpr int64_t kB = (int64_t)sizeof(T);
   if (n < 0 || ld < n) return DASTAC_EINVAL;
-  if (n > kDenseMaxN) return DASTAC_EOVERFLOW;
+  if (n > kDenseMaxN || ld_too_large(ld)) return DASTAC_EOVERFLOW;
   if (n == 0) return DASTAC_OK;
   if (!dense || !R || (n > 1 && !S)) return DASTAC_ENULL;
-  if (overlaps(dense, n * ld * kB, R, n * kB) || overlaps(dense, n * ld * kB, S, (n - 1) * kB) ||
+  if (overlaps(dense, view_bytes(n, ld, n, kB), R, n * kB) || overlaps(dense, view_bytes(n, ld, n, kB), S, (n - 1) * kB) ||
       overlaps(R, n * kB, S, (n - 1) * kB))
     return DASTAC_EALIAS;
   pack_leslie_kernel<T><<<(unsigned)ceil_div(n, kBlock), kBlock, 0, (hipStream_t)stream>>>(n, dense, ld, R, S);
@@ -300,10 +300,10 @@ template <typename T>
 int unpack_leslie(int64_t n, const T *R, const T *S, T *dense, int64_t ld, void *stream) {
   constexpr int64_t kB = (int64_t)sizeof(T);
   if (n < 0 || ld < n) return DASTAC_EINVAL;
-  if (n > kDenseMaxN) return DASTAC_EOVERFLOW;
+  if (n > kDenseMaxN || ld_too_large(ld)) return DASTAC_EOVERFLOW;
   if (n == 0) return DASTAC_OK;
   if (!dense || !R || (n > 1 && !S)) return DASTAC_ENULL;
-  if (overlaps(dense, n * ld * kB, R, n * kB) || overlaps(dense, n * ld * kB, S, (n - 1) * kB)) return DASTAC_EALIAS;
+  if (overlaps(dense, view_bytes(n, ld, n, kB), R, n * kB) || overlaps(dense, view_bytes(n, ld, n, kB), S, (n - 1) * kB)) return DASTAC_EALIAS;
   const int64_t pieces = ceil_div(n, kBlock), nblocks = n * pieces;
   unpack_leslie_kernel<T><<<grid_for(nblocks), kBlock, 0, (hipStream_t)stream>>>(n, R, S, dense, ld, pieces, nblocks);
   return launch_status();

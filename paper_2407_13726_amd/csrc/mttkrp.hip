@@ -288,15 +288,14 @@ __global__ __launch_bounds__(256) void mttkrp_clear_kernel(int64_t n, int64_t R,
 
 extern "C" int dastac_tet_mttkrp_f32(int64_t n, int64_t R, const float *Ap, const float *B, int64_t ldb,
                                      const float *C, int64_t ldc, float *M, int64_t ldm, void *stream) {
-  constexpr int64_t kMaxLd = (int64_t)1 << 32;
   if (n < 0 || R < 1 || R > (1 << 20) || ldb < R || ldc < R || ldm < R) return DASTAC_EINVAL;
-  if (n > DASTAC_TET_MAX_N || tet(n) > ((int64_t)1 << 40) || ldb > kMaxLd || ldc > kMaxLd || ldm > kMaxLd)
+  if (n > DASTAC_TET_MAX_N || tet(n) > ((int64_t)1 << 40) || ld_too_large(ldb, ldc, ldm))
     return DASTAC_EOVERFLOW;
   if (n == 0) return DASTAC_OK;
   if (!Ap || !B || !C || !M) return DASTAC_ENULL;
-  const int64_t mb = ((n - 1) * ldm + R) * 4;
-  if (overlaps(M, mb, Ap, tet(n) * 4) || overlaps(M, mb, B, ((n - 1) * ldb + R) * 4) ||
-      overlaps(M, mb, C, ((n - 1) * ldc + R) * 4))
+  const int64_t mb = view_bytes(n, ldm, R, 4);
+  if (overlaps(M, mb, Ap, tet(n) * 4) || overlaps(M, mb, B, view_bytes(n, ldb, R, 4)) ||
+      overlaps(M, mb, C, view_bytes(n, ldc, R, 4)))
     return DASTAC_EALIAS;
   hipStream_t st = (hipStream_t)stream;
   mttkrp_clear_kernel<<<(unsigned)ceil_div(n * R, 256), 256, 0, st>>>(n, R, Ap, B, ldb, C, ldc, M, ldm, tet(n));

@@ -267,13 +267,14 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) 
 extern "C" int dastac_tet_mttkrp_f64(int64_t n, int64_t R, const double *Ap, const double *B, int64_t ldb,
                                      const double *C, int64_t ldc, double *M, int64_t ldm, void *stream) {
   if (n < 0 || R < 1 || R > (1 << 20) || ldb < R || ldc < R || ldm < R) return DASTAC_EINVAL;
-  if (n > DASTAC_TET_MAX_N || tet(n) > ((int64_t)1 << 40)) return DASTAC_EOVERFLOW;
+  if (n > DASTAC_TET_MAX_N || tet(n) > ((int64_t)1 << 40) || ld_too_large(ldb, ldc, ldm)) return DASTAC_EOVERFLOW;
   // packed row bases inside a slice are kept as 32-bit element offsets
   if (tri(n) > ((int64_t)1 << 28)) return DASTAC_EOVERFLOW;
   if (n == 0) return DASTAC_OK;
   if (!Ap || !B || !C || !M) return DASTAC_ENULL;
-  if (overlaps(M, n * ldm * 8, Ap, tet(n) * 8) || overlaps(M, n * ldm * 8, B, n * ldb * 8) ||
-      overlaps(M, n * ldm * 8, C, n * ldc * 8))
+  const int64_t mb = view_bytes(n, ldm, R, 8);
+  if (overlaps(M, mb, Ap, tet(n) * 8) || overlaps(M, mb, B, view_bytes(n, ldb, R, 8)) ||
+      overlaps(M, mb, C, view_bytes(n, ldc, R, 8)))
     return DASTAC_EALIAS;
   // the kernel takes up to 32 columns of the factor matrices; wider ones go block by block (each
   // block reads the packed tetrahedron once)

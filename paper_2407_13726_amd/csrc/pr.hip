@@ -261,11 +261,11 @@ template <bool CUBE, int BK>
 int run(int64_t N, int64_t d, const float *B, int64_t ldb, float *out, void *stream) {
   constexpr int kBlock = 4 * BK;
   if (N < 0 || d < 0 || ldb < d) return DASTAC_EINVAL;
-  if (d > (CUBE ? kMaxD3 : kMaxD2) || N > kMaxN) return DASTAC_EOVERFLOW;
+  if (d > (CUBE ? kMaxD3 : kMaxD2) || N > kMaxN || ld_too_large(ldb)) return DASTAC_EOVERFLOW;
   if (d == 0) return DASTAC_OK;
   if (!out || (N > 0 && !B)) return DASTAC_ENULL;
   const int64_t count = CUBE ? tet(d) : tri(d);
-  if (overlaps(out, count * 4, B, N * ldb * 4)) return DASTAC_EALIAS;
+  if (overlaps(out, count * 4, B, view_bytes(N, ldb, d, 4))) return DASTAC_EALIAS;
   hipStream_t st = (hipStream_t)stream;
 
   const int64_t tiles = total_tiles(d, CUBE, BK);

@@ -193,10 +193,11 @@ __global__ __launch_bounds__(kBlock) void symm_mfma_kernel(int64_t n, int64_t m,
 extern "C" int dastac_symm_f32(int64_t n, int64_t m, const float *Up, const float *B, int64_t ldb, float *C,
                                int64_t ldc, void *stream) {
   if (n < 0 || m < 1 || ldb < m || ldc < m) return DASTAC_EINVAL;
-  if (n > (1 << 24) || m > (1 << 24)) return DASTAC_EOVERFLOW;
+  if (n > (1 << 24) || m > (1 << 24) || ld_too_large(ldb, ldc)) return DASTAC_EOVERFLOW;
   if (n == 0) return DASTAC_OK;
   if (!Up || !B || !C) return DASTAC_ENULL;
-  if (overlaps(C, n * ldc * 4, Up, tri(n) * 4) || overlaps(C, n * ldc * 4, B, n * ldb * 4)) return DASTAC_EALIAS;
+  const int64_t cb = view_bytes(n, ldc, m, 4);
+  if (overlaps(C, cb, Up, tri(n) * 4) || overlaps(C, cb, B, view_bytes(n, ldb, m, 4))) return DASTAC_EALIAS;
   const int nb = (int)ceil_div(n, kBM);
   const int ncb = (int)ceil_div(m, kBN);
   const int64_t grid = (int64_t)8 * ceil_div(nb, 8) * ncb;

@@ -191,10 +191,11 @@ __global__ __launch_bounds__(kBlock) void symm_f64_kernel(int64_t n, int64_t m, 
 extern "C" int dastac_symm_f64(int64_t n, int64_t m, const double *Up, const double *B, int64_t ldb, double *C,
                                int64_t ldc, void *stream) {
   if (n < 0 || m < 1 || ldb < m || ldc < m) return DASTAC_EINVAL;
-  if (n > (1 << 24) || m > (1 << 24)) return DASTAC_EOVERFLOW;
+  if (n > (1 << 24) || m > (1 << 24) || ld_too_large(ldb, ldc)) return DASTAC_EOVERFLOW;
   if (n == 0) return DASTAC_OK;
   if (!Up || !B || !C) return DASTAC_ENULL;
-  if (overlaps(C, n * ldc * 8, Up, tri(n) * 8) || overlaps(C, n * ldc * 8, B, n * ldb * 8)) return DASTAC_EALIAS;
+  const int64_t cb = view_bytes(n, ldc, m, 8);
+  if (overlaps(C, cb, Up, tri(n) * 8) || overlaps(C, cb, B, view_bytes(n, ldb, m, 8))) return DASTAC_EALIAS;
   const int nb = (int)ceil_div(n, kBM);
   const int ncb = (int)ceil_div(m, kBN);
   const int64_t grid = (int64_t)8 * ceil_div(nb, 8) * ncb;

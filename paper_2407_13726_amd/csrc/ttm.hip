@@ -252,11 +252,11 @@ int dastac_unpack_uhc_f64(int64_t n, int64_t Q, const double *packed, double *de
 int dastac_ttm_ut_f32(int64_t n, int64_t Q, int64_t K, const float *Bp, const float *C, int64_t ldc, float *Ap,
                       void *stream) {
   if (n < 0 || Q < 1 || K < 1 || ldc < Q) return DASTAC_EINVAL;
-  if (!uhc_ok(n, Q) || !uhc_ok(n, K) || K > ((int64_t)1 << 40) / ldc) return DASTAC_EOVERFLOW;
+  if (!uhc_ok(n, Q) || !uhc_ok(n, K) || ld_too_large(ldc) || K > ((int64_t)1 << 40) / ldc) return DASTAC_EOVERFLOW;
   if (n == 0) return DASTAC_OK;
   if (!Bp || !C || !Ap) return DASTAC_ENULL;
   const int64_t rows = tri(n);
-  if (overlaps(Ap, rows * K * 4, Bp, rows * Q * 4) || overlaps(Ap, rows * K * 4, C, K * ldc * 4)) return DASTAC_EALIAS;
+  if (overlaps(Ap, rows * K * 4, Bp, rows * Q * 4) || overlaps(Ap, rows * K * 4, C, view_bytes(K, ldc, Q, 4))) return DASTAC_EALIAS;
   const int64_t nrb = ceil_div(rows, kBM), ncb = ceil_div(K, kBN);
   if (ncb > (1 << 20)) return DASTAC_EOVERFLOW;
   // about two workgroups per compute unit (256 of them), each walking a strided set of row blocks

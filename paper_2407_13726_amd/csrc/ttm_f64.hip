@@ -185,11 +185,11 @@ inline bool uhc_ok(int64_t n, int64_t Q) {
 extern "C" int dastac_ttm_ut_f64(int64_t n, int64_t Q, int64_t K, const double *Bp, const double *C, int64_t ldc,
                                  double *Ap, void *stream) {
   if (n < 0 || Q < 1 || K < 1 || ldc < Q) return DASTAC_EINVAL;
-  if (!uhc_ok(n, Q) || !uhc_ok(n, K) || K > ((int64_t)1 << 40) / ldc) return DASTAC_EOVERFLOW;
+  if (!uhc_ok(n, Q) || !uhc_ok(n, K) || ld_too_large(ldc) || K > ((int64_t)1 << 40) / ldc) return DASTAC_EOVERFLOW;
   if (n == 0) return DASTAC_OK;
   if (!Bp || !C || !Ap) return DASTAC_ENULL;
   const int64_t rows = tri(n);
-  if (overlaps(Ap, rows * K * 8, Bp, rows * Q * 8) || overlaps(Ap, rows * K * 8, C, K * ldc * 8)) return DASTAC_EALIAS;
+  if (overlaps(Ap, rows * K * 8, Bp, rows * Q * 8) || overlaps(Ap, rows * K * 8, C, view_bytes(K, ldc, Q, 8))) return DASTAC_EALIAS;
   const int64_t nrb = ceil_div(rows, kBM), ncb = ceil_div(K, kBN);
   if (ncb > (1 << 20)) return DASTAC_EOVERFLOW;
   // about two workgroups per compute unit (256 of them), each walking a strided set of row blocks

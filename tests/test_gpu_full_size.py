@@ -1,10 +1,15 @@
 """GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
 
-The small problems are compared element by element; for the two large contractions
-the oracle computes a sample of output rows one by one (its row-window argument),
-chosen to hit the first and last rows, tile boundaries and random interior rows.
-Bars as in test_gpu_parity.py: 1e-4 * sum|products| per element.
+Every output element of all five configurations is compared with the oracle; for the two
+large contractions the oracle's row-window argument spreads its loops over the host's
+cores (windows of output rows, one thread each -- the oracle itself is unchanged), once on
+the seeded benchmark inputs at the tolerance and once on small-integer inputs, where every
+partial sum is exact in fp32 and the result must equal the oracle's bit for bit whatever
+the order of summation.  Bars as in test_gpu_parity.py: 1e-4 * sum|products| per element.
 """
+import os
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 import pytest
 
@@ -23,6 +28,20 @@ def check(got, want, scale, what):
     assert (err <= TOL * scale).all(), "%s: worst err/scale %.3g" % (what, (err / np.maximum(scale, 1e-300)).max())
 
 
+def by_windows(fn, rows, width):
+    """fn(lo, hi) -> (values, scale) with the rows outside [lo, hi) NaN; the windows of `width` rows run on
+    up to 16 host threads (the oracle's C loops run outside the interpreter lock) and are merged."""
+    cuts = [(lo, min(lo + width, rows)) for lo in range(0, rows, width)]
+    threads = max(1, min(16, len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else os.cpu_count() or 1))
+    with ThreadPoolExecutor(threads) as pool:
+        parts = list(pool.map(lambda c: fn(*c), cuts))
+    want, scale = parts[0]
+    for (lo, hi), (w, sc) in zip(cuts[1:], parts[1:]):
+        want[lo:hi], scale[lo:hi] = w[lo:hi], sc[lo:hi]
+    assert not np.isnan(scale).any()
+    return want, scale
+
+
 def test_c1_trmv_512(gpu, oracle):
     w = wl.trmv_inputs()
     want, scale = oracle.trmv(w["n"], w["Up"], w["x"])
@@ -31,19 +50,25 @@ def test_c1_trmv_512(gpu, oracle):
     check(gpu.down(y), want, scale, "C1 trmv")
 
 
-def test_c2_trmm_16384_sampled_rows(gpu, oracle):
+def test_c2_trmm_16384_every_element(gpu, oracle):
     w = wl.trmm_inputs()
     n, m = w["n"], w["m"]
     C = gpu.empty(n, m)
     gpu.d.trmm_f32(n, m, gpu.up(w["Up"]), gpu.up(w["B"]), m, C, m)
     got = gpu.down(C)
-    assert np.isfinite(got).all()
-    rng = np.random.default_rng(2)
-    rows = sorted({0, 1, 31, 32, 63, 64, 127, 128, 129, 8191, 8192, n - 129, n - 128, n - 65, n - 64, n - 33,
-                   n - 32, n - 2, n - 1} | {int(r) for r in rng.integers(0, n, 12)})
-    for i in rows:
-        want, scale = oracle.trmm(n, m, w["Up"], w["B"], rows=(i, i + 1))
-        check(got[i], want[i], scale[i], "C2 trmm row %d" % i)
+    want, scale = by_windows(lambda lo, hi: oracle.trmm(n, m, w["Up"], w["B"], rows=(lo, hi)), n, 64)
+    check(got, want, scale, "C2 trmm")
+
+
+def test_c2_trmm_16384_small_integers_bit_exact(gpu, oracle):
+    n, m = 16384, 256
+    Up = inputs.small_int(2001, -2, 2, n * (n + 1) // 2)
+    B = inputs.small_int(2002, -2, 2, n, m)
+    C = gpu.empty(n, m)
+    gpu.d.trmm_f32(n, m, gpu.up(Up), gpu.up(B), m, C, m)
+    got = gpu.down(C)
+    want, _ = by_windows(lambda lo, hi: oracle.trmm(n, m, Up, B, rows=(lo, hi)), n, 64)
+    assert got.tobytes() == want.tobytes(), "rows that differ: %r" % (np.nonzero((got != want).any(axis=1))[0][:10],)
 
 
 def test_c3_band_4m(gpu, oracle):
@@ -64,19 +89,26 @@ def test_c4_ttv_512(gpu, oracle):
     check(gpu.down(M), want, scale, "C4 ttv")
 
 
-def test_c5_mttkrp_1024_sampled_slices(gpu, oracle):
+def test_c5_mttkrp_1024_every_element(gpu, oracle):
     w = wl.mttkrp_inputs()
     n, R = w["n"], w["R"]
     M = gpu.empty(n, R)
     gpu.d.tet_mttkrp_f32(n, R, gpu.up(w["Ap"]), gpu.up(w["B"]), R, gpu.up(w["C"]), R, M, R)
     got = gpu.down(M)
-    assert np.isfinite(got).all()
-    rng = np.random.default_rng(3)
-    rows = sorted({0, 1, 31, 32, 33, 511, 512, n - 65, n - 33, n - 32, n - 2, n - 1} |
-                  {int(r) for r in rng.integers(0, n, 8)})
-    for i in rows:
-        want, scale = oracle.tet_mttkrp(n, R, w["Ap"], w["B"], w["C"], rows=(i, i + 1))
-        check(got[i], want[i], scale[i], "C5 mttkrp slice %d" % i)
+    want, scale = by_windows(lambda lo, hi: oracle.tet_mttkrp(n, R, w["Ap"], w["B"], w["C"], rows=(lo, hi)), n, 8)
+    check(got, want, scale, "C5 mttkrp")
+
+
+def test_c5_mttkrp_1024_small_integers_bit_exact(gpu, oracle):
+    # |A| <= 1, |B|, |C| <= 2: a slice's sum stays below 2^24 in magnitude, so every partial sum is exact
+    n, R = 1024, 32
+    Ap = inputs.small_int(5001, -1, 1, n * (n + 1) * (n + 2) // 6)
+    B, C = inputs.small_int(5002, -2, 2, n, R), inputs.small_int(5003, -2, 2, n, R)
+    M = gpu.empty(n, R)
+    gpu.d.tet_mttkrp_f32(n, R, gpu.up(Ap), gpu.up(B), R, gpu.up(C), R, M, R)
+    got = gpu.down(M)
+    want, _ = by_windows(lambda lo, hi: oracle.tet_mttkrp(n, R, Ap, B, C, rows=(lo, hi)), n, 8)
+    assert got.tobytes() == want.tobytes(), "slices that differ: %r" % (np.nonzero((got != want).any(axis=1))[0][:10],)
 
 
 def test_running_example_ttm_ut_512_sampled_pairs(gpu, oracle):

@@ -100,6 +100,45 @@ def test_trmv_integer_inputs_bit_exact(gpu, oracle, n):
     assert gpu.down(y).tobytes() == want.tobytes()
 
 
+@pytest.mark.parametrize("bad", [np.inf, -np.inf, np.nan])
+def test_trmv_and_ttv_zero_factor_drops_a_non_finite_element(gpu, oracle, bad):
+    """The documented exception to IEEE propagation (dastac.h, "Non-finite inputs"): in these two kernels a
+    product with a zero factor contributes nothing.  An Inf/NaN element of the packed operand that meets a zero
+    of x therefore gives the result the oracle computes with that element removed -- while the same element
+    meeting a non-zero of x poisons its output as the plain rule says."""
+    n = 300
+    tri, tet = n * (n + 1) // 2, n * (n + 1) * (n + 2) // 6
+    x = inputs.uniform(91, n).copy()
+    x[17] = 0.0
+    U = inputs.uniform(92, tri).copy()
+    # row 5, column 17 (meets the zero) and row 9, column 40 (meets a non-zero)
+    at = lambda i, j: i * n - i * (i - 1) // 2 + (j - i)
+    U[at(5, 17)] = bad
+    U[at(9, 40)] = bad
+    clean = U.copy()
+    clean[at(5, 17)] = 0.0
+    clean[at(9, 40)] = 0.0
+    want, scale = oracle.trmv(n, clean, x)
+    y = gpu.empty(n)
+    gpu.d.trmv_f32(n, gpu.up(U), gpu.up(x), y)
+    got = gpu.down(y)
+    assert not np.isfinite(got[9])
+    keep = np.arange(n) != 9
+    assert_within(got[keep], want[keep], scale[keep], "trmv with a dropped non-finite element")
+    # the same triangle as slice 0 of a tetrahedron
+    A = inputs.uniform(93, tet).copy()
+    A[:tri] = U
+    cleanA = A.copy()
+    cleanA[:tri] = clean
+    want, scale = oracle.tet_ttv(n, cleanA, x)
+    M = gpu.empty(tri)
+    gpu.d.tet_ttv_f32(n, gpu.up(A), gpu.up(x), M)
+    got = gpu.down(M)
+    assert not np.isfinite(got[9])  # M(0,9) is output 9
+    keep = np.arange(tri) != 9
+    assert_within(got[keep], want[keep], scale[keep], "tet_ttv with a dropped non-finite element")
+
+
 def test_trmv_unaligned_operands(gpu, oracle):
     """Pointers that are only 4-byte aligned are accepted."""
     n = 777
@@ -330,6 +369,22 @@ def test_ttm_ut_leading_dimension_integer_exactness_and_identity(gpu, oracle):
     A2 = gpu.empty(tri(n) * Q)
     gpu.d.ttm_ut_f32(n, Q, Q, gpu.up(Bq), gpu.up(np.eye(Q, dtype=np.float32)), Q, A2)
     assert gpu.down(A2).tobytes() == Bq.tobytes()
+
+
+def test_trmm_operand_that_begins_where_a_strided_output_ends(gpu, oracle):
+    """A strided matrix ends at the last used element of its last row: an input placed right behind that element,
+    inside what would be the unused tail of the output's last row, does not overlap it."""
+    n, m, ldc = 40, 24, 64
+    U, B = inputs.uniform(301, n * (n + 1) // 2), inputs.uniform(302, n, m)
+    used = (n - 1) * ldc + m
+    buf = gpu.torch.full((used + n * m,), float("nan"), dtype=gpu.torch.float32, device=gpu.dev)
+    buf[used:] = gpu.up(B.ravel())
+    gpu.d.trmm_f32(n, m, gpu.up(U), buf[used:], m, buf[:used], ldc)
+    want, scale = oracle.trmm(n, m, U, B)
+    got = gpu.down(buf)
+    rows = np.stack([got[i * ldc: i * ldc + m] for i in range(n)])
+    assert_within(rows, want, scale, "trmm into a strided view")
+    assert got[used:].tobytes() == B.ravel().tobytes()
 
 
 # ------------------------------------------------------------------- MTTKRP ----

@@ -376,3 +376,39 @@ def test_device_entry_points_reject_bad_arguments():
     assert L.dastac_pack_triu_f32(0, None, 0, None, None) == dastac.OK
     assert L.dastac_unpack_tet_f32(0, None, None, None) == dastac.OK
     assert L.dastac_pack_band_f32(0, 2, None, 0, None, None) == dastac.OK
+
+
+def test_row_strides_are_bounded_and_views_end_at_their_last_used_element():
+    """Row strides above DASTAC_MAX_LD (2^28 elements) are refused before any product with them is formed, and a
+    strided matrix occupies the bytes up to the last used element of its last row -- not a whole further row."""
+    L = dastac.lib()
+    big = 2 ** 28 + 1
+    assert L.dastac_trmm_f32(4, 2, _p(A), _p(B), big, _p(C), 2, None) == dastac.EOVERFLOW
+    assert L.dastac_trmm_f64(4, 2, _p(A), _p(B), 2, _p(C), big, None) == dastac.EOVERFLOW
+    assert L.dastac_symm_f32(4, 2, _p(A), _p(B), 2 ** 62, _p(C), 2, None) == dastac.EOVERFLOW
+    assert L.dastac_symm_f64(4, 2, _p(A), _p(B), big, _p(C), 2, None) == dastac.EOVERFLOW
+    assert L.dastac_tet_mttkrp_f32(4, 2, _p(A), _p(B), 2, _p(C), big, _p(D), 2, None) == dastac.EOVERFLOW
+    assert L.dastac_tet_mttkrp_f64(4, 2, _p(A), _p(B), 2, _p(C), 2, _p(D), 2 ** 62, None) == dastac.EOVERFLOW
+    assert L.dastac_pack_triu_f32(4, _p(A), big, _p(B), None) == dastac.EOVERFLOW
+    assert L.dastac_unpack_tril_f64(4, _p(A), _p(B), big, None) == dastac.EOVERFLOW
+    assert L.dastac_pack_band_f32(4, 1, _p(A), 2 ** 62, _p(B), None) == dastac.EOVERFLOW
+    assert L.dastac_pr_a2_f32(10, 4, _p(A), big, _p(B), None) == dastac.EOVERFLOW
+    assert L.dastac_ttm_ut_f32(4, 4, 4, _p(A), _p(B), big, _p(C), None) == dastac.EOVERFLOW
+    assert L.dastac_pack_subtri_f32(8, 4, _p(A), big, _p(B), None) == dastac.EOVERFLOW
+    assert L.dastac_pack_leslie_f64(8, _p(A), big, _p(B), _p(C), None) == dastac.EOVERFLOW
+    # C is 4 x 2 with row stride 8: its last used element ends at byte (3*8+2)*4 = 104, so an input whose
+    # range begins before that byte overlaps it (the accepting case, an input that begins AT byte 104, needs
+    # real memory and is in the GPU tests)
+    assert L.dastac_trmm_f32(4, 2, _p(A), _p(B + 100), 2, _p(B), 8, None) == dastac.EALIAS
+    assert L.dastac_tet_mttkrp_f32(4, 2, _p(A), _p(B + 100), 2, _p(C), 2, _p(B), 8, None) == dastac.EALIAS
+
+
+def test_stream_sum_rejects_bad_arguments():
+    L = dastac.lib()
+    assert L.dastac_stream_sum_f32(-1, _p(A), _p(B), 4, None) == dastac.EINVAL
+    assert L.dastac_stream_sum_f32(16, _p(A), _p(B), 0, None) == dastac.EINVAL
+    assert L.dastac_stream_sum_f32(16, _p(A), _p(B), 2 ** 24 + 1, None) == dastac.EINVAL
+    assert L.dastac_stream_sum_f32(2 ** 40 + 1, _p(A), _p(B), 4, None) == dastac.EOVERFLOW
+    assert L.dastac_stream_sum_f32(16, None, _p(B), 4, None) == dastac.ENULL
+    assert L.dastac_stream_sum_f32(16, _p(A), None, 4, None) == dastac.ENULL
+    assert L.dastac_stream_sum_f32(16, _p(A), _p(A + 32), 4, None) == dastac.EALIAS
