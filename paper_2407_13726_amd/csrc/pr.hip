@@ -92,16 +92,25 @@ __device__ inline void decode_tile(int64_t d, bool cube, int BK, int64_t t, int6
 
 template <bool CUBE, bool ATOMIC, int BK>
 __global__ __launch_bounds__(4 * BK) void pr_mfma_kernel(int64_t N, int64_t d, const float *__restrict__ B,
-                                                         int64_t ldb, float *__restrict__ out, int64_t chunk) {
+                                                         int64_t ldb, float *__restrict__ out, int64_t chunk,
+                                                         int64_t tiles, int64_t split) {
   __shared__ __attribute__((aligned(16))) float As[2][kXT * kJP];
   __shared__ __attribute__((aligned(16))) float Bs[2][kXT * BK];
   constexpr int kThreads = 4 * BK, kWC = BK / 32;  // wavefronts: 2 rows of kWC
 
+  // Work items are (sample share, tile) pairs, share-major.  Workgroup ids are dealt to the eight XCDs in turn,
+  // so id%8 picks the XCD and id/8 the position in that XCD's run of CONSECUTIVE items: the tiles of one share
+  // read the same rows of B (each its own columns) and sweep them at the same pace, so on one XCD a row is
+  // fetched from memory once and served to the other tiles by that L2.
+  const int64_t items = tiles * split, xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int64_t item = items * xcd / 8 + slot;
+  if (item >= items * (xcd + 1) / 8) return;
+  const int64_t share = uniform64(item / tiles);
   int64_t i;  // slice: every column index of this workgroup is >= i
   int J, K;
-  decode_tile(d, CUBE, BK, uniform64((int64_t)blockIdx.x), i, J, K);
+  decode_tile(d, CUBE, BK, uniform64(item - share * tiles), i, J, K);
   const int64_t q = d - i;  // order of the slice's triangle
-  const int64_t xbeg = (int64_t)blockIdx.y * chunk;
+  const int64_t xbeg = share * chunk;
   const int64_t xend = xbeg + chunk < N ? xbeg + chunk : N;
   if (xbeg >= xend) return;
   const int nk = (int)ceil_div(xend - xbeg, kXT);
@@ -291,7 +300,9 @@ int run(int64_t N, int64_t d, const float *B, int64_t ldb, float *out, void *str
     chunk = ceil_div(ceil_div(N, split), kXT) * kXT;
     split = ceil_div(N, chunk);
   }
-  if (split > 65535) return DASTAC_EOVERFLOW;
+  // one-dimensional grid: every XCD gets ceil(items / 8) ids, of which it uses its share of the items
+  const int64_t per_xcd = ceil_div(tiles * split, 8);
+  if (8 * per_xcd > 0x7fffffff) return DASTAC_EOVERFLOW;
 
   const bool atomic = split > 1;
   if (atomic || N == 0) {
@@ -300,11 +311,11 @@ int run(int64_t N, int64_t d, const float *B, int64_t ldb, float *out, void *str
     if (hipGetLastError() != hipSuccess) return DASTAC_EHIP;
     if (N == 0) return DASTAC_OK;
   }
-  const dim3 grid((unsigned)tiles, (unsigned)split);
+  const unsigned grid = (unsigned)(8 * per_xcd);
   if (atomic)
-    pr_mfma_kernel<CUBE, true, BK><<<grid, kBlock, 0, st>>>(N, d, B, ldb, out, chunk);
+    pr_mfma_kernel<CUBE, true, BK><<<grid, kBlock, 0, st>>>(N, d, B, ldb, out, chunk, tiles, split);
   else
-    pr_mfma_kernel<CUBE, false, BK><<<grid, kBlock, 0, st>>>(N, d, B, ldb, out, chunk);
+    pr_mfma_kernel<CUBE, false, BK><<<grid, kBlock, 0, st>>>(N, d, B, ldb, out, chunk, tiles, split);
   return launch_status();
 }
 
