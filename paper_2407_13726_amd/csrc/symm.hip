@@ -1,4 +1,4 @@
-// SYMM over a packed upper triangle on the fp32 matrix cores:
+// SYMM over a packed upper triangle on the matrix cores, single and double precision:
 //
 //   C(i,c) := S(i,k) * B(k,c),   S(i,k) = S(k,i) = U(min(i,k), max(i,k))
 //
@@ -7,44 +7,44 @@
 // reach its unique element (Section 3, "Redundancy map").
 //
 // A workgroup (8 wavefronts) owns a 64-row x 128-column tile of C and sweeps k over the whole
-// range 0..n in steps of 32.  Right of its diagonal block the 64x32 tile of S is a tile of packed
+// range 0..n in steps of kKT = 32 (fp32) or 16 (fp64), with the sweep and the per-type matrix-core
+// pieces of mfma_tile.h.  Right of its diagonal block the 64 x kKT tile of S is a tile of packed
 // rows i (each piece 128 contiguous bytes), as in the triangular product.  Left of it, S(i,k) is
-// U(k,i): the tile is 32 packed rows k, each contributing the 64 contiguous elements i0..i0+63,
+// U(k,i): the tile is kKT packed rows k, each contributing the 64 contiguous elements i0..i0+63,
 // so it arrives transposed, is kept transposed in LDS, and the matrix cores' S operand is read
-// from it element by element instead of four at a time.  The two k-steps on the diagonal block
+// from it element by element (in fp32: instead of four at a time).  The k-steps on the diagonal block
 // and every tile of a ragged last row block take a scalar loader that picks U(i,k) or U(k,i)
 // element by element.  Each packed element is therefore read twice in total (once as part of a
 // row tile, once as part of a column tile), and no atomics are needed: a tile of C has one owner.
 //
-// Every row block costs the same n/32 k-steps.  Workgroups that share a row block (different
+// Every row block costs the same n/kKT k-steps.  Workgroups that share a row block (different
 // column blocks) get ids that are equal modulo 8, i.e. land on the same XCD and share its L2.
-#include "common.h"
+#include "mfma_tile.h"
 
 using namespace dastac;
 
 namespace {
 
-constexpr int kBM = 64;    // rows of C per workgroup tile
-constexpr int kBN = 128;   // columns of C per workgroup tile
-constexpr int kKT = 32;    // k-step
-constexpr int kUP = kKT + 4;   // LDS pitch of a row tile [i][k]
-constexpr int kTP = kBM + 4;   // LDS pitch of a transposed tile [k][i]
-constexpr int kUS = kBM * kUP;  // floats per S buffer (>= kKT * kTP)
-constexpr int kBlock = 512;
-static_assert(kKT * kTP <= kUS, "a transposed tile fits the S buffer");
-
-typedef float f16v __attribute__((ext_vector_type(16)));
-
+template <typename T>
 struct Stage {
-  f4a u;     // S: four consecutive elements of one packed row
-  f4a b[2];  // B: k rows bk and bk+16, four columns each
+  typename Core<T>::vec u;     // S: one 16-byte piece of one packed row
+  typename Core<T>::vec b[2];  // B: k rows bk and bk + kKT/2, one 16-byte piece of columns each
 };
 
-__global__ __launch_bounds__(kBlock) void symm_mfma_kernel(int64_t n, int64_t m, const float *__restrict__ U,
-                                                           const float *__restrict__ B, int64_t ldb,
-                                                           float *__restrict__ C, int64_t ldc, int nb, int ncb) {
-  __shared__ __attribute__((aligned(16))) float Ss[2][kUS];
-  __shared__ __attribute__((aligned(16))) float Bs[2][kKT * kBN];
+template <typename T>
+__global__ __launch_bounds__(kTileThreads) void symm_mfma_kernel(int64_t n, int64_t m, const T *__restrict__ U,
+                                                                 const T *__restrict__ B, int64_t ldb,
+                                                                 T *__restrict__ C, int64_t ldc, int nb, int ncb) {
+  typedef Core<T> K;
+  typedef typename K::vec vec;
+  typedef typename K::uvec uvec;
+  constexpr int kBM = kTileM, kBN = kTileN, kKT = K::kKT, kV = K::kVec;
+  constexpr int kUP = K::kRowPitch;  // pitch of a row tile [i][k]
+  constexpr int kTP = K::kColPitch;  // pitch of a transposed tile [k][i]
+  constexpr int kUS = kBM * kUP;     // elements per S buffer
+  static_assert(kKT * kTP <= kUS, "a transposed tile fits the S buffer");
+  __shared__ __attribute__((aligned(16))) T Ss[2][kUS];
+  __shared__ __attribute__((aligned(16))) T Bs[2][kKT * kBN];
 
   const int L = blockIdx.x;
   const int xcd = L & 7, slot = L >> 3;
@@ -54,12 +54,11 @@ __global__ __launch_bounds__(kBlock) void symm_mfma_kernel(int64_t n, int64_t m,
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave >> 2, wc = wave & 3;  // 2x4 wavefronts: 32 rows x 32 columns each
-  const int l32 = lane & 31, h = lane >> 5;
 
   // staging roles
-  const int ur = tid >> 3, uk = (tid & 7) * 4;     // row tile: row ur, k offset uk
-  const int tk = tid >> 4, ti = (tid & 15) * 4;    // transposed tile: packed row tk, i offset ti
-  const int bk = tid >> 5, bc = (tid & 31) * 4;    // B: k row bk (+16), column offset bc
+  const int ur = tid >> 3, uk = (tid & 7) * kV;                     // row tile: row ur, k offset uk
+  const int tk = tid / (kBM / kV), ti = (tid % (kBM / kV)) * kV;    // transposed tile: packed row tk, i offset ti
+  const int bk = tid / (kBN / kV), bc = (tid % (kBN / kV)) * kV;    // B: k row bk (and bk + kKT/2), column offset bc
   const int64_t col0 = (int64_t)cb * kBN;
   const bool cols_full = col0 + kBN <= m;
 
@@ -71,137 +70,95 @@ __global__ __launch_bounds__(kBlock) void symm_mfma_kernel(int64_t n, int64_t m,
   // element (i,k), k>=i, of the packed triangle is at rowbase(i) + k with rowbase(i) = tri_row_start(n,i) - i
   const int64_t iu = i0 + ur;
   const bool urow_ok = iu < n;
-  const float *ub = U + (urow_ok ? tri_row_start(n, iu) - iu : 0);
-  // transposed tiles: this thread's piece of step kt starts at rowbase(32 kt + tk) + i0 + ti; rowbase
-  // moves by 16(2n-1) - 32 k - 512 from row k to row k+32
+  const T *ub = U + (urow_ok ? tri_row_start(n, iu) - iu : 0);
+  // transposed tiles: this thread's piece of step kt starts at rowbase(kKT kt + tk) + i0 + ti; rowbase moves
+  // by kKT (2n - 2k - 1 - kKT) / 2 from row k to row k + kKT, and that step shrinks by kKT^2 per k-step
   int64_t tofs = tri_row_start(n, tk) - tk + i0 + ti;
-  int64_t tstep = 16 * (2 * n - 1) - 32 * (int64_t)tk - 512;
+  int64_t tstep = (kKT / 2) * (2 * n - 2 * (int64_t)tk - 1 - kKT);
 
-  auto load_stage = [&](int kt, Stage &s) {
+  auto load_stage = [&](int kt, Stage<T> &s) {
     const int64_t k0 = (int64_t)kt * kKT;
     const bool k_full = k0 + kKT <= n;
     if (kt < nleft) {
-      s.u = *reinterpret_cast<const f4u *>(U + tofs);
+      s.u = *reinterpret_cast<const uvec *>(U + tofs);
       tofs += tstep;
-      tstep -= 32 * kKT;
+      tstep -= kKT * kKT;
     } else if (rows_full && k_full && k0 >= i0 + kBM) {
-      s.u = *reinterpret_cast<const f4u *>(ub + k0 + uk);
+      s.u = *reinterpret_cast<const uvec *>(ub + k0 + uk);
     } else {
-      float v[4];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
+      for (int e = 0; e < kV; ++e) {
         const int64_t k = k0 + uk + e;
-        float t = 0.0f;
+        T t = T(0);
         if (urow_ok && k < n) t = k >= iu ? ub[k] : U[tri_offset(n, k, iu)];
-        v[e] = t;
+        s.u[e] = t;
       }
-      s.u = f4a{v[0], v[1], v[2], v[3]};
     }
     if (k_full && cols_full) {
 #pragma unroll
       for (int q = 0; q < 2; ++q)
-        s.b[q] = *reinterpret_cast<const f4u *>(B + (k0 + bk + 16 * q) * ldb + col0 + bc);
+        s.b[q] = *reinterpret_cast<const uvec *>(B + (k0 + bk + (kKT / 2) * q) * ldb + col0 + bc);
     } else {
 #pragma unroll
       for (int q = 0; q < 2; ++q) {
-        const int64_t k = k0 + bk + 16 * q;
-        float v[4];
+        const int64_t k = k0 + bk + (kKT / 2) * q;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = (k < n && col0 + bc + e < m) ? B[k * ldb + col0 + bc + e] : 0.0f;
-        s.b[q] = f4a{v[0], v[1], v[2], v[3]};
+        for (int e = 0; e < kV; ++e) s.b[q][e] = (k < n && col0 + bc + e < m) ? B[k * ldb + col0 + bc + e] : T(0);
       }
     }
   };
-  auto store_stage = [&](int buf, bool left, const Stage &s) {
-    if (left)
-      *reinterpret_cast<f4a *>(&Ss[buf][tk * kTP + ti]) = s.u;
+  auto store_stage = [&](int buf, int kt, const Stage<T> &s) {
+    if (kt < nleft)
+      *reinterpret_cast<vec *>(&Ss[buf][tk * kTP + ti]) = s.u;
     else
-      *reinterpret_cast<f4a *>(&Ss[buf][ur * kUP + uk]) = s.u;
+      *reinterpret_cast<vec *>(&Ss[buf][ur * kUP + uk]) = s.u;
 #pragma unroll
-    for (int q = 0; q < 2; ++q) *reinterpret_cast<f4a *>(&Bs[buf][(bk + 16 * q) * kBN + bc]) = s.b[q];
+    for (int q = 0; q < 2; ++q) *reinterpret_cast<vec *>(&Bs[buf][(bk + (kKT / 2) * q) * kBN + bc]) = s.b[q];
+  };
+  auto read_ops = [&](int buf, int kt, int t, typename K::Ops &o) {
+    if (kt < nleft)
+      K::read_a_t(&Ss[buf][wr * 32], kTP, lane, t, o);
+    else
+      K::read_a(&Ss[buf][wr * 32 * kUP], lane, t, o);
+    K::read_b(&Bs[buf][wc * 32], kBN, lane, t, o);
   };
 
-  f16v acc;
-#pragma unroll
-  for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+  typename K::Acc acc;
+  K::clear(acc);
+  sweep_steps<T, Stage<T>>(0, nk, acc, load_stage, store_stage, read_ops);
 
-  // Operands of one group of eight k values: lane half h takes k = 8t+4h .. 8t+4h+3 (a sum over k may
-  // be taken in any order), four MFMA steps on the wavefront's 32x32 sub-tile.
-  struct Ops {
-    float a[4];
-    float b0[4];
-  };
-  auto read_ops = [&](int buf, bool left, int t, Ops &o) {
-    if (left) {
-      const float *ss = &Ss[buf][(4 * h) * kTP + wr * 32 + l32];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) o.a[q] = ss[(8 * t + q) * kTP];
-    } else {
-      const f4a a = *reinterpret_cast<const f4a *>(&Ss[buf][(wr * 32 + l32) * kUP + 4 * h + 8 * t]);
-      o.a[0] = a.x, o.a[1] = a.y, o.a[2] = a.z, o.a[3] = a.w;
-    }
-    const float *bs = &Bs[buf][(4 * h) * kBN + wc * 32 + l32];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) o.b0[q] = bs[(8 * t + q) * kBN];
-  };
-  auto mma = [&](const Ops &o) {
-#pragma unroll
-    for (int q = 0; q < 4; ++q) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(o.a[q], o.b0[q], acc, 0, 0, 0);
-  };
+  K::for_each(acc, lane, [&](int r, int c, T v) {
+    const int64_t i = i0 + wr * 32 + r, col = col0 + wc * 32 + c;
+    if (i < n && col < m) C[i * ldc + col] = v;
+  });
+}
 
-  Stage st;
-  Ops oa, ob;
-  load_stage(0, st);
-  store_stage(0, 0 < nleft, st);
-  __syncthreads();
-  read_ops(0, 0 < nleft, 0, oa);
-
-  // One k-step on LDS buffer `buf`.  The global loads of the next step are in flight throughout; its
-  // LDS stores and the workgroup barrier sit before the last group's matrix instructions, whose
-  // operands are already in registers.
-  auto step = [&](int kt, int buf) {
-    const bool more = kt + 1 < nk;
-    const bool left = kt < nleft, next_left = kt + 1 < nleft;
-    if (more) load_stage(kt + 1, st);
-    read_ops(buf, left, 1, ob);
-    mma(oa);
-    read_ops(buf, left, 2, oa);
-    mma(ob);
-    read_ops(buf, left, 3, ob);
-    mma(oa);
-    if (more) store_stage(buf ^ 1, next_left, st);
-    __syncthreads();
-    if (more) read_ops(buf ^ 1, next_left, 0, oa);
-    mma(ob);
-  };
-  for (int kt = 0; kt < nk; kt += 2) {
-    step(kt, 0);
-    if (kt + 1 < nk) step(kt + 1, 1);
-  }
-
-  // D layout of the 32x32 tile: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32
-  const int64_t col = col0 + wc * 32 + l32;
-#pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    const int64_t i = i0 + wr * 32 + 8 * (v / 4) + 4 * h + (v % 4);
-    if (i < n && col < m) C[i * ldc + col] = acc[v];
-  }
+template <typename T>
+int run(int64_t n, int64_t m, const T *Up, const T *B, int64_t ldb, T *C, int64_t ldc, void *stream) {
+  constexpr int64_t kB = (int64_t)sizeof(T);
+  if (n < 0 || m < 1 || ldb < m || ldc < m) return DASTAC_EINVAL;
+  if (n > (1 << 24) || m > (1 << 24) || ld_too_large(ldb, ldc)) return DASTAC_EOVERFLOW;
+  if (n == 0) return DASTAC_OK;
+  if (!Up || !B || !C) return DASTAC_ENULL;
+  const int64_t cb = view_bytes(n, ldc, m, kB);
+  if (overlaps(C, cb, Up, tri(n) * kB) || overlaps(C, cb, B, view_bytes(n, ldb, m, kB))) return DASTAC_EALIAS;
+  const int nb = (int)ceil_div(n, kTileM);
+  const int ncb = (int)ceil_div(m, kTileN);
+  const int64_t grid = (int64_t)8 * ceil_div(nb, 8) * ncb;
+  if (grid > 0x7fffffff) return DASTAC_EOVERFLOW;
+  symm_mfma_kernel<T><<<(unsigned)grid, kTileThreads, 0, (hipStream_t)stream>>>(n, m, Up, B, ldb, C, ldc, nb, ncb);
+  return launch_status();
 }
 
 }  // namespace
 
 extern "C" int dastac_symm_f32(int64_t n, int64_t m, const float *Up, const float *B, int64_t ldb, float *C,
                                int64_t ldc, void *stream) {
-  if (n < 0 || m < 1 || ldb < m || ldc < m) return DASTAC_EINVAL;
-  if (n > (1 << 24) || m > (1 << 24) || ld_too_large(ldb, ldc)) return DASTAC_EOVERFLOW;
-  if (n == 0) return DASTAC_OK;
-  if (!Up || !B || !C) return DASTAC_ENULL;
-  const int64_t cb = view_bytes(n, ldc, m, 4);
-  if (overlaps(C, cb, Up, tri(n) * 4) || overlaps(C, cb, B, view_bytes(n, ldb, m, 4))) return DASTAC_EALIAS;
-  const int nb = (int)ceil_div(n, kBM);
-  const int ncb = (int)ceil_div(m, kBN);
-  const int64_t grid = (int64_t)8 * ceil_div(nb, 8) * ncb;
-  if (grid > 0x7fffffff) return DASTAC_EOVERFLOW;
-  symm_mfma_kernel<<<(unsigned)grid, kBlock, 0, (hipStream_t)stream>>>(n, m, Up, B, ldb, C, ldc, nb, ncb);
-  return launch_status();
+  return run<float>(n, m, Up, B, ldb, C, ldc, stream);
+}
+
+// Double precision (the paper's element type): the same kernel on the fp64 matrix cores.
+extern "C" int dastac_symm_f64(int64_t n, int64_t m, const double *Up, const double *B, int64_t ldb, double *C,
+                               int64_t ldc, void *stream) {
+  return run<double>(n, m, Up, B, ldb, C, ldc, stream);
 }
