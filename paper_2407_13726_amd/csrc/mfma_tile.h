@@ -67,6 +67,11 @@ struct Core<float> {
 #pragma unroll
     for (int q = 0; q < 4; ++q) o.b[q] = p[q * pitch];
   }
+  // second operand, staged [column][k] with pitch kRowPitch (k contiguous, like the first): one 16-byte read
+  __device__ static void read_b_rows(const float *rows, int lane, int t, Ops &o) {
+    const f4a b = *reinterpret_cast<const f4a *>(rows + (lane & 31) * kRowPitch + 4 * (lane >> 5) + 8 * t);
+    o.b[0] = b.x, o.b[1] = b.y, o.b[2] = b.z, o.b[3] = b.w;
+  }
   __device__ static void mma(const Ops &o, Acc &c) {
 #pragma unroll
     for (int q = 0; q < 4; ++q) c.v = __builtin_amdgcn_mfma_f32_32x32x2f32(o.a[q], o.b[q], c.v, 0, 0, 0);
@@ -114,6 +119,11 @@ struct Core<double> {
     o.b[0] = p[0];
     o.b[1] = p[16];
   }
+  __device__ static void read_b_rows(const double *rows, int lane, int t, Ops &o) {
+    const double *p = rows + (lane & 15) * kRowPitch + 4 * t + (lane >> 4);
+    o.b[0] = p[0];
+    o.b[1] = p[16 * kRowPitch];
+  }
   __device__ static void mma(const Ops &o, Acc &c) {
     c.v[0] = __builtin_amdgcn_mfma_f64_16x16x4f64(o.a[0], o.b[0], c.v[0], 0, 0, 0);
     c.v[1] = __builtin_amdgcn_mfma_f64_16x16x4f64(o.a[0], o.b[1], c.v[1], 0, 0, 0);
@@ -141,9 +151,11 @@ struct Core<double> {
 // operands are already in registers, so the matrix pipe has work while the barrier settles and while the
 // first operands of the next step come back from LDS.  Both buffers appear as literals (the loop is unrolled
 // by two), so every LDS address is a compile-time offset.  The caller places a barrier between two sweeps
-// that use the same buffers.
+// that use the same buffers.  A wavefront with `active` false stages and synchronises like the others but
+// reads no operands and issues no matrix instructions (its sub-tile holds nothing to compute).
 template <typename T, typename Stage, typename Load, typename Store, typename Read>
-__device__ inline void sweep_steps(int lo, int hi, typename Core<T>::Acc &acc, Load load, Store store, Read read) {
+__device__ inline void sweep_steps(int lo, int hi, typename Core<T>::Acc &acc, Load load, Store store, Read read,
+                                   bool active = true) {
   typedef Core<T> K;
   static_assert(K::kGroups == 4, "the step below is written for four operand groups");
   Stage st;
@@ -151,20 +163,24 @@ __device__ inline void sweep_steps(int lo, int hi, typename Core<T>::Acc &acc, L
   load(lo, st);
   store(0, lo, st);
   __syncthreads();
-  read(0, lo, 0, oa);
+  if (active) read(0, lo, 0, oa);
   auto step = [&](int kt, int buf) {
     const bool more = kt + 1 < hi;
     if (more) load(kt + 1, st);
-    read(buf, kt, 1, ob);
-    K::mma(oa, acc);
-    read(buf, kt, 2, oa);
-    K::mma(ob, acc);
-    read(buf, kt, 3, ob);
-    K::mma(oa, acc);
+    if (active) {
+      read(buf, kt, 1, ob);
+      K::mma(oa, acc);
+      read(buf, kt, 2, oa);
+      K::mma(ob, acc);
+      read(buf, kt, 3, ob);
+      K::mma(oa, acc);
+    }
     if (more) store(buf ^ 1, kt + 1, st);
     __syncthreads();
-    if (more) read(buf ^ 1, kt + 1, 0, oa);
-    K::mma(ob, acc);
+    if (active) {
+      if (more) read(buf ^ 1, kt + 1, 0, oa);
+      K::mma(ob, acc);
+    }
   };
   for (int kt = lo; kt < hi; kt += 2) {
     step(kt, 0);

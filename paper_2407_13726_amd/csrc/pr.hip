@@ -1,5 +1,5 @@
 // Polynomial-regression tensors (Table 1, "Polynomial Regression Degree-D") written straight
-// into packed hyper-triangles on the fp32 matrix cores:
+// into packed hyper-triangles on the matrix cores, single and double precision:
 //
 //   A2(i,j)   := B(x,i) * B(x,j)            i<=j        packed upper triangle,   tri(d,i,j)
 //   A3(i,j,k) := B(x,i) * B(x,j) * B(x,k)   i<=j<=k     packed upper tetrahedron, tet(d,i,j,k)
@@ -11,37 +11,35 @@
 // tet_slice_start(d,i); A2 is the same with w = 1 and a single slice.  One kernel serves both.
 //
 // A workgroup owns a 64 (j) x 128 (k) tile of one slice (eight wavefronts; for small d a 64 x 64 tile and
-// four wavefronts) and a range of samples x, which is the reduction index: per step of 32 samples, the
-// 32x64 tile of B columns j (multiplied by w on the way in) and the tile of B columns k are staged in
-// LDS, double-buffered against the global loads of the next step, and each wavefront runs
-// v_mfma_f32_32x32x2_f32 on a 32x32 sub-tile.  Tiles that lie wholly below the diagonal are never
+// four wavefronts) and a range of samples x, which is the reduction index: per step of kXT samples (32 in
+// fp32, 16 in fp64), the kXT x 64 tile of B columns j (multiplied by w on the way in) and the tile of B
+// columns k are staged in LDS, double-buffered against the global loads of the next step, and each
+// wavefront multiplies its 32x32 sub-tile (sweep and per-type matrix-core pieces: mfma_tile.h; both tiles
+// keep the sample index first, so both operands are read element by element).  Tiles that lie wholly below the diagonal are never
 // launched; tiles on the diagonal stage their full rectangle, wavefronts whose sub-tile lies below it
 // skip their matrix instructions, and only j<=k is stored.  When the tile count alone cannot fill the
 // chip the sample range is split over several workgroups, which then add into a pre-zeroed output with
 // floating-point atomics.
-#include "common.h"
+#include "mfma_tile.h"
 
 using namespace dastac;
 
 namespace {
 
-constexpr int kBJ = 64;    // j extent of a workgroup tile
+constexpr int kBJ = kTileM;  // j extent of a workgroup tile
 // k extent of a workgroup tile: BK = 128 (eight wavefronts) or BK = 64 (four), a template parameter
-constexpr int kXT = 32;    // samples per step
-constexpr int kJP = kBJ + 4;  // LDS pitch of the j tile [x][j]
 constexpr int64_t kMaxD2 = 1 << 16;  // A2: tile grid and tri(d) stay small
 constexpr int64_t kMaxD3 = 1 << 13;  // A3: the tile count stays inside gridDim.x
 constexpr int64_t kMaxN = (int64_t)1 << 31;
 // Up to these d the 64 x 64 tile is used: it wastes less on the diagonal and leaves more workgroups per CU,
-// which outweighs its lower operand reuse while diagonal tiles are a large share of all tiles (measured, N=100000
-// resp. 10000: A2 d=512 73 against 49 TFLOP/s, d=1024 91 against 103; A3 d=256 46 against 36, d=1024 78 against 72).
+// which outweighs its lower operand reuse while diagonal tiles are a large share of all tiles (measured in fp32,
+// N=100000 resp. 10000: A2 d=512 73 against 49 TFLOP/s, d=1024 91 against 103; A3 d=256 46 against 36, d=1024 78 against 72).
 constexpr int64_t kNarrowMaxD2 = 768, kNarrowMaxD3 = 2048;
 
-typedef float f16v __attribute__((ext_vector_type(16)));
-
+template <typename T>
 struct Stage {
-  f4a a[2];  // j tile: one or two sample rows, four columns each
-  f4a b[2];  // k tile: sample rows bk and bk+16, four columns each
+  typename Core<T>::vec a[2];  // j tile: one or two sample rows, one 16-byte piece of columns each
+  typename Core<T>::vec b[2];  // k tile: sample rows bk and bk + kXT/2, one 16-byte piece of columns each
 };
 
 // Tiles with work.  A slice of order q has m = ceil(q/64) blocks of rows j and ceil(m/2) blocks of columns k;
@@ -90,12 +88,16 @@ __device__ inline void decode_tile(int64_t d, bool cube, int BK, int64_t t, int6
   K = (int)(Jr * kBJ / BK + t);
 }
 
-template <bool CUBE, bool ATOMIC, int BK>
-__global__ __launch_bounds__(4 * BK) void pr_mfma_kernel(int64_t N, int64_t d, const float *__restrict__ B,
-                                                         int64_t ldb, float *__restrict__ out, int64_t chunk,
-                                                         int64_t tiles, int64_t split) {
-  __shared__ __attribute__((aligned(16))) float As[2][kXT * kJP];
-  __shared__ __attribute__((aligned(16))) float Bs[2][kXT * BK];
+template <typename T, bool CUBE, bool ATOMIC, int BK>
+__global__ __launch_bounds__(4 * BK) void pr_mfma_kernel(int64_t N, int64_t d, const T *__restrict__ B, int64_t ldb,
+                                                         T *__restrict__ out, int64_t chunk, int64_t tiles,
+                                                         int64_t split) {
+  typedef Core<T> K;
+  typedef typename K::vec vec;
+  typedef typename K::uvec uvec;
+  constexpr int kXT = K::kKT, kV = K::kVec, kJP = K::kColPitch;  // samples per step; pitch of the j tile [x][j]
+  __shared__ __attribute__((aligned(16))) T As[2][kXT * kJP];
+  __shared__ __attribute__((aligned(16))) T Bs[2][kXT * BK];
   constexpr int kThreads = 4 * BK, kWC = BK / 32;  // wavefronts: 2 rows of kWC
 
   // Work items are (sample share, tile) pairs, share-major.  Workgroup ids are dealt to the eight XCDs in turn,
@@ -107,8 +109,8 @@ __global__ __launch_bounds__(4 * BK) void pr_mfma_kernel(int64_t N, int64_t d, c
   if (item >= items * (xcd + 1) / 8) return;
   const int64_t share = uniform64(item / tiles);
   int64_t i;  // slice: every column index of this workgroup is >= i
-  int J, K;
-  decode_tile(d, CUBE, BK, uniform64(item - share * tiles), i, J, K);
+  int J, Kb;
+  decode_tile(d, CUBE, BK, uniform64(item - share * tiles), i, J, Kb);
   const int64_t q = d - i;  // order of the slice's triangle
   const int64_t xbeg = share * chunk;
   const int64_t xend = xbeg + chunk < N ? xbeg + chunk : N;
@@ -117,164 +119,117 @@ __global__ __launch_bounds__(4 * BK) void pr_mfma_kernel(int64_t N, int64_t d, c
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave / kWC, wc = wave % kWC;  // 2 x kWC wavefronts: 32 (j) x 32 (k) each
-  const int l32 = lane & 31, h = lane >> 5;
   // A wavefront whose 32x32 sub-tile lies wholly below the diagonal (largest k < smallest j) still helps
   // to stage the tiles but issues no matrix instructions, which leaves the SIMD's matrix pipe to the
   // wavefronts of the other workgroups resident on it.
-  const bool live = uniform32(K * BK + wc * 32 + 31 >= J * kBJ + wr * 32) != 0;
+  const bool live = uniform32(Kb * BK + wc * 32 + 31 >= J * kBJ + wr * 32) != 0;
 
-  // j tile: sample rows tk + kJRows*r (r < kJRep), column offset ti; k tile: sample rows bk and bk+16, column offset bc
-  constexpr int kJRows = kThreads / 16, kJRep = kXT / kJRows;
-  const int tk = tid >> 4, ti = (tid & 15) * 4;
-  const int bk = tid / (BK / 4), bc = (tid % (BK / 4)) * 4;
-  const int64_t j0 = i + (int64_t)J * kBJ, k0 = i + (int64_t)K * BK;  // absolute first columns
+  // j tile: sample rows tk + kJRows*r (r < kJRep), column offset ti; k tile: sample rows bk and bk + kXT/2, column offset bc
+  constexpr int kJRows = kThreads / (kBJ / kV), kJRep = kXT / kJRows;
+  static_assert(kJRep == 1 || kJRep == 2, "a thread stages one or two pieces of the j tile");
+  const int tk = tid / (kBJ / kV), ti = (tid % (kBJ / kV)) * kV;
+  const int bk = tid / (BK / kV), bc = (tid % (BK / kV)) * kV;
+  const int64_t j0 = i + (int64_t)J * kBJ, k0 = i + (int64_t)Kb * BK;  // absolute first columns
   const bool j_full = j0 + kBJ <= d, k_full = k0 + BK <= d;
 
-  // Columns c..c+3 of one row of B, zero from column d on, with one vector load whose address is pulled
-  // back inside the row (needs d >= 4): a lane that straddles the end shifts what it fetched.
-  auto load4_clamped = [&](const float *row, int64_t c) -> f4a {
-    const int64_t cc = c + 4 <= d ? c : d - 4;
-    const f4a v = *reinterpret_cast<const f4u *>(row + cc);
-    const int64_t sh = c - cc;  // 0: all four inside; 1..3: that many beyond the end; >= 4: all beyond
-    f4a r;
-    r.x = sh == 0 ? v.x : sh == 1 ? v.y : sh == 2 ? v.z : sh == 3 ? v.w : 0.0f;
-    r.y = sh == 0 ? v.y : sh == 1 ? v.z : sh == 2 ? v.w : 0.0f;
-    r.z = sh == 0 ? v.z : sh == 1 ? v.w : 0.0f;
-    r.w = sh == 0 ? v.w : 0.0f;
+  // Columns c..c+kV-1 of one row of B, zero from column d on, with one vector load whose address is pulled
+  // back inside the row (needs d >= kV): a lane that straddles the end shifts what it fetched.
+  auto load_clamped = [&](const T *row, int64_t c) -> vec {
+    const int64_t cc = c + kV <= d ? c : d - kV;
+    const vec v = *reinterpret_cast<const uvec *>(row + cc);
+    const int64_t sh = c - cc;  // 0: all inside; 1..kV-1: that many beyond the end; >= kV: all beyond
+    vec r;
+#pragma unroll
+    for (int e = 0; e < kV; ++e) {
+      T t = T(0);
+#pragma unroll
+      for (int f = e; f < kV; ++f) t = sh == f - e ? v[f] : t;
+      r[e] = t;
+    }
     return r;
   };
-  const bool wide = d >= 4;
+  const bool wide = d >= kV;
 
-  auto load_stage = [&](int kt, Stage &s) {
+  auto load_stage = [&](int kt, Stage<T> &s) {
     const int64_t x0 = xbeg + (int64_t)kt * kXT;
     const bool x_full = x0 + kXT <= xend;
 #pragma unroll
     for (int r = 0; r < kJRep; ++r) {
       const int64_t xa = x0 + tk + kJRows * r;
       if (x_full && j_full) {
-        s.a[r] = *reinterpret_cast<const f4u *>(B + xa * ldb + j0 + ti);
+        s.a[r] = *reinterpret_cast<const uvec *>(B + xa * ldb + j0 + ti);
       } else if (x_full && wide) {
-        s.a[r] = load4_clamped(B + xa * ldb, j0 + ti);
+        s.a[r] = load_clamped(B + xa * ldb, j0 + ti);
       } else {
-        float v[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = (xa < xend && j0 + ti + e < d) ? B[xa * ldb + j0 + ti + e] : 0.0f;
-        s.a[r] = f4a{v[0], v[1], v[2], v[3]};
+        for (int e = 0; e < kV; ++e) s.a[r][e] = (xa < xend && j0 + ti + e < d) ? B[xa * ldb + j0 + ti + e] : T(0);
       }
       if (CUBE) {
-        const float w = xa < xend ? B[xa * ldb + i] : 0.0f;
+        const T w = xa < xend ? B[xa * ldb + i] : T(0);
         s.a[r] *= w;
       }
     }
     if (x_full && k_full) {
 #pragma unroll
-      for (int r = 0; r < 2; ++r) s.b[r] = *reinterpret_cast<const f4u *>(B + (x0 + bk + 16 * r) * ldb + k0 + bc);
+      for (int r = 0; r < 2; ++r)
+        s.b[r] = *reinterpret_cast<const uvec *>(B + (x0 + bk + (kXT / 2) * r) * ldb + k0 + bc);
     } else if (x_full && wide) {
 #pragma unroll
-      for (int r = 0; r < 2; ++r) s.b[r] = load4_clamped(B + (x0 + bk + 16 * r) * ldb, k0 + bc);
+      for (int r = 0; r < 2; ++r) s.b[r] = load_clamped(B + (x0 + bk + (kXT / 2) * r) * ldb, k0 + bc);
     } else {
 #pragma unroll
       for (int r = 0; r < 2; ++r) {
-        const int64_t x = x0 + bk + 16 * r;
-        float v[4];
+        const int64_t x = x0 + bk + (kXT / 2) * r;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = (x < xend && k0 + bc + e < d) ? B[x * ldb + k0 + bc + e] : 0.0f;
-        s.b[r] = f4a{v[0], v[1], v[2], v[3]};
+        for (int e = 0; e < kV; ++e) s.b[r][e] = (x < xend && k0 + bc + e < d) ? B[x * ldb + k0 + bc + e] : T(0);
       }
     }
   };
-  auto store_stage = [&](int buf, const Stage &s) {
+  auto store_stage = [&](int buf, int, const Stage<T> &s) {
 #pragma unroll
-    for (int r = 0; r < kJRep; ++r) *reinterpret_cast<f4a *>(&As[buf][(tk + kJRows * r) * kJP + ti]) = s.a[r];
+    for (int r = 0; r < kJRep; ++r) *reinterpret_cast<vec *>(&As[buf][(tk + kJRows * r) * kJP + ti]) = s.a[r];
 #pragma unroll
-    for (int r = 0; r < 2; ++r) *reinterpret_cast<f4a *>(&Bs[buf][(bk + 16 * r) * BK + bc]) = s.b[r];
+    for (int r = 0; r < 2; ++r) *reinterpret_cast<vec *>(&Bs[buf][(bk + (kXT / 2) * r) * BK + bc]) = s.b[r];
+  };
+  auto read_ops = [&](int buf, int, int t, typename K::Ops &o) {
+    K::read_a_t(&As[buf][wr * 32], kJP, lane, t, o);
+    K::read_b(&Bs[buf][wc * 32], BK, lane, t, o);
   };
 
-  f16v acc;
-#pragma unroll
-  for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+  typename K::Acc acc;
+  K::clear(acc);
+  sweep_steps<T, Stage<T>>(0, nk, acc, load_stage, store_stage, read_ops, live);
 
-  // Operands of one group of eight samples: lane half h takes samples 8t+4h .. 8t+4h+3 (the sum over x
-  // may be taken in any order), four MFMA steps on the wavefront's 32x32 sub-tile.
-  struct Ops {
-    float a[4];
-    float b[4];
-  };
-  auto read_ops = [&](int buf, int t, Ops &o) {
-    if (!live) return;
-    const float *as = &As[buf][(4 * h) * kJP + wr * 32 + l32];
-    const float *bs = &Bs[buf][(4 * h) * BK + wc * 32 + l32];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      o.a[r] = as[(8 * t + r) * kJP];
-      o.b[r] = bs[(8 * t + r) * BK];
-    }
-  };
-  auto mma = [&](const Ops &o) {
-    if (!live) return;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(o.a[r], o.b[r], acc, 0, 0, 0);
-  };
-
-  Stage st;
-  Ops oa = {}, ob = {};
-  load_stage(0, st);
-  store_stage(0, st);
-  __syncthreads();
-  read_ops(0, 0, oa);
-
-  // One step on LDS buffer `buf`: the next step's global loads are in flight throughout; its LDS
-  // stores and the barrier sit before the last group's matrix instructions.
-  auto step = [&](int kt, int buf) {
-    const bool more = kt + 1 < nk;
-    if (more) load_stage(kt + 1, st);
-    read_ops(buf, 1, ob);
-    mma(oa);
-    read_ops(buf, 2, oa);
-    mma(ob);
-    read_ops(buf, 3, ob);
-    mma(oa);
-    if (more) store_stage(buf ^ 1, st);
-    __syncthreads();
-    if (more) read_ops(buf ^ 1, 0, oa);
-    mma(ob);
-  };
-  for (int kt = 0; kt < nk; kt += 2) {
-    step(kt, 0);
-    if (kt + 1 < nk) step(kt + 1, 1);
-  }
-
-  // D layout of the 32x32 tile: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32.
   // Rows are j, columns are k; both relative to the slice's first column i.
-  float *slice = out + (CUBE ? tet_slice_start(d, i) : 0);
-  const int64_t kr = (int64_t)K * BK + wc * 32 + l32;
-#pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    const int64_t jr = (int64_t)J * kBJ + wr * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+  T *slice = out + (CUBE ? tet_slice_start(d, i) : 0);
+  K::for_each(acc, lane, [&](int r, int c, T v) {
+    const int64_t jr = (int64_t)J * kBJ + wr * 32 + r, kr = (int64_t)Kb * BK + wc * 32 + c;
     if (jr <= kr && kr < q) {
-      float *p = slice + tri_offset(q, jr, kr);
+      T *p = slice + tri_offset(q, jr, kr);
       if (ATOMIC)
-        unsafeAtomicAdd(p, acc[v]);
+        unsafeAtomicAdd(p, v);
       else
-        *p = acc[v];
+        *p = v;
     }
-  }
+  });
 }
 
-__global__ void fill_zero_kernel(float *__restrict__ y, int64_t count) {
+template <typename T>
+__global__ void fill_zero_kernel(T *__restrict__ y, int64_t count) {
   for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < count; t += (int64_t)gridDim.x * blockDim.x)
-    y[t] = 0.0f;
+    y[t] = T(0);
 }
 
-template <bool CUBE, int BK>
-int run(int64_t N, int64_t d, const float *B, int64_t ldb, float *out, void *stream) {
-  constexpr int kBlock = 4 * BK;
+template <typename T, bool CUBE, int BK>
+int run(int64_t N, int64_t d, const T *B, int64_t ldb, T *out, void *stream) {
+  constexpr int kBlock = 4 * BK, kXT = Core<T>::kKT;
+  constexpr int64_t kB = (int64_t)sizeof(T);
   if (N < 0 || d < 0 || ldb < d) return DASTAC_EINVAL;
   if (d > (CUBE ? kMaxD3 : kMaxD2) || N > kMaxN || ld_too_large(ldb)) return DASTAC_EOVERFLOW;
   if (d == 0) return DASTAC_OK;
   if (!out || (N > 0 && !B)) return DASTAC_ENULL;
   const int64_t count = CUBE ? tet(d) : tri(d);
-  if (overlaps(out, count * 4, B, view_bytes(N, ldb, d, 4))) return DASTAC_EALIAS;
+  if (overlaps(out, count * kB, B, view_bytes(N, ldb, d, kB))) return DASTAC_EALIAS;
   hipStream_t st = (hipStream_t)stream;
 
   const int64_t tiles = total_tiles(d, CUBE, BK);
@@ -284,7 +239,7 @@ int run(int64_t N, int64_t d, const float *B, int64_t ldb, float *out, void *str
   // round to 90 %, or else the best one found; every share is a multiple of a step and at least 8 steps.
   int64_t split = 1, chunk = kXT;
   if (N > 0) {
-    const int64_t slots = resident_blocks(pr_mfma_kernel<CUBE, true, BK>, kBlock);
+    const int64_t slots = resident_blocks(pr_mfma_kernel<T, CUBE, true, BK>, kBlock);
     if (slots <= 0) return DASTAC_EHIP;
     const int64_t max_split = N / (8 * kXT) > 1 ? N / (8 * kXT) : 1;
     double best = -1.0;
@@ -307,15 +262,15 @@ int run(int64_t N, int64_t d, const float *B, int64_t ldb, float *out, void *str
   const bool atomic = split > 1;
   if (atomic || N == 0) {
     const int64_t zb = ceil_div(count, 256);
-    fill_zero_kernel<<<(unsigned)(zb < 8192 ? zb : 8192), 256, 0, st>>>(out, count);
+    fill_zero_kernel<T><<<(unsigned)(zb < 8192 ? zb : 8192), 256, 0, st>>>(out, count);
     if (hipGetLastError() != hipSuccess) return DASTAC_EHIP;
     if (N == 0) return DASTAC_OK;
   }
   const unsigned grid = (unsigned)(8 * per_xcd);
   if (atomic)
-    pr_mfma_kernel<CUBE, true, BK><<<grid, kBlock, 0, st>>>(N, d, B, ldb, out, chunk, tiles, split);
+    pr_mfma_kernel<T, CUBE, true, BK><<<grid, kBlock, 0, st>>>(N, d, B, ldb, out, chunk, tiles, split);
   else
-    pr_mfma_kernel<CUBE, false, BK><<<grid, kBlock, 0, st>>>(N, d, B, ldb, out, chunk, tiles, split);
+    pr_mfma_kernel<T, CUBE, false, BK><<<grid, kBlock, 0, st>>>(N, d, B, ldb, out, chunk, tiles, split);
   return launch_status();
 }
 
@@ -324,11 +279,24 @@ int run(int64_t N, int64_t d, const float *B, int64_t ldb, float *out, void *str
 extern "C" {
 
 int dastac_pr_a2_f32(int64_t N, int64_t d, const float *B, int64_t ldb, float *A2p, void *stream) {
-  return d <= kNarrowMaxD2 ? run<false, 64>(N, d, B, ldb, A2p, stream) : run<false, 128>(N, d, B, ldb, A2p, stream);
+  return d <= kNarrowMaxD2 ? run<float, false, 64>(N, d, B, ldb, A2p, stream)
+                           : run<float, false, 128>(N, d, B, ldb, A2p, stream);
 }
 
 int dastac_pr_a3_f32(int64_t N, int64_t d, const float *B, int64_t ldb, float *A3p, void *stream) {
-  return d <= kNarrowMaxD3 ? run<true, 64>(N, d, B, ldb, A3p, stream) : run<true, 128>(N, d, B, ldb, A3p, stream);
+  return d <= kNarrowMaxD3 ? run<float, true, 64>(N, d, B, ldb, A3p, stream)
+                           : run<float, true, 128>(N, d, B, ldb, A3p, stream);
+}
+
+// Double precision (the paper's element type): the same kernel on the fp64 matrix cores.
+int dastac_pr_a2_f64(int64_t N, int64_t d, const double *B, int64_t ldb, double *A2p, void *stream) {
+  return d <= kNarrowMaxD2 ? run<double, false, 64>(N, d, B, ldb, A2p, stream)
+                           : run<double, false, 128>(N, d, B, ldb, A2p, stream);
+}
+
+int dastac_pr_a3_f64(int64_t N, int64_t d, const double *B, int64_t ldb, double *A3p, void *stream) {
+  return d <= kNarrowMaxD3 ? run<double, true, 64>(N, d, B, ldb, A3p, stream)
+                           : run<double, true, 128>(N, d, B, ldb, A3p, stream);
 }
 
 }  // extern "C"

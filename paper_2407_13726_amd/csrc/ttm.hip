@@ -11,42 +11,40 @@
 //   Ap[p, k] = sum_l Bp[p, l] * C[k, l],      p = 0 .. Tri(n)-1
 //
 // with no structural zero left to skip and no index arithmetic beyond the row number: that is
-// the point of the layout.  It runs on the fp32 matrix cores.
+// the point of the layout.  It runs on the matrix cores, in single and in double precision.
 //
 // Tiling.  A workgroup (8 wavefronts, 2 x 4) owns 64 packed rows x 128 values of k and sweeps l in
-// steps of 32; the 64x32 tile of Bp and the 128x32 tile of C are staged in LDS, double-buffered
-// against the global loads of the next step.  Both tiles keep l contiguous, so -- with lane half h
-// taking the four consecutive l values 8t+4h..8t+4h+3 of every group of eight, as in the TRMM
-// kernel -- both operands of v_mfma_f32_32x32x2_f32 are single 16-byte LDS reads.  Workgroups
+// steps of kKT = 32 (fp32) or 16 (fp64); the 64 x kKT tile of Bp and the 128 x kKT tile of C are staged
+// in LDS, double-buffered against the global loads of the next step.  Both tiles keep l contiguous, so
+// in fp32 -- with lane half h taking the four consecutive l values 8t+4h..8t+4h+3 of every group of
+// eight, as in the TRMM kernel -- both operands of v_mfma_f32_32x32x2_f32 are single 16-byte LDS reads
+// (the per-type matrix-core pieces are those of mfma_tile.h).  Workgroups
 // that share a row block (different blocks of k) get ids that are equal modulo 8, i.e. the same
 // XCD, so the rows of Bp they both read come from HBM once.  About two workgroups per compute unit
 // are launched; each walks a strided set of row blocks with one uninterrupted pipeline, so the
 // first loads of a row block are in flight while the previous block's last step is multiplied.
-#include "common.h"
+#include "mfma_tile.h"
 
 using namespace dastac;
 
 namespace {
 
-constexpr int kBM = 64;    // packed rows per workgroup tile
-constexpr int kBN = 128;   // values of k per workgroup tile
-constexpr int kKT = 32;    // step along l
-constexpr int kP = kKT + 4;  // LDS pitch (floats): 16-byte reads of 8 lanes cover all banks
-constexpr int kBlock = 512;
-
-typedef float f16v __attribute__((ext_vector_type(16)));
-
+template <typename T>
 struct Stage {
-  f4a a;     // Bp: row ar of the tile, four l values
-  f4a c[2];  // C: rows cr and cr+64 of the tile, four l values
+  typename Core<T>::vec a;     // Bp: row sr of the tile, one 16-byte piece of l values
+  typename Core<T>::vec c[2];  // C: rows sr and sr+64 of the tile, one 16-byte piece of l values each
 };
 
-__global__ __launch_bounds__(kBlock) void ttm_mfma_kernel(int64_t rows, int64_t Q, int64_t K,
-                                                          const float *__restrict__ Bp,
-                                                          const float *__restrict__ C, int64_t ldc,
-                                                          float *__restrict__ Ap, int lanes, int ncb) {
-  __shared__ __attribute__((aligned(16))) float As[2][kBM * kP];
-  __shared__ __attribute__((aligned(16))) float Cs[2][kBN * kP];
+template <typename T>
+__global__ __launch_bounds__(kTileThreads) void ttm_mfma_kernel(int64_t rows, int64_t Q, int64_t K,
+                                                                const T *__restrict__ Bp, const T *__restrict__ C,
+                                                                int64_t ldc, T *__restrict__ Ap, int lanes, int ncb) {
+  typedef Core<T> Kc;
+  typedef typename Kc::vec vec;
+  typedef typename Kc::uvec uvec;
+  constexpr int kBM = kTileM, kBN = kTileN, kKT = Kc::kKT, kV = Kc::kVec, kP = Kc::kRowPitch;
+  __shared__ __attribute__((aligned(16))) T As[2][kBM * kP];
+  __shared__ __attribute__((aligned(16))) T Cs[2][kBN * kP];
 
   // workgroup id -> (first row block, block of k); ids equal mod 8 share an XCD.  A workgroup
   // then walks every (8*lanes)-th row block, keeping its pipeline full across blocks.
@@ -57,16 +55,15 @@ __global__ __launch_bounds__(kBlock) void ttm_mfma_kernel(int64_t rows, int64_t 
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave >> 2, wc = wave & 3;  // 2x4 wavefronts: 32 rows x 32 values of k each
-  const int l32 = lane & 31, h = lane >> 5;
 
-  // staging role: tile row tid/8 (and +64 for C), l offset 4*(tid%8)
-  const int sr = tid >> 3, sl = (tid & 7) * 4;
+  // staging role: tile row tid/8 (and +64 for C), l offset kV*(tid%8)
+  const int sr = tid >> 3, sl = (tid & 7) * kV;
   const int64_t c0 = (int64_t)cb * kBN;
   const bool full_c = c0 + kBN <= K;
   const int nk = (int)ceil_div(Q, kKT);
 
-  const float *cp0 = C + (c0 + sr < K ? c0 + sr : K - 1) * ldc;
-  const float *cp1 = C + (c0 + sr + 64 < K ? c0 + sr + 64 : K - 1) * ldc;
+  const T *cp0 = C + (c0 + sr < K ? c0 + sr : K - 1) * ldc;
+  const T *cp1 = C + (c0 + sr + 64 < K ? c0 + sr + 64 : K - 1) * ldc;
 
   struct Cur {  // wave-uniform cursor over the steps of this workgroup: row block, step along l
     int64_t r0;
@@ -85,58 +82,42 @@ __global__ __launch_bounds__(kBlock) void ttm_mfma_kernel(int64_t rows, int64_t 
     return c;
   };
 
-  auto load_stage = [&](const Cur &cu, Stage &s) {
+  auto load_stage = [&](const Cur &cu, Stage<T> &s) {
     const int64_t l0 = (int64_t)cu.kt * kKT + sl;
-    const float *ap = Bp + (cu.r0 + sr < rows ? cu.r0 + sr : rows - 1) * Q;
+    const T *ap = Bp + (cu.r0 + sr < rows ? cu.r0 + sr : rows - 1) * Q;
     if (full_c && cu.r0 + kBM <= rows && (int64_t)cu.kt * kKT + kKT <= Q) {
-      s.a = *reinterpret_cast<const f4u *>(ap + l0);
-      s.c[0] = *reinterpret_cast<const f4u *>(cp0 + l0);
-      s.c[1] = *reinterpret_cast<const f4u *>(cp1 + l0);
+      s.a = *reinterpret_cast<const uvec *>(ap + l0);
+      s.c[0] = *reinterpret_cast<const uvec *>(cp0 + l0);
+      s.c[1] = *reinterpret_cast<const uvec *>(cp1 + l0);
     } else {  // ragged edge: zeros outside the operands
-      float a[4], u[4], v[4];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
+      for (int e = 0; e < kV; ++e) {
         const bool lok = l0 + e < Q;
-        a[e] = (lok && cu.r0 + sr < rows) ? ap[l0 + e] : 0.0f;
-        u[e] = (lok && c0 + sr < K) ? cp0[l0 + e] : 0.0f;
-        v[e] = (lok && c0 + sr + 64 < K) ? cp1[l0 + e] : 0.0f;
+        s.a[e] = (lok && cu.r0 + sr < rows) ? ap[l0 + e] : T(0);
+        s.c[0][e] = (lok && c0 + sr < K) ? cp0[l0 + e] : T(0);
+        s.c[1][e] = (lok && c0 + sr + 64 < K) ? cp1[l0 + e] : T(0);
       }
-      s.a = f4a{a[0], a[1], a[2], a[3]};
-      s.c[0] = f4a{u[0], u[1], u[2], u[3]};
-      s.c[1] = f4a{v[0], v[1], v[2], v[3]};
     }
   };
-  auto store_stage = [&](int buf, const Stage &s) {
-    *reinterpret_cast<f4a *>(&As[buf][sr * kP + sl]) = s.a;
-    *reinterpret_cast<f4a *>(&Cs[buf][sr * kP + sl]) = s.c[0];
-    *reinterpret_cast<f4a *>(&Cs[buf][(sr + 64) * kP + sl]) = s.c[1];
+  auto store_stage = [&](int buf, const Stage<T> &s) {
+    *reinterpret_cast<vec *>(&As[buf][sr * kP + sl]) = s.a;
+    *reinterpret_cast<vec *>(&Cs[buf][sr * kP + sl]) = s.c[0];
+    *reinterpret_cast<vec *>(&Cs[buf][(sr + 64) * kP + sl]) = s.c[1];
   };
 
-  f16v acc;
-#pragma unroll
-  for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
-
-  // Operands of one group of eight l values: four MFMA steps on the wavefront's 32x32 sub-tile.
-  struct Ops {
-    f4a a, c;
-  };
-  auto read_ops = [&](int buf, int t, Ops &o) {
-    o.a = *reinterpret_cast<const f4a *>(&As[buf][(wr * 32 + l32) * kP + 4 * h + 8 * t]);
-    o.c = *reinterpret_cast<const f4a *>(&Cs[buf][(wc * 32 + l32) * kP + 4 * h + 8 * t]);
-  };
-  auto mma = [&](const Ops &o) {
-    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(o.a.x, o.c.x, acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(o.a.y, o.c.y, acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(o.a.z, o.c.z, acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(o.a.w, o.c.w, acc, 0, 0, 0);
+  typename Kc::Acc acc;
+  Kc::clear(acc);
+  auto read_ops = [&](int buf, int t, typename Kc::Ops &o) {
+    Kc::read_a(&As[buf][wr * 32 * kP], lane, t, o);
+    Kc::read_b_rows(&Cs[buf][wc * 32 * kP], lane, t, o);
   };
 
   Cur cc{(int64_t)kBM * (xcd + 8 * (slot / ncb)), 0, true};  // the step being multiplied
   cc.valid = cc.r0 < rows;
   if (!cc.valid) return;
   Cur cl = cc;  // the step being loaded: one ahead
-  Stage st;
-  Ops oa, ob;
+  Stage<T> st;
+  typename Kc::Ops oa, ob;
   load_stage(cl, st);
   store_stage(0, st);
   __syncthreads();
@@ -145,30 +126,28 @@ __global__ __launch_bounds__(kBlock) void ttm_mfma_kernel(int64_t rows, int64_t 
   // One step on LDS buffer `buf` (a literal at both call sites).  The global loads of the next
   // step -- of the next row block, at a block's last step -- are in flight throughout; its LDS
   // stores and the workgroup barrier sit before the last group's matrix instructions, whose
-  // operands are already in registers.
+  // operands are already in registers.  (The schedule of mfma_tile.h's sweep, run as ONE pipeline over
+  // all the workgroup's row blocks.)
   auto step = [&](int buf) {
     cl = next(cl);
     const bool more = cl.valid;
     if (more) load_stage(cl, st);
     read_ops(buf, 1, ob);
-    mma(oa);
+    Kc::mma(oa, acc);
     read_ops(buf, 2, oa);
-    mma(ob);
+    Kc::mma(ob, acc);
     read_ops(buf, 3, ob);
-    mma(oa);
+    Kc::mma(oa, acc);
     if (more) store_stage(buf ^ 1, st);
     __syncthreads();
     if (more) read_ops(buf ^ 1, 0, oa);
-    mma(ob);
+    Kc::mma(ob, acc);
     if (cc.kt == nk - 1) {
-      // D layout of the 32x32 tile: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32
-      const int64_t col = c0 + wc * 32 + l32;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int64_t r = cc.r0 + wr * 32 + 8 * (v / 4) + 4 * h + (v % 4);
-        if (r < rows && col < K) Ap[r * K + col] = acc[v];
-        acc[v] = 0.0f;
-      }
+      Kc::for_each(acc, lane, [&](int r, int c, T v) {
+        const int64_t row = cc.r0 + wr * 32 + r, col = c0 + wc * 32 + c;
+        if (row < rows && col < K) Ap[row * K + col] = v;
+      });
+      Kc::clear(acc);
     }
     cc = next(cc);
   };
@@ -219,6 +198,27 @@ int uhc_copy(int64_t n, int64_t Q, const T *src, T *dst, void *stream) {
   return launch_status();
 }
 
+template <typename T>
+int ttm_ut(int64_t n, int64_t Q, int64_t K, const T *Bp, const T *C, int64_t ldc, T *Ap, void *stream) {
+  constexpr int64_t kB = (int64_t)sizeof(T);
+  if (n < 0 || Q < 1 || K < 1 || ldc < Q) return DASTAC_EINVAL;
+  if (!uhc_ok(n, Q) || !uhc_ok(n, K) || ld_too_large(ldc) || K > ((int64_t)1 << 40) / ldc) return DASTAC_EOVERFLOW;
+  if (n == 0) return DASTAC_OK;
+  if (!Bp || !C || !Ap) return DASTAC_ENULL;
+  const int64_t rows = tri(n);
+  if (overlaps(Ap, rows * K * kB, Bp, rows * Q * kB) || overlaps(Ap, rows * K * kB, C, view_bytes(K, ldc, Q, kB)))
+    return DASTAC_EALIAS;
+  const int64_t nrb = ceil_div(rows, kTileM), ncb = ceil_div(K, kTileN);
+  if (ncb > (1 << 20)) return DASTAC_EOVERFLOW;
+  // about two workgroups per compute unit (256 of them), each walking a strided set of row blocks
+  int64_t lanes = ceil_div(512, 8 * ncb);
+  if (lanes > ceil_div(nrb, 8)) lanes = ceil_div(nrb, 8);
+  const int64_t grid = 8 * lanes * ncb;
+  ttm_mfma_kernel<T><<<(unsigned)grid, kTileThreads, 0, (hipStream_t)stream>>>(rows, Q, K, Bp, C, ldc, Ap, (int)lanes,
+                                                                             (int)ncb);
+  return launch_status();
+}
+
 }  // namespace
 
 extern "C" {
@@ -251,20 +251,13 @@ int dastac_unpack_uhc_f64(int64_t n, int64_t Q, const double *packed, double *de
 
 int dastac_ttm_ut_f32(int64_t n, int64_t Q, int64_t K, const float *Bp, const float *C, int64_t ldc, float *Ap,
                       void *stream) {
-  if (n < 0 || Q < 1 || K < 1 || ldc < Q) return DASTAC_EINVAL;
-  if (!uhc_ok(n, Q) || !uhc_ok(n, K) || ld_too_large(ldc) || K > ((int64_t)1 << 40) / ldc) return DASTAC_EOVERFLOW;
-  if (n == 0) return DASTAC_OK;
-  if (!Bp || !C || !Ap) return DASTAC_ENULL;
-  const int64_t rows = tri(n);
-  if (overlaps(Ap, rows * K * 4, Bp, rows * Q * 4) || overlaps(Ap, rows * K * 4, C, view_bytes(K, ldc, Q, 4))) return DASTAC_EALIAS;
-  const int64_t nrb = ceil_div(rows, kBM), ncb = ceil_div(K, kBN);
-  if (ncb > (1 << 20)) return DASTAC_EOVERFLOW;
-  // about two workgroups per compute unit (256 of them), each walking a strided set of row blocks
-  int64_t lanes = ceil_div(512, 8 * ncb);
-  if (lanes > ceil_div(nrb, 8)) lanes = ceil_div(nrb, 8);
-  const int64_t grid = 8 * lanes * ncb;
-  ttm_mfma_kernel<<<(unsigned)grid, kBlock, 0, (hipStream_t)stream>>>(rows, Q, K, Bp, C, ldc, Ap, (int)lanes, (int)ncb);
-  return launch_status();
+  return ttm_ut<float>(n, Q, K, Bp, C, ldc, Ap, stream);
+}
+
+// Double precision (the paper's element type): the same kernel on the fp64 matrix cores.
+int dastac_ttm_ut_f64(int64_t n, int64_t Q, int64_t K, const double *Bp, const double *C, int64_t ldc, double *Ap,
+                      void *stream) {
+  return ttm_ut<double>(n, Q, K, Bp, C, ldc, Ap, stream);
 }
 
 }  // extern "C"
