@@ -83,6 +83,12 @@ int trmm_few_columns(int64_t n, int64_t m, const double *Up, const double *B, in
 // element offsets, and gfx950 global loads of four dwords need dword alignment only.
 typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
 typedef float f4a __attribute__((ext_vector_type(4)));
+// the same for doubles: 16 bytes that only promise 8-byte alignment
+typedef double d2u __attribute__((ext_vector_type(2), aligned(8)));
+typedef double d2a __attribute__((ext_vector_type(2)));
+// result registers of one matrix instruction: v_mfma_f32_32x32x2_f32 and v_mfma_f64_16x16x4_f64
+typedef float f16v __attribute__((ext_vector_type(16)));
+typedef double d4v __attribute__((ext_vector_type(4)));
 
 // Make a wave-uniform 64-bit value provably scalar for the compiler.
 __device__ inline int64_t uniform64(int64_t v) {

@@ -23,10 +23,6 @@ constexpr int kTileM = 64;    // rows of the result per workgroup tile
 constexpr int kTileN = 128;   // columns of the result per workgroup tile
 constexpr int kTileThreads = 512;
 
-typedef float f16v __attribute__((ext_vector_type(16)));
-typedef double d2u __attribute__((ext_vector_type(2), aligned(8)));
-typedef double d2a __attribute__((ext_vector_type(2)));
-typedef double d4v __attribute__((ext_vector_type(4)));
 
 template <typename T>
 struct Core;

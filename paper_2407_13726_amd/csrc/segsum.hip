@@ -125,8 +125,6 @@ __device__ inline float dot0(f4a a, f4a x) {
 
 // Double precision has no multiply that returns 0 for 0 * Inf: a product with a zero of x is dropped by a
 // select instead (the same meaning: a zero of x contributes nothing, whatever it multiplies).
-typedef double d2u __attribute__((ext_vector_type(2), aligned(8)));
-typedef double d2a __attribute__((ext_vector_type(2)));
 __device__ inline double dot0(d2a a, d2a x) {
   return (x.x == 0.0 ? 0.0 : a.x * x.x) + (x.y == 0.0 ? 0.0 : a.y * x.y);
 }

@@ -44,8 +44,6 @@ constexpr int kMaxN = 524288;  // 512 panels of 1024 columns; such a triangle is
 
 enum { MODE_ROWS = 0, MODE_COLS = 1, MODE_SYM = 2 };
 
-typedef double d2u __attribute__((ext_vector_type(2), aligned(8)));
-typedef double d2a __attribute__((ext_vector_type(2)));
 
 // Per element type: elements in a 16-byte piece, and the piece as a register vector and as a
 // load type that only promises the element's own alignment.

@@ -24,7 +24,6 @@ constexpr int kPanel = 512;  // k values per staged panel of B
 constexpr int kRB = 32;      // rows of a block
 constexpr int kTP = 36;      // pitch (floats) of a wavefront's private 32x32 tile
 
-typedef float f16v __attribute__((ext_vector_type(16)));
 
 // Orders LDS traffic between the lanes of ONE wavefront (which executes in lockstep).
 __device__ inline void wave_sync_lds() {

@@ -22,9 +22,6 @@ constexpr int kRB = 32;      // rows of a block
 constexpr int kTK = 16;      // k values per tile
 constexpr int kTP = kTK + 2;  // pitch (doubles) of a wavefront's private 32 x 16 tile
 
-typedef double d2u __attribute__((ext_vector_type(2), aligned(8)));
-typedef double d2a __attribute__((ext_vector_type(2)));
-typedef double d4v __attribute__((ext_vector_type(4)));
 
 // Orders LDS traffic between the lanes of ONE wavefront (which executes in lockstep).
 __device__ inline void wave_sync_lds() {

@@ -111,6 +111,33 @@ def test_c5_mttkrp_1024_small_integers_bit_exact(gpu, oracle):
     assert got.tobytes() == want.tobytes(), "slices that differ: %r" % (np.nonzero((got != want).any(axis=1))[0][:10],)
 
 
+def test_mttkrp_f64_768_every_element(gpu, oracle):
+    """Double-precision MTTKRP at the size bench.py reports beside the step: every slice order up to 768, so every
+    shape of block (full, cut by the diagonal, narrow at the left edge, short at the top) occurs many times."""
+    n, R = 768, 32
+    Ap = inputs.uniform64(5101, n * (n + 1) * (n + 2) // 6)
+    B, C = inputs.uniform64(5102, n, R), inputs.uniform64(5103, n, R)
+    M = gpu.torch.full((n, R), float("nan"), dtype=gpu.torch.float64, device=gpu.dev)
+    gpu.d.tet_mttkrp_f64(n, R, gpu.up(Ap), gpu.up(B), R, gpu.up(C), R, M, R)
+    got = gpu.down(M)
+    want, scale = by_windows(lambda lo, hi: oracle.tet_mttkrp_f64(n, R, Ap, B, C, rows=(lo, hi)), n, 8)
+    got, want, scale = (np.asarray(a, dtype=np.float64).ravel() for a in (got, want, scale))
+    assert np.isfinite(got).all()
+    err = np.abs(got - want)
+    assert (err <= 1e-12 * scale).all(), "worst err/scale %.3g" % (err / np.maximum(scale, 1e-300)).max()
+
+
+def test_mttkrp_f64_530_small_integers_bit_exact(gpu, oracle):
+    n, R = 530, 29
+    Ap = inputs.small_int(5111, -3, 3, n * (n + 1) * (n + 2) // 6).astype(np.float64)
+    B, C = inputs.small_int(5112, -3, 3, n, R).astype(np.float64), inputs.small_int(5113, -3, 3, n, R).astype(np.float64)
+    M = gpu.torch.full((n, R), float("nan"), dtype=gpu.torch.float64, device=gpu.dev)
+    gpu.d.tet_mttkrp_f64(n, R, gpu.up(Ap), gpu.up(B), R, gpu.up(C), R, M, R)
+    got = gpu.down(M)
+    want, _ = by_windows(lambda lo, hi: oracle.tet_mttkrp_f64(n, R, Ap, B, C, rows=(lo, hi)), n, 8)
+    assert got.tobytes() == want.tobytes(), "slices that differ: %r" % (np.nonzero((got != want).any(axis=1))[0][:10],)
+
+
 def test_running_example_ttm_ut_512_sampled_pairs(gpu, oracle):
     """The paper's running example at the size bench.py reports beside the five configurations."""
     w = wl.ttm_ut_inputs()
