@@ -71,10 +71,9 @@ inline int64_t resident_blocks(Kernel kernel, int block) {
 // defined in trimv.hip
 int trmv_upper_by_panels(int64_t n, const float *Up, const float *x, float *y, void *stream);
 int trmv_upper_by_panels(int64_t n, const double *Up, const double *x, double *y, void *stream);
-// defined in trmm_skinny.hip: C := U B for few columns (arguments already validated)
+// defined in trmm_skinny.hip: C := U B for few columns (arguments already validated), both precisions
 int trmm_few_columns(int64_t n, int64_t m, const float *Up, const float *B, int64_t ldb, float *C, int64_t ldc,
                      void *stream);
-// defined in trmm_skinny_f64.hip
 int trmm_few_columns(int64_t n, int64_t m, const double *Up, const double *B, int64_t ldb, double *C, int64_t ldc,
                      void *stream);
 
