@@ -139,23 +139,23 @@ struct Core<double> {
 };
 
 // The sweep over k-steps [lo, hi) of one workgroup tile, written once for every kernel and element type.
-//   load(kt, stage)      requests the global pieces of step kt into registers
+//   load(kt, stage)       requests the global pieces of step kt into registers
 //   store(buf, kt, stage) writes them to LDS buffer buf
 //   read(buf, kt, t, ops) reads the operands of group t of step kt from LDS buffer buf
+//   mma(ops)              issues the matrix instructions of one group
 // Step kt computes on buffer (kt - lo) & 1.  The global loads of the next step are in flight throughout a
 // step; its LDS stores and the workgroup barrier sit BEFORE the last group's matrix instructions, whose
 // operands are already in registers, so the matrix pipe has work while the barrier settles and while the
-// first operands of the next step come back from LDS.  Both buffers appear as literals (the loop is unrolled
-// by two), so every LDS address is a compile-time offset.  The caller places a barrier between two sweeps
-// that use the same buffers.  A wavefront with `active` false stages and synchronises like the others but
-// reads no operands and issues no matrix instructions (its sub-tile holds nothing to compute).
-template <typename T, typename Stage, typename Load, typename Store, typename Read>
-__device__ inline void sweep_steps(int lo, int hi, typename Core<T>::Acc &acc, Load load, Store store, Read read,
-                                   bool active = true) {
-  typedef Core<T> K;
-  static_assert(K::kGroups == 4, "the step below is written for four operand groups");
+// first operands of the next step come back from LDS.  (Everything a group needs from LDS therefore has to
+// be part of `ops`: after the barrier the other wavefronts may already be overwriting the buffer.)  Both
+// buffers appear as literals (the loop is unrolled by two), so every LDS address is a compile-time offset.
+// The caller places a barrier between two sweeps that use the same buffers.  A wavefront with `active`
+// false stages and synchronises like the others but reads no operands and issues no matrix instructions
+// (its sub-tile holds nothing to compute).
+template <typename Ops, typename Stage, typename Load, typename Store, typename Read, typename Mma>
+__device__ inline void sweep_groups(int lo, int hi, Load load, Store store, Read read, Mma mma, bool active = true) {
   Stage st;
-  typename K::Ops oa, ob;
+  Ops oa, ob;
   load(lo, st);
   store(0, lo, st);
   __syncthreads();
@@ -165,23 +165,33 @@ __device__ inline void sweep_steps(int lo, int hi, typename Core<T>::Acc &acc, L
     if (more) load(kt + 1, st);
     if (active) {
       read(buf, kt, 1, ob);
-      K::mma(oa, acc);
+      mma(oa);
       read(buf, kt, 2, oa);
-      K::mma(ob, acc);
+      mma(ob);
       read(buf, kt, 3, ob);
-      K::mma(oa, acc);
+      mma(oa);
     }
     if (more) store(buf ^ 1, kt + 1, st);
     __syncthreads();
     if (active) {
       if (more) read(buf ^ 1, kt + 1, 0, oa);
-      K::mma(ob, acc);
+      mma(ob);
     }
   };
   for (int kt = lo; kt < hi; kt += 2) {
     step(kt, 0);
     if (kt + 1 < hi) step(kt + 1, 1);
   }
+}
+
+// The common case: one accumulator per wavefront, the operand groups and matrix instructions of Core<T>.
+template <typename T, typename Stage, typename Load, typename Store, typename Read>
+__device__ inline void sweep_steps(int lo, int hi, typename Core<T>::Acc &acc, Load load, Store store, Read read,
+                                   bool active = true) {
+  typedef Core<T> K;
+  static_assert(K::kGroups == 4, "the step schedule is written for four operand groups");
+  sweep_groups<typename K::Ops, Stage>(
+      lo, hi, load, store, read, [&](const typename K::Ops &o) { K::mma(o, acc); }, active);
 }
 
 // Zero-fills the n x m matrix C (row stride ldc), leaving the padding columns of every row alone.

@@ -6,20 +6,29 @@
 //
 // B is the dense N x d sample matrix; both outputs are symmetric under any permutation of their
 // indices and only the unique elements are computed and stored (the output inherits the structure,
-// Section 3).  Slice i of A3 is a weighted Gram matrix, sum_x w(x) B(x,j) B(x,k) with w = B(.,i),
-// restricted to j,k >= i, whose upper triangle of order d-i is stored contiguously at
-// tet_slice_start(d,i); A2 is the same with w = 1 and a single slice.  One kernel serves both.
+// Section 3).  A2 is the upper triangle of the Gram matrix; slice i of A3 is a weighted Gram matrix,
+// sum_x w(x) B(x,j) B(x,k) with w = B(.,i), restricted to i <= j <= k, stored contiguously at
+// tet_slice_start(d,i).
 //
-// A workgroup owns a 64 (j) x 128 (k) tile of one slice (eight wavefronts; for small d a 64 x 64 tile and
-// four wavefronts) and a range of samples x, which is the reduction index: per step of kXT samples (32 in
-// fp32, 16 in fp64), the kXT x 64 tile of B columns j (multiplied by w on the way in) and the tile of B
-// columns k are staged in LDS, double-buffered against the global loads of the next step, and each
-// wavefront multiplies its 32x32 sub-tile (sweep and per-type matrix-core pieces: mfma_tile.h; both tiles
-// keep the sample index first, so both operands are read element by element).  Tiles that lie wholly below the diagonal are never
-// launched; tiles on the diagonal stage their full rectangle, wavefronts whose sub-tile lies below it
-// skip their matrix instructions, and only j<=k is stored.  When the tile count alone cannot fill the
-// chip the sample range is split over several workgroups, which then add into a pre-zeroed output with
-// floating-point atomics.
+// A workgroup owns a 64 (j) x 128 (k) tile of the (j,k) plane (eight wavefronts; for small d a 64 x 64
+// tile and four wavefronts) and a range of samples x, which is the reduction index: per step of kXT
+// samples (32 in fp32, 16 in fp64) the kXT x 64 tile of B's columns j and the tile of B's columns k are
+// staged in LDS, double-buffered against the global loads of the next step, and each wavefront
+// multiplies its 32x32 sub-tile (sweep and per-type matrix-core pieces: mfma_tile.h; both tiles keep the
+// sample index first, so both operands are read element by element).  Tiles that lie wholly below the
+// diagonal are never launched; tiles on the diagonal stage their full rectangle, wavefronts whose
+// sub-tile lies below it skip their matrix instructions, and only j<=k is stored.
+//
+// For A3 the tiles are cut on a grid that is the same for every slice, and a workgroup takes its tile
+// for several consecutive slices i at once (four in fp32, two in fp64): the two staged tiles are shared
+// by those slices, whose weights B(x,i) are staged beside them and multiplied onto the first operand in
+// registers, one accumulator per slice.  The global loads, LDS traffic and barriers of a step are thus
+// spent once per 64 (fp32) matrix instructions of a wavefront instead of once per 16.  A tile serves
+// the slices i <= its last row; a wavefront whose rows all lie above the slices of the workgroup
+// (j < i) has nothing to compute.
+//
+// When the work items alone cannot fill the chip the sample range is split over several workgroups,
+// which then add into a pre-zeroed output with floating-point atomics.
 #include "mfma_tile.h"
 
 using namespace dastac;
@@ -29,112 +38,79 @@ namespace {
 constexpr int kBJ = kTileM;  // j extent of a workgroup tile
 // k extent of a workgroup tile: BK = 128 (eight wavefronts) or BK = 64 (four), a template parameter
 constexpr int64_t kMaxD2 = 1 << 16;  // A2: tile grid and tri(d) stay small
-constexpr int64_t kMaxD3 = 1 << 13;  // A3: the tile count stays inside gridDim.x
+constexpr int64_t kMaxD3 = 1 << 13;  // A3: the item count stays inside gridDim.x
 constexpr int64_t kMaxN = (int64_t)1 << 31;
 // Up to these d the 64 x 64 tile is used: it wastes less on the diagonal and leaves more workgroups per CU,
-// which outweighs its lower operand reuse while diagonal tiles are a large share of all tiles (measured in fp32,
-// N=100000 resp. 10000: A2 d=512 73 against 49 TFLOP/s, d=1024 91 against 103; A3 d=256 46 against 36, d=1024 78 against 72).
+// which outweighs its lower operand reuse while diagonal tiles are a large share of all tiles.
 constexpr int64_t kNarrowMaxD2 = 768, kNarrowMaxD3 = 2048;
+
+// Slices of A3 that share a workgroup's staged tiles, and how their weights reach the first operand.
+template <typename T>
+struct Slices;
+template <>
+struct Slices<float> {
+  static constexpr int kNI = 4;
+  // group t of a step: this lane's samples are 8t + 4*(lane/32) + q, q < 4; ws is [slice][sample]
+  template <typename Ops3>
+  __device__ static void scale(const Core<float>::Ops &r, const float *ws, int lane, int t, Ops3 &o) {
+#pragma unroll
+    for (int ii = 0; ii < kNI; ++ii) {
+      const f4a w = *reinterpret_cast<const f4a *>(ws + ii * Core<float>::kKT + 8 * t + 4 * (lane >> 5));
+#pragma unroll
+      for (int q = 0; q < 4; ++q) o.a[ii][q] = r.a[q] * w[q];
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) o.b[q] = r.b[q];
+  }
+};
+template <>
+struct Slices<double> {
+  static constexpr int kNI = 2;
+  // group t of a step: this lane's sample is 4t + lane/16
+  template <typename Ops3>
+  __device__ static void scale(const Core<double>::Ops &r, const double *ws, int lane, int t, Ops3 &o) {
+#pragma unroll
+    for (int ii = 0; ii < kNI; ++ii) {
+      const double w = ws[ii * Core<double>::kKT + 4 * t + (lane >> 4)];
+      o.a[ii][0] = r.a[0] * w;
+      o.a[ii][1] = r.a[1] * w;
+    }
+    o.b[0] = r.b[0];
+    o.b[1] = r.b[1];
+  }
+};
 
 template <typename T>
 struct Stage {
   typename Core<T>::vec a[2];  // j tile: one or two sample rows, one 16-byte piece of columns each
   typename Core<T>::vec b[2];  // k tile: sample rows bk and bk + kXT/2, one 16-byte piece of columns each
+  typename Core<T>::vec w;     // A3: one piece of the weights (first threads only)
 };
 
-// Tiles with work.  A slice of order q has m = ceil(q/64) blocks of rows j and ceil(m/2) blocks of columns k;
-// tile (J,K) holds an element with j<=k exactly when K >= J/2 (integer division), so row block J has
-// ceil(m/2) - J/2 tiles and the slice has tiles_of(m) in all.  Tiles are numbered densely, slice after slice,
-// row block after row block, so that consecutive workgroup ids (which the hardware deals out to the XCDs in
-// turn) all carry work: numbering the whole J x K rectangle and letting the empty tiles exit would leave
-// the XCDs with very different loads, because the id modulo 8 would select the column block.
-// (With BK = 64 the condition is K >= J: row block J has m - J tiles, a slice m(m+1)/2.)
-DASTAC_HD int64_t tiles_of(int64_t m, int BK) {
-  if (BK == 64) return m * (m + 1) / 2;
-  const int64_t p = m / 2;
-  return (m & 1) ? p * p + 3 * p + 1 : p * (p + 1);
-}
-
-DASTAC_HD int64_t total_tiles(int64_t d, bool cube, int BK) {
-  const int64_t m0 = ceil_div(d, kBJ);
-  if (!cube) return tiles_of(m0, BK);
-  int64_t total = (d - kBJ * (m0 - 1)) * tiles_of(m0, BK);  // slices whose order needs m0 row blocks
-  for (int64_t m = m0 - 1; m >= 1; --m) total += kBJ * tiles_of(m, BK);
-  return total;
-}
-
-// Dense tile number -> slice i and tile (J,K).
-__device__ inline void decode_tile(int64_t d, bool cube, int BK, int64_t t, int64_t &i, int &J, int &K) {
-  int64_t m = ceil_div(d, kBJ);
-  i = 0;
-  if (cube) {
-    int64_t first = 0, count = d - kBJ * (m - 1);  // slices first .. first+count-1 need m row blocks
-    while (t >= count * tiles_of(m, BK)) {
-      t -= count * tiles_of(m, BK);
-      first += count;
-      count = kBJ;
-      --m;
-    }
-    i = first + t / tiles_of(m, BK);
-    t = t % tiles_of(m, BK);
-  }
-  const int64_t nK = BK == 64 ? m : (m + 1) / 2;  // column blocks of the slice
-  int64_t Jr = 0;
-  while (t >= nK - Jr * kBJ / BK) {  // row block Jr has column blocks Jr*64/BK .. nK-1
-    t -= nK - Jr * kBJ / BK;
-    ++Jr;
-  }
-  J = (int)Jr;
-  K = (int)(Jr * kBJ / BK + t);
-}
-
-template <typename T, bool CUBE, bool ATOMIC, int BK>
-__global__ __launch_bounds__(4 * BK) void pr_mfma_kernel(int64_t N, int64_t d, const T *__restrict__ B, int64_t ldb,
-                                                         T *__restrict__ out, int64_t chunk, int64_t tiles,
-                                                         int64_t split) {
+// Staging of the two column tiles of B, the same for both kernels: columns j0.. (64 of them) and k0.. (BK),
+// sample rows x0 .. x0+kXT-1, zeros from column d and from sample xend on.
+template <typename T, int BK>
+struct Tiles {
   typedef Core<T> K;
   typedef typename K::vec vec;
   typedef typename K::uvec uvec;
-  constexpr int kXT = K::kKT, kV = K::kVec, kJP = K::kColPitch;  // samples per step; pitch of the j tile [x][j]
-  __shared__ __attribute__((aligned(16))) T As[2][kXT * kJP];
-  __shared__ __attribute__((aligned(16))) T Bs[2][kXT * BK];
-  constexpr int kThreads = 4 * BK, kWC = BK / 32;  // wavefronts: 2 rows of kWC
-
-  // Work items are (sample share, tile) pairs, share-major.  Workgroup ids are dealt to the eight XCDs in turn,
-  // so id%8 picks the XCD and id/8 the position in that XCD's run of CONSECUTIVE items: the tiles of one share
-  // read the same rows of B (each its own columns) and sweep them at the same pace, so on one XCD a row is
-  // fetched from memory once and served to the other tiles by that L2.
-  const int64_t items = tiles * split, xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int64_t item = items * xcd / 8 + slot;
-  if (item >= items * (xcd + 1) / 8) return;
-  const int64_t share = uniform64(item / tiles);
-  int64_t i;  // slice: every column index of this workgroup is >= i
-  int J, Kb;
-  decode_tile(d, CUBE, BK, uniform64(item - share * tiles), i, J, Kb);
-  const int64_t q = d - i;  // order of the slice's triangle
-  const int64_t xbeg = share * chunk;
-  const int64_t xend = xbeg + chunk < N ? xbeg + chunk : N;
-  if (xbeg >= xend) return;
-  const int nk = (int)ceil_div(xend - xbeg, kXT);
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wr = wave / kWC, wc = wave % kWC;  // 2 x kWC wavefronts: 32 (j) x 32 (k) each
-  // A wavefront whose 32x32 sub-tile lies wholly below the diagonal (largest k < smallest j) still helps
-  // to stage the tiles but issues no matrix instructions, which leaves the SIMD's matrix pipe to the
-  // wavefronts of the other workgroups resident on it.
-  const bool live = uniform32(Kb * BK + wc * 32 + 31 >= J * kBJ + wr * 32) != 0;
-
-  // j tile: sample rows tk + kJRows*r (r < kJRep), column offset ti; k tile: sample rows bk and bk + kXT/2, column offset bc
-  constexpr int kJRows = kThreads / (kBJ / kV), kJRep = kXT / kJRows;
+  static constexpr int kXT = K::kKT, kV = K::kVec, kJP = K::kColPitch, kThreads = 4 * BK;
+  static constexpr int kJRows = kThreads / (kBJ / kV), kJRep = kXT / kJRows;
   static_assert(kJRep == 1 || kJRep == 2, "a thread stages one or two pieces of the j tile");
-  const int tk = tid / (kBJ / kV), ti = (tid % (kBJ / kV)) * kV;
-  const int bk = tid / (BK / kV), bc = (tid % (BK / kV)) * kV;
-  const int64_t j0 = i + (int64_t)J * kBJ, k0 = i + (int64_t)Kb * BK;  // absolute first columns
-  const bool j_full = j0 + kBJ <= d, k_full = k0 + BK <= d;
+  const T *B;
+  int64_t ldb, d, j0, k0;
+  int tk, ti, bk, bc;  // j tile: sample rows tk + kJRows*r, column offset ti; k tile: rows bk, bk + kXT/2, offset bc
+  bool j_full, k_full, wide;
 
+  __device__ Tiles(const T *B_, int64_t ldb_, int64_t d_, int64_t j0_, int64_t k0_, int tid)
+      : B(B_), ldb(ldb_), d(d_), j0(j0_), k0(k0_) {
+    tk = tid / (kBJ / kV), ti = (tid % (kBJ / kV)) * kV;
+    bk = tid / (BK / kV), bc = (tid % (BK / kV)) * kV;
+    j_full = j0 + kBJ <= d, k_full = k0 + BK <= d, wide = d >= kV;
+  }
   // Columns c..c+kV-1 of one row of B, zero from column d on, with one vector load whose address is pulled
   // back inside the row (needs d >= kV): a lane that straddles the end shifts what it fetched.
-  auto load_clamped = [&](const T *row, int64_t c) -> vec {
+  __device__ vec load_clamped(const T *row, int64_t c) const {
     const int64_t cc = c + kV <= d ? c : d - kV;
     const vec v = *reinterpret_cast<const uvec *>(row + cc);
     const int64_t sh = c - cc;  // 0: all inside; 1..kV-1: that many beyond the end; >= kV: all beyond
@@ -147,11 +123,8 @@ __global__ __launch_bounds__(4 * BK) void pr_mfma_kernel(int64_t N, int64_t d, c
       r[e] = t;
     }
     return r;
-  };
-  const bool wide = d >= kV;
-
-  auto load_stage = [&](int kt, Stage<T> &s) {
-    const int64_t x0 = xbeg + (int64_t)kt * kXT;
+  }
+  __device__ void load(int64_t x0, int64_t xend, Stage<T> &s) const {
     const bool x_full = x0 + kXT <= xend;
 #pragma unroll
     for (int r = 0; r < kJRep; ++r) {
@@ -163,10 +136,6 @@ __global__ __launch_bounds__(4 * BK) void pr_mfma_kernel(int64_t N, int64_t d, c
       } else {
 #pragma unroll
         for (int e = 0; e < kV; ++e) s.a[r][e] = (xa < xend && j0 + ti + e < d) ? B[xa * ldb + j0 + ti + e] : T(0);
-      }
-      if (CUBE) {
-        const T w = xa < xend ? B[xa * ldb + i] : T(0);
-        s.a[r] *= w;
       }
     }
     if (x_full && k_full) {
@@ -184,13 +153,83 @@ __global__ __launch_bounds__(4 * BK) void pr_mfma_kernel(int64_t N, int64_t d, c
         for (int e = 0; e < kV; ++e) s.b[r][e] = (x < xend && k0 + bc + e < d) ? B[x * ldb + k0 + bc + e] : T(0);
       }
     }
-  };
-  auto store_stage = [&](int buf, int, const Stage<T> &s) {
+  }
+  __device__ void store(T *As, T *Bs, const Stage<T> &s) const {
 #pragma unroll
-    for (int r = 0; r < kJRep; ++r) *reinterpret_cast<vec *>(&As[buf][(tk + kJRows * r) * kJP + ti]) = s.a[r];
+    for (int r = 0; r < kJRep; ++r) *reinterpret_cast<vec *>(&As[(tk + kJRows * r) * kJP + ti]) = s.a[r];
 #pragma unroll
-    for (int r = 0; r < 2; ++r) *reinterpret_cast<vec *>(&Bs[buf][(bk + (kXT / 2) * r) * BK + bc]) = s.b[r];
-  };
+    for (int r = 0; r < 2; ++r) *reinterpret_cast<vec *>(&Bs[(bk + (kXT / 2) * r) * BK + bc]) = s.b[r];
+  }
+};
+
+// Work items are (sample share, unit) pairs, share-major.  Workgroup ids are dealt to the eight XCDs in turn,
+// so id%8 picks the XCD and id/8 the position in that XCD's run of CONSECUTIVE items: the units of one share
+// read the same rows of B (each its own columns) and sweep them at the same pace, so on one XCD a row is
+// fetched from memory once and served to the other units by that L2.  False: this workgroup has no item.
+__device__ inline bool my_item(int64_t units, int64_t split, int64_t &share, int64_t &unit) {
+  const int64_t items = units * split, xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int64_t item = items * xcd / 8 + slot;
+  if (item >= items * (xcd + 1) / 8) return false;
+  share = uniform64(item / units);
+  unit = uniform64(item - share * units);
+  return true;
+}
+
+// ---- A2 ----------------------------------------------------------------------------------------------
+
+// Tiles with work.  With m = ceil(d/64) blocks of rows j there are ceil(m/2) blocks of 128 columns k; tile
+// (J,K) holds an element with j<=k exactly when K >= J/2 (integer division), so row block J has
+// ceil(m/2) - J/2 tiles.  Tiles are numbered densely, row block after row block, so that consecutive
+// workgroup ids (which the hardware deals out to the XCDs in turn) all carry work: numbering the whole
+// J x K rectangle and letting the empty tiles exit would leave the XCDs with very different loads,
+// because the id modulo 8 would select the column block.  (With BK = 64 the condition is K >= J: row
+// block J has m - J tiles, m(m+1)/2 in all.)
+DASTAC_HD int64_t tiles_of(int64_t m, int BK) {
+  if (BK == 64) return m * (m + 1) / 2;
+  const int64_t p = m / 2;
+  return (m & 1) ? p * p + 3 * p + 1 : p * (p + 1);
+}
+
+__device__ inline void decode_tile(int64_t d, int BK, int64_t t, int &J, int &K) {
+  const int64_t m = ceil_div(d, kBJ);
+  const int64_t nK = BK == 64 ? m : (m + 1) / 2;  // column blocks
+  int64_t Jr = 0;
+  while (t >= nK - Jr * kBJ / BK) {  // row block Jr has column blocks Jr*64/BK .. nK-1
+    t -= nK - Jr * kBJ / BK;
+    ++Jr;
+  }
+  J = (int)Jr;
+  K = (int)(Jr * kBJ / BK + t);
+}
+
+template <typename T, bool ATOMIC, int BK>
+__global__ __launch_bounds__(4 * BK) void pr2_mfma_kernel(int64_t N, int64_t d, const T *__restrict__ B, int64_t ldb,
+                                                          T *__restrict__ out, int64_t chunk, int64_t tiles,
+                                                          int64_t split) {
+  typedef Core<T> K;
+  constexpr int kXT = K::kKT, kJP = K::kColPitch, kWC = BK / 32;  // wavefronts: 2 rows of kWC
+  __shared__ __attribute__((aligned(16))) T As[2][kXT * kJP];
+  __shared__ __attribute__((aligned(16))) T Bs[2][kXT * BK];
+
+  int64_t share, unit;
+  if (!my_item(tiles, split, share, unit)) return;
+  int J, Kb;
+  decode_tile(d, BK, unit, J, Kb);
+  const int64_t xbeg = share * chunk;
+  const int64_t xend = xbeg + chunk < N ? xbeg + chunk : N;
+  if (xbeg >= xend) return;
+  const int nk = (int)ceil_div(xend - xbeg, kXT);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wr = wave / kWC, wc = wave % kWC;  // 2 x kWC wavefronts: 32 (j) x 32 (k) each
+  // A wavefront whose 32x32 sub-tile lies wholly below the diagonal (largest k < smallest j) still helps
+  // to stage the tiles but issues no matrix instructions, which leaves the SIMD's matrix pipe to the
+  // wavefronts of the other workgroups resident on it.
+  const bool live = uniform32(Kb * BK + wc * 32 + 31 >= J * kBJ + wr * 32) != 0;
+  const Tiles<T, BK> tiles_io(B, ldb, d, (int64_t)J * kBJ, (int64_t)Kb * BK, tid);
+
+  auto load_stage = [&](int kt, Stage<T> &s) { tiles_io.load(xbeg + (int64_t)kt * kXT, xend, s); };
+  auto store_stage = [&](int buf, int, const Stage<T> &s) { tiles_io.store(As[buf], Bs[buf], s); };
   auto read_ops = [&](int buf, int, int t, typename K::Ops &o) {
     K::read_a_t(&As[buf][wr * 32], kJP, lane, t, o);
     K::read_b(&Bs[buf][wc * 32], BK, lane, t, o);
@@ -200,12 +239,10 @@ __global__ __launch_bounds__(4 * BK) void pr_mfma_kernel(int64_t N, int64_t d, c
   K::clear(acc);
   sweep_steps<T, Stage<T>>(0, nk, acc, load_stage, store_stage, read_ops, live);
 
-  // Rows are j, columns are k; both relative to the slice's first column i.
-  T *slice = out + (CUBE ? tet_slice_start(d, i) : 0);
   K::for_each(acc, lane, [&](int r, int c, T v) {
-    const int64_t jr = (int64_t)J * kBJ + wr * 32 + r, kr = (int64_t)Kb * BK + wc * 32 + c;
-    if (jr <= kr && kr < q) {
-      T *p = slice + tri_offset(q, jr, kr);
+    const int64_t j = (int64_t)J * kBJ + wr * 32 + r, k = (int64_t)Kb * BK + wc * 32 + c;
+    if (j <= k && k < d) {
+      T *p = out + tri_offset(d, j, k);
       if (ATOMIC)
         unsafeAtomicAdd(p, v);
       else
@@ -214,10 +251,137 @@ __global__ __launch_bounds__(4 * BK) void pr_mfma_kernel(int64_t N, int64_t d, c
   });
 }
 
+// ---- A3 ----------------------------------------------------------------------------------------------
+
+// Units of A3: tile (J,K) of the (j,k) plane -- the same grid for every slice -- times a group of NI
+// consecutive slices.  Row block J serves the slices 0 .. min(64(J+1), d)-1 (a slice needs i <= j), in
+// ceil(that / NI) groups, and has as many tiles as in A2; units are numbered densely: row block after row
+// block, slice group after slice group, column block after column block.
+DASTAC_HD int64_t units_of_row_block(int64_t d, int BK, int NI, int64_t J) {
+  const int64_t m = ceil_div(d, kBJ), nK = BK == 64 ? m : (m + 1) / 2;
+  const int64_t slices = kBJ * (J + 1) < d ? kBJ * (J + 1) : d;
+  return (nK - J * kBJ / BK) * ceil_div(slices, NI);
+}
+
+DASTAC_HD int64_t total_units(int64_t d, int BK, int NI) {
+  int64_t total = 0;
+  for (int64_t J = 0; J < ceil_div(d, kBJ); ++J) total += units_of_row_block(d, BK, NI, J);
+  return total;
+}
+
+// One operand group of a step for NI slices: the first operand scaled by each slice's weights, the second shared.
+template <typename T>
+struct Ops3 {
+  static constexpr int kNA = (int)(sizeof(typename Core<T>::Ops) / sizeof(T)) / 2;
+  T a[Slices<T>::kNI][kNA];
+  T b[kNA];
+};
+
+// (Three wavefronts per SIMD in fp64, where the register allocator reaches that with a few spilled dwords and the
+// third wavefront gains 15 %; in fp32 the accumulators of four slices leave room for two.)
+template <typename T, bool ATOMIC, int BK>
+__global__ __launch_bounds__(4 * BK) __attribute__((amdgpu_waves_per_eu(sizeof(T) == 8 ? 3 : 2, sizeof(T) == 8 ? 3 : 2)))
+void pr3_mfma_kernel(int64_t N, int64_t d, const T *__restrict__ B, int64_t ldb,
+                                                          T *__restrict__ out, int64_t chunk, int64_t units,
+                                                          int64_t split) {
+  typedef Core<T> K;
+  constexpr int kXT = K::kKT, kV = K::kVec, kJP = K::kColPitch, kWC = BK / 32, kNI = Slices<T>::kNI;
+  constexpr int kWThreads = kXT * (kNI / kV);  // threads that stage one 16-byte piece of the weights each
+  static_assert(kNI % kV == 0 && 32 % kNI == 0, "slice groups are whole pieces and never straddle a sub-tile's first row");
+  __shared__ __attribute__((aligned(16))) T As[2][kXT * kJP];
+  __shared__ __attribute__((aligned(16))) T Bs[2][kXT * BK];
+  __shared__ __attribute__((aligned(16))) T Ws[2][kNI * kXT];  // [slice][sample]
+
+  int64_t share, unit;
+  if (!my_item(units, split, share, unit)) return;
+  int64_t J = 0;
+  while (unit >= units_of_row_block(d, BK, kNI, J)) unit -= units_of_row_block(d, BK, kNI, J), ++J;
+  const int64_t m = ceil_div(d, kBJ), nK = BK == 64 ? m : (m + 1) / 2, firstK = J * kBJ / BK;
+  const int64_t i0 = kNI * (unit / (nK - firstK));  // first slice of the group
+  const int64_t Kb = firstK + unit % (nK - firstK);
+  const int64_t xbeg = share * chunk;
+  const int64_t xend = xbeg + chunk < N ? xbeg + chunk : N;
+  if (xbeg >= xend) return;
+  const int nk = (int)ceil_div(xend - xbeg, kXT);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wr = wave / kWC, wc = wave % kWC;  // 2 x kWC wavefronts: 32 (j) x 32 (k) each
+  const int64_t jw = J * kBJ + wr * 32, kw = Kb * BK + wc * 32;  // first row and column of this wavefront's sub-tile
+  // Nothing to compute where the sub-tile lies wholly below the diagonal (largest k < smallest j) or wholly
+  // above the group's slices (largest j < i0; i0 and the sub-tile's first row are both multiples of kNI, so
+  // the group's slices are then all above it or all not).
+  const bool live = uniform32((kw + 31 >= jw && jw + 31 >= i0) ? 1 : 0) != 0;
+  const Tiles<T, BK> tiles_io(B, ldb, d, J * kBJ, Kb * BK, tid);
+  const int wx = tid % kXT, wp = tid / kXT;  // weights: sample wx, piece wp (threads below kWThreads)
+
+  auto load_stage = [&](int kt, Stage<T> &s) {
+    const int64_t x0 = xbeg + (int64_t)kt * kXT;
+    tiles_io.load(x0, xend, s);
+    if (tid < kWThreads) {
+      const int64_t xw = x0 + wx, iw = i0 + wp * kV;
+#pragma unroll
+      for (int e = 0; e < kV; ++e) s.w[e] = (xw < xend && iw + e < d) ? B[xw * ldb + iw + e] : T(0);
+    }
+  };
+  auto store_stage = [&](int buf, int, const Stage<T> &s) {
+    tiles_io.store(As[buf], Bs[buf], s);
+    if (tid < kWThreads) {
+#pragma unroll
+      for (int e = 0; e < kV; ++e) Ws[buf][(wp * kV + e) * kXT + wx] = s.w[e];
+    }
+  };
+  auto read_ops = [&](int buf, int, int t, Ops3<T> &o) {
+    typename K::Ops r;
+    K::read_a_t(&As[buf][wr * 32], kJP, lane, t, r);
+    K::read_b(&Bs[buf][wc * 32], BK, lane, t, r);
+    Slices<T>::scale(r, Ws[buf], lane, t, o);
+  };
+  typename K::Acc acc[kNI];
+#pragma unroll
+  for (int ii = 0; ii < kNI; ++ii) K::clear(acc[ii]);
+  auto mma = [&](const Ops3<T> &o) {
+#pragma unroll
+    for (int ii = 0; ii < kNI; ++ii) {
+      typename K::Ops r;
+#pragma unroll
+      for (int q = 0; q < Ops3<T>::kNA; ++q) r.a[q] = o.a[ii][q], r.b[q] = o.b[q];
+      K::mma(r, acc[ii]);
+    }
+  };
+  sweep_groups<Ops3<T>, Stage<T>>(0, nk, load_stage, store_stage, read_ops, mma, live);
+  if (!live) return;
+
+#pragma unroll
+  for (int ii = 0; ii < kNI; ++ii) {
+    const int64_t i = i0 + ii, q = d - i;  // slice and the order of its triangle
+    if (i >= d) break;
+    T *slice = out + tet_slice_start(d, i);
+    K::for_each(acc[ii], lane, [&](int r, int c, T v) {
+      const int64_t j = jw + r, k = kw + c;
+      if (i <= j && j <= k && k < d) {
+        T *p = slice + tri_offset(q, j - i, k - i);
+        if (ATOMIC)
+          unsafeAtomicAdd(p, v);
+        else
+          *p = v;
+      }
+    });
+  }
+}
+
 template <typename T>
 __global__ void fill_zero_kernel(T *__restrict__ y, int64_t count) {
   for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < count; t += (int64_t)gridDim.x * blockDim.x)
     y[t] = T(0);
+}
+
+template <typename T, bool CUBE, bool ATOMIC, int BK>
+void launch(unsigned grid, hipStream_t st, int64_t N, int64_t d, const T *B, int64_t ldb, T *out, int64_t chunk,
+            int64_t units, int64_t split) {
+  if (CUBE)
+    pr3_mfma_kernel<T, ATOMIC, BK><<<grid, 4 * BK, 0, st>>>(N, d, B, ldb, out, chunk, units, split);
+  else
+    pr2_mfma_kernel<T, ATOMIC, BK><<<grid, 4 * BK, 0, st>>>(N, d, B, ldb, out, chunk, units, split);
 }
 
 template <typename T, bool CUBE, int BK>
@@ -232,19 +396,20 @@ int run(int64_t N, int64_t d, const T *B, int64_t ldb, T *out, void *stream) {
   if (overlaps(out, count * kB, B, view_bytes(N, ldb, d, kB))) return DASTAC_EALIAS;
   hipStream_t st = (hipStream_t)stream;
 
-  const int64_t tiles = total_tiles(d, CUBE, BK);
-  if (tiles > 0x7fffffff) return DASTAC_EOVERFLOW;
-  // Split the samples when the tiles alone cannot fill the chip.  All workgroups cost the same, so the
+  const int64_t units = CUBE ? total_units(d, BK, Slices<T>::kNI) : tiles_of(ceil_div(d, kBJ), BK);
+  if (units > 0x7fffffff) return DASTAC_EOVERFLOW;
+  // Split the samples when the units alone cannot fill the chip.  All workgroups cost the same, so the
   // launch runs in rounds of `slots` resident workgroups: take the smallest split that fills its last
   // round to 90 %, or else the best one found; every share is a multiple of a step and at least 8 steps.
   int64_t split = 1, chunk = kXT;
   if (N > 0) {
-    const int64_t slots = resident_blocks(pr_mfma_kernel<T, CUBE, true, BK>, kBlock);
+    const int64_t slots = CUBE ? resident_blocks(pr3_mfma_kernel<T, true, BK>, kBlock)
+                               : resident_blocks(pr2_mfma_kernel<T, true, BK>, kBlock);
     if (slots <= 0) return DASTAC_EHIP;
     const int64_t max_split = N / (8 * kXT) > 1 ? N / (8 * kXT) : 1;
     double best = -1.0;
     for (int64_t s = 1; s <= max_split && s <= 4096; ++s) {
-      const int64_t blocks = tiles * s, rounds = ceil_div(blocks, slots);
+      const int64_t blocks = units * s, rounds = ceil_div(blocks, slots);
       const double fill = (double)blocks / (double)(rounds * slots);
       if (fill > best + 1e-9) best = fill, split = s;
       if (fill >= 0.9 || blocks >= 16 * slots) {
@@ -256,7 +421,7 @@ int run(int64_t N, int64_t d, const T *B, int64_t ldb, T *out, void *stream) {
     split = ceil_div(N, chunk);
   }
   // one-dimensional grid: every XCD gets ceil(items / 8) ids, of which it uses its share of the items
-  const int64_t per_xcd = ceil_div(tiles * split, 8);
+  const int64_t per_xcd = ceil_div(units * split, 8);
   if (8 * per_xcd > 0x7fffffff) return DASTAC_EOVERFLOW;
 
   const bool atomic = split > 1;
@@ -268,9 +433,9 @@ int run(int64_t N, int64_t d, const T *B, int64_t ldb, T *out, void *stream) {
   }
   const unsigned grid = (unsigned)(8 * per_xcd);
   if (atomic)
-    pr_mfma_kernel<T, CUBE, true, BK><<<grid, kBlock, 0, st>>>(N, d, B, ldb, out, chunk, tiles, split);
+    launch<T, CUBE, true, BK>(grid, st, N, d, B, ldb, out, chunk, units, split);
   else
-    pr_mfma_kernel<T, CUBE, false, BK><<<grid, kBlock, 0, st>>>(N, d, B, ldb, out, chunk, tiles, split);
+    launch<T, CUBE, false, BK>(grid, st, N, d, B, ldb, out, chunk, units, split);
   return launch_status();
 }
 
