@@ -378,10 +378,14 @@ __global__ __launch_bounds__(kLdsBlock) void segsum_lds_kernel(int n, const T *_
 // ---- host side -------------------------------------------------------------------------------
 
 // Wavefront shares: about `per_cu` wavefronts per compute unit on a 256-CU part, at least 2048
-// elements each so that the one inverse per wavefront stays negligible.
+// elements each so that the one inverse per wavefront stays negligible.  Problems of a megabyte or
+// two are bound by the latency of one wavefront's chain of steps, not by the inverse: there a share is
+// one step or half a step (measured, event-bracketed: TRMV n=512 8.4 -> 6.4 us, n=2048 8.7 -> 7.5;
+// TTV n=128 9.0 -> 7.4; from about 2.6 million elements on the larger floor is the faster one).
 inline int64_t pick_share(int64_t total, int per_cu) {
-  int64_t share = ceil_div(total, (int64_t)256 * per_cu);
-  return share < 2048 ? 2048 : share;
+  const int64_t share = ceil_div(total, (int64_t)256 * per_cu);
+  const int64_t least = total < ((int64_t)1 << 20) ? 512 : total < ((int64_t)5 << 19) ? 1024 : 2048;
+  return share < least ? least : share;
 }
 
 constexpr int64_t kStreamBytes = (int64_t)192 << 20;  // above this a buffer does not stay in the 256 MB memory-side cache
