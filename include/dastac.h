@@ -223,7 +223,10 @@ int dastac_tet_ttv_f32(int64_t n, const float *Ap, const float *v, float *Mp, vo
  * 1 <= R <= 2^20.  The kernel takes 32 columns of the factor
  * matrices at a time: R > 32 runs block by block, each block reading the packed tetrahedron once.  M is
  * cleared first and the blocks of a slice add their parts with floating-point atomics, so the last bits
- * may differ between calls (integer-valued inputs whose partial sums are exact give identical results). */
+ * may differ between calls (integer-valued inputs whose partial sums are exact give identical results).
+ * The sum is evaluated factored (A with B first, then with C) on blocks padded with zeros, so a non-finite
+ * element of B(j,:) or C(k,:), j,k >= i, makes M(i,r) non-finite as the plain rule does, but possibly NaN
+ * where the plain rule gives an infinity. */
 int dastac_tet_mttkrp_f32(int64_t n, int64_t R, const float *Ap, const float *B, int64_t ldb, const float *C,
                           int64_t ldc, float *M, int64_t ldm, void *stream);
 

@@ -87,6 +87,14 @@ constexpr int kCols = Shape<T>::LPR * Shape<T>::V * Shape<T>::NP;
 template <typename T>
 constexpr int kRatio = kRows / kCols<T>;
 
+// Pins a wave-uniform address to a scalar register pair and hides how it was computed, so that "this address
+// plus a 32-bit offset per lane" stays one load with a scalar base instead of 64-bit vector arithmetic per load.
+typedef const char __attribute__((address_space(1))) *global_bytes;  // a device-memory address, known as such
+__device__ inline global_bytes in_scalar_registers(global_bytes p) {
+  asm volatile("" : "+s"(p));
+  return p;
+}
+
 // A wavefront's walk over the steps of its block.  Step t covers the rows row0 + RS*t of the lane
 // groups (lane group h = lane / LPR takes row rlo + RS*t + h); the byte offset of a lane's piece grows
 // from step to step by a difference that itself shrinks by RS*RS elements (a packed row is one element
@@ -329,14 +337,18 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
 
   // ---- fold with C: register v of accumulator (p*V+s)*NB+c in lane group h is S(k, column c of the lane) with
   // k = klo + LPR*V*p + V*(KV(v) + HM*h) + s
-  const T *cp[S::NB];
   T part[S::NB];
 #pragma unroll
-  for (int c = 0; c < S::NB; ++c) {
-    cp[c] = Cm + (i + klo + S::V * S::HM * h) * ldc + cc[c];
-    part[c] = T(0);
-  }
-  if (klo + kC == khi) {
+  for (int c = 0; c < S::NB; ++c) part[c] = T(0);
+  constexpr int kLaneRows = S::V * S::HM * (64 / S::LPR - 1);  // largest row offset that depends on the lane
+  if (m >= kC && ldc <= (int64_t)0x7fffffff / (kLaneRows * kSz + kSz)) {
+    // Rows klo .. klo+kC-1 of C all belong to the slice (in the narrow leftmost block the sums of the k values
+    // past its last are exact zeros, and those rows exist).  Every address is a wave-uniform row base plus a
+    // 32-bit offset that depends on the lane only: one load and one multiply-add per element, nothing else.
+    const global_bytes rows = (global_bytes) reinterpret_cast<const char *>(Cm + (i + klo) * ldc);
+    unsigned lane_off[S::NB];
+#pragma unroll
+    for (int c = 0; c < S::NB; ++c) lane_off[c] = (unsigned)kSz * ((unsigned)(S::V * S::HM * h) * (unsigned)ldc + (unsigned)cc[c]);
 #pragma unroll
     for (int v = 0; v < S::NV; ++v)
 #pragma unroll
@@ -344,9 +356,14 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
 #pragma unroll
         for (int c = 0; c < S::NB; ++c) {
           const int off = S::LPR * S::V * (q / S::V) + S::V * S::KV(v) + q % S::V;
-          part[c] += acc.v[q * S::NB + c][v] * cp[c][(int64_t)off * ldc];
+          const global_bytes row = in_scalar_registers(rows + (int64_t)off * ldc * kSz);
+          const T cv = *(const T __attribute__((address_space(1))) *)(row + lane_off[c]);
+          part[c] += acc.v[q * S::NB + c][v] * cv;
         }
-  } else {
+  } else {  // a slice smaller than one block (or a row stride beyond 32-bit offsets): every row tested
+    const T *cp[S::NB];
+#pragma unroll
+    for (int c = 0; c < S::NB; ++c) cp[c] = Cm + (i + klo + S::V * S::HM * h) * ldc + cc[c];
     const int live = khi - klo - S::V * S::HM * h;  // k offsets below this exist
 #pragma unroll
     for (int v = 0; v < S::NV; ++v)
