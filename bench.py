@@ -10,7 +10,8 @@ one stream through the C ABI.  `value` is the useful GFLOP/s of the whole step
 form the kernel executes).  Inside the timed steps the kernel that dominates the step is
 bracketed by HIP events on the launch stream (`roofline`); a second pass of the same steps
 brackets every launch, so each kernel's own duration, GFLOP/s, GB/s and roofline fraction
-are reported too (an event pair adds a few microseconds of dispatch gap).  The CPU oracle is
+are reported too (an event pair adds a few microseconds of dispatch gap; `ms_in_step` is the
+kernel's share of an uninterrupted step instead, the difference of steps with and without it).  The CPU oracle is
 timed on a bounded sample of the same inputs as a baseline (not a target), and what it computes is
 compared with what the timed launches left in their output buffers: the run fails (exit status 1)
 when an element is further than 1e-4 * sum|products| from the oracle.
@@ -173,6 +174,27 @@ def main() -> int:
     # what the launches left in their output buffers, for the comparison with the oracle further down
     produced = {k: g[k][-1].cpu().numpy() for k in order}
 
+    # third measure, without any event between the launches of a step: what a kernel adds to the step, as the
+    # difference between steps with and without it (an event pair costs a launch its 3-6 us of dispatch gap, a
+    # twentieth of the band kernel's time and a fifth of TTV's).  Each difference is taken between two runs that
+    # follow each other; it is noise for a kernel of a few microseconds.
+    def plain_steps(skip, count):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(count):
+            for k in order:
+                if k != skip:
+                    launch[k]()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / count
+
+    loo_steps = max(args.steps, 50)
+    plain_steps(None, 5)
+    in_step = {}
+    for k in order:
+        in_step[k] = float(np.median([plain_steps(None, loo_steps) - plain_steps(k, loo_steps) for _ in range(3)]))
+
     kernels = {}
     for q, k in enumerate(order):
         samples = [a.elapsed_time(b) for a, b in dev_ev] if k == dom else per_kernel[q]
@@ -189,6 +211,11 @@ def main() -> int:
         # measured bytes per launch past the L2 (committed counter runs; null once the kernel source changed)
         ent["traffic"] = measured_traffic(k)
         ent["traffic_over_algorithmic"] = ent["traffic"] / by if ent["traffic"] else None
+        # inside an uninterrupted step (difference of steps with and without this kernel)
+        ent["ms_in_step"] = in_step[k]
+        if in_step[k] > 0:
+            ent["frac_in_step"] = (by / in_step[k] / 1e6 / HBM_PEAK_GBPS if bound[k] == "hbm"
+                                   else fl / in_step[k] / 1e9 / MFMA_F32_PEAK_TFLOPS)
         kernels[k] = ent
     kernels["mttkrp"]["gflops_paper_convention"] = acct["mttkrp"]["flops_paper_convention"] / kernels["mttkrp"]["ms"] / 1e6
 
