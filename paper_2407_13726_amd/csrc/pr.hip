@@ -20,7 +20,7 @@
 // sub-tile lies below it skip their matrix instructions, and only j<=k is stored.
 //
 // For A3 the tiles are cut on a grid that is the same for every slice, and a workgroup takes its tile
-// for several consecutive slices i at once (four in fp32, two in fp64): the two staged tiles are shared
+// for several consecutive slices i at once (two or four in fp32, two in fp64): the two staged tiles are shared
 // by those slices, whose weights B(x,i) are staged beside them and multiplied onto the first operand in
 // registers, one accumulator per slice.  The global loads, LDS traffic and barriers of a step are thus
 // spent once per 64 (fp32) matrix instructions of a wavefront instead of once per 16.  A tile serves
@@ -43,15 +43,15 @@ constexpr int64_t kMaxN = (int64_t)1 << 31;
 // Up to these d the 64 x 64 tile is used: it wastes less on the diagonal and leaves more workgroups per CU,
 // which outweighs its lower operand reuse while diagonal tiles are a large share of all tiles.
 constexpr int64_t kNarrowMaxD2 = 768, kNarrowMaxD3 = 2048;
+constexpr int64_t kFewSlicesMaxD3 = 768;  // fp32 A3: two slices per workgroup up to here, four beyond
 
 // Slices of A3 that share a workgroup's staged tiles, and how their weights reach the first operand.
 template <typename T>
 struct Slices;
 template <>
 struct Slices<float> {
-  static constexpr int kNI = 4;
   // group t of a step: this lane's samples are 8t + 4*(lane/32) + q, q < 4; ws is [slice][sample]
-  template <typename Ops3>
+  template <int kNI, typename Ops3>
   __device__ static void scale(const Core<float>::Ops &r, const float *ws, int lane, int t, Ops3 &o) {
 #pragma unroll
     for (int ii = 0; ii < kNI; ++ii) {
@@ -65,9 +65,8 @@ struct Slices<float> {
 };
 template <>
 struct Slices<double> {
-  static constexpr int kNI = 2;
   // group t of a step: this lane's sample is 4t + lane/16
-  template <typename Ops3>
+  template <int kNI, typename Ops3>
   __device__ static void scale(const Core<double>::Ops &r, const double *ws, int lane, int t, Ops3 &o) {
 #pragma unroll
     for (int ii = 0; ii < kNI; ++ii) {
@@ -84,7 +83,7 @@ template <typename T>
 struct Stage {
   typename Core<T>::vec a[2];  // j tile: one or two sample rows, one 16-byte piece of columns each
   typename Core<T>::vec b[2];  // k tile: sample rows bk and bk + kXT/2, one 16-byte piece of columns each
-  typename Core<T>::vec w;     // A3: one piece of the weights (first threads only)
+  T w;                         // A3: one weight (first threads only)
 };
 
 // Staging of the two column tiles of B, the same for both kernels: columns j0.. (64 of them) and k0.. (BK),
@@ -270,24 +269,26 @@ DASTAC_HD int64_t total_units(int64_t d, int BK, int NI) {
 }
 
 // One operand group of a step for NI slices: the first operand scaled by each slice's weights, the second shared.
-template <typename T>
+template <typename T, int NI>
 struct Ops3 {
   static constexpr int kNA = (int)(sizeof(typename Core<T>::Ops) / sizeof(T)) / 2;
-  T a[Slices<T>::kNI][kNA];
+  T a[NI][kNA];
   T b[kNA];
 };
 
-// (Three wavefronts per SIMD in fp64, where the register allocator reaches that with a few spilled dwords and the
-// third wavefront gains 15 %; in fp32 the accumulators of four slices leave room for two.)
-template <typename T, bool ATOMIC, int BK>
-__global__ __launch_bounds__(4 * BK) __attribute__((amdgpu_waves_per_eu(sizeof(T) == 8 ? 3 : 2, sizeof(T) == 8 ? 3 : 2)))
+// NI slices per workgroup: four in fp32 (two up to d = 768, where a third wavefront per SIMD is worth more than the
+// reuse: d=256 61 -> 63 TFLOP/s, d=512 82 -> 86, d=1024 104 -> 102), two in fp64.  Three wavefronts per SIMD with two
+// slices (in fp64 the register allocator reaches that with a few spilled dwords and the third wavefront gains 15 %);
+// the accumulators of four slices leave room for two.
+template <typename T, bool ATOMIC, int BK, int NI>
+__global__ __launch_bounds__(4 * BK) __attribute__((amdgpu_waves_per_eu(NI == 2 ? 3 : 2, NI == 2 ? 3 : 2)))
 void pr3_mfma_kernel(int64_t N, int64_t d, const T *__restrict__ B, int64_t ldb,
                                                           T *__restrict__ out, int64_t chunk, int64_t units,
                                                           int64_t split) {
   typedef Core<T> K;
-  constexpr int kXT = K::kKT, kV = K::kVec, kJP = K::kColPitch, kWC = BK / 32, kNI = Slices<T>::kNI;
-  constexpr int kWThreads = kXT * (kNI / kV);  // threads that stage one 16-byte piece of the weights each
-  static_assert(kNI % kV == 0 && 32 % kNI == 0, "slice groups are whole pieces and never straddle a sub-tile's first row");
+  constexpr int kXT = K::kKT, kJP = K::kColPitch, kWC = BK / 32, kNI = NI;
+  constexpr int kWThreads = kXT * kNI;  // threads that stage one weight each
+  static_assert(32 % kNI == 0 && kWThreads <= 4 * BK, "slice groups never straddle a sub-tile's first row");
   __shared__ __attribute__((aligned(16))) T As[2][kXT * kJP];
   __shared__ __attribute__((aligned(16))) T Bs[2][kXT * BK];
   __shared__ __attribute__((aligned(16))) T Ws[2][kNI * kXT];  // [slice][sample]
@@ -312,43 +313,39 @@ void pr3_mfma_kernel(int64_t N, int64_t d, const T *__restrict__ B, int64_t ldb,
   // the group's slices are then all above it or all not).
   const bool live = uniform32((kw + 31 >= jw && jw + 31 >= i0) ? 1 : 0) != 0;
   const Tiles<T, BK> tiles_io(B, ldb, d, J * kBJ, Kb * BK, tid);
-  const int wx = tid % kXT, wp = tid / kXT;  // weights: sample wx, piece wp (threads below kWThreads)
+  const int wx = tid % kXT, wi = tid / kXT;  // weights: sample wx of slice i0 + wi (threads below kWThreads)
 
   auto load_stage = [&](int kt, Stage<T> &s) {
     const int64_t x0 = xbeg + (int64_t)kt * kXT;
     tiles_io.load(x0, xend, s);
     if (tid < kWThreads) {
-      const int64_t xw = x0 + wx, iw = i0 + wp * kV;
-#pragma unroll
-      for (int e = 0; e < kV; ++e) s.w[e] = (xw < xend && iw + e < d) ? B[xw * ldb + iw + e] : T(0);
+      const int64_t xw = x0 + wx, iw = i0 + wi;
+      s.w = (xw < xend && iw < d) ? B[xw * ldb + iw] : T(0);
     }
   };
   auto store_stage = [&](int buf, int, const Stage<T> &s) {
     tiles_io.store(As[buf], Bs[buf], s);
-    if (tid < kWThreads) {
-#pragma unroll
-      for (int e = 0; e < kV; ++e) Ws[buf][(wp * kV + e) * kXT + wx] = s.w[e];
-    }
+    if (tid < kWThreads) Ws[buf][wi * kXT + wx] = s.w;
   };
-  auto read_ops = [&](int buf, int, int t, Ops3<T> &o) {
+  auto read_ops = [&](int buf, int, int t, Ops3<T, NI> &o) {
     typename K::Ops r;
     K::read_a_t(&As[buf][wr * 32], kJP, lane, t, r);
     K::read_b(&Bs[buf][wc * 32], BK, lane, t, r);
-    Slices<T>::scale(r, Ws[buf], lane, t, o);
+    Slices<T>::template scale<NI>(r, Ws[buf], lane, t, o);
   };
   typename K::Acc acc[kNI];
 #pragma unroll
   for (int ii = 0; ii < kNI; ++ii) K::clear(acc[ii]);
-  auto mma = [&](const Ops3<T> &o) {
+  auto mma = [&](const Ops3<T, NI> &o) {
 #pragma unroll
     for (int ii = 0; ii < kNI; ++ii) {
       typename K::Ops r;
 #pragma unroll
-      for (int q = 0; q < Ops3<T>::kNA; ++q) r.a[q] = o.a[ii][q], r.b[q] = o.b[q];
+      for (int q = 0; q < Ops3<T, NI>::kNA; ++q) r.a[q] = o.a[ii][q], r.b[q] = o.b[q];
       K::mma(r, acc[ii]);
     }
   };
-  sweep_groups<Ops3<T>, Stage<T>>(0, nk, load_stage, store_stage, read_ops, mma, live);
+  sweep_groups<Ops3<T, NI>, Stage<T>>(0, nk, load_stage, store_stage, read_ops, mma, live);
   if (!live) return;
 
 #pragma unroll
@@ -375,16 +372,17 @@ __global__ void fill_zero_kernel(T *__restrict__ y, int64_t count) {
     y[t] = T(0);
 }
 
-template <typename T, bool CUBE, bool ATOMIC, int BK>
+template <typename T, bool CUBE, bool ATOMIC, int BK, int NI>
 void launch(unsigned grid, hipStream_t st, int64_t N, int64_t d, const T *B, int64_t ldb, T *out, int64_t chunk,
             int64_t units, int64_t split) {
   if (CUBE)
-    pr3_mfma_kernel<T, ATOMIC, BK><<<grid, 4 * BK, 0, st>>>(N, d, B, ldb, out, chunk, units, split);
+    pr3_mfma_kernel<T, ATOMIC, BK, NI><<<grid, 4 * BK, 0, st>>>(N, d, B, ldb, out, chunk, units, split);
   else
     pr2_mfma_kernel<T, ATOMIC, BK><<<grid, 4 * BK, 0, st>>>(N, d, B, ldb, out, chunk, units, split);
 }
 
-template <typename T, bool CUBE, int BK>
+// NI: slices per workgroup of the A3 kernel (not used for A2)
+template <typename T, bool CUBE, int BK, int NI = 2>
 int run(int64_t N, int64_t d, const T *B, int64_t ldb, T *out, void *stream) {
   constexpr int kBlock = 4 * BK, kXT = Core<T>::kKT;
   constexpr int64_t kB = (int64_t)sizeof(T);
@@ -396,14 +394,14 @@ int run(int64_t N, int64_t d, const T *B, int64_t ldb, T *out, void *stream) {
   if (overlaps(out, count * kB, B, view_bytes(N, ldb, d, kB))) return DASTAC_EALIAS;
   hipStream_t st = (hipStream_t)stream;
 
-  const int64_t units = CUBE ? total_units(d, BK, Slices<T>::kNI) : tiles_of(ceil_div(d, kBJ), BK);
+  const int64_t units = CUBE ? total_units(d, BK, NI) : tiles_of(ceil_div(d, kBJ), BK);
   if (units > 0x7fffffff) return DASTAC_EOVERFLOW;
   // Split the samples when the units alone cannot fill the chip.  All workgroups cost the same, so the
   // launch runs in rounds of `slots` resident workgroups: take the smallest split that fills its last
   // round to 90 %, or else the best one found; every share is a multiple of a step and at least 8 steps.
   int64_t split = 1, chunk = kXT;
   if (N > 0) {
-    const int64_t slots = CUBE ? resident_blocks(pr3_mfma_kernel<T, true, BK>, kBlock)
+    const int64_t slots = CUBE ? resident_blocks(pr3_mfma_kernel<T, true, BK, NI>, kBlock)
                                : resident_blocks(pr2_mfma_kernel<T, true, BK>, kBlock);
     if (slots <= 0) return DASTAC_EHIP;
     const int64_t max_split = N / (8 * kXT) > 1 ? N / (8 * kXT) : 1;
@@ -433,9 +431,9 @@ int run(int64_t N, int64_t d, const T *B, int64_t ldb, T *out, void *stream) {
   }
   const unsigned grid = (unsigned)(8 * per_xcd);
   if (atomic)
-    launch<T, CUBE, true, BK>(grid, st, N, d, B, ldb, out, chunk, units, split);
+    launch<T, CUBE, true, BK, NI>(grid, st, N, d, B, ldb, out, chunk, units, split);
   else
-    launch<T, CUBE, false, BK>(grid, st, N, d, B, ldb, out, chunk, units, split);
+    launch<T, CUBE, false, BK, NI>(grid, st, N, d, B, ldb, out, chunk, units, split);
   return launch_status();
 }
 
@@ -449,8 +447,9 @@ int dastac_pr_a2_f32(int64_t N, int64_t d, const float *B, int64_t ldb, float *A
 }
 
 int dastac_pr_a3_f32(int64_t N, int64_t d, const float *B, int64_t ldb, float *A3p, void *stream) {
-  return d <= kNarrowMaxD3 ? run<float, true, 64>(N, d, B, ldb, A3p, stream)
-                           : run<float, true, 128>(N, d, B, ldb, A3p, stream);
+  return d <= kFewSlicesMaxD3 ? run<float, true, 64, 2>(N, d, B, ldb, A3p, stream)
+         : d <= kNarrowMaxD3  ? run<float, true, 64, 4>(N, d, B, ldb, A3p, stream)
+                              : run<float, true, 128, 4>(N, d, B, ldb, A3p, stream);
 }
 
 // Double precision (the paper's element type): the same kernel on the fp64 matrix cores.
@@ -460,8 +459,8 @@ int dastac_pr_a2_f64(int64_t N, int64_t d, const double *B, int64_t ldb, double 
 }
 
 int dastac_pr_a3_f64(int64_t N, int64_t d, const double *B, int64_t ldb, double *A3p, void *stream) {
-  return d <= kNarrowMaxD3 ? run<double, true, 64>(N, d, B, ldb, A3p, stream)
-                           : run<double, true, 128>(N, d, B, ldb, A3p, stream);
+  return d <= kNarrowMaxD3 ? run<double, true, 64, 2>(N, d, B, ldb, A3p, stream)
+                           : run<double, true, 128, 2>(N, d, B, ldb, A3p, stream);
 }
 
 }  // extern "C"
