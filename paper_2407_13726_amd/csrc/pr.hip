@@ -282,9 +282,8 @@ struct Ops3 {
 // the accumulators of four slices leave room for two.
 template <typename T, bool ATOMIC, int BK, int NI>
 __global__ __launch_bounds__(4 * BK) __attribute__((amdgpu_waves_per_eu(NI == 2 ? 3 : 2, NI == 2 ? 3 : 2)))
-void pr3_mfma_kernel(int64_t N, int64_t d, const T *__restrict__ B, int64_t ldb,
-                                                          T *__restrict__ out, int64_t chunk, int64_t units,
-                                                          int64_t split) {
+void pr3_mfma_kernel(int64_t N, int64_t d, const T *__restrict__ B, int64_t ldb, T *__restrict__ out, int64_t chunk,
+                     int64_t units, int64_t split) {
   typedef Core<T> K;
   constexpr int kXT = K::kKT, kJP = K::kColPitch, kWC = BK / 32, kNI = NI;
   constexpr int kWThreads = kXT * kNI;  // threads that stage one weight each
