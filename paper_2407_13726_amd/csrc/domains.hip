@@ -56,6 +56,39 @@ __global__ __launch_bounds__(kBlock) void sband_kernel(int64_t n, int w, int64_t
   __builtin_nontemporal_store(acc, y + i);
 }
 
+// The printed rule (w = 1): three streams of D and three windows of x carry too few bytes per lane when a lane
+// takes one row, so a lane takes the 16 bytes of consecutive rows (four in single, two in double precision) of
+// every stream at once.  Groups of rows whose windows leave the matrix take the tested path row by row.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void sband_w1_kernel(int64_t n, int64_t s, const T *__restrict__ D,
+                                                          const T *__restrict__ x, T *__restrict__ y) {
+  constexpr int V = 16 / (int)sizeof(T);
+  typedef T vecu __attribute__((ext_vector_type(V), aligned(sizeof(T))));  // rows start at any element
+  const int64_t i = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * V;
+  if (i >= n) return;
+  if (i >= s && i + V - 1 + s < n) {  // interior rows: every column exists
+    const vecu d0 = __builtin_nontemporal_load(reinterpret_cast<const vecu *>(D + i));
+    const vecu d1 = __builtin_nontemporal_load(reinterpret_cast<const vecu *>(D + n + i));
+    const vecu d2 = __builtin_nontemporal_load(reinterpret_cast<const vecu *>(D + 2 * n + i));
+    const vecu x0 = *reinterpret_cast<const vecu *>(x + i - s);
+    const vecu x1 = *reinterpret_cast<const vecu *>(x + i);
+    const vecu x2 = *reinterpret_cast<const vecu *>(x + i + s);
+    vecu acc;
+#pragma unroll
+    for (int v = 0; v < V; ++v) acc[v] = ((T(0) + d0[v] * x0[v]) + d1[v] * x1[v]) + d2[v] * x2[v];  // from +0, like a running sum
+    __builtin_nontemporal_store(acc, reinterpret_cast<vecu *>(y + i));
+  } else {
+    for (int64_t r = i; r < i + V && r < n; ++r) {
+      T acc = T(0);
+      for (int dd = 0; dd < 3; ++dd) {
+        const int64_t c = r + (int64_t)(dd - 1) * s;
+        if (c >= 0 && c < n) acc += D[(int64_t)dd * n + r] * x[c];
+      }
+      y[r] = acc;
+    }
+  }
+}
+
 template <typename T>
 __global__ __launch_bounds__(kBlock) void pack_sband_kernel(int64_t n, int64_t w, int64_t s,
                                                             const T *__restrict__ dense, int64_t ld,
@@ -113,31 +146,36 @@ __global__ __launch_bounds__(kBlock) void leslie_kernel(int64_t n, const T *__re
                                                         const T *__restrict__ S, const T *__restrict__ x,
                                                         T *__restrict__ y) {
   __shared__ T part[kBlock / 64];
-  const int64_t stride = (int64_t)gridDim.x * kBlock;
+  constexpr int V = 16 / (int)sizeof(T);  // a lane takes the 16 bytes of consecutive rows of every stream at once
+  typedef T vecu __attribute__((ext_vector_type(V), aligned(sizeof(T))));
+  const int64_t stride = (int64_t)gridDim.x * kBlock * V;
   T acc = T(0);
-  int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  for (; j + 3 * stride < n; j += 4 * stride) {  // four independent rows in flight per lane
-    T xv[4], rv[4], sv[4];
-    const bool last = j + 3 * stride + 1 < n;  // only the fourth can be the row without a successor
+  int64_t j = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * V;
+  for (; j + 3 * stride + V < n; j += 4 * stride) {  // four independent groups of rows in flight per lane, all with successors
+    vecu xv[4], rv[4], sv[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      xv[q] = x[j + q * stride];
-      rv[q] = __builtin_nontemporal_load(R + j + q * stride);
+      xv[q] = *reinterpret_cast<const vecu *>(x + j + q * stride);
+      rv[q] = __builtin_nontemporal_load(reinterpret_cast<const vecu *>(R + j + q * stride));
+      sv[q] = __builtin_nontemporal_load(reinterpret_cast<const vecu *>(S + j + q * stride));
     }
 #pragma unroll
-    for (int q = 0; q < 3; ++q) sv[q] = __builtin_nontemporal_load(S + j + q * stride);
-    sv[3] = last ? __builtin_nontemporal_load(S + j + 3 * stride) : T(0);
+    for (int q = 0; q < 4; ++q) {
+      vecu p;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) acc += rv[q] * xv[q];
-#pragma unroll
-    for (int q = 0; q < 3; ++q) __builtin_nontemporal_store(sv[q] * xv[q], y + j + q * stride + 1);
-    if (last) __builtin_nontemporal_store(sv[3] * xv[3], y + j + 3 * stride + 1);
+      for (int v = 0; v < V; ++v) {
+        acc += rv[q][v] * xv[q][v];
+        p[v] = sv[q][v] * xv[q][v];
+      }
+      __builtin_nontemporal_store(p, reinterpret_cast<vecu *>(y + j + q * stride + 1));
+    }
   }
-  for (; j < n; j += stride) {
-    const T xj = x[j];
-    acc += __builtin_nontemporal_load(R + j) * xj;
-    if (j + 1 < n) __builtin_nontemporal_store(__builtin_nontemporal_load(S + j) * xj, y + j + 1);
-  }
+  for (; j < n; j += stride)
+    for (int64_t r = j; r < j + V && r < n; ++r) {
+      const T xr = x[r];
+      acc += R[r] * xr;
+      if (r + 1 < n) y[r + 1] = S[r] * xr;
+    }
   for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
   if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
   __syncthreads();
@@ -231,7 +269,7 @@ int sband_spmv(int64_t n, int64_t w, int64_t s, const T *D, const T *x, T *y, vo
   hipStream_t st = (hipStream_t)stream;
   const unsigned blocks = (unsigned)ceil_div(n, kBlock);
   if (w == 1)
-    sband_kernel<1, T><<<blocks, kBlock, 0, st>>>(n, 1, s, D, x, y);
+    sband_w1_kernel<T><<<(unsigned)ceil_div(n, kBlock * (16 / kB)), kBlock, 0, st>>>(n, s, D, x, y);
   else
     sband_kernel<-1, T><<<blocks, kBlock, 0, st>>>(n, (int)w, s, D, x, y);
   return launch_status();
@@ -321,7 +359,7 @@ int leslie_spmv(int64_t n, const T *R, const T *S, const T *x, T *y, void *strea
   hipStream_t st = (hipStream_t)stream;
   zero_tail_kernel<T><<<1, kBlock, 0, st>>>(y, 1);
   if (hipGetLastError() != hipSuccess) return DASTAC_EHIP;
-  const int64_t want = ceil_div(n, 4 * kBlock);  // about four rows per lane before the cap
+  const int64_t want = ceil_div(n, 4 * kBlock * (16 / kB));  // about four 16-byte groups of rows per lane before the cap
   const unsigned blocks = (unsigned)(want < 1 ? 1 : want > kLeslieMaxBlocks ? kLeslieMaxBlocks : want);
   leslie_kernel<T><<<blocks, kBlock, 0, st>>>(n, R, S, x, y);
   return launch_status();
