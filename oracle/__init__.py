@@ -445,26 +445,39 @@ def symm(n, m, Up, B, rows=None):
     return C, sc
 
 
-def _pr(fn, count, B, window):
+def _shifted(a: np.ndarray, ptr_type, lo: int):
+    """Pointer to where element 0 of the full array would be when `a` holds its elements lo.. only (the C
+    functions touch nothing outside the window they are given)."""
+    return ctypes.cast(a.ctypes.data - lo * a.itemsize, ptr_type)
+
+
+def _pr(fn, count, B, window, compact=False):
     B = _f32(B)
     N, d = B.shape
     lo, hi = (0, count) if window is None else (int(window[0]), int(window[1]))
+    assert 0 <= lo <= hi <= count
+    if compact:  # only the window is allocated and returned (the full tensor may not fit in host memory)
+        out = np.full(hi - lo, np.nan, dtype=np.float32)
+        sc = np.full(hi - lo, np.nan, dtype=np.float64)
+        fn(N, d, _f(B), d, _shifted(out, _fp, lo), _shifted(sc, _dp, lo), lo, hi)
+        return out, sc
     out = np.full(count, np.nan, dtype=np.float32)
     sc = np.full(count, np.nan, dtype=np.float64)
     fn(N, d, _f(B), d, _f(out), _d(sc), lo, hi)
     return out, sc
 
 
-def pr_a2(B, window=None):
-    """A2(i,j) = sum_x B(x,i) B(x,j), i<=j, packed; `window` selects packed positions [lo, hi)."""
+def pr_a2(B, window=None, compact=False):
+    """A2(i,j) = sum_x B(x,i) B(x,j), i<=j, packed; `window` selects packed positions [lo, hi) (with
+    `compact` only those are returned)."""
     d = B.shape[1]
-    return _pr(lib().oracle_pr_a2_f32, d * (d + 1) // 2, B, window)
+    return _pr(lib().oracle_pr_a2_f32, d * (d + 1) // 2, B, window, compact)
 
 
-def pr_a3(B, window=None):
+def pr_a3(B, window=None, compact=False):
     """A3(i,j,k) = sum_x B(x,i) B(x,j) B(x,k), i<=j<=k, packed."""
     d = B.shape[1]
-    return _pr(lib().oracle_pr_a3_f32, d * (d + 1) * (d + 2) // 6, B, window)
+    return _pr(lib().oracle_pr_a3_f32, d * (d + 1) * (d + 2) // 6, B, window, compact)
 
 
 # ---- double precision ---------------------------------------------------------
@@ -589,24 +602,30 @@ def ttm_ut_f64(n, Q, K, Bp, C, rows=None):
     return A, sc
 
 
-def _pr64(fn, count, B, window):
+def _pr64(fn, count, B, window, compact=False):
     B = _f64(B)
     N, d = B.shape
     lo, hi = (0, count) if window is None else (int(window[0]), int(window[1]))
+    assert 0 <= lo <= hi <= count
+    if compact:
+        out = np.full(hi - lo, np.nan, dtype=np.float64)
+        sc = np.full(hi - lo, np.nan, dtype=np.float64)
+        fn(N, d, _d(B), d, _shifted(out, _dp, lo), _shifted(sc, _dp, lo), lo, hi)
+        return out, sc
     out = np.full(count, np.nan, dtype=np.float64)
     sc = np.full(count, np.nan, dtype=np.float64)
     fn(N, d, _d(B), d, _d(out), _d(sc), lo, hi)
     return out, sc
 
 
-def pr_a2_f64(B, window=None):
+def pr_a2_f64(B, window=None, compact=False):
     d = B.shape[1]
-    return _pr64(lib().oracle_pr_a2_f64, d * (d + 1) // 2, B, window)
+    return _pr64(lib().oracle_pr_a2_f64, d * (d + 1) // 2, B, window, compact)
 
 
-def pr_a3_f64(B, window=None):
+def pr_a3_f64(B, window=None, compact=False):
     d = B.shape[1]
-    return _pr64(lib().oracle_pr_a3_f64, d * (d + 1) * (d + 2) // 6, B, window)
+    return _pr64(lib().oracle_pr_a3_f64, d * (d + 1) * (d + 2) // 6, B, window, compact)
 
 
 def tet_mttkrp_f64(n, R, Ap, B, C, rows=None):

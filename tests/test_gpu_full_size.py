@@ -199,6 +199,31 @@ def test_pr_tensors_sampled_positions(gpu, oracle, which, N, d):
         check(got[p:p + 3], want[p:p + 3], scale[p:p + 3], "pr_a%d position %d" % (which, p))
 
 
+@pytest.mark.parametrize("which,N,d,f64,samples", [(3, 64, 800, False, 24), (3, 24, 2100, False, 5), (3, 24, 2100, True, 3),
+                                                  (2, 200, 2100, True, 24)])
+def test_pr_tensors_larger_feature_counts_sampled_positions(gpu, oracle, which, N, d, f64, samples):
+    """The launch shapes that only larger d selects: four slices per workgroup of the third-order kernel (fp32,
+    d > 768), 64 x 128 tiles (d > 2048), 64 x 128 tiles of the second-order kernel in double precision."""
+    t = gpu.torch
+    B = inputs.normal(5200 + d + which, N, d)
+    if f64:
+        B = B.astype(np.float64)
+    count = d * (d + 1) // 2 if which == 2 else d * (d + 1) * (d + 2) // 6
+    out = t.full((count,), float("nan"), dtype=t.float64 if f64 else t.float32, device=gpu.dev)
+    fn = {(2, False): gpu.d.pr_a2_f32, (3, False): gpu.d.pr_a3_f32, (2, True): gpu.d.pr_a2_f64, (3, True): gpu.d.pr_a3_f64}[(which, f64)]
+    fn(N, d, gpu.up(B), d, out)
+    t.cuda.synchronize()
+    assert bool(t.isfinite(out).all())
+    orc = {(2, False): oracle.pr_a2, (3, False): oracle.pr_a3, (2, True): oracle.pr_a2_f64, (3, True): oracle.pr_a3_f64}[(which, f64)]
+    rng = np.random.default_rng(20 + which + d)
+    starts = sorted({0, d - 2, count - 3} | {int(r) for r in rng.integers(0, count - 3, samples)})
+    tol = 1e-12 if f64 else TOL
+    for p in starts:
+        want, scale = orc(B, window=(p, p + 3), compact=True)
+        got = out[p:p + 3].cpu().numpy().astype(np.float64)
+        assert (np.abs(got - want) <= tol * scale).all(), "position %d: %r against %r" % (p, got, want)
+
+
 def test_trmm_f64_16384_sampled_rows(gpu, oracle):
     """The double-precision TRMM at the shape bench.py reports beside the step (two shares of the k range per
     row-block pair): sampled rows against the long-double oracle, 1e-12 * sum|products|."""
