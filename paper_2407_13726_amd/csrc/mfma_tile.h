@@ -152,7 +152,11 @@ struct Core<double> {
 // The caller places a barrier between two sweeps that use the same buffers.  A wavefront with `active`
 // false stages and synchronises like the others but reads no operands and issues no matrix instructions
 // (its sub-tile holds nothing to compute).
-template <typename Ops, typename Stage, typename Load, typename Store, typename Read, typename Mma>
+// PIN: scheduling barriers keep the order as written.  Left alone, the compiler merges the two operand register
+// sets and issues a group's LDS reads after the previous group's matrix instructions instead of before them;
+// that is the faster code with one workgroup per CU or with run-time step bounds, the written order is faster
+// (by up to 8 %) where two workgroups share a CU and the bounds are literals, so the kernels choose.
+template <typename Ops, typename Stage, bool PIN = false, typename Load, typename Store, typename Read, typename Mma>
 __device__ inline void sweep_groups(int lo, int hi, Load load, Store store, Read read, Mma mma, bool active = true) {
   Stage st;
   Ops oa, ob;
@@ -163,19 +167,30 @@ __device__ inline void sweep_groups(int lo, int hi, Load load, Store store, Read
   auto step = [&](int kt, int buf) {
     const bool more = kt + 1 < hi;
     if (more) load(kt + 1, st);
+    auto pin = [] {
+      if (PIN) __builtin_amdgcn_sched_barrier(0);
+    };
     if (active) {
       read(buf, kt, 1, ob);
+      pin();
       mma(oa);
+      pin();
       read(buf, kt, 2, oa);
+      pin();
       mma(ob);
+      pin();
       read(buf, kt, 3, ob);
+      pin();
       mma(oa);
+      pin();
     }
     if (more) store(buf ^ 1, kt + 1, st);
     __syncthreads();
     if (active) {
       if (more) read(buf ^ 1, kt + 1, 0, oa);
+      pin();
       mma(ob);
+      pin();
     }
   };
   for (int kt = lo; kt < hi; kt += 2) {
@@ -185,12 +200,12 @@ __device__ inline void sweep_groups(int lo, int hi, Load load, Store store, Read
 }
 
 // The common case: one accumulator per wavefront, the operand groups and matrix instructions of Core<T>.
-template <typename T, typename Stage, typename Load, typename Store, typename Read>
+template <typename T, typename Stage, bool PIN = false, typename Load, typename Store, typename Read>
 __device__ inline void sweep_steps(int lo, int hi, typename Core<T>::Acc &acc, Load load, Store store, Read read,
                                    bool active = true) {
   typedef Core<T> K;
   static_assert(K::kGroups == 4, "the step schedule is written for four operand groups");
-  sweep_groups<typename K::Ops, Stage>(
+  sweep_groups<typename K::Ops, Stage, PIN>(
       lo, hi, load, store, read, [&](const typename K::Ops &o) { K::mma(o, acc); }, active);
 }
 

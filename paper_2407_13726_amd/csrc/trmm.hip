@@ -41,7 +41,8 @@ struct Stage {
   typename Core<T>::vec b[2];  // B: k rows bk and bk + kKT/2, one 16-byte piece of columns each
 };
 
-template <typename T, bool SPLIT>
+// PIN: the sweep's instructions stay in the written order (mfma_tile.h); chosen where two workgroups share a CU.
+template <typename T, bool SPLIT, bool PIN>
 __global__ __launch_bounds__(kTileThreads) void trmm_mfma_kernel(int64_t n, int64_t m, const T *__restrict__ U,
                                                                  const T *__restrict__ B, int64_t ldb,
                                                                  T *__restrict__ C, int64_t ldc, int nb, int npairs,
@@ -136,7 +137,7 @@ __global__ __launch_bounds__(kTileThreads) void trmm_mfma_kernel(int64_t n, int6
     typename K::Acc acc;
     K::clear(acc);
     __syncthreads();  // the previous row block's last reads of buffer 0 are done
-    sweep_steps<T, Stage<T>>(kt_lo, nk, acc, load_stage, store_stage, read_ops);
+    sweep_steps<T, Stage<T>, PIN>(kt_lo, nk, acc, load_stage, store_stage, read_ops);
     __syncthreads();  // all reads of this row block's buffers are done before the next block's stores
 
     K::for_each(acc, lane, [&](int r, int c, T v) {
@@ -204,13 +205,17 @@ int run(int64_t n, int64_t m, const T *Up, const T *B, int64_t ldb, T *C, int64_
     }
   }
   if (S <= 1) {
-    trmm_mfma_kernel<T, false><<<(unsigned)base, kBlock, 0, st>>>(n, m, Up, B, ldb, C, ldc, nb, npairs, ncb, 1);
+    // two or more workgroups per compute unit (n = 16384: m >= 512): the pinned schedule, 0.76 -> 0.82 of peak there
+    if (sizeof(T) == 4 && base >= 2 * (int64_t)cus)
+      trmm_mfma_kernel<T, false, true><<<(unsigned)base, kBlock, 0, st>>>(n, m, Up, B, ldb, C, ldc, nb, npairs, ncb, 1);
+    else
+      trmm_mfma_kernel<T, false, false><<<(unsigned)base, kBlock, 0, st>>>(n, m, Up, B, ldb, C, ldc, nb, npairs, ncb, 1);
     return launch_status();
   }
   const int64_t zb = ceil_div(n * ceil_div(m, 16 / kB), 256);
   zero_matrix_kernel<T><<<(unsigned)(zb < 4096 ? zb : 4096), 256, 0, st>>>(C, n, m, ldc);
   if (hipGetLastError() != hipSuccess) return DASTAC_EHIP;
-  trmm_mfma_kernel<T, true><<<(unsigned)(base * S), kBlock, 0, st>>>(n, m, Up, B, ldb, C, ldc, nb, npairs, ncb, (int)S);
+  trmm_mfma_kernel<T, true, false><<<(unsigned)(base * S), kBlock, 0, st>>>(n, m, Up, B, ldb, C, ldc, nb, npairs, ncb, (int)S);
   return launch_status();
 }
 

@@ -132,16 +132,27 @@ __global__ __launch_bounds__(kTileThreads) void ttm_mfma_kernel(int64_t rows, in
     cl = next(cl);
     const bool more = cl.valid;
     if (more) load_stage(cl, st);
+    // (Scheduling barriers keep the written order: left alone, the compiler merges the two operand register
+    // sets and issues a group's LDS reads after the previous group's matrix instructions instead of before
+    // them.  With two workgroups per CU and no shares, as here, the written order is 2.5 % faster.)
     read_ops(buf, 1, ob);
+    __builtin_amdgcn_sched_barrier(0);
     Kc::mma(oa, acc);
+    __builtin_amdgcn_sched_barrier(0);
     read_ops(buf, 2, oa);
+    __builtin_amdgcn_sched_barrier(0);
     Kc::mma(ob, acc);
+    __builtin_amdgcn_sched_barrier(0);
     read_ops(buf, 3, ob);
+    __builtin_amdgcn_sched_barrier(0);
     Kc::mma(oa, acc);
+    __builtin_amdgcn_sched_barrier(0);
     if (more) store_stage(buf ^ 1, st);
     __syncthreads();
     if (more) read_ops(buf ^ 1, 0, oa);
+    __builtin_amdgcn_sched_barrier(0);
     Kc::mma(ob, acc);
+    __builtin_amdgcn_sched_barrier(0);
     if (cc.kt == nk - 1) {
       Kc::for_each(acc, lane, [&](int r, int c, T v) {
         const int64_t row = cc.r0 + wr * 32 + r, col = c0 + wc * 32 + c;
