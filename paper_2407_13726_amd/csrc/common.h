@@ -68,6 +68,10 @@ inline int64_t resident_blocks(Kernel kernel, int block) {
 }
 #endif
 
+// defined in segsum.hip: y[0..n) := U x on the packed upper triangle and y[n..n+zeros) := 0, n >= 1, in one launch
+// while x fits in LDS (arguments otherwise already validated), both precisions
+int trmv_then_zeros(int64_t n, const float *Up, const float *x, float *y, int64_t zeros, void *stream);
+int trmv_then_zeros(int64_t n, const double *Up, const double *x, double *y, int64_t zeros, void *stream);
 // defined in trimv.hip
 int trmv_upper_by_panels(int64_t n, const float *Up, const float *x, float *y, void *stream);
 int trmv_upper_by_panels(int64_t n, const double *Up, const double *x, double *y, void *stream);

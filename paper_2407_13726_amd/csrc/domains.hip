@@ -220,12 +220,6 @@ inline int pack_triu(int64_t n, const float *d, int64_t ld, float *p, void *st) 
 inline int pack_triu(int64_t n, const double *d, int64_t ld, double *p, void *st) {
   return dastac_pack_triu_f64(n, d, ld, p, st);
 }
-inline int trmv(int64_t n, const float *U, const float *x, float *y, void *st) {
-  return dastac_trmv_f32(n, U, x, y, st);
-}
-inline int trmv(int64_t n, const double *U, const double *x, double *y, void *st) {
-  return dastac_trmv_f64(n, U, x, y, st);
-}
 
 template <typename T>
 int pack_sband(int64_t n, int64_t w, int64_t s, const T *dense, int64_t ld, T *diag_major, void *stream) {
@@ -309,15 +303,9 @@ int subtri_spmv(int64_t N, int64_t k, const T *Ap, const T *x, T *y, void *strea
   if (N == 0) return DASTAC_OK;
   if (!x || !y || (k > 0 && !Ap)) return DASTAC_ENULL;
   if (overlaps(y, N * kB, x, N * kB) || overlaps(y, N * kB, Ap, tri(k) * kB)) return DASTAC_EALIAS;
-  if (k > 0) {
-    const int rc = trmv(k, Ap, x + (N - k), y, stream);  // also bounds k
-    if (rc != DASTAC_OK) return rc;
-  }
-  if (k < N) {
-    zero_tail_kernel<T><<<(unsigned)ceil_div(N - k, kBlock), kBlock, 0, (hipStream_t)stream>>>(y + k, N - k);
-    return launch_status();
-  }
-  return DASTAC_OK;
+  if (k > 0) return trmv_then_zeros(k, Ap, x + (N - k), y, N - k, stream);  // also bounds k
+  zero_tail_kernel<T><<<(unsigned)ceil_div(N, kBlock), kBlock, 0, (hipStream_t)stream>>>(y, N);
+  return launch_status();
 }
 
 template <typename T>

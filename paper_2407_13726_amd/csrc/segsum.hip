@@ -172,12 +172,14 @@ struct Step32 {
 // STREAM: the packed buffer is larger than the memory-side cache, so its loads are non-temporal
 // (measured 10 % faster there); a smaller buffer is read through the caches, where the lines
 // shared by two neighbouring rows are fetched once (measured 9 % faster at 90 MB).
-template <typename T, bool TET, bool STREAM>
+// PAD: the output vector goes on for `zeros` entries behind the n sums, and they are zeros of the product (the
+// sub-triangular domain of Section 6.4 has no element in those rows); the launch clears them on its way.
+template <typename T, bool TET, bool STREAM, bool PAD = false>
 __global__ __launch_bounds__(kLdsBlock) void segsum_lds_kernel(int n, const T *__restrict__ A,
                                                                const T *__restrict__ x,
                                                                T *__restrict__ out, int64_t total,
                                                                int64_t total_a, int64_t share, int64_t waves_a,
-                                                               int tail_order) {
+                                                               int tail_order, int64_t zeros) {
   constexpr int kPer = Elem<T>::kPer, kLg = Elem<T>::kLg, kSpan = kSpanOf<T>, kPad = kPadOf<T>;
   typedef typename Elem<T>::vec vec;
   typedef typename Elem<T>::uvec uvec;
@@ -191,6 +193,9 @@ __global__ __launch_bounds__(kLdsBlock) void segsum_lds_kernel(int n, const T *_
     const int t = threadIdx.x + q * kLdsBlock;
     xr[q] = t < n ? x[t] : T(0);
   }
+  if (PAD)
+    for (int64_t t = (int64_t)blockIdx.x * kLdsBlock + threadIdx.x; t < zeros; t += (int64_t)gridDim.x * kLdsBlock)
+      out[n + t] = T(0);
   const int lane = threadIdx.x & 63;
   const int64_t wave = (int64_t)blockIdx.x * kLdsWaves + uniform32(threadIdx.x >> 6);
 
@@ -390,8 +395,8 @@ inline int64_t pick_share(int64_t total, int per_cu) {
 
 constexpr int64_t kStreamBytes = (int64_t)192 << 20;  // above this a buffer does not stay in the 256 MB memory-side cache
 
-template <typename T, bool TET>
-int launch_lds(int64_t n, const T *A, const T *x, T *out, int64_t total, void *stream) {
+template <typename T, bool TET, bool PAD = false>
+int launch_lds(int64_t n, const T *A, const T *x, T *out, int64_t total, void *stream, int64_t zeros = 0) {
   int64_t tail_order = 0, total_a = total;
   if (TET) {  // slices whose triangle is below about half a share get a wavefront of their own
     int64_t m0 = (int64_t)sqrt((double)pick_share(total, 24));
@@ -404,15 +409,41 @@ int launch_lds(int64_t n, const T *A, const T *x, T *out, int64_t total, void *s
   const int64_t blocks = ceil_div(waves_a + tail_order, kLdsWaves);
   const size_t lds = (size_t)(n + kPadOf<T>) * sizeof(T);
   if (total * (int64_t)sizeof(T) > kStreamBytes)
-    segsum_lds_kernel<T, TET, true><<<(unsigned)blocks, kLdsBlock, lds, (hipStream_t)stream>>>(
-        (int)n, A, x, out, total, total_a, share, waves_a, (int)tail_order);
+    segsum_lds_kernel<T, TET, true, PAD><<<(unsigned)blocks, kLdsBlock, lds, (hipStream_t)stream>>>(
+        (int)n, A, x, out, total, total_a, share, waves_a, (int)tail_order, zeros);
   else
-    segsum_lds_kernel<T, TET, false><<<(unsigned)blocks, kLdsBlock, lds, (hipStream_t)stream>>>(
-        (int)n, A, x, out, total, total_a, share, waves_a, (int)tail_order);
+    segsum_lds_kernel<T, TET, false, PAD><<<(unsigned)blocks, kLdsBlock, lds, (hipStream_t)stream>>>(
+        (int)n, A, x, out, total, total_a, share, waves_a, (int)tail_order, zeros);
+  return launch_status();
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void zero_entries_kernel(T *__restrict__ y, int64_t count) {
+  for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < count; t += (int64_t)gridDim.x * 256) y[t] = T(0);
+}
+
+template <typename T>
+int padded_trmv(int64_t n, const T *Up, const T *x, T *y, int64_t zeros, void *stream) {
+  if (n < 1 || zeros < 0) return DASTAC_EINVAL;
+  if (n > DASTAC_TRI_MAX_N || tri(n) > ((int64_t)1 << 40)) return DASTAC_EOVERFLOW;
+  if (n <= kLdsMaxN) return launch_lds<T, false, true>(n, Up, x, y, tri(n), stream, zeros);
+  const int rc = trmv_upper_by_panels(n, Up, x, y, stream);
+  if (rc != DASTAC_OK || zeros == 0) return rc;
+  const int64_t blocks = ceil_div(zeros, 256);
+  zero_entries_kernel<T><<<(unsigned)(blocks < 4096 ? blocks : 4096), 256, 0, (hipStream_t)stream>>>(y + n, zeros);
   return launch_status();
 }
 
 }  // namespace
+
+namespace dastac {
+int trmv_then_zeros(int64_t n, const float *Up, const float *x, float *y, int64_t zeros, void *stream) {
+  return padded_trmv<float>(n, Up, x, y, zeros, stream);
+}
+int trmv_then_zeros(int64_t n, const double *Up, const double *x, double *y, int64_t zeros, void *stream) {
+  return padded_trmv<double>(n, Up, x, y, zeros, stream);
+}
+}  // namespace dastac
 
 extern "C" {
 
