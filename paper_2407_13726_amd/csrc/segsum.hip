@@ -426,8 +426,10 @@ template <typename T>
 int padded_trmv(int64_t n, const T *Up, const T *x, T *y, int64_t zeros, void *stream) {
   if (n < 1 || zeros < 0) return DASTAC_EINVAL;
   if (n > DASTAC_TRI_MAX_N || tri(n) > ((int64_t)1 << 40)) return DASTAC_EOVERFLOW;
-  if (n <= kLdsMaxN) return launch_lds<T, false, true>(n, Up, x, y, tri(n), stream, zeros);
-  const int rc = trmv_upper_by_panels(n, Up, x, y, stream);
+  // the fill rides in the product's launch while it is small beside the triangle (its workgroups then clear a few
+  // entries each); a long tail behind a small triangle gets a launch of its own, sized for it
+  if (n <= kLdsMaxN && zeros <= tri(n) / 16) return launch_lds<T, false, true>(n, Up, x, y, tri(n), stream, zeros);
+  const int rc = n <= kLdsMaxN ? launch_lds<T, false>(n, Up, x, y, tri(n), stream) : trmv_upper_by_panels(n, Up, x, y, stream);
   if (rc != DASTAC_OK || zeros == 0) return rc;
   const int64_t blocks = ceil_div(zeros, 256);
   zero_entries_kernel<T><<<(unsigned)(blocks < 4096 ? blocks : 4096), 256, 0, (hipStream_t)stream>>>(y + n, zeros);

@@ -100,7 +100,7 @@ def test_pack_unpack_subtri_bit_exact(gpu, oracle, N, k, ld):
 
 
 @pytest.mark.parametrize("N,k", [(1, 0), (1, 1), (50, 0), (50, 1), (333, 100), (1000, 1000), (2048, 64), (2048, 511),
-                                 (4099, 4097), (9000, 8500)])
+                                 (4099, 4097), (9000, 8500), (300000, 100)])
 def test_subtri_spmv_parity(gpu, oracle, N, k):
     Ap, x = inputs.uniform(1310 + N + k, max(tri(k), 1)), inputs.normal(1311 + N, N)
     want, scale = oracle.subtri_spmv(N, k, Ap[: tri(k)], x)

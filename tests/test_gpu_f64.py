@@ -473,7 +473,7 @@ def test_pack_unpack_subtri_f64_bit_exact(gpu, oracle, N, k, ld):
 
 
 @pytest.mark.parametrize("N,k", [(1, 0), (1, 1), (50, 0), (50, 1), (333, 100), (1000, 1000), (2048, 511), (4099, 4097),
-                                 (9000, 8500)])
+                                 (9000, 8500), (200000, 90)])
 def test_subtri_spmv_f64_parity(gpu, oracle, N, k):
     Ap, x = inputs.uniform64(3630 + N + k, max(tri(k), 1)), inputs.uniform64(3631 + N, N)
     want, scale = oracle.subtri_spmv_f64(N, k, Ap[: tri(k)], x)
