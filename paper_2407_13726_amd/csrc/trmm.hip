@@ -16,7 +16,8 @@
 // pairing of row blocks, the XCD numbering and the shares.
 //
 // Only the k-steps that touch the diagonal block (and the ragged last step / last row block) take
-// the masked loader, which writes zeros for k<i; every other tile is loaded without predicates.
+// the masked loader, which writes zeros for k<i; every other tile is loaded without predicates, and those
+// steps run as a sweep of their own whose loop holds no test of the kind of step (benchmark shape: 585 -> 565 us).
 //
 // Load balance: row block b needs (n - 64 b)/32 k-steps, so a workgroup processes the pair
 // (b, nb-1-b), and every workgroup does the same amount of work.  Workgroups that share a
@@ -42,8 +43,14 @@ struct Stage {
 };
 
 // PIN: the sweep's instructions stay in the written order (mfma_tile.h); chosen where two workgroups share a CU.
+// The three sweeps of a whole tile (below) take the kernel past 128 registers.  Every launch but the one with a
+// single workgroup per CU (fp32, no shares, unpinned) wants two workgroups on a CU, so those instantiations are
+// held to the 128 registers of four wavefronts per SIMD; the few spilled values cost less than the second
+// workgroup brings (fp32 with shares, which had silently been running one workgroup per CU at 134 registers:
+// n=16384, m=384 0.92 -> 0.83 ms).
 template <typename T, bool SPLIT, bool PIN>
-__global__ __launch_bounds__(kTileThreads) void trmm_mfma_kernel(int64_t n, int64_t m, const T *__restrict__ U,
+__global__ __launch_bounds__(kTileThreads) __attribute__((amdgpu_waves_per_eu((SPLIT || PIN || sizeof(T) == 8) ? 4 : 1)))
+void trmm_mfma_kernel(int64_t n, int64_t m, const T *__restrict__ U,
                                                                  const T *__restrict__ B, int64_t ldb,
                                                                  T *__restrict__ C, int64_t ldc, int nb, int npairs,
                                                                  int ncb, int S) {
@@ -89,7 +96,7 @@ __global__ __launch_bounds__(kTileThreads) void trmm_mfma_kernel(int64_t n, int6
     // k-steps [kt_lo, nk) of this row block fall into the share
     const int first = which == 0 ? 0 : steps_a;  // number of the block's step 0 in the pair's list
     const int steps_blk = which == 0 ? steps_a : steps_b;
-    // (literal bounds without shares: the compiler then peels the masked steps off the loop)
+    // (literal bounds without shares: the first sweep below then has a compile-time trip count)
     const int kt_lo = SPLIT ? (t_lo > first ? t_lo - first : 0) : 0;
     const int nk = SPLIT ? (t_hi - first < steps_blk ? t_hi - first : steps_blk) : (int)ceil_div(n - i0, kKT);
     if (SPLIT && kt_lo >= nk) continue;
@@ -137,7 +144,39 @@ __global__ __launch_bounds__(kTileThreads) void trmm_mfma_kernel(int64_t n, int6
     typename K::Acc acc;
     K::clear(acc);
     __syncthreads();  // the previous row block's last reads of buffer 0 are done
-    sweep_steps<T, Stage<T>, PIN>(kt_lo, nk, acc, load_stage, store_stage, read_ops);
+    if (rows_full && cols_full) {
+      // A whole tile: the masked steps on the diagonal block, the whole steps behind it and a ragged last step are
+      // three sweeps, so that the long one carries no test of which kind of step it is on.
+      const int nfull = (int)((n - i0) / kKT);
+      const int a_hi = nk < kDiagSteps ? nk : kDiagSteps;
+      const int b_lo = kt_lo > kDiagSteps ? kt_lo : kDiagSteps, b_hi = nk < nfull ? nk : nfull;
+      const int c_lo = kt_lo > nfull ? kt_lo : nfull;
+      bool between = false;  // a sweep has run: barrier before the next one reuses the buffers
+      if (kt_lo < a_hi) {
+        sweep_steps<T, Stage<T>, PIN>(kt_lo, a_hi, acc, load_stage, store_stage, read_ops);
+        between = true;
+      }
+      if (b_lo < b_hi) {
+        if (between) __syncthreads();
+        sweep_steps<T, Stage<T>, PIN>(
+            b_lo, b_hi, acc,
+            [&](int kt, Stage<T> &s) {
+              const int64_t k0 = i0 + (int64_t)kt * kKT;
+              s.u = *reinterpret_cast<const uvec *>(ub + k0 + uk);
+#pragma unroll
+              for (int q = 0; q < 2; ++q)
+                s.b[q] = *reinterpret_cast<const uvec *>(B + (k0 + bk + (kKT / 2) * q) * ldb + col0 + bc);
+            },
+            store_stage, read_ops);
+        between = true;
+      }
+      if (c_lo < nk) {
+        if (between) __syncthreads();
+        sweep_steps<T, Stage<T>, PIN>(c_lo, nk, acc, load_stage, store_stage, read_ops);
+      }
+    } else {
+      sweep_steps<T, Stage<T>, PIN>(kt_lo, nk, acc, load_stage, store_stage, read_ops);
+    }
     __syncthreads();  // all reads of this row block's buffers are done before the next block's stores
 
     K::for_each(acc, lane, [&](int r, int c, T v) {
@@ -205,8 +244,8 @@ int run(int64_t n, int64_t m, const T *Up, const T *B, int64_t ldb, T *C, int64_
     }
   }
   if (S <= 1) {
-    // two or more workgroups per compute unit (n = 16384: m >= 512): the pinned schedule, 0.76 -> 0.82 of peak there
-    if (sizeof(T) == 4 && base >= 2 * (int64_t)cus)
+    // workgroups that share a compute unit (n = 16384: m >= 512): the pinned schedule, 0.76 -> 0.82 of peak there
+    if (sizeof(T) == 4 && base > cus)
       trmm_mfma_kernel<T, false, true><<<(unsigned)base, kBlock, 0, st>>>(n, m, Up, B, ldb, C, ldc, nb, npairs, ncb, 1);
     else
       trmm_mfma_kernel<T, false, false><<<(unsigned)base, kBlock, 0, st>>>(n, m, Up, B, ldb, C, ldc, nb, npairs, ncb, 1);
