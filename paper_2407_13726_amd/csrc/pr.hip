@@ -153,6 +153,15 @@ struct Tiles {
       }
     }
   }
+  // the same for a step that lies wholly inside the samples and the columns: no tests
+  __device__ void load_whole(int64_t x0, Stage<T> &s) const {
+#pragma unroll
+    for (int r = 0; r < kJRep; ++r)
+      s.a[r] = *reinterpret_cast<const uvec *>(B + (x0 + tk + kJRows * r) * ldb + j0 + ti);
+#pragma unroll
+    for (int r = 0; r < 2; ++r)
+      s.b[r] = *reinterpret_cast<const uvec *>(B + (x0 + bk + (kXT / 2) * r) * ldb + k0 + bc);
+  }
   __device__ void store(T *As, T *Bs, const Stage<T> &s) const {
 #pragma unroll
     for (int r = 0; r < kJRep; ++r) *reinterpret_cast<vec *>(&As[(tk + kJRows * r) * kJP + ti]) = s.a[r];
@@ -236,8 +245,16 @@ __global__ __launch_bounds__(4 * BK) void pr2_mfma_kernel(int64_t N, int64_t d, 
 
   typename K::Acc acc;
   K::clear(acc);
-  // (pinned order in double precision: 6 % faster there, no gain in single)
-  sweep_steps<T, Stage<T>, sizeof(T) == 8>(0, nk, acc, load_stage, store_stage, read_ops, live);
+  // The whole steps of a whole tile run as a sweep of their own, whose loop holds none of the edge tests; the
+  // ragged last step follows.  (Pinned order in double precision: 6 % faster there, no gain in single.)
+  const int nwhole = (tiles_io.j_full && tiles_io.k_full) ? (int)((xend - xbeg) / kXT) : 0;
+  if (nwhole > 0) {
+    sweep_steps<T, Stage<T>, sizeof(T) == 8>(
+        0, nwhole, acc, [&](int kt, Stage<T> &s) { tiles_io.load_whole(xbeg + (int64_t)kt * kXT, s); }, store_stage,
+        read_ops, live);
+    if (nk > nwhole) __syncthreads();
+  }
+  if (nk > nwhole) sweep_steps<T, Stage<T>, sizeof(T) == 8>(nwhole, nk, acc, load_stage, store_stage, read_ops, live);
 
   K::for_each(acc, lane, [&](int r, int c, T v) {
     const int64_t j = (int64_t)J * kBJ + wr * 32 + r, k = (int64_t)Kb * BK + wc * 32 + c;
@@ -345,7 +362,21 @@ void pr3_mfma_kernel(int64_t N, int64_t d, const T *__restrict__ B, int64_t ldb,
       K::mma(r, acc[ii]);
     }
   };
-  sweep_groups<Ops3<T, NI>, Stage<T>>(0, nk, load_stage, store_stage, read_ops, mma, live);
+  // whole steps of a whole tile first, in a sweep without edge tests, then the ragged last step
+  const int nwhole = (tiles_io.j_full && tiles_io.k_full) ? (int)((xend - xbeg) / kXT) : 0;
+  if (nwhole > 0) {
+    const bool w_mine = tid < kWThreads && i0 + wi < d;
+    sweep_groups<Ops3<T, NI>, Stage<T>>(
+        0, nwhole,
+        [&](int kt, Stage<T> &s) {
+          const int64_t x0 = xbeg + (int64_t)kt * kXT;
+          tiles_io.load_whole(x0, s);
+          if (tid < kWThreads) s.w = w_mine ? B[(x0 + wx) * ldb + i0 + wi] : T(0);
+        },
+        store_stage, read_ops, mma, live);
+    if (nk > nwhole) __syncthreads();
+  }
+  if (nk > nwhole) sweep_groups<Ops3<T, NI>, Stage<T>>(nwhole, nk, load_stage, store_stage, read_ops, mma, live);
   if (!live) return;
 
 #pragma unroll
