@@ -29,6 +29,14 @@ using namespace dastac;
 
 namespace {
 
+// tags that pick a step's flavour at compile time
+struct Whole {
+  static constexpr bool value = true;
+};
+struct Any {
+  static constexpr bool value = false;
+};
+
 template <typename T>
 struct Stage {
   typename Core<T>::vec a;     // Bp: row sr of the tile, one 16-byte piece of l values
@@ -123,15 +131,27 @@ __global__ __launch_bounds__(kTileThreads) void ttm_mfma_kernel(int64_t rows, in
   __syncthreads();
   read_ops(0, 0, oa);
 
-  // One step on LDS buffer `buf` (a literal at both call sites).  The global loads of the next
+  // One step on LDS buffer `buf` (a literal at every call site).  The global loads of the next
   // step -- of the next row block, at a block's last step -- are in flight throughout; its LDS
   // stores and the workgroup barrier sit before the last group's matrix instructions, whose
   // operands are already in registers.  (The schedule of mfma_tile.h's sweep, run as ONE pipeline over
   // all the workgroup's row blocks.)
-  auto step = [&](int buf) {
+  // WHOLE: the step being loaded exists and lies in a whole row block of a whole column block, with Q a
+  // multiple of the step (so does the step being multiplied, which comes before it): loads and the stores of
+  // a finished tile then need no test and no clamped row, and the loop made of such steps holds none.
+  const int64_t aoff = (int64_t)sr * Q + sl;
+  auto step = [&](int buf, auto whole_tag) {
+    constexpr bool WHOLE = decltype(whole_tag)::value;
     cl = next(cl);
-    const bool more = cl.valid;
-    if (more) load_stage(cl, st);
+    const bool more = WHOLE || cl.valid;
+    if (WHOLE) {
+      const int64_t l0 = (int64_t)cl.kt * kKT;
+      st.a = *reinterpret_cast<const uvec *>(Bp + (cl.r0 * Q + l0) + aoff);
+      st.c[0] = *reinterpret_cast<const uvec *>(cp0 + l0 + sl);
+      st.c[1] = *reinterpret_cast<const uvec *>(cp1 + l0 + sl);
+    } else if (more) {
+      load_stage(cl, st);
+    }
     // (Scheduling barriers keep the written order: left alone, the compiler merges the two operand register
     // sets and issues a group's LDS reads after the previous group's matrix instructions instead of before
     // them.  With two workgroups per CU and no shares, as here, the written order is 2.5 % faster.)
@@ -156,16 +176,26 @@ __global__ __launch_bounds__(kTileThreads) void ttm_mfma_kernel(int64_t rows, in
     if (cc.kt == nk - 1) {
       Kc::for_each(acc, lane, [&](int r, int c, T v) {
         const int64_t row = cc.r0 + wr * 32 + r, col = c0 + wc * 32 + c;
-        if (row < rows && col < K) Ap[row * K + col] = v;
+        if (WHOLE || (row < rows && col < K)) Ap[row * K + col] = v;
       });
       Kc::clear(acc);
     }
     cc = next(cc);
   };
+  // whole steps two at a time (all whole row blocks come before the ragged one), then the rest
+  if (full_c && Q % kKT == 0) {
+    auto whole = [&](const Cur &c) { return c.valid && c.r0 + kBM <= rows; };
+    for (;;) {
+      const Cur n1 = next(cl);
+      if (!whole(n1) || !whole(next(n1))) break;
+      step(0, Whole{});
+      step(1, Whole{});
+    }
+  }
   for (;;) {
-    step(0);
+    step(0, Any{});
     if (!cc.valid) break;
-    step(1);
+    step(1, Any{});
     if (!cc.valid) break;
   }
 }
