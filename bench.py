@@ -16,9 +16,10 @@ timed on a bounded sample of the same inputs as a baseline (not a target), and w
 compared with what the timed launches left in their output buffers: the run fails (exit status 1)
 when an element is further than 1e-4 * sum|products| from the oracle.
 
-Besides the K timed steps the line carries: `steady_state` (200 further steps, by which time the clocks
-have settled -- after an idle period the matrix-core kernels run about 10 % slower for the first ~15
-steps, so the figures of a short timed region depend on the warm-up), `stream_ref` (a plain read-only
+After an idle period the matrix-core kernels run about 10 % slower for the first ~15 steps, so K steps timed
+right after W warm-up steps give a figure that depends on W.  That figure is reported as `after_idle`; the
+timed region proper (`value`, `roofline`) times the same K steps again after `--settle-steps` further untimed
+steps (default 100), and `steady_state` times 200 more at the end.  Besides these the line carries `stream_ref` (a plain read-only
 stream over the same byte count as each bandwidth-bound contraction, measured the same way), `sweep`
 (TRMV, TTV and MTTKRP at larger sizes) and `pack` (compression / decompression throughput).
 
@@ -65,6 +66,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20,
                     help="untimed steps before the timed ones (default 20: after an idle period the matrix-core "
                          "kernels run about 10 %% slower for the first ~15 steps)")
+    ap.add_argument("--settle-steps", type=int, default=100,
+                    help="further untimed steps between the `after_idle` timing of the K steps and the timed region "
+                         "(0: no `after_idle` leg, the timed region follows the warm-up directly)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--no-sweep", action="store_true",
                     help="skip the size sweep of TRMV, TTV and MTTKRP (reported under \"sweep\", never in value)")
@@ -153,20 +157,37 @@ def main() -> int:
     # Timed region: K steps.  Only the dominant kernel, whose duration the roofline needs, is bracketed by
     # events here: an event pair costs 3-6 us of dispatch gap per launch, which would otherwise add about
     # 2 % to the step.  The other kernels' durations come from a second, fully bracketed pass below.
-    dev_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for s in range(args.steps):
-        for k in order:
-            if k == dom:
-                dev_ev[s][0].record()
+    def timed_region():
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(args.steps):
+            for k in order:
+                if k == dom:
+                    evs[s][0].record()
+                    launch[k]()
+                    evs[s][1].record()
+                else:
+                    launch[k]()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        return (t1 - t0) * 1e3 / args.steps, evs
+
+    # The same K steps are timed twice.  First right after the W warm-up steps, as a short job that finds the
+    # device idle would see them: for its first ~15 ms of matrix-core work the device runs about 10 % slower, so
+    # this figure depends on W; it is reported as `after_idle`.  Then, after `--settle-steps` further untimed
+    # steps (default 100, about 90 ms), the timed region proper, whose figures (`value`, `roofline`) therefore do
+    # not depend on W.
+    after_idle = None
+    if args.settle_steps > 0:
+        ms_idle, ev_idle = timed_region()
+        dom_idle = float(np.mean([a.elapsed_time(b) for a, b in ev_idle]))
+        after_idle = {"steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_idle, "kernel": dom,
+                      "kernel_ms": dom_idle}
+        for _ in range(args.settle_steps):
+            for k in order:
                 launch[k]()
-                dev_ev[s][1].record()
-            else:
-                launch[k]()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step, dev_ev = timed_region()
     dom_ms_timed = float(np.mean([a.elapsed_time(b) for a, b in dev_ev]))
 
     # second pass, same K steps, every launch bracketed: per-kernel durations
@@ -247,6 +268,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": "one pass over all five packed contractions: TRMV n=512; TRMM n=16384 m=256; "
                                "band SpMV n=4194304 w=16; tet TTV n=512; tet MTTKRP n=1024 R=32"},
+        "settle_steps": args.settle_steps,
         "step_gbps": total_bytes / ms_per_step / 1e6,
         "roofline": roof,
         "kernels": kernels,
@@ -256,6 +278,15 @@ def main() -> int:
                          "at 2.2 GHz (Clang 18, -O3 -fopenmp -ffast-math); it has no GPU figures and its absolute "
                          "throughputs are only in plots (Section 6.1 and 6.2)",
     }
+
+    if after_idle:
+        fl_dom = acct[dom]["flops"]
+        after_idle["value"] = total_flops / after_idle["ms_per_step"] / 1e6
+        after_idle["unit"] = "GFLOP/s"
+        after_idle["roofline_frac"] = (acct[dom]["bytes"] / after_idle["kernel_ms"] / 1e6 / HBM_PEAK_GBPS
+                                       if bound[dom] == "hbm"
+                                       else fl_dom / after_idle["kernel_ms"] / 1e9 / MFMA_F32_PEAK_TFLOPS)
+        result["after_idle"] = after_idle
 
     # The measured streaming reference: the library's read-only stream (non-temporal 16-byte loads, one
     # partial sum per workgroup) over the same number of bytes as each bandwidth-bound contraction moves,
@@ -342,8 +373,15 @@ def main() -> int:
         # symmetric product on a packed triangle, and the strided-band, sub-triangular and Leslie SpMVs,
         # which are not among the five benchmark configurations.
         def beside(fn):
-            for _ in range(args.warmup):
-                fn()
+            # warm-up: at least W launches and at least 30 ms of this kernel, so that the figure does not depend
+            # on W (the clocks have dropped while the host prepared the inputs; see `after_idle`)
+            w0 = time.perf_counter()
+            while True:
+                for _ in range(max(args.warmup, 1)):
+                    fn()
+                torch.cuda.synchronize()
+                if time.perf_counter() - w0 > 0.03:
+                    break
             ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
             ev[0].record()
             for s in range(args.steps):
