@@ -221,8 +221,8 @@ int run(int64_t n, int64_t m, const T *Up, const T *B, int64_t ldb, T *C, int64_
   // Shares of the k range per pair: the smallest S <= 16, with at least 32 k-steps per share, whose
   // workgroups come in whole layers of two per compute unit (fp32, n = 16384: m = 128 58 -> 111 TFLOP/s, m = 384
   // 93 -> 120; n = 8192, m = 256 114).  In fp32, where the column blocks alone give one full layer of one
-  // workgroup per compute unit (m = 256 at n = 16384), a second layer gains 1 % (0.589 -> 0.582 ms with the
-  // clearing of C): not worth giving up plain stores and one writer per element, so S = 1 there.  In fp64 the
+  // workgroup per compute unit (m = 256 at n = 16384), a second layer gains nothing (0.57 ms either way, the
+  // clearing of C included): no reason to give up plain stores and one writer per element, so S = 1 there.  In fp64 the
   // second layer pays at every shape measured (n = 16384: m = 256 1.19 -> 1.12 ms, m = 128 0.63 -> 0.59;
   // n = 8192, m = 256 0.32 -> 0.29), so there is no such exception; with two shares an element of C still gets
   // at most two addends, whose sum does not depend on their order.
